@@ -1,0 +1,8 @@
+"""MI355X-native exact low-bit integer GEMM (IM-Unpack, arXiv 2403.07339).
+
+``paper_2403_07339_amd.binding`` wraps the C-ABI HIP library (it raises if the
+library has not been built); ``paper_2403_07339_amd.workloads`` draws the seeded
+synthetic operands.  Nothing is imported eagerly so that the input generators
+can be used on machines without the built library.
+"""
+__all__ = ["binding", "workloads"]
