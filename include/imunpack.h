@@ -1,0 +1,174 @@
+/*
+ * imunpack.h -- C ABI of the MI355X (gfx950) exact low-bit integer GEMM library.
+ *
+ * The operations are those of "IM-Unpack: Training and Inference with Arbitrarily Low
+ * Precision Integers" (arXiv 2403.07339):
+ *
+ *   Sec. 1, Eq. (gemm)            C = A B^T,  A: n x d,  B: h x d,  C: n x h
+ *   Sec. 2, Eq. (quantized_A)     A_q = round(A / scale)            (all entries, no clipping)
+ *   Sec. 2, Eq. (quantized_gemm)  C  ~= scale_A * scale_B * (A_q B_q^T)
+ *   Sec. 4                        s = 2^(b-1); an entry v is In-Bound iff |v| <= s-1, else
+ *                                 Out-of-Bound (OB, a "heavy hitter")
+ *   Sec. 4, Eq. (mod)             digits m(v, s, i), each In-Bound, v = sum_i s^i m(v, s, i)
+ *   Alg. 1 / 2 / 4 / 5            UnpackRow, UnpackColumn, UnpackBoth and the dispatcher Unpack
+ *   Sec. 4 "Combining everything" (A_u, B_e, S_u, Pi_A)    = Unpack(A,   B,   I,   b, strategy_A)
+ *                                 (B_eu, A_ue, S_uu, Pi_B) = Unpack(B_e, A_u, S_u, b, strategy_B)
+ *                                 A B^T = Pi_A A_ue S_uu B_eu^T Pi_B^T
+ *   Alg. 3                        ScaledMatMul: one low-bit GEMM per distinct diagonal entry of S
+ *   Sec. 4.2                      unpack ratio r = n' d' h' / (n d h)
+ *
+ * Throughout, "row" is the non-contracted index (n or h) and "column" the contracted one (d).
+ * Digits follow the sign-magnitude reading of floor/mod: digit i of v is
+ * sign(v) * ((|v| >> (b-1) i) & (s-1)), which is the only reading under which every digit lies in
+ * the symmetric In-Bound interval the paper states.  Rounding is IEEE binary32 division followed
+ * by round-half-to-even.  UnpackBoth breaks ties between equal OB counts by the lowest index
+ * (rows before columns when the two top counts are equal, as Alg. 4 prints).
+ *
+ * Conventions
+ *   - Every pointer named "device" is GPU memory owned by the caller (hipMalloc / a PyTorch
+ *     tensor); "host" pointers are ordinary host memory.  The library owns only plan objects.
+ *   - Every function returns IMUNPACK_OK (0) or a negative error code; nothing throws or aborts.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on it unless stated otherwise.
+ *   - All matrices are row-major; ld* is the distance in elements between consecutive rows.
+ *   - 2 <= b <= 8: unpacked operands are stored as int8 for every b.
+ */
+#ifndef IMUNPACK_H
+#define IMUNPACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *imunpack_stream_t;
+typedef struct imunpack_plan imunpack_plan_t;
+
+enum { IMUNPACK_ROW = 0, IMUNPACK_COL = 1, IMUNPACK_BOTH = 2 };
+
+enum {
+    IMUNPACK_OK = 0,
+    IMUNPACK_EINVAL = -1, /* null pointer, b outside [2,8], unknown strategy, bad sizes or strides */
+    IMUNPACK_ERANGE = -2, /* a value or an accumulator bound does not fit (see each call)           */
+    IMUNPACK_ENOMEM = -3, /* device or host allocation failed                                       */
+    IMUNPACK_EHIP = -4,   /* a HIP call failed; see imunpack_last_hip_error()                       */
+    IMUNPACK_ESMALL = -5  /* a caller buffer or workspace is too small                              */
+};
+
+/* Heavy-hitter statistics of one integer operand (device pointers, lengths rows / cols):
+ * OB count and largest magnitude per row and per column.  (Sec. 4: the IB/OB predicate;
+ * Alg. 1 line 3, Alg. 2 line 3, Alg. 4 line 3 consume them.) */
+typedef struct {
+    int32_t *rowcnt;
+    int32_t *colcnt;
+    int32_t *rowmax;
+    int32_t *colmax;
+} imunpack_stats_t;
+
+/* ---- (1)+(2) RTN quantisation fused with the heavy-hitter scan --------------------------------
+ * Sec. 2, Eq. (quantized_A) with the step supplied by the caller:
+ *     Q[r*ldq + c] = rint(X[r*sx_r + c*sx_c] / scale)      (int32, no clipping)
+ * and, in the same pass, the statistics of Q for bit width b (any of the four stats pointers, or
+ * stats itself, may be NULL to skip it).  X, Q, stats, status: device.  X may be any strided view
+ * (sx_c == 1 and sx_r == 1 have fast paths); Q is written row-major.
+ * status (device int32, may be NULL) is set to 0, then to 1 if any input is NaN/Inf or any
+ * quotient has magnitude >= 2^31 (such outputs are written as 0); the call itself still returns
+ * IMUNPACK_OK -- read status when convenient.
+ * Errors: EINVAL (null X/Q, rows/cols < 0, ldq < cols, scale not finite or <= 0, b outside [2,8]). */
+int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                      float scale, int b, int32_t *Q, int64_t ldq,
+                      const imunpack_stats_t *stats, int32_t *status, imunpack_stream_t stream);
+
+/* ---- (2) stand-alone scan of an integer operand (Sec. 4, IB/OB definition) -------------------- */
+int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
+                  const imunpack_stats_t *stats, imunpack_stream_t stream);
+
+/* ---- (3) unpack plan (Alg. 1, 2, 4, 5 and the two-operand composition of Sec. 4) -------------
+ * Decides every row / column split for A (with B as partner) and then for B (with A_u as partner
+ * and S_u carried over) without moving the operands.  A: n x d, B: h x d, int32, device.
+ * stats_A / stats_B: statistics of A / B for this b as written by imunpack_quantize or
+ * imunpack_scan; NULL lets the call scan the operand itself.
+ * *plan == NULL creates a plan object; a non-NULL *plan is re-planned in place and its device
+ * buffers are reused (they only grow), so that steady-state calls allocate nothing.
+ * Synchronises the stream (the sizes n', d', h' are needed on the host).
+ * Errors: EINVAL; ERANGE if an exponent group is too long for int32 accumulation or a weight
+ * s^k would not fit 62 bits; ENOMEM; EHIP. */
+int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda,
+                  const int32_t *B, int64_t h, int64_t ldb,
+                  int b, int strategy_A, int strategy_B,
+                  const imunpack_stats_t *stats_A, const imunpack_stats_t *stats_B,
+                  imunpack_plan_t **plan, imunpack_stream_t stream);
+
+/* Sizes of the unpacked problem (host outputs; any may be NULL): n', d', h' of Sec. 4.2 and the
+ * number of distinct diagonal entries of S_uu (the GEMM groups of Alg. 3). */
+int imunpack_plan_dims(const imunpack_plan_t *plan, int64_t *n_u, int64_t *d_u, int64_t *h_u,
+                       int32_t *n_groups);
+
+/* The plan in the order the paper's algorithms produce it (host buffers sized from
+ * imunpack_plan_dims; any may be NULL).  Pi_A column R is s^rowA_exp[R] at row rowA_src[R]; Pi_B
+ * likewise; S_uu[c,c] = s^col_exp[c]; col_src[c] is the original column that unpacked column c
+ * descends from.  Synchronises the stream used by imunpack_plan. */
+int imunpack_plan_export(const imunpack_plan_t *plan,
+                         int32_t *rowA_src, int32_t *rowA_exp,  /* n' */
+                         int32_t *rowB_src, int32_t *rowB_exp,  /* h' */
+                         int32_t *col_src, int32_t *col_exp);   /* d' */
+
+int imunpack_plan_destroy(imunpack_plan_t *plan);
+
+/* ---- (4) digit scatter (Eq. (mod); Alg. 1 l.4-5, Alg. 2 l.4-6, Alg. 4 l.7-8, 11-13) -----------
+ * Writes A_ue and B_eu as int8 in the plan's *physical* layout: rows grouped by source row (all
+ * digit levels of a row inside one GEMM tile), columns grouped by diagonal entry of S_uu, both
+ * zero-padded to tile multiples.  The partner's columns are duplicated where a column was split.
+ * imunpack_unpacked_bytes gives the buffer sizes and the workspace an un-fused GEMM needs.
+ * A, B: the int32 operands the plan was made from.  A_ue, B_eu: device, caller-allocated.
+ * imunpack_unpack synchronises the stream once at its end (it returns the accumulator bound that
+ * selects the GEMM path to the host). */
+int imunpack_unpacked_bytes(const imunpack_plan_t *plan, size_t *bytes_A, size_t *bytes_B,
+                            size_t *bytes_workspace);
+int imunpack_unpack(imunpack_plan_t *plan, const int32_t *A, int64_t lda,
+                    const int32_t *B, int64_t ldb, int8_t *A_ue, int8_t *B_eu,
+                    imunpack_stream_t stream);
+
+/* Test aid: re-orders the physical operands into the paper's order, dense n' x d' and h' x d'. */
+int imunpack_unpack_canonical(const imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
+                              int8_t *A_canon, int8_t *B_canon, imunpack_stream_t stream);
+
+/* ---- (5) int8 MFMA GEMM (Alg. 3) ---------------------------------------------------------------
+ * Runs C_g = A_ue[:, I_g] B_eu[:, I_g]^T for every group g of equal diagonal entry with int32
+ * accumulation on v_mfma_i32_*_i8 and combines the groups by shifts.
+ * fuse != 0: one launch; the recombination (6) and the dequantisation run in the epilogue and
+ *   C_int (n x h int64, device, may be NULL) and/or C_fp (n x h fp32, device, may be NULL) are
+ *   written directly.  This needs the shifted sum of all groups to fit int32 for this plan's
+ *   operands (bound measured by imunpack_unpack); if it does not, the call falls back to the
+ *   un-fused path when workspace != NULL and returns ERANGE otherwise.
+ * fuse == 0: writes the unpacked product C_u = A_ue S_uu B_eu^T as int64 into workspace
+ *   (imunpack_unpacked_bytes) for imunpack_recombine; C_int / C_fp are ignored.
+ * ldc: row stride of C_int and C_fp in elements (>= h).  scale_A, scale_B: the RTN steps. */
+int imunpack_gemm(const imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
+                  void *workspace, int64_t *C_int, float *C_fp, int64_t ldc,
+                  float scale_A, float scale_B, int fuse, imunpack_stream_t stream);
+
+/* ---- (6) recombination and dequantisation (Sec. 4 "Reconstructing A"; Eq. (quantized_gemm)) ---
+ * C_int = Pi_A C_u Pi_B^T by shift-and-add in int64 from the workspace of an un-fused
+ * imunpack_gemm, and C_fp = scale_A * scale_B * C_int (one rounding to fp32).  Either output may
+ * be NULL. */
+int imunpack_recombine(const imunpack_plan_t *plan, const void *workspace,
+                       float scale_A, float scale_B, int64_t *C_int, float *C_fp, int64_t ldc,
+                       imunpack_stream_t stream);
+
+/* ---- diagnostics ------------------------------------------------------------------------------- */
+/* Per-kernel device time of the last call of each stage on this plan is not kept; callers time
+ * with events.  These two describe errors. */
+const char *imunpack_strerror(int code);
+int imunpack_last_hip_error(void);
+
+/* Which GEMM path the plan's last imunpack_unpack selected: 1 = single fused launch is exact,
+ * 0 = the shifted group sum may exceed int32 and the un-fused path is required. */
+int imunpack_plan_fusable(const imunpack_plan_t *plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IMUNPACK_H */

@@ -1,0 +1,264 @@
+"""Thin ctypes binding of libimunpack.so: argument marshalling only.
+
+Function names and argument order follow ``include/imunpack.h``.  PyTorch is used for device
+memory and streams; every step of the path runs in the library's HIP kernels.  Importing this
+module raises if the library has not been built (``python -m paper_2403_07339_amd.build``); there
+is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+ROW, COL, BOTH = 0, 1, 2
+OK, EINVAL, ERANGE, ENOMEM, EHIP, ESMALL = 0, -1, -2, -3, -4, -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libimunpack.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_07339_amd.build`")
+_lib = C.CDLL(LIB_PATH)
+
+EXPORTS = [
+    "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
+    "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
+    "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
+    "imunpack_plan_fusable",
+]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("rowcnt", C.c_void_p), ("colcnt", C.c_void_p), ("rowmax", C.c_void_p), ("colmax", C.c_void_p)]
+
+
+_vp, _i64, _i32, _f32 = C.c_void_p, C.c_int64, C.c_int, C.c_float
+_lib.imunpack_quantize.argtypes = [_vp, _i64, _i64, _i64, _i64, _f32, _i32, _vp, _i64, C.POINTER(_Stats), _vp, _vp]
+_lib.imunpack_scan.argtypes = [_vp, _i64, _i64, _i64, _i32, C.POINTER(_Stats), _vp]
+_lib.imunpack_plan.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32,
+                               C.POINTER(_Stats), C.POINTER(_Stats), C.POINTER(_vp), _vp]
+_lib.imunpack_plan_dims.argtypes = [_vp, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), C.POINTER(C.c_int32)]
+_lib.imunpack_plan_export.argtypes = [_vp] + [_vp] * 6
+_lib.imunpack_plan_destroy.argtypes = [_vp]
+_lib.imunpack_unpacked_bytes.argtypes = [_vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+_lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
+_lib.imunpack_unpack_canonical.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
+_lib.imunpack_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _i32, _vp]
+_lib.imunpack_recombine.argtypes = [_vp, _vp, _f32, _f32, _vp, _vp, _i64, _vp]
+_lib.imunpack_strerror.argtypes = [_i32]
+_lib.imunpack_strerror.restype = C.c_char_p
+_lib.imunpack_plan_fusable.argtypes = [_vp]
+for _name in EXPORTS:
+    if _name != "imunpack_strerror":
+        getattr(_lib, _name).restype = C.c_int
+
+
+class ImunpackError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib.imunpack_strerror(code).decode()
+        if code == EHIP:
+            msg += f" (hipError {_lib.imunpack_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise ImunpackError(code, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class Stats:
+    """OB count and largest magnitude per row and per column of an integer operand (device int32)."""
+    rowcnt: torch.Tensor
+    colcnt: torch.Tensor
+    rowmax: torch.Tensor
+    colmax: torch.Tensor
+
+    @staticmethod
+    def empty(rows: int, cols: int, device) -> "Stats":
+        buf = torch.empty(2 * (rows + cols), dtype=torch.int32, device=device)
+        return Stats(buf[:rows], buf[rows:rows + cols], buf[rows + cols:2 * rows + cols], buf[2 * rows + cols:])
+
+    def _c(self) -> _Stats:
+        return _Stats(self.rowcnt.data_ptr(), self.colcnt.data_ptr(), self.rowmax.data_ptr(), self.colmax.data_ptr())
+
+
+def imunpack_quantize(X: torch.Tensor, scale: float, b: int, Q: torch.Tensor | None = None,
+                      stats: Stats | None = None, status: torch.Tensor | None = None,
+                      want_stats: bool = True):
+    """Q = rint(X / scale) (int32, row-major) fused with the heavy-hitter scan.  X: 2-D fp32 device
+    tensor, any strides.  Returns (Q, stats, status)."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+    rows, cols = X.shape
+    if Q is None:
+        Q = torch.empty((rows, cols), dtype=torch.int32, device=X.device)
+    if stats is None and want_stats:
+        stats = Stats.empty(rows, cols, X.device)
+    if status is None:
+        status = torch.empty(1, dtype=torch.int32, device=X.device)
+    cs = stats._c() if stats is not None else None
+    _check(_lib.imunpack_quantize(X.data_ptr(), rows, cols, X.stride(0), X.stride(1), float(scale), b,
+                                  Q.data_ptr(), Q.stride(0), C.byref(cs) if cs else None,
+                                  status.data_ptr(), _stream()), "imunpack_quantize")
+    return Q, stats, status
+
+
+def imunpack_scan(Q: torch.Tensor, b: int, stats: Stats | None = None) -> Stats:
+    assert Q.is_cuda and Q.dtype == torch.int32 and Q.dim() == 2 and Q.stride(1) == 1
+    rows, cols = Q.shape
+    if stats is None:
+        stats = Stats.empty(rows, cols, Q.device)
+    cs = stats._c()
+    _check(_lib.imunpack_scan(Q.data_ptr(), rows, cols, Q.stride(0), b, C.byref(cs), _stream()), "imunpack_scan")
+    return stats
+
+
+class Plan:
+    """Owns an imunpack_plan_t; re-planning through the same object reuses its device buffers."""
+
+    def __init__(self):
+        self._h = _vp(None)
+        self.n = self.d = self.h = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def destroy(self):
+        if self._h and self._h.value:
+            _lib.imunpack_plan_destroy(self._h)
+            self._h = _vp(None)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def dims(self):
+        n_u, d_u, h_u, ng = _i64(), _i64(), _i64(), C.c_int32()
+        _check(_lib.imunpack_plan_dims(self._h, C.byref(n_u), C.byref(d_u), C.byref(h_u), C.byref(ng)),
+               "imunpack_plan_dims")
+        return n_u.value, d_u.value, h_u.value, ng.value
+
+    def unpack_ratio(self) -> float:
+        n_u, d_u, h_u, _ = self.dims()
+        return (n_u * d_u * h_u) / (self.n * self.d * self.h)
+
+    def export(self):
+        """Canonical plan as host int32 tensors: rowA_src, rowA_exp, rowB_src, rowB_exp, col_src, col_exp."""
+        n_u, d_u, h_u, _ = self.dims()
+        outs = [torch.empty(k, dtype=torch.int32) for k in (n_u, n_u, h_u, h_u, d_u, d_u)]
+        _check(_lib.imunpack_plan_export(self._h, *[o.data_ptr() for o in outs]), "imunpack_plan_export")
+        return outs
+
+    def unpacked_bytes(self):
+        a, b_, w = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(_lib.imunpack_unpacked_bytes(self._h, C.byref(a), C.byref(b_), C.byref(w)), "imunpack_unpacked_bytes")
+        return a.value, b_.value, w.value
+
+    def fusable(self) -> bool:
+        return bool(_lib.imunpack_plan_fusable(self._h))
+
+
+def imunpack_plan(A: torch.Tensor, B: torch.Tensor, b: int, strategy_a: int, strategy_b: int,
+                  stats_a: Stats | None = None, stats_b: Stats | None = None, plan: Plan | None = None) -> Plan:
+    """Plans Unpack(A, B, I, b, strategy_a) then Unpack(B_e, A_u, S_u, b, strategy_b).  A: n x d, B: h x d int32."""
+    assert A.is_cuda and B.is_cuda and A.dtype == torch.int32 and B.dtype == torch.int32
+    assert A.stride(1) == 1 and B.stride(1) == 1 and A.shape[1] == B.shape[1]
+    if plan is None:
+        plan = Plan()
+    ca = stats_a._c() if stats_a is not None else None
+    cb = stats_b._c() if stats_b is not None else None
+    _check(_lib.imunpack_plan(A.data_ptr(), A.shape[0], A.shape[1], A.stride(0), B.data_ptr(), B.shape[0],
+                              B.stride(0), b, strategy_a, strategy_b, C.byref(ca) if ca else None,
+                              C.byref(cb) if cb else None, C.byref(plan._h), _stream()), "imunpack_plan")
+    plan.n, plan.d, plan.h = A.shape[0], A.shape[1], B.shape[0]
+    return plan
+
+
+def imunpack_unpack(plan: Plan, A: torch.Tensor, B: torch.Tensor, A_ue: torch.Tensor | None = None,
+                    B_eu: torch.Tensor | None = None):
+    """Writes the int8 operands in the plan's physical layout; returns (A_ue, B_eu) as flat int8 buffers."""
+    ba, bb, _ = plan.unpacked_bytes()
+    if A_ue is None:
+        A_ue = torch.empty(ba, dtype=torch.int8, device=A.device)
+    if B_eu is None:
+        B_eu = torch.empty(bb, dtype=torch.int8, device=A.device)
+    assert A_ue.numel() >= ba and B_eu.numel() >= bb
+    _check(_lib.imunpack_unpack(plan.handle, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0),
+                                A_ue.data_ptr(), B_eu.data_ptr(), _stream()), "imunpack_unpack")
+    return A_ue, B_eu
+
+
+def imunpack_unpack_canonical(plan: Plan, A_ue: torch.Tensor, B_eu: torch.Tensor):
+    """Test aid: the unpacked operands in the paper's order, dense (n' x d', h' x d') int8."""
+    n_u, d_u, h_u, _ = plan.dims()
+    Ac = torch.empty((n_u, d_u), dtype=torch.int8, device=A_ue.device)
+    Bc = torch.empty((h_u, d_u), dtype=torch.int8, device=A_ue.device)
+    _check(_lib.imunpack_unpack_canonical(plan.handle, A_ue.data_ptr(), B_eu.data_ptr(), Ac.data_ptr(),
+                                          Bc.data_ptr(), _stream()), "imunpack_unpack_canonical")
+    return Ac, Bc
+
+
+def imunpack_gemm(plan: Plan, A_ue: torch.Tensor, B_eu: torch.Tensor, scale_a: float, scale_b: float,
+                  C_int: torch.Tensor | None = None, C_fp: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None, fuse: bool = True):
+    """int8 MFMA GEMM; with fuse=True also recombines and dequantises into C_int / C_fp."""
+    ldc = 0
+    for t in (C_int, C_fp):
+        if t is not None:
+            assert t.stride(1) == 1
+            ldc = t.stride(0)
+    if C_int is not None and C_fp is not None:
+        assert C_int.stride(0) == C_fp.stride(0)
+    _check(_lib.imunpack_gemm(plan.handle, A_ue.data_ptr(), B_eu.data_ptr(), _ptr(workspace), _ptr(C_int),
+                              _ptr(C_fp), ldc, float(scale_a), float(scale_b), 1 if fuse else 0, _stream()),
+           "imunpack_gemm")
+
+
+def imunpack_recombine(plan: Plan, workspace: torch.Tensor, scale_a: float, scale_b: float,
+                       C_int: torch.Tensor | None = None, C_fp: torch.Tensor | None = None):
+    ldc = 0
+    for t in (C_int, C_fp):
+        if t is not None:
+            ldc = t.stride(0)
+    _check(_lib.imunpack_recombine(plan.handle, workspace.data_ptr(), float(scale_a), float(scale_b),
+                                   _ptr(C_int), _ptr(C_fp), ldc, _stream()), "imunpack_recombine")
+
+
+def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale_b: float, b: int,
+                   strategy_a: int, strategy_b: int, want_int: bool = True, want_fp: bool = True,
+                   plan: Plan | None = None, fuse: bool = True):
+    """The whole hot path: quantize -> plan -> unpack -> GEMM (+ recombine, dequantise).
+    Returns (C_int or None, C_fp or None, plan)."""
+    dev = A_fp.device
+    Aq, sa, st_a = imunpack_quantize(A_fp, scale_a, b)
+    Bq, sb, st_b = imunpack_quantize(B_fp, scale_b, b)
+    plan = imunpack_plan(Aq, Bq, b, strategy_a, strategy_b, sa, sb, plan)
+    A_ue, B_eu = imunpack_unpack(plan, Aq, Bq)
+    n, h = A_fp.shape[0], B_fp.shape[0]
+    C_int = torch.empty((n, h), dtype=torch.int64, device=dev) if want_int else None
+    C_fp = torch.empty((n, h), dtype=torch.float32, device=dev) if want_fp else None
+    ws = None
+    if not fuse or not plan.fusable():
+        ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device=dev)
+    if fuse:
+        imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, C_int, C_fp, ws, fuse=True)
+    else:
+        imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, None, None, ws, fuse=False)
+        imunpack_recombine(plan, ws, scale_a, scale_b, C_int, C_fp)
+    if int(st_a.item()) or int(st_b.item()):
+        raise ImunpackError(ERANGE, "imunpack_quantize status")
+    return C_int, C_fp, plan

@@ -1,0 +1,129 @@
+// Shared declarations of the gfx950 IM-Unpack library (host + device).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/imunpack.h"
+
+namespace imu {
+
+// ---- error plumbing ---------------------------------------------------------------------------
+extern thread_local int g_last_hip_error;
+
+#define IMU_HIP(call)                                   \
+    do {                                                \
+        hipError_t e__ = (call);                        \
+        if (e__ != hipSuccess) {                        \
+            imu::g_last_hip_error = (int)e__;           \
+            return IMUNPACK_EHIP;                       \
+        }                                               \
+    } while (0)
+
+#define IMU_TRY(expr)                                   \
+    do {                                                \
+        int rc__ = (expr);                              \
+        if (rc__ != IMUNPACK_OK) return rc__;           \
+    } while (0)
+
+static inline int launch_status() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return IMUNPACK_EHIP;
+    }
+    return IMUNPACK_OK;
+}
+
+// ---- geometry shared by planner, scatter and GEMM ----------------------------------------------
+constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both operands)
+constexpr int kKPad = 64;        // every exponent group is padded to a multiple of this many columns
+constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
+constexpr uint32_t kNever = 0xFFFFFFFFu;  // split time of a row/column that is never split
+
+// One set of growing row (or column) slots: what Pi (or S) needs per slot, plus the split
+// bookkeeping that lets the scatter kernel follow an entry's digits.
+struct SlotSet {
+    int32_t *root;    // original row / phase-entry column this slot descends from
+    int32_t *exp;     // number of splits between root and this slot (digit level along this axis)
+    uint32_t *time;   // when this slot was split (order among all splits of the phase), kNever if not
+    int32_t *child;   // slot created by that split, -1 if none
+    int32_t cap;
+};
+
+// Header kept on the device and mirrored to the host after planning.
+struct PlanHeader {
+    int32_t n_u, h_u, d1, d_u;       // n', h', columns after unpacking A, d'
+    int32_t Mp, Np, Kp;              // physical (padded) sizes
+    int32_t mtiles, ntiles;
+    int32_t lmaxA, lmaxB;            // largest number of digit levels of a row of A / B
+    int32_t ngroups;
+    int32_t grp_exp[kMaxGroups];     // exponent of s per group, descending
+    int32_t grp_k0[kMaxGroups];      // first physical column
+    int32_t grp_len[kMaxGroups];     // real columns (without padding)
+    int32_t edgesA, edgesB, rawB;    // OB entry lists built for UnpackBoth
+    int32_t overflow;                // bit set: which capacity was too small
+    int32_t need[8];                 // size that would have been needed, per capacity
+    int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
+    uint32_t pad_;
+    unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
+};
+
+enum CapIndex { CAP_ROWA = 0, CAP_ROWB = 1, CAP_C1 = 2, CAP_C2 = 3, CAP_EDGEA = 4, CAP_EDGEB = 5, CAP_RAWB = 6 };
+
+// Physical-row description used by scatter and by the GEMM epilogue.
+struct RowLayout {
+    int32_t *prow_slot;   // [Mp]  canonical slot of physical row, -1 = padding
+    int32_t *prow_src;    // [Mp]  source row, -1 = padding
+    int32_t *prow_exp;    // [Mp]  digit level of the row
+    int32_t *row_phys;    // [n']  physical row of canonical slot
+    int32_t *src_pstart;  // [n]   first physical row of source row i
+    int32_t *src_nlev;    // [n]   number of levels of source row i
+    int32_t *tile_src0;   // [tiles+1] first source row of each tile
+    int32_t *tile_flat;   // [tiles]   1 if every source row of the tile has a single level
+};
+
+struct ColLayout {
+    int32_t *pcol_slot;   // [Kp] canonical column slot, -1 = padding
+    int32_t *col_phys;    // [d'] physical column of canonical slot
+    int32_t *colA_k;      // [Kp] original column k (-1 = padding)
+    int32_t *colA_c1;     // [Kp] column slot after unpacking A that this column copies
+    int32_t *colA_e;      // [Kp] its digit level along the columns of A
+    int32_t *colB_e;      // [Kp] digit level along the columns of B_e
+    int32_t *col_sexp;    // [Kp] exponent of the diagonal entry of S
+};
+
+}  // namespace imu
+
+// Opaque plan object.
+struct imunpack_plan {
+    // problem
+    int64_t n, d, h;
+    int b, sA, sB;
+    int s, sh;
+    hipStream_t stream;
+    // device arena
+    char *arena;
+    size_t arena_bytes;
+    // capacities (grow on overflow)
+    int32_t cap[8];
+    // views into the arena (valid after a successful imunpack_plan)
+    imu::PlanHeader *d_hdr;
+    imu::PlanHeader hdr;          // host mirror
+    imu::SlotSet rowA, rowB, c1, c2;
+    imu::RowLayout layA, layB;
+    imu::ColLayout cols;
+    int32_t *statsA[4], *statsB[4];   // rowcnt, colcnt, rowmax, colmax actually used
+    // greedy scratch
+    int32_t *eR, *eC, *eV, *redge, *cedge;
+    int32_t *rcnt, *ccnt, *rstart, *rlen, *cstart, *clen, *batch;
+    int32_t *rawJ, *rawK, *rawV;
+    int32_t *tmpL, *tmpCur, *tmpP;
+    int fusable;      // set by imunpack_unpack
+    int unpacked;
+    int valid;
+};
+
+namespace imu {
+using Plan = struct ::imunpack_plan;  // the C function imunpack_plan() hides the bare struct name
+}

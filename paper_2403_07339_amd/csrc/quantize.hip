@@ -1,0 +1,230 @@
+// RTN quantisation (Sec. 2, Eq. quantized_A) fused with the heavy-hitter scan (Sec. 4, IB/OB
+// definition): one pass reads fp32 (or int32 for the stand-alone scan), writes int32 and reduces
+// the OB count and the largest magnitude of every row and every column.
+//
+// HBM-bound: 4 B read + 4 B written per element (4 B read for the stand-alone scan).
+#include "common.h"
+
+namespace imu {
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// q = rint(x / scale): correctly rounded binary32 division, then round half to even.
+__device__ __forceinline__ int32_t rtn_one(float x, float scale, int &bad) {
+    float r = rintf(__fdiv_rn(x, scale));
+    if (!(fabsf(r) < 2147483648.0f)) {  // also catches NaN and Inf
+        bad = 1;
+        return 0;
+    }
+    return (int32_t)r;
+}
+
+__device__ __forceinline__ int iabs_sat(int32_t v) { return v < 0 ? (v == INT32_MIN ? INT32_MAX : -v) : v; }
+
+__global__ void fill_i32_kernel(int32_t *p, int64_t count, int32_t value) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += step) p[i] = value;
+}
+
+// Column partials of one workgroup: wave w holds, per lane, the statistics of its own columns over
+// the rows that wave visited; they are combined through LDS and one atomic per column is issued.
+template <int COLS_PER_LANE>
+__device__ __forceinline__ void flush_columns(int (&ccnt)[COLS_PER_LANE], int (&cmax)[COLS_PER_LANE],
+                                              int64_t c_first, int64_t cols, int32_t *colcnt,
+                                              int32_t *colmax, int *lds /* [2][4][64*CPL] */) {
+    constexpr int W = 64 * COLS_PER_LANE;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < COLS_PER_LANE; ++u) {
+        lds[(0 * 4 + wave) * W + lane * COLS_PER_LANE + u] = ccnt[u];
+        lds[(1 * 4 + wave) * W + lane * COLS_PER_LANE + u] = cmax[u];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < W; c += 256) {
+        int cnt = 0, mx = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            cnt += lds[(0 * 4 + w) * W + c];
+            mx = max(mx, lds[(1 * 4 + w) * W + c]);
+        }
+        int64_t col = c_first + c;
+        if (col < cols) {
+            if (colcnt && cnt) atomicAdd(&colcnt[col], cnt);
+            if (colmax && mx) atomicMax(&colmax[col], mx);
+        }
+    }
+}
+
+// Fast path: unit column stride, 16-byte aligned rows.  Workgroup = 64 rows x 256 columns;
+// a wave reads one 1 KiB row segment per instruction (float4 per lane).
+template <bool FROM_FLOAT>
+__global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__ Xv, int64_t rows,
+                                                        int64_t cols, int64_t ldx, float scale, int s,
+                                                        int32_t *__restrict__ Q, int64_t ldq,
+                                                        int32_t *rowcnt, int32_t *colcnt,
+                                                        int32_t *rowmax, int32_t *colmax,
+                                                        int32_t *status) {
+    __shared__ int lds[2 * 4 * 256];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t c0 = (int64_t)blockIdx.x * 256 + lane * 4;
+    const int64_t r_base = (int64_t)blockIdx.y * 64;
+    int ccnt[4] = {0, 0, 0, 0}, cmax[4] = {0, 0, 0, 0};
+    int bad = 0;
+    const bool in_cols = c0 < cols;  // cols % 4 == 0 on this path
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const int64_t r = r_base + wave + 4 * it;
+        if (r >= rows) break;  // uniform per wave
+        int4 q = make_int4(0, 0, 0, 0);
+        if (in_cols) {
+            if (FROM_FLOAT) {
+                const float4 x = *reinterpret_cast<const float4 *>(
+                    reinterpret_cast<const float *>(Xv) + r * ldx + c0);
+                q.x = rtn_one(x.x, scale, bad);
+                q.y = rtn_one(x.y, scale, bad);
+                q.z = rtn_one(x.z, scale, bad);
+                q.w = rtn_one(x.w, scale, bad);
+                *reinterpret_cast<int4 *>(Q + r * ldq + c0) = q;
+            } else {
+                q = *reinterpret_cast<const int4 *>(reinterpret_cast<const int32_t *>(Xv) + r * ldx + c0);
+            }
+        }
+        const int a0 = iabs_sat(q.x), a1 = iabs_sat(q.y), a2 = iabs_sat(q.z), a3 = iabs_sat(q.w);
+        const int o0 = a0 >= s, o1 = a1 >= s, o2 = a2 >= s, o3 = a3 >= s;
+        ccnt[0] += o0; ccnt[1] += o1; ccnt[2] += o2; ccnt[3] += o3;
+        cmax[0] = max(cmax[0], a0); cmax[1] = max(cmax[1], a1);
+        cmax[2] = max(cmax[2], a2); cmax[3] = max(cmax[3], a3);
+        // row statistics: popcount of the wave's ballots, wave-wide max
+        const int rc = __popcll(__ballot(o0)) + __popcll(__ballot(o1)) + __popcll(__ballot(o2)) +
+                       __popcll(__ballot(o3));
+        const int rm = wave_max_i32(max(max(a0, a1), max(a2, a3)));
+        if (lane == 0) {
+            if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
+            if (rowmax && rm) atomicMax(&rowmax[r], rm);
+        }
+    }
+    if (colcnt || colmax)
+        flush_columns<4>(ccnt, cmax, (int64_t)blockIdx.x * 256, cols, colcnt, colmax, lds);
+    if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
+}
+
+// General path: any strides.  Workgroup = 64 x 64 tile staged through LDS so that reads follow the
+// input's unit-stride axis (if it has one) and writes follow the rows of Q.
+template <bool FROM_FLOAT>
+__global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict__ Xv, int64_t rows,
+                                                         int64_t cols, int64_t sx_r, int64_t sx_c,
+                                                         float scale, int s, int32_t *__restrict__ Q,
+                                                         int64_t ldq, int32_t *rowcnt, int32_t *colcnt,
+                                                         int32_t *rowmax, int32_t *colmax,
+                                                         int32_t *status) {
+    __shared__ int32_t tile[64][65];
+    __shared__ int lds[2 * 4 * 64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    int bad = 0;
+    const bool along_rows = (sx_r == 1 && sx_c != 1);  // unit stride runs down the rows
+    for (int it = 0; it < 16; ++it) {
+        const int a = wave + 4 * it;  // slow index of this pass
+        const int rr = along_rows ? lane : a;
+        const int cc = along_rows ? a : lane;
+        const int64_t r = r0 + rr, c = c0 + cc;
+        int32_t q = 0;
+        if (r < rows && c < cols) {
+            if (FROM_FLOAT)
+                q = rtn_one(reinterpret_cast<const float *>(Xv)[r * sx_r + c * sx_c], scale, bad);
+            else
+                q = reinterpret_cast<const int32_t *>(Xv)[r * sx_r + c * sx_c];
+        }
+        tile[rr][cc] = q;
+    }
+    __syncthreads();
+    int ccnt[1] = {0}, cmax[1] = {0};
+    for (int it = 0; it < 16; ++it) {
+        const int rr = wave + 4 * it;
+        const int64_t r = r0 + rr, c = c0 + lane;
+        const bool ok = r < rows && c < cols;
+        const int32_t q = tile[rr][lane];
+        if (FROM_FLOAT && ok) Q[r * ldq + c] = q;
+        const int a = iabs_sat(q);
+        const int o = a >= s;
+        ccnt[0] += o;
+        cmax[0] = max(cmax[0], a);
+        const int rc = __popcll(__ballot(o));
+        const int rm = wave_max_i32(a);
+        if (lane == 0 && r < rows) {
+            if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
+            if (rowmax && rm) atomicMax(&rowmax[r], rm);
+        }
+    }
+    if (colcnt || colmax) flush_columns<1>(ccnt, cmax, c0, cols, colcnt, colmax, lds);
+    if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
+}
+
+static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, int32_t *status,
+                      hipStream_t stream) {
+    if (st) {
+        int32_t *p[4] = {st->rowcnt, st->colcnt, st->rowmax, st->colmax};
+        int64_t len[4] = {rows, cols, rows, cols};
+        for (int i = 0; i < 4; ++i)
+            if (p[i] && len[i] > 0) {
+                int blocks = (int)((len[i] + 255) / 256);
+                if (blocks > 1024) blocks = 1024;
+                hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks), dim3(256), 0, stream, p[i], len[i], 0);
+            }
+    }
+    if (status) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, status, (int64_t)1, 0);
+    return launch_status();
+}
+
+template <bool FROM_FLOAT>
+static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
+                     int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status,
+                     hipStream_t stream) {
+    if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
+    if (FROM_FLOAT && (!Q || ldq < cols || !(scale > 0.0f) || !(scale < INFINITY))) return IMUNPACK_EINVAL;
+    IMU_TRY(zero_stats(st, rows, cols, FROM_FLOAT ? status : nullptr, stream));
+    if (rows == 0 || cols == 0) return IMUNPACK_OK;
+    const int s = 1 << (b - 1);
+    int32_t *rowcnt = st ? st->rowcnt : nullptr, *colcnt = st ? st->colcnt : nullptr;
+    int32_t *rowmax = st ? st->rowmax : nullptr, *colmax = st ? st->colmax : nullptr;
+    if (!FROM_FLOAT && !rowcnt && !colcnt && !rowmax && !colmax) return IMUNPACK_OK;
+    const bool vec = sx_c == 1 && (cols % 4) == 0 && (sx_r % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
+                     (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0));
+    if (vec) {
+        dim3 grid((unsigned)((cols + 255) / 256), (unsigned)((rows + 63) / 64));
+        if (grid.y > 65535u * 16u) return IMUNPACK_EINVAL;
+        hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
+                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status);
+    } else {
+        dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+        hipLaunchKernelGGL(qscan_tile_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
+                           sx_c, scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status);
+    }
+    return launch_status();
+}
+
+int scan_i32(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
+             const imunpack_stats_t *st, hipStream_t stream) {
+    return run_qscan<false>(Q, rows, cols, ldq, 1, 1.0f, b, nullptr, 0, st, nullptr, stream);
+}
+
+}  // namespace imu
+
+extern "C" int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                                 float scale, int b, int32_t *Q, int64_t ldq,
+                                 const imunpack_stats_t *stats, int32_t *status,
+                                 imunpack_stream_t stream) {
+    return imu::run_qscan<true>(X, rows, cols, sx_r, sx_c, scale, b, Q, ldq, stats, status,
+                                (hipStream_t)stream);
+}
+
+extern "C" int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
+                             const imunpack_stats_t *stats, imunpack_stream_t stream) {
+    if (!Q || ldq < cols) return IMUNPACK_EINVAL;
+    return imu::scan_i32(Q, rows, cols, ldq, b, stats, (hipStream_t)stream);
+}

@@ -1,0 +1,230 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, element by element, through the
+C ABI.  Integer results must match bit for bit; the dequantised fp32 output must be within 1e-6
+relative of the oracle's fp64 value."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_07339_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+ROW, COL, BOTH = 0, 1, 2
+STRATS = (ROW, COL, BOTH)
+REL_TOL = 1e-6  # relative error allowed on the dequantised fp32 output
+
+
+@pytest.fixture(scope="module")
+def imu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2403_07339_amd import binding
+    return binding
+
+
+def dev(x):
+    return x.to("cuda")
+
+
+def oracle_quant(x: torch.Tensor, scale):
+    q, st = oracle.rtn_quantize(x.contiguous().numpy(), scale)
+    assert st == 0
+    return q
+
+
+def np_stats(q, s):
+    a = np.abs(q.astype(np.int64))
+    ob = a >= s
+    return ob.sum(1), ob.sum(0), a.max(1), a.max(0)
+
+
+# ------------------------------------------------------------------ quantize + scan
+@pytest.mark.parametrize("shape", [(64, 256), (200, 1000), (77, 130), (1, 5), (513, 260), (300, 64)])
+@pytest.mark.parametrize("b", [8, 4])
+def test_quantize_and_scan(imu, shape, b):
+    g = torch.Generator().manual_seed(shape[0] * 1000 + shape[1] + b)
+    x = torch.randn(shape, generator=g) * 3
+    x[torch.rand(shape, generator=g) < 0.01] *= 100
+    # exact ties in units of the step
+    scale = float(np.float32(0.0371))
+    x.view(-1)[: min(64, x.numel())] = (torch.arange(min(64, x.numel())) - 20 + 0.5) * np.float32(scale)
+    s = 1 << (b - 1)
+    want = oracle_quant(x, scale)
+    Q, st, status = imu.imunpack_quantize(dev(x), scale, b)
+    assert int(status.item()) == 0
+    assert np.array_equal(Q.cpu().numpy(), want)
+    rc, cc, rm, cm = np_stats(want, s)
+    assert np.array_equal(st.rowcnt.cpu().numpy(), rc) and np.array_equal(st.colcnt.cpu().numpy(), cc)
+    assert np.array_equal(st.rowmax.cpu().numpy(), rm) and np.array_equal(st.colmax.cpu().numpy(), cm)
+    st2 = imu.imunpack_scan(Q, b)
+    for f in ("rowcnt", "colcnt", "rowmax", "colmax"):
+        assert torch.equal(getattr(st, f), getattr(st2, f))
+    # transposed view (unit stride down the rows) and a general strided view
+    xt = dev(x.t().contiguous()).t()
+    Qt, stt, _ = imu.imunpack_quantize(xt, scale, b)
+    assert np.array_equal(Qt.cpu().numpy(), want)
+    assert np.array_equal(stt.colmax.cpu().numpy(), cm) and np.array_equal(stt.rowcnt.cpu().numpy(), rc)
+    wide = dev(torch.zeros(shape[0], 2 * shape[1]))
+    wide[:, ::2] = dev(x)
+    Qs, sts, _ = imu.imunpack_quantize(wide[:, ::2], scale, b)
+    assert np.array_equal(Qs.cpu().numpy(), want)
+    assert np.array_equal(sts.colcnt.cpu().numpy(), cc) and np.array_equal(sts.rowmax.cpu().numpy(), rm)
+
+
+def test_quantize_flags_bad_input(imu):
+    x = torch.ones(8, 8)
+    x[3, 4] = float("nan")
+    _, _, status = imu.imunpack_quantize(dev(x), 1.0, 8)
+    assert int(status.item()) == 1
+    x[3, 4] = 3.0e9
+    Q, _, status = imu.imunpack_quantize(dev(x), 1.0, 8)
+    assert int(status.item()) == 1 and int(Q[3, 4].item()) == 0
+    x[3, 4] = 2.0e9
+    Q, _, status = imu.imunpack_quantize(dev(x), 1.0, 8)
+    assert int(status.item()) == 0 and int(Q[3, 4].item()) == 2000000000
+    with pytest.raises(imu.ImunpackError):
+        imu.imunpack_quantize(dev(x), 0.0, 8)
+    with pytest.raises(imu.ImunpackError):
+        imu.imunpack_quantize(dev(x), 1.0, 9)
+
+
+# ------------------------------------------------------------------ plan + operands + product
+def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, full_product=True):
+    """Aq, Bq: int32 numpy.  Compares plan, unpacked operands, int64 product (fused and un-fused)
+    and the fp32 output with the oracle."""
+    n, h = Aq.shape[0], Bq.shape[0]
+    s = 1 << (b - 1)
+    hnd = oracle.unpack_pair_handle(Aq, Bq, b, sa, sb)
+    S, pas, paw, pbs, pbw = hnd.meta()
+    assert hnd.max_abs() <= s - 1
+    A_d, B_d = dev(torch.from_numpy(Aq)), dev(torch.from_numpy(Bq))
+    plan = imu.imunpack_plan(A_d, B_d, b, sa, sb)
+    n_u, d_u, h_u, ng = plan.dims()
+    assert (n_u, d_u, h_u) == (hnd.n_u, hnd.d_u, hnd.h_u)
+    ra_s, ra_e, rb_s, rb_e, c_s, c_e = [t.numpy().astype(np.int64) for t in plan.export()]
+    assert np.array_equal(ra_s, pas) and np.array_equal(s ** ra_e.astype(object), paw.astype(object))
+    assert np.array_equal(rb_s, pbs) and np.array_equal(s ** rb_e.astype(object), pbw.astype(object))
+    assert np.array_equal(s ** c_e.astype(object), S.astype(object))
+    assert ng == len(np.unique(S))
+    A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d)
+    Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
+    oa, ob = hnd.operands_i8()
+    assert np.array_equal(Ac.cpu().numpy(), oa)
+    assert np.array_equal(Bc.cpu().numpy(), ob)
+    # padding of the physical layout must be zero: total magnitude is preserved
+    assert int(A_ue.to(torch.int64).abs().sum().item()) == int(np.abs(oa.astype(np.int64)).sum())
+    assert int(B_eu.to(torch.int64).abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
+    want = oracle.int_gemm(Aq, Bq)
+    want_fp = oracle.dequantize(want, scale_a, scale_b)
+    ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+    results = []
+    # un-fused: GEMM into the int64 workspace, then recombine
+    C_int = torch.full((n, h), -7, dtype=torch.int64, device="cuda")
+    C_fp = torch.full((n, h), -7.0, dtype=torch.float32, device="cuda")
+    imu.imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, None, None, ws, fuse=False)
+    imu.imunpack_recombine(plan, ws, scale_a, scale_b, C_int, C_fp)
+    results.append(("unfused", C_int, C_fp))
+    # fused (falls back to the un-fused kernels by itself when the int32 bound does not hold)
+    C_int2 = torch.full((n, h), -7, dtype=torch.int64, device="cuda")
+    C_fp2 = torch.full((n, h), -7.0, dtype=torch.float32, device="cuda")
+    imu.imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, C_int2, C_fp2, ws, fuse=True)
+    results.append(("fused" if plan.fusable() else "fused->fallback", C_int2, C_fp2))
+    for name, ci, cf in results:
+        assert np.array_equal(ci.cpu().numpy(), want), name
+        got = cf.cpu().numpy().astype(np.float64)
+        err = np.abs(got - want_fp)
+        assert (err <= REL_TOL * np.abs(want_fp)).all(), name
+    hnd.close()
+    return plan
+
+
+def rand_ints(rng, rows, cols, s, p_ob, depth):
+    M = rng.integers(-(s - 1), s, size=(rows, cols))
+    mask = rng.random((rows, cols)) < p_ob
+    big = rng.integers(-(s ** depth), s ** depth + 1, size=(rows, cols))
+    return np.where(mask, big, M).astype(np.int32)
+
+
+@pytest.mark.parametrize("sa,sb", list(itertools.product(STRATS, STRATS)))
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_small_random_all_strategies(imu, sa, sb, b):
+    rng = np.random.default_rng(100 * b + 10 * sa + sb)
+    s = 1 << (b - 1)
+    depth = 3 if b > 2 else 5
+    Aq = rand_ints(rng, 70, 90, s, 0.03, depth)
+    Bq = rand_ints(rng, 50, 90, s, 0.03, depth)
+    check_against_oracle(imu, Aq, Bq, b, sa, sb)
+
+
+@pytest.mark.parametrize("kind", ["scattered", "channels", "rows", "heavy", "clean", "deep"])
+@pytest.mark.parametrize("sa,sb", [(BOTH, BOTH), (ROW, COL), (COL, ROW), (COL, COL)])
+def test_structured_multi_tile(imu, kind, sa, sb):
+    """Shapes that span several GEMM tiles with ragged tails, heavy hitters laid out as in the
+    paper's workloads (a few channels, scattered entries, heavy tails)."""
+    w = workloads.small(7, 300, 330, 270, kind=kind, b=8)
+    Aq = oracle_quant(w.A, w.scale_a)
+    Bq = oracle_quant(w.B, w.scale_b)
+    check_against_oracle(imu, Aq, Bq, 8, sa, sb, w.scale_a, w.scale_b)
+
+
+@pytest.mark.parametrize("b", [3, 5, 6, 7])
+def test_other_bit_widths(imu, b):
+    w = workloads.small(11, 130, 200, 140, kind="scattered", b=b)
+    Aq = oracle_quant(w.A, w.scale_a)
+    Bq = oracle_quant(w.B, w.scale_b)
+    check_against_oracle(imu, Aq, Bq, b, BOTH, COL, w.scale_a, w.scale_b)
+    check_against_oracle(imu, Aq, Bq, b, ROW, BOTH, w.scale_a, w.scale_b)
+
+
+def test_degenerate_shapes(imu):
+    rng = np.random.default_rng(5)
+    for (n, d, h) in [(1, 1, 1), (1, 300, 1), (257, 1, 3), (2, 65, 600)]:
+        Aq = rand_ints(rng, n, d, 128, 0.1, 3)
+        Bq = rand_ints(rng, h, d, 128, 0.1, 3)
+        for sa, sb in [(ROW, ROW), (COL, COL), (BOTH, BOTH)]:
+            check_against_oracle(imu, Aq, Bq, 8, sa, sb)
+    # the scalar example of Sec. 4: five base-128 digits each, 25 low-bit multiplications
+    Aq = np.array([[2 ** 31 - 1]], dtype=np.int32)
+    Bq = np.array([[-(128 ** 4) - 77]], dtype=np.int32)
+    for sa, sb in itertools.product(STRATS, STRATS):
+        plan = check_against_oracle(imu, Aq, Bq, 8, sa, sb)
+        n_u, d_u, h_u, _ = plan.dims()
+        assert n_u * d_u * h_u == 25
+
+
+def test_plan_object_is_reusable(imu):
+    rng = np.random.default_rng(9)
+    plan = None
+    for (n, d, h, sa, sb) in [(40, 50, 30, BOTH, BOTH), (300, 100, 80, ROW, COL), (40, 50, 30, COL, BOTH)]:
+        Aq = rand_ints(rng, n, d, 128, 0.05, 3)
+        Bq = rand_ints(rng, h, d, 128, 0.05, 3)
+        A_d, B_d = dev(torch.from_numpy(Aq)), dev(torch.from_numpy(Bq))
+        plan = imu.imunpack_plan(A_d, B_d, 8, sa, sb, plan=plan)
+        hnd = oracle.unpack_pair_handle(Aq, Bq, 8, sa, sb)
+        assert plan.dims()[:3] == (hnd.n_u, hnd.d_u, hnd.h_u)
+        A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d)
+        C_int = torch.empty((n, h), dtype=torch.int64, device="cuda")
+        ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C_int, None, ws, fuse=True)
+        assert np.array_equal(C_int.cpu().numpy(), oracle.int_gemm(Aq, Bq))
+
+
+def test_end_to_end_config1(imu):
+    """Workload 1 (256 x 256 x 256, scattered heavy hitters, UnpackBoth on both operands) through the
+    whole path, full comparison of every stage."""
+    w = workloads.make(1)
+    Aq = oracle_quant(w.A, w.scale_a)
+    Bq = oracle_quant(w.B, w.scale_b)
+    Qa, _, _ = imu.imunpack_quantize(dev(w.A), w.scale_a, w.b)
+    Qb, _, _ = imu.imunpack_quantize(dev(w.B), w.scale_b, w.b)
+    assert np.array_equal(Qa.cpu().numpy(), Aq) and np.array_equal(Qb.cpu().numpy(), Bq)
+    check_against_oracle(imu, Aq, Bq, w.b, w.strategy_a, w.strategy_b, w.scale_a, w.scale_b)
+    C_int, C_fp, plan = imu.exact_int_gemm(dev(w.A), dev(w.B), w.scale_a, w.scale_b, w.b, w.strategy_a,
+                                           w.strategy_b)
+    want = oracle.int_gemm(Aq, Bq)
+    assert np.array_equal(C_int.cpu().numpy(), want)
+    ref = oracle.dequantize(want, w.scale_a, w.scale_b)
+    assert (np.abs(C_fp.cpu().numpy().astype(np.float64) - ref) <= REL_TOL * np.abs(ref)).all()
