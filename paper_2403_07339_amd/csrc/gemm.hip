@@ -19,6 +19,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BM = kTile, BN = kTile, BK = 64;   // bytes of K per stage = int8 elements
 constexpr int kGemmThreads = 256;                // 4 waves, 2 x 2, each 128 x 128
+constexpr int kStages = 4;                       // LDS ring of k-tiles filled by direct-to-LDS loads
+constexpr int kStageBytes = (BM + BN) * BK;      // 32 KiB: A tile then B tile
+constexpr int kGemmLds = kStages * kStageBytes;  // 128 KiB of the CU's 160 KiB
+constexpr int kDmaPerStage = 8;                  // direct-to-LDS loads one wave issues per k-tile
 
 struct GemmArgs {
     const int8_t *A, *B;      // [Mp][Kp], [Np][Kp]
@@ -41,10 +45,6 @@ struct GemmArgs {
     int seg_shift, seg_first;
 };
 
-// LDS tile: [rows][64 B]; the four 16-byte chunks of a row are XOR-swizzled with bits 2..3 of
-// the row so that 16 consecutive rows at one k-chunk hit 16 different bank groups.
-__device__ __forceinline__ int lds_off(int row, int kc) { return row * BK + ((kc ^ ((row >> 2) & 3)) << 4); }
-
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2,
 // so ids that land on one XCD are given one contiguous run of tiles; inside a run the tiles walk
 // bands of 4 tile-rows so that an XCD's resident workgroups share A and B panels.
@@ -63,40 +63,71 @@ __device__ __forceinline__ void tile_of(int wg, int mtiles, int ntiles, int &tm,
     tn = in_band / rows_in_band;
 }
 
+// One direct-to-LDS load: every lane fetches 16 bytes from gbase + voff and the wave's 1 KiB lands
+// contiguously at LDS byte address lds_addr (lane l at lds_addr + 16 l).  The LDS base travels in M0.
+__device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, const int8_t *gbase) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory");
+}
+
+__device__ __forceinline__ const int8_t *uniform_ptr(const int8_t *p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const int8_t *)(((uint64_t)hi << 32) | lo);
+}
+
+// LDS tile: [256 rows][64 B]; the four 16-byte chunks of a row are XOR-swizzled with bits 1..2 of
+// the row, which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks)
+// conflict-free.  Chunk kc of row r lives at r*64 + ((kc ^ ((r >> 1) & 3)) << 4).
 template <int MODE>  // 0: fused epilogue, 1: int64 segment into C_u
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) int8_t smem[2 * 2 * BM * BK];  // [buf][A|B][256][64] = 64 KiB
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
     tile_of(blockIdx.x, g.mtiles, g.ntiles, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
+    const unsigned lds0 = (unsigned)(size_t)smem;
 
-    // global -> register staging: 1024 chunks of 16 B per operand tile, 4 per thread
-    const int8_t *gA[4], *gB[4];
-    int soff[4];
+    // ---- global -> LDS: wave w fills rows [64w, 64w+64) of the A tile and of the B tile, 16 rows
+    // (1 KiB) per load; lane l writes slot l&3 of row l>>2, so it fetches the chunk that belongs there
+    unsigned voff[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int id = tid + u * kGemmThreads;
-        const int row = id >> 2, kc = id & 3;
-        gA[u] = g.A + (int64_t)(m0 + row) * g.Kp + kc * 16;
-        gB[u] = g.B + (int64_t)(n0 + row) * g.Kp + kc * 16;
-        soff[u] = lds_off(row, kc);
+        const int row = 64 * wave + 16 * u + (lane >> 2);
+        const int kc = (lane & 3) ^ ((row >> 1) & 3);
+        voff[u] = (unsigned)row * (unsigned)g.Kp + (unsigned)(kc * 16);
     }
-    v4i ra[4], rb[4];
-    auto gload = [&](int kt) {
+    const int8_t *gA = g.A + (int64_t)m0 * g.Kp, *gB = g.B + (int64_t)n0 * g.Kp;
+    auto issue = [&](int kt) {
+        const int8_t *pa = uniform_ptr(gA + (int64_t)kt * BK), *pb = uniform_ptr(gB + (int64_t)kt * BK);
+        const unsigned l = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)((kt & (kStages - 1)) * kStageBytes) +
+                                                          (unsigned)(wave * 4096));
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            ra[u] = *reinterpret_cast<const v4i *>(gA[u] + (int64_t)kt * BK);
-            rb[u] = *reinterpret_cast<const v4i *>(gB[u] + (int64_t)kt * BK);
+            dma16(l + u * 1024, voff[u], pa);
+            dma16(l + BM * BK + u * 1024, voff[u], pb);
         }
     };
-    auto swrite = [&](int buf) {
-        int8_t *sa = smem + buf * (2 * BM * BK), *sb = sa + BM * BK;
+
+    // ---- LDS -> registers: operand fragments of v_mfma_i32_32x32x32_i8 (lane: row lane%32, 16 K-bytes
+    // at chunk 2*ks + lane/32)
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int swz = (lrow >> 1) & 3;
+    const unsigned fa_base = (unsigned)((wm * 128 + lrow) * BK);
+    const unsigned fb_base = (unsigned)(BM * BK + (wn * 128 + lrow) * BK);
+    const unsigned kc_off[2] = {(unsigned)(((0 + lhalf) ^ swz) << 4), (unsigned)(((2 + lhalf) ^ swz) << 4)};
+    v4i fa[2][4], fb[2][4];
+    auto load_frags = [&](int kt, int ks, v4i(&a)[4], v4i(&b)[4]) {
+        const int8_t *st = smem + (kt & (kStages - 1)) * kStageBytes;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            *reinterpret_cast<v4i *>(sa + soff[u]) = ra[u];
-            *reinterpret_cast<v4i *>(sb + soff[u]) = rb[u];
+        for (int i = 0; i < 4; ++i) {
+            a[i] = *reinterpret_cast<const v4i *>(st + fa_base + kc_off[ks] + i * 32 * BK);
+            b[i] = *reinterpret_cast<const v4i *>(st + fb_base + kc_off[ks] + i * 32 * BK);
         }
     };
 
@@ -108,49 +139,52 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    int nb = 0;
-    int next_kt = g.nbound > 0 ? g.bound_kt[0] : -1;
+    // ---- prologue: three k-tiles in flight, first one landed, its first fragments loaded
+    const int kt0 = g.kt0, kt1 = g.kt1;
+    for (int p = 0; p < kStages - 1; ++p)
+        if (kt0 + p < kt1) issue(kt0 + p);
+    if (kt0 + 2 < kt1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (kt0 + 1 < kt1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt0 < kt1) load_frags(kt0, 0, fa[0], fb[0]);
 
-    if (g.kt0 < g.kt1) {
-        gload(g.kt0);
-        swrite(0);
-    }
-    __syncthreads();
-    for (int kt = g.kt0; kt < g.kt1; ++kt) {
-        const int buf = (kt - g.kt0) & 1;
-        const bool more = kt + 1 < g.kt1;
-        if (more) gload(kt + 1);
-        const int8_t *sa = smem + buf * (2 * BM * BK), *sb = sa + BM * BK;
-#pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            v4i fa[4], fb[4];
-            const int kc = ks * 2 + lhalf;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                fa[i] = *reinterpret_cast<const v4i *>(sa + lds_off(wm * 128 + i * 32 + lrow, kc));
-                fb[i] = *reinterpret_cast<const v4i *>(sb + lds_off(wn * 128 + i * 32 + lrow, kc));
-            }
+    int kt = kt0;
+    for (int seg = 0; seg <= g.nbound; ++seg) {
+        const int kend = seg < g.nbound ? g.bound_kt[seg] + 1 : kt1;
+        for (; kt < kend; ++kt) {
+            // k-tile kt+1 must be complete in LDS for every wave before anyone reads it below; the
+            // same barrier retires k-tile kt-1, whose buffer the load of k-tile kt+3 then overwrites
+            if (kt + 2 < kt1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (kt + 3 < kt1) issue(kt + 3);
+            load_frags(kt, 1, fa[1], fb[1]);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
+            if (kt + 1 < kt1) load_frags(kt + 1, 0, fa[0], fb[0]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
         }
-        if (kt == next_kt) {  // end of an exponent group: Horner step
-            const int shv = g.bound_sh[nb];
+        if (seg < g.nbound) {  // end of an exponent group: Horner step
+            const int shv = g.bound_sh[seg];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] <<= shv;
-            ++nb;
-            next_kt = nb < g.nbound ? g.bound_kt[nb] : -1;
         }
-        if (more) swrite(buf ^ 1);
-        __syncthreads();
     }
+    __syncthreads();  // all fragment reads done: the ring may be reused by the epilogue
 
     // accumulator element r of block (i, j): row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
     if (MODE == 1) {
@@ -192,7 +226,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     }
 
     // general tile: fold the digit levels of both operands through LDS, 64 physical rows at a time
-    int32_t *fold = reinterpret_cast<int32_t *>(smem);  // [64][256] int32 = 64 KiB
+    int32_t *fold = reinterpret_cast<int32_t *>(smem);  // [64][256] int32 = 64 KiB of the ring
     const int j = jsrc0 + tid;
     const bool have_col = tid < nsrcB;
     const int q0 = have_col ? g.layB.src_pstart[j] - n0 : 0;
@@ -260,6 +294,16 @@ __global__ __launch_bounds__(256) void recombine_kernel(const int64_t *__restric
 
 using namespace imu;
 
+static int gemm_lds_opt_in() {
+    static int done = 0;  // the kernels use 128 KiB of dynamic LDS, above the default limit
+    if (!done) {
+        IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
+        IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
+        done = 1;
+    }
+    return IMUNPACK_OK;
+}
+
 static int check_shifts(const Plan *p) {
     // every weight s^(levelA + levelB + e) applied in int64 must stay below 2^62
     const int maxexp = (p->hdr.lmaxA - 1) + (p->hdr.lmaxB - 1) + (p->hdr.ngroups ? p->hdr.grp_exp[0] : 0);
@@ -288,6 +332,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
     const PlanHeader &h = p->hdr;
     if (h.mtiles <= 0 || h.ntiles <= 0) return IMUNPACK_OK;
     IMU_TRY(check_shifts(p));
+    IMU_TRY(gemm_lds_opt_in());
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = A_ue; g.B = B_eu;
@@ -314,7 +359,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
         g.final_shift = h.ngroups ? p->sh * h.grp_exp[h.ngroups - 1] : 0;
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
-        hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), 0, st, g);
+        hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
         return launch_status();
     }
     if (!workspace) return IMUNPACK_EINVAL;
@@ -325,7 +370,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
         g.nbound = 0;
         g.seg_shift = p->sh * h.grp_exp[q];
         g.seg_first = q == 0;
-        hipLaunchKernelGGL(gemm_i8_kernel<1>, dim3(grid), dim3(kGemmThreads), 0, st, g);
+        hipLaunchKernelGGL(gemm_i8_kernel<1>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
     }
     IMU_TRY(launch_status());
     if (fuse != 0)  // the caller asked for final outputs: finish the job here
