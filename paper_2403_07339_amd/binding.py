@@ -17,7 +17,7 @@ ROW, COL, BOTH = 0, 1, 2
 OK, EINVAL, ERANGE, ENOMEM, EHIP, ESMALL = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libimunpack.so")
+LIB_PATH = os.environ.get("IMUNPACK_LIB") or os.path.join(_HERE, "libimunpack.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_07339_amd.build`")
 _lib = C.CDLL(LIB_PATH)

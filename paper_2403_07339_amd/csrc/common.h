@@ -37,7 +37,7 @@ static inline int launch_status() {
 
 // ---- geometry shared by planner, scatter and GEMM ----------------------------------------------
 constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both operands)
-constexpr int kKPad = 64;        // every exponent group is padded to a multiple of this many columns
+constexpr int kKPad = 128;       // every exponent group is padded to a multiple of this many columns
 constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
 constexpr uint32_t kNever = 0xFFFFFFFFu;  // split time of a row/column that is never split
 

@@ -10,19 +10,23 @@
 // launched on its own and accumulated in int64 (the un-fused path).
 #include "common.h"
 
+#include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 namespace imu {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef long v2l __attribute__((ext_vector_type(2)));
 
-constexpr int BM = kTile, BN = kTile, BK = 64;   // bytes of K per stage = int8 elements
+constexpr int BM = kTile, BN = kTile, BK = 128;  // bytes (= int8 elements) of K per LDS stage: one full 128-byte line per row
 constexpr int kGemmThreads = 256;                // 4 waves, 2 x 2, each 128 x 128
-constexpr int kStages = 4;                       // LDS ring of k-tiles filled by direct-to-LDS loads
-constexpr int kStageBytes = (BM + BN) * BK;      // 32 KiB: A tile then B tile
+constexpr int kStages = 2;                       // LDS double buffer filled by direct-to-LDS loads
+constexpr int kStageBytes = (BM + BN) * BK;      // 64 KiB: A tile then B tile
 constexpr int kGemmLds = kStages * kStageBytes;  // 128 KiB of the CU's 160 KiB
-constexpr int kDmaPerStage = 8;                  // direct-to-LDS loads one wave issues per k-tile
+constexpr int kDmaPerStage = 16;                 // direct-to-LDS loads one wave issues per k-tile
 
 struct GemmArgs {
     const int8_t *A, *B;      // [Mp][Kp], [Np][Kp]
@@ -79,12 +83,15 @@ __device__ __forceinline__ const int8_t *uniform_ptr(const int8_t *p) {
     return (const int8_t *)(((uint64_t)hi << 32) | lo);
 }
 
-// LDS tile: [256 rows][64 B]; the four 16-byte chunks of a row are XOR-swizzled with bits 1..2 of
+// LDS tile: [256 rows][64 B]; the four 16-byte chunks of a row are XOR-swizzled with bits 2..3 of
 // the row, which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks)
-// conflict-free.  Chunk kc of row r lives at r*64 + ((kc ^ ((r >> 1) & 3)) << 4).
+// conflict-free.  Chunk kc of row r lives at r*64 + ((kc ^ ((r >> 2) & 3)) << 4).
 template <int MODE>  // 0: fused epilogue, 1: int64 segment into C_u
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+#ifdef IMU_GEMM_DIAG
+    constexpr int g_diag = IMU_GEMM_DIAG;  // diagnostics build only (wrong results by design)
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -93,42 +100,58 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     const int m0 = tm * BM, n0 = tn * BN;
     const unsigned lds0 = (unsigned)(size_t)smem;
 
-    // ---- global -> LDS: wave w fills rows [64w, 64w+64) of the A tile and of the B tile, 16 rows
-    // (1 KiB) per load; lane l writes slot l&3 of row l>>2, so it fetches the chunk that belongs there
-    unsigned voff[4];
+    // ---- global -> LDS: wave w fills rows [64w, 64w+64) of the A tile and of the B tile, 8 rows x 128 B
+    // (1 KiB) per load; lane l writes slot l&7 of row l>>3, so it fetches the 16-byte chunk that
+    // belongs there under the swizzle: chunk kc of row r lives at r*128 + ((kc ^ ((r >> 1) & 7)) << 4),
+    // which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks) conflict-free.
+    unsigned voff[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int row = 64 * wave + 16 * u + (lane >> 2);
-        const int kc = (lane & 3) ^ ((row >> 1) & 3);
+    for (int u = 0; u < 8; ++u) {
+        const int row = 64 * wave + 8 * u + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row >> 1) & 7);
         voff[u] = (unsigned)row * (unsigned)g.Kp + (unsigned)(kc * 16);
     }
     const int8_t *gA = g.A + (int64_t)m0 * g.Kp, *gB = g.B + (int64_t)n0 * g.Kp;
-    auto issue = [&](int kt) {
-        const int8_t *pa = uniform_ptr(gA + (int64_t)kt * BK), *pb = uniform_ptr(gB + (int64_t)kt * BK);
-        const unsigned l = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)((kt & (kStages - 1)) * kStageBytes) +
-                                                          (unsigned)(wave * 4096));
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            dma16(l + u * 1024, voff[u], pa);
-            dma16(l + BM * BK + u * 1024, voff[u], pb);
-        }
+    // Loads past the end of the range are clamped to the last k-tile: they land in the free buffer
+    // and are never read, which keeps the count of outstanding loads the same in every iteration.
+    const int kt0 = g.kt0, kt1 = g.kt1;
+    const int8_t *pa = nullptr, *pb = nullptr;
+    unsigned dl = 0;
+    auto stage_setup = [&](int kt, int slot) {
+#ifdef IMU_GEMM_DIAG
+        const int ktc = (g_diag & 1) ? (kt & 1) : min(kt, kt1 - 1);
+#else
+        const int ktc = min(kt, kt1 - 1);
+#endif
+        pa = uniform_ptr(gA + (int64_t)ktc * BK);
+        pb = uniform_ptr(gB + (int64_t)ktc * BK);
+        dl = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(slot * kStageBytes) + (unsigned)(wave * 8192));
+    };
+    auto dma_one = [&](int q) {  // q = 0..15: A block q/2 or B block q/2
+        const int u = q >> 1;
+#ifdef IMU_GEMM_DIAG
+        if constexpr ((g_diag & 2) != 0) return;
+#endif
+        if (q & 1) dma16(dl + BM * BK + u * 1024, voff[u], pb);
+        else dma16(dl + u * 1024, voff[u], pa);
     };
 
     // ---- LDS -> registers: operand fragments of v_mfma_i32_32x32x32_i8 (lane: row lane%32, 16 K-bytes
-    // at chunk 2*ks + lane/32)
+    // at chunk 2*ks + lane/32 of the row)
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int swz = (lrow >> 1) & 3;
+    const int swz = (lrow >> 1) & 7;
     const unsigned fa_base = (unsigned)((wm * 128 + lrow) * BK);
     const unsigned fb_base = (unsigned)(BM * BK + (wn * 128 + lrow) * BK);
-    const unsigned kc_off[2] = {(unsigned)(((0 + lhalf) ^ swz) << 4), (unsigned)(((2 + lhalf) ^ swz) << 4)};
-    v4i fa[2][4], fb[2][4];
-    auto load_frags = [&](int kt, int ks, v4i(&a)[4], v4i(&b)[4]) {
-        const int8_t *st = smem + (kt & (kStages - 1)) * kStageBytes;
+    unsigned kc_off[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i] = *reinterpret_cast<const v4i *>(st + fa_base + kc_off[ks] + i * 32 * BK);
-            b[i] = *reinterpret_cast<const v4i *>(st + fb_base + kc_off[ks] + i * 32 * BK);
-        }
+    for (int ks = 0; ks < 4; ++ks) kc_off[ks] = (unsigned)(((2 * ks + lhalf) ^ swz) << 4);
+    v4i fa[2][4], fb[2][4];
+    // fragment q of a k-step in the order the MFMA sequence below first needs them: a0 b0 b1 a1 b2 b3 a2 a3
+    auto load_frag = [&](const int8_t *st, int ks, int buf, int q) {
+        constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
+        constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
+        if (isA[q]) fa[buf][idx[q]] = *reinterpret_cast<const v4i *>(st + fa_base + kc_off[ks] + idx[q] * 32 * BK);
+        else fb[buf][idx[q]] = *reinterpret_cast<const v4i *>(st + fb_base + kc_off[ks] + idx[q] * 32 * BK);
     };
 
     v16i acc[4][4];
@@ -138,41 +161,63 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    // MFMA order: 2 x 2 sub-blocks, so that the fragments of the next k-step can trickle in
+    constexpr int mi[16] = {0, 0, 1, 1, 0, 0, 1, 1, 2, 2, 3, 3, 2, 2, 3, 3};
+    constexpr int mj[16] = {0, 1, 0, 1, 2, 3, 2, 3, 0, 1, 0, 1, 2, 3, 2, 3};
 
-    // ---- prologue: three k-tiles in flight, first one landed, its first fragments loaded
-    const int kt0 = g.kt0, kt1 = g.kt1;
-    for (int p = 0; p < kStages - 1; ++p)
-        if (kt0 + p < kt1) issue(kt0 + p);
-    if (kt0 + 2 < kt1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (kt0 + 1 < kt1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // One step = 16 MFMAs on the fragments in buffer `cur`, interleaved with the 8 fragment loads of
+    // the next k-step into the other buffer and, optionally, all 16 direct-to-LDS loads of a k-tile.
+    auto step = [&](int cur, const int8_t *next_stage, int next_ks, bool with_dma) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            load_frag(next_stage, next_ks, cur ^ 1, q);
+            acc[mi[2 * q]][mj[2 * q]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                fa[cur][mi[2 * q]], fb[cur][mj[2 * q]], acc[mi[2 * q]][mj[2 * q]], 0, 0, 0);
+            if (with_dma) dma_one(2 * q);
+            acc[mi[2 * q + 1]][mj[2 * q + 1]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                fa[cur][mi[2 * q + 1]], fb[cur][mj[2 * q + 1]], acc[mi[2 * q + 1]][mj[2 * q + 1]], 0, 0, 0);
+            if (with_dma) dma_one(2 * q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- prologue: first k-tile landed, second in flight, first fragments loaded
+    stage_setup(kt0, 0);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dma_one(q);
+    stage_setup(kt0 + 1, 1);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dma_one(q);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt0 < kt1) load_frags(kt0, 0, fa[0], fb[0]);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) load_frag(smem, 0, 0, q);
 
+    // ---- main loop, one 128-byte k-tile (4 k-steps, 64 MFMAs) and one barrier per iteration.  After
+    // the third k-step every fragment of k-tile kt has been read (lgkmcnt(0)) and this wave's part
+    // of k-tile kt+1 has landed in the other buffer (vmcnt(0)); past the barrier that holds for all
+    // waves, so the last k-step may prefetch from k-tile kt+1 and its loads may refill this buffer
+    // with k-tile kt+2.
     int kt = kt0;
     for (int seg = 0; seg <= g.nbound; ++seg) {
         const int kend = seg < g.nbound ? g.bound_kt[seg] + 1 : kt1;
         for (; kt < kend; ++kt) {
-            // k-tile kt+1 must be complete in LDS for every wave before anyone reads it below; the
-            // same barrier retires k-tile kt-1, whose buffer the load of k-tile kt+3 then overwrites
-            if (kt + 2 < kt1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const int slot = (kt - kt0) & 1;
+            const int8_t *st = smem + slot * kStageBytes, *sto = smem + (slot ^ 1) * kStageBytes;
+            __builtin_amdgcn_sched_barrier(0);
+            step(0, st, 1, false);
+            step(1, st, 2, false);
+            step(0, st, 3, false);
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#ifdef IMU_GEMM_DIAG
+            if constexpr ((g_diag & 4) == 0)
+#endif
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (kt + 3 < kt1) issue(kt + 3);
-            load_frags(kt, 1, fa[1], fb[1]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
-            if (kt + 1 < kt1) load_frags(kt + 1, 0, fa[0], fb[0]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+            stage_setup(kt + 2, slot);
+            __builtin_amdgcn_sched_barrier(0);
+            step(1, sto, 0, true);
         }
         if (seg < g.nbound) {  // end of an exponent group: Horner step
             const int shv = g.bound_sh[seg];
@@ -184,88 +229,127 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                     for (int r = 0; r < 16; ++r) acc[i][j][r] <<= shv;
         }
     }
-    __syncthreads();  // all fragment reads done: the ring may be reused by the epilogue
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before LDS is reused
+    __syncthreads();  // all fragment reads done: the buffers may be reused by the epilogue
 
-    // accumulator element r of block (i, j): row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
     if (MODE == 1) {
+        // un-fused: the int32 partial product of this exponent group goes, shifted, into the int64
+        // unpacked product C_u (physical coordinates, padded to tiles: no bounds to check)
+        constexpr int FLD1 = 260;
+        int32_t *buf = reinterpret_cast<int32_t *>(smem);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int c = 0; c < 4; ++c) {
+            __syncthreads();
+            if (wm == (c >> 1)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int p = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-                    const int q = n0 + wn * 128 + j * 32 + lrow;
-                    int64_t *dst = g.C_u + (int64_t)p * g.Np + q;
-                    const int64_t v = (int64_t)acc[i][j][r] << g.seg_shift;
-                    *dst = g.seg_first ? v : *dst + v;
+                    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            buf[(ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD1 + wn * 128 + jj * 32 + lrow] =
+                                acc[(c & 1) * 2 + ii][jj][r];
+            }
+            __syncthreads();
+            const int col4 = (tid & 63) * 4;
+            for (int it = 0; it < 16; ++it) {
+                const int row = (tid >> 6) + 4 * it;
+                const v4i v = *reinterpret_cast<const v4i *>(buf + row * FLD1 + col4);
+                int64_t *dst = g.C_u + (int64_t)(m0 + c * 64 + row) * g.Np + n0 + col4;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t x = (int64_t)v[k] << g.seg_shift;
+                    dst[k] = g.seg_first ? x : dst[k] + x;
                 }
+            }
+        }
         return;
     }
 
+    // ---- fused epilogue.  The accumulators leave the registers through LDS, 64 physical rows of the
+    // tile at a time ([64][256] int32, rows padded to 260), so that global stores are row-contiguous
+    // and the digit levels of a source row / column (which the planner keeps inside one tile) can be
+    // added up: C_int[i,j] = sum_{levels a of i, c of j} s^(a+c) * acc[row(i,a)][col(j,c)].
     const int isrc0 = g.layA.tile_src0[tm], nsrcA = g.layA.tile_src0[tm + 1] - isrc0;
     const int jsrc0 = g.layB.tile_src0[tn], nsrcB = g.layB.tile_src0[tn + 1] - jsrc0;
-    if (g.flatA[tm] && g.flatB[tn]) {
-        // no row of this tile was split on either side: physical = source order, store directly
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int pi = wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-                    const int qj = wn * 128 + j * 32 + lrow;
-                    if (pi < nsrcA && qj < nsrcB) {
-                        const int64_t v = (int64_t)acc[i][j][r] << g.final_shift;
-                        const int64_t o = (int64_t)(isrc0 + pi) * g.ldc + (jsrc0 + qj);
-                        if (g.C_int) g.C_int[o] = v;
-                        if (g.C_fp) g.C_fp[o] = (float)((double)v * g.scale);
-                    }
-                }
-        return;
-    }
-
-    // general tile: fold the digit levels of both operands through LDS, 64 physical rows at a time
-    int32_t *fold = reinterpret_cast<int32_t *>(smem);  // [64][256] int32 = 64 KiB of the ring
-    const int j = jsrc0 + tid;
-    const bool have_col = tid < nsrcB;
-    const int q0 = have_col ? g.layB.src_pstart[j] - n0 : 0;
-    const int lj = have_col ? g.layB.src_nlev[j] : 0;
+    const bool flat = g.flatA[tm] && g.flatB[tn];
+    constexpr int FLD = 260;
+    int32_t *fold = reinterpret_cast<int32_t *>(smem);
+    // scale * 2^final_shift is exact: one multiplication in binary64, one rounding to fp32
+    const double scale2 = g.scale * (double)(1ull << g.final_shift);
+    const bool vec_ok = flat && (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (nsrcB % 4) == 0 &&
+                        (!g.C_fp || ((uintptr_t)g.C_fp % 16) == 0) && (!g.C_int || ((uintptr_t)g.C_int % 16) == 0);
+    const int jf = jsrc0 + tid;
+    const bool have_col = !flat && tid < nsrcB;
+    const int q0 = have_col ? g.layB.src_pstart[jf] - n0 : 0;
+    const int lj = have_col ? g.layB.src_nlev[jf] : 0;
     int64_t run = 0;
+#pragma unroll
     for (int c = 0; c < 4; ++c) {
         __syncthreads();
         if (wm == (c >> 1)) {
 #pragma unroll
-            for (int ii = 0; ii < 2; ++ii) {
-                const int i = (c & 1) * 2 + ii;
+            for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-                        const int col = wn * 128 + jj * 32 + lrow;
-                        fold[row * 256 + (col ^ (((row >> 2) & 1) << 5))] = acc[i][jj][r];
-                    }
-            }
+                    for (int r = 0; r < 16; ++r)
+                        fold[(ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD + wn * 128 + jj * 32 + lrow] =
+                            acc[(c & 1) * 2 + ii][jj][r];
         }
         __syncthreads();
-        for (int row = 0; row < 64; ++row) {
-            const int p = m0 + c * 64 + row;
-            const int i = g.layA.prow_src[p];
-            if (i < 0) continue;  // padding row (uniform)
-            const int lvl = g.layA.prow_exp[p];
-            const bool last = lvl == g.layA.src_nlev[i] - 1;
-            if (have_col) {
-                int64_t v = 0;
-                const int sw = ((row >> 2) & 1) << 5;
-                for (int l = 0; l < lj; ++l) v += (int64_t)fold[row * 256 + ((q0 + l) ^ sw)] << (g.sh * l);
-                run += v << (g.sh * lvl);
-                if (last) {
-                    const int64_t outv = run << g.final_shift;
-                    const int64_t o = (int64_t)i * g.ldc + j;
-                    if (g.C_int) g.C_int[o] = outv;
-                    if (g.C_fp) g.C_fp[o] = (float)((double)outv * g.scale);
-                    run = 0;
+        if (flat) {
+            // physical order = source order: thread t streams rows (t>>6) + 4*it, columns 4*(t&63)..+3
+            const int col4 = (tid & 63) * 4;
+            for (int it = 0; it < 16; ++it) {
+                const int row = (tid >> 6) + 4 * it;
+                const int pi = c * 64 + row;
+                if (pi >= nsrcA) break;
+                const v4i v = *reinterpret_cast<const v4i *>(fold + row * FLD + col4);
+                const int64_t o = (int64_t)(isrc0 + pi) * g.ldc + jsrc0 + col4;
+                if (vec_ok) {
+                    if (col4 < nsrcB) {
+                        if (g.C_fp) {
+                            v4f f;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
+                            __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+                        }
+                        if (g.C_int) {
+                            v2l lo, hi;
+                            lo[0] = (int64_t)v[0] << g.final_shift; lo[1] = (int64_t)v[1] << g.final_shift;
+                            hi[0] = (int64_t)v[2] << g.final_shift; hi[1] = (int64_t)v[3] << g.final_shift;
+                            __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
+                            __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (col4 + k < nsrcB) {
+                            if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
+                            if (g.C_int) g.C_int[o + k] = (int64_t)v[k] << g.final_shift;
+                        }
+                }
+            }
+        } else {
+            for (int row = 0; row < 64; ++row) {
+                const int p = m0 + c * 64 + row;
+                const int i = g.layA.prow_src[p];
+                if (i < 0) continue;  // padding row (uniform)
+                const int lvl = g.layA.prow_exp[p];
+                const bool last = lvl == g.layA.src_nlev[i] - 1;
+                if (have_col) {
+                    int64_t v = 0;
+                    for (int l = 0; l < lj; ++l) v += (int64_t)fold[row * FLD + q0 + l] << (g.sh * l);
+                    run += v << (g.sh * lvl);
+                    if (last) {
+                        const int64_t outv = run << g.final_shift;
+                        const int64_t o = (int64_t)i * g.ldc + jf;
+                        if (g.C_int) g.C_int[o] = outv;
+                        if (g.C_fp) g.C_fp[o] = (float)((double)run * scale2);
+                        run = 0;
+                    }
                 }
             }
         }
