@@ -69,7 +69,8 @@ def main():
     # buffers reused by every step (allocation is not part of the path)
     Qa = torch.empty((n, d), dtype=torch.int32, device=dev)
     Qb = torch.empty((h, d), dtype=torch.int32, device=dev)
-    st_a, st_b = imu.Stats.empty(n, d, dev), imu.Stats.empty(h, d, dev)
+    st_a = imu.Stats.empty(n, d, dev, imu.Stats.default_ob_cap(n, d) if w.strategy_a == imu.BOTH else 0)
+    st_b = imu.Stats.empty(h, d, dev, imu.Stats.default_ob_cap(h, d) if w.strategy_b == imu.BOTH else 0)
     status = torch.zeros(2, dtype=torch.int32, device=dev)
     C_fp = torch.empty((n, h), dtype=torch.float32, device=dev)
     C_int = torch.empty((n, h), dtype=torch.int64, device=dev) if args.with_int64 else None

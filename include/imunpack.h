@@ -59,12 +59,19 @@ enum {
 
 /* Heavy-hitter statistics of one integer operand (device pointers, lengths rows / cols):
  * OB count and largest magnitude per row and per column.  (Sec. 4: the IB/OB predicate;
- * Alg. 1 line 3, Alg. 2 line 3, Alg. 4 line 3 consume them.) */
+ * Alg. 1 line 3, Alg. 2 line 3, Alg. 4 line 3 consume them.)
+ * Optionally also the list of the OB entries themselves, which UnpackBoth (Alg. 4) works on:
+ * ob holds 3 * ob_cap int32 laid out as [rows | cols | values], *ob_count (device) the number of
+ * OB entries found -- if that exceeds ob_cap the list is incomplete and the planner scans the
+ * operand itself.  ob == NULL (ob_cap == 0) skips the list. */
 typedef struct {
     int32_t *rowcnt;
     int32_t *colcnt;
     int32_t *rowmax;
     int32_t *colmax;
+    int32_t *ob;
+    int64_t ob_cap;
+    int32_t *ob_count;
 } imunpack_stats_t;
 
 /* ---- (1)+(2) RTN quantisation fused with the heavy-hitter scan --------------------------------

@@ -31,7 +31,8 @@ EXPORTS = [
 
 
 class _Stats(C.Structure):
-    _fields_ = [("rowcnt", C.c_void_p), ("colcnt", C.c_void_p), ("rowmax", C.c_void_p), ("colmax", C.c_void_p)]
+    _fields_ = [("rowcnt", C.c_void_p), ("colcnt", C.c_void_p), ("rowmax", C.c_void_p), ("colmax", C.c_void_p),
+                ("ob", C.c_void_p), ("ob_cap", C.c_int64), ("ob_count", C.c_void_p)]
 
 
 _vp, _i64, _i32, _f32 = C.c_void_p, C.c_int64, C.c_int, C.c_float
@@ -84,19 +85,33 @@ class Stats:
     colcnt: torch.Tensor
     rowmax: torch.Tensor
     colmax: torch.Tensor
+    ob: torch.Tensor | None = None        # [3, ob_cap] int32: rows | cols | values of the OB entries
+    ob_count: torch.Tensor | None = None  # [1] int32
 
     @staticmethod
-    def empty(rows: int, cols: int, device) -> "Stats":
+    def empty(rows: int, cols: int, device, ob_cap: int = 0) -> "Stats":
+        """ob_cap > 0 also allocates the OB entry list that UnpackBoth plans from."""
         buf = torch.empty(2 * (rows + cols), dtype=torch.int32, device=device)
-        return Stats(buf[:rows], buf[rows:rows + cols], buf[rows + cols:2 * rows + cols], buf[2 * rows + cols:])
+        st = Stats(buf[:rows], buf[rows:rows + cols], buf[rows + cols:2 * rows + cols], buf[2 * rows + cols:])
+        if ob_cap > 0:
+            st.ob = torch.empty((3, ob_cap), dtype=torch.int32, device=device)
+            st.ob_count = torch.zeros(1, dtype=torch.int32, device=device)
+        return st
+
+    @staticmethod
+    def default_ob_cap(rows: int, cols: int) -> int:
+        return max(4096, rows * cols // 64)
 
     def _c(self) -> _Stats:
-        return _Stats(self.rowcnt.data_ptr(), self.colcnt.data_ptr(), self.rowmax.data_ptr(), self.colmax.data_ptr())
+        return _Stats(self.rowcnt.data_ptr(), self.colcnt.data_ptr(), self.rowmax.data_ptr(), self.colmax.data_ptr(),
+                      self.ob.data_ptr() if self.ob is not None else None,
+                      self.ob.shape[1] if self.ob is not None else 0,
+                      self.ob_count.data_ptr() if self.ob_count is not None else None)
 
 
 def imunpack_quantize(X: torch.Tensor, scale: float, b: int, Q: torch.Tensor | None = None,
                       stats: Stats | None = None, status: torch.Tensor | None = None,
-                      want_stats: bool = True):
+                      want_stats: bool = True, want_ob_list: bool = False):
     """Q = rint(X / scale) (int32, row-major) fused with the heavy-hitter scan.  X: 2-D fp32 device
     tensor, any strides.  Returns (Q, stats, status)."""
     assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
@@ -104,7 +119,7 @@ def imunpack_quantize(X: torch.Tensor, scale: float, b: int, Q: torch.Tensor | N
     if Q is None:
         Q = torch.empty((rows, cols), dtype=torch.int32, device=X.device)
     if stats is None and want_stats:
-        stats = Stats.empty(rows, cols, X.device)
+        stats = Stats.empty(rows, cols, X.device, Stats.default_ob_cap(rows, cols) if want_ob_list else 0)
     if status is None:
         status = torch.empty(1, dtype=torch.int32, device=X.device)
     cs = stats._c() if stats is not None else None
@@ -244,8 +259,8 @@ def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale
     """The whole hot path: quantize -> plan -> unpack -> GEMM (+ recombine, dequantise).
     Returns (C_int or None, C_fp or None, plan)."""
     dev = A_fp.device
-    Aq, sa, st_a = imunpack_quantize(A_fp, scale_a, b)
-    Bq, sb, st_b = imunpack_quantize(B_fp, scale_b, b)
+    Aq, sa, st_a = imunpack_quantize(A_fp, scale_a, b, want_ob_list=strategy_a == BOTH)
+    Bq, sb, st_b = imunpack_quantize(B_fp, scale_b, b, want_ob_list=strategy_b == BOTH)
     plan = imunpack_plan(Aq, Bq, b, strategy_a, strategy_b, sa, sb, plan)
     A_ue, B_eu = imunpack_unpack(plan, Aq, Bq)
     n, h = A_fp.shape[0], B_fp.shape[0]

@@ -48,6 +48,7 @@ struct SlotSet {
     int32_t *exp;     // number of splits between root and this slot (digit level along this axis)
     uint32_t *time;   // when this slot was split (order among all splits of the phase), kNever if not
     int32_t *child;   // slot created by that split, -1 if none
+    unsigned long long *key;  // appended slots: order among the appended slots (batch, count desc, split slot)
     int32_t cap;
 };
 
@@ -61,15 +62,16 @@ struct PlanHeader {
     int32_t grp_exp[kMaxGroups];     // exponent of s per group, descending
     int32_t grp_k0[kMaxGroups];      // first physical column
     int32_t grp_len[kMaxGroups];     // real columns (without padding)
-    int32_t edgesA, edgesB, rawB;    // OB entry lists built for UnpackBoth
+    int32_t edgesA, edgesB, obcount; // OB entry lists built for UnpackBoth
     int32_t overflow;                // bit set: which capacity was too small
-    int32_t need[8];                 // size that would have been needed, per capacity
+    int32_t need[10];                // size that would have been needed, per capacity
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
     uint32_t pad_;
     unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
 };
 
-enum CapIndex { CAP_ROWA = 0, CAP_ROWB = 1, CAP_C1 = 2, CAP_C2 = 3, CAP_EDGEA = 4, CAP_EDGEB = 5, CAP_RAWB = 6 };
+enum CapIndex { CAP_ROWA = 0, CAP_ROWB = 1, CAP_C1 = 2, CAP_C2 = 3, CAP_EDGEA = 4, CAP_EDGEB = 5, CAP_OB = 6,
+                CAP_LISTA = 7, CAP_LISTB = 8 };  // the last two: a caller's OB list was too short
 
 // Physical-row description used by scatter and by the GEMM epilogue.
 struct RowLayout {
@@ -106,7 +108,7 @@ struct imunpack_plan {
     char *arena;
     size_t arena_bytes;
     // capacities (grow on overflow)
-    int32_t cap[8];
+    int32_t cap[10];
     // views into the arena (valid after a successful imunpack_plan)
     imu::PlanHeader *d_hdr;
     imu::PlanHeader hdr;          // host mirror
@@ -115,10 +117,15 @@ struct imunpack_plan {
     imu::ColLayout cols;
     int32_t *statsA[4], *statsB[4];   // rowcnt, colcnt, rowmax, colmax actually used
     // greedy scratch
-    int32_t *eR, *eC, *eV, *redge, *cedge;
-    int32_t *rcnt, *ccnt, *rstart, *rlen, *cstart, *clen, *batch;
-    int32_t *rawJ, *rawK, *rawV;
+    int32_t *eR, *eC, *eV;
+    int32_t *rcnt, *ccnt, *batch;
+    int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
     int32_t *tmpL, *tmpCur, *tmpP;
+    int ignore_listA, ignore_listB;   // a caller's OB list overflowed: scan the operand ourselves
+    int bothA, bothB;                 // slot numbering of the set needs the export-time sort
+    // canonical (paper-order) numbering, built lazily by the export / test paths
+    int canon_valid;
+    int32_t *canon_rowphysA, *canon_rowphysB, *canon_colphys;   // device, indexed by canonical slot
     int fusable;      // set by imunpack_unpack
     int unpacked;
     int valid;

@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <vector>
 
 namespace imu {
 
@@ -158,6 +159,7 @@ __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
                 set.time[slot] = kNever;
                 set.child[slot] = -1;
                 const int prev = tmpCur[x];
+                set.key[slot] = ((unsigned long long)l << 48) | (unsigned)prev;
                 set.child[prev] = slot;
                 set.time[prev] = 0;  // split (only this axis splits in this phase, any finite time will do)
                 tmpCur[x] = slot;
@@ -174,111 +176,34 @@ __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
 // ---------------------------------------------------------------------------------------------
 // UnpackBoth (Alg. 4): OB entry lists
 // ---------------------------------------------------------------------------------------------
-// Appends every OB entry (|v| >= s) of M (rows x cols, row stride ld) as (row, col, value).
-__global__ __launch_bounds__(256) void coo_extract_kernel(const int32_t *__restrict__ M, int64_t rows,
-                                                          int64_t cols, int64_t ld, int s,
-                                                          int32_t *oR, int32_t *oC, int32_t *oV, int cap,
-                                                          int32_t *counter, PlanHeader *hdr) {
+// Turns the list of OB entries (row, column k, value) of an operand into the edge list the greedy
+// works on.  For the first operand every entry is one edge.  After UnpackA the matrix B_e repeats
+// column k of B once per column slot that descends from k (Alg. 2 line 6 / Alg. 4 line 13), so each
+// OB entry (j, k) of B becomes one edge per such slot.
+__global__ void expand_edges_kernel(const int32_t *ob, int ob_cap, const int32_t *ob_count, SlotSet c1,
+                                    int32_t *eR, int32_t *eC, int32_t *eV, int cap, int32_t *counter,
+                                    PlanHeader *hdr, int which_list, int which_edges) {
     if (hdr->overflow) return;
-    const int lane = threadIdx.x & 63;
-    const int64_t wave_id = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    const int64_t chunks_per_row = (cols + 63) / 64;
-    for (int64_t w = wave_id; w < rows * chunks_per_row; w += nwaves) {
-        const int64_t r = w / chunks_per_row;
-        const int64_t c = (w % chunks_per_row) * 64 + lane;
-        int32_t v = 0;
-        if (c < cols) v = M[r * ld + c];
-        const bool ob = v >= s || v <= -s;
-        const unsigned long long mask = __ballot(ob);
-        if (mask == 0) continue;
-        int base = 0;
-        if (lane == 0) base = atomicAdd(counter, __popcll(mask));
-        base = __shfl(base, 0, 64);
-        if (ob) {
-            const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
-            if (pos < cap) {
-                oR[pos] = (int32_t)r;
-                oC[pos] = (int32_t)c;
-                oV[pos] = v;
-            }
-        }
+    const int N = *ob_count;
+    if (N > ob_cap) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) flag_overflow(hdr, which_list, N);
+        return;
     }
-}
-
-// After UnpackA the matrix B_e repeats column k of B once per column slot that descends from k
-// (Alg. 2 line 6 / Alg. 4 line 13), so each OB entry (j, k) of B becomes one edge per such slot.
-__global__ void expand_edges_kernel(const int32_t *rawJ, const int32_t *rawK, const int32_t *rawV,
-                                    const int32_t *raw_count, int raw_cap, SlotSet c1, int32_t *eR,
-                                    int32_t *eC, int32_t *eV, int cap, int32_t *counter, PlanHeader *hdr) {
-    if (hdr->overflow) return;
-    const int N = min(*raw_count, raw_cap);
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < N; t += gridDim.x * blockDim.x) {
+        const int j = ob[t], k = ob[ob_cap + t], v = ob[2 * ob_cap + t];
         int len = 0;
-        for (int c = rawK[t]; c >= 0 && len < 64; c = c1.child[c]) ++len;
+        for (int c = k; c >= 0 && len < 64; c = c1.child[c]) ++len;
         int pos = atomicAdd(counter, len);
         int left = len;
-        for (int c = rawK[t]; c >= 0 && left > 0; c = c1.child[c], ++pos, --left) {
+        for (int c = k; c >= 0 && left > 0; c = c1.child[c], ++pos, --left) {
             if (pos < cap) {
-                eR[pos] = rawJ[t];
+                eR[pos] = j;
                 eC[pos] = c;
-                eV[pos] = rawV[t];
+                eV[pos] = v;
             }
         }
     }
-}
-
-__global__ void check_count_kernel(const int32_t *count, int cap, PlanHeader *hdr, int which) {
-    if (threadIdx.x == 0 && blockIdx.x == 0 && *count > cap) flag_overflow(hdr, which, *count);
-}
-
-__global__ void edge_count_kernel(const int32_t *eR, const int32_t *eC, const int32_t *ecount, int32_t *rcnt,
-                                  int32_t *ccnt, PlanHeader *hdr) {
-    if (hdr->overflow) return;
-    const int E = *ecount;
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < E; e += gridDim.x * blockDim.x) {
-        atomicAdd(&rcnt[eR[e]], 1);
-        atomicAdd(&ccnt[eC[e]], 1);
-    }
-}
-
-// exclusive prefix sums of the two count vectors -> list starts; cursors zeroed
-__global__ __launch_bounds__(kPlanThreads) void edge_scan_kernel(const int32_t *rcnt, const int32_t *ccnt,
-                                                                 const int32_t *nr_dev, const int32_t *nc_dev,
-                                                                 int32_t *rstart, int32_t *rlen,
-                                                                 int32_t *cstart, int32_t *clen,
-                                                                 PlanHeader *hdr) {
-    __shared__ int lds[40];
-    if (hdr->overflow) return;
-    for (int pass = 0; pass < 2; ++pass) {
-        const int32_t *cnt = pass ? ccnt : rcnt;
-        int32_t *start = pass ? cstart : rstart, *len = pass ? clen : rlen;
-        const int N = pass ? *nc_dev : *nr_dev;
-        int base = 0;
-        for (int x0 = 0; x0 < N; x0 += kPlanThreads) {
-            const int x = x0 + threadIdx.x;
-            const int v = x < N ? cnt[x] : 0;
-            int total;
-            const int ex = block_excl_scan(v, total, lds);
-            if (x < N) {
-                start[x] = base + ex;
-                len[x] = 0;
-            }
-            base += total;
-        }
-    }
-}
-
-__global__ void edge_fill_kernel(const int32_t *eR, const int32_t *eC, const int32_t *ecount,
-                                 const int32_t *rstart, int32_t *rlen, const int32_t *cstart, int32_t *clen,
-                                 int32_t *redge, int32_t *cedge, PlanHeader *hdr) {
-    if (hdr->overflow) return;
-    const int E = *ecount;
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < E; e += gridDim.x * blockDim.x) {
-        const int R = eR[e], C = eC[e];
-        redge[rstart[R] + atomicAdd(&rlen[R], 1)] = e;
-        cedge[cstart[C] + atomicAdd(&clen[C], 1)] = e;
-    }
+    (void)which_edges;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -286,112 +211,130 @@ __global__ void edge_fill_kernel(const int32_t *eR, const int32_t *eC, const int
 // ---------------------------------------------------------------------------------------------
 struct GreedyArgs {
     SlotSet rows, cols;
-    int32_t *rcnt, *ccnt;          // live OB count per row / column slot
-    int32_t *rstart, *rlen;        // per row slot: segment of redge
-    int32_t *cstart, *clen;        // per column slot: segment of cedge
-    int32_t *redge, *cedge;        // edge ids grouped by row / by column
+    int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
     int32_t *eR, *eC, *eV;         // current row slot, column slot and remaining value of each edge
-    int32_t *batch;
+    const int32_t *ecount;
+    int ecap;
+    int32_t *batch, *bcnt, *rank_of;
     int batch_cap;
     int32_t *nr_io, *nc_io;        // slot counts (header fields), read at entry, written at exit
-    const int32_t *ecount;         // number of edges
     PlanHeader *hdr;
-    int whichR, whichC;
+    int whichR, whichC, whichE;
     int s, sh;
+    int use_lds;
 };
 
-// One batch: split every slot of `mine` listed in batch[0..nb) (ascending index), in that order.
-// A split keeps digit 0 in place and moves floor(v / s) to the new slot (Alg. 4 lines 7-9 / 11-14);
-// an entry that becomes In-Bound leaves the count of the crossing slot, one that stays OB moves on.
-__device__ __forceinline__ void split_batch(const GreedyArgs &g, bool isrow, int N, int nb, uint32_t T) {
-    const SlotSet &mine = isrow ? g.rows : g.cols;
-    int32_t *cnt = isrow ? g.rcnt : g.ccnt, *other = isrow ? g.ccnt : g.rcnt;
-    int32_t *start = isrow ? g.rstart : g.cstart, *len = isrow ? g.rlen : g.clen;
-    int32_t *list = isrow ? g.redge : g.cedge;
-    int32_t *epos = isrow ? g.eR : g.eC, *ecross = isrow ? g.eC : g.eR;
-    for (int r = threadIdx.x; r < nb; r += kPlanThreads) {
-        const int X = g.batch[r], newX = N + r;
-        mine.time[X] = T + (uint32_t)r;
-        mine.child[X] = newX;
-        mine.root[newX] = mine.root[X];
-        mine.exp[newX] = mine.exp[X] + 1;
-        mine.time[newX] = kNever;
-        mine.child[newX] = -1;
-        start[newX] = start[X];
-    }
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = wave; r < nb; r += kPlanWaves) {
-        const int X = g.batch[r], newX = N + r;
-        const int st = start[X], ln = len[X];
-        int out = 0;
-        for (int off = 0; off < ln; off += 64) {
-            const int idx = off + lane;
-            const bool valid = idx < ln;
-            const int e = valid ? list[st + idx] : 0;
-            const int v = valid ? g.eV[e] : 0;
-            const int av = v < 0 ? -v : v;
-            const bool alive = valid && av >= g.s;
-            const int av2 = av >> g.sh;
-            const bool surv = alive && av2 >= g.s;
-            if (alive) {
-                g.eV[e] = v < 0 ? -av2 : av2;
-                if (surv)
-                    epos[e] = newX;
-                else
-                    atomicSub(&other[ecross[e]], 1);
-            }
-            const unsigned long long mask = __ballot(surv);
-            if (surv) list[st + out + __popcll(mask & ((1ull << lane) - 1ull))] = e;
-            out += __popcll(mask);
-        }
-        if (lane == 0) {
-            len[newX] = out;
-            __hip_atomic_store(&cnt[newX], out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&cnt[X], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __syncthreads();
-}
-
+// The sequential algorithm splits, at every step, the row or column with the top OB count (rows win
+// ties, then the lowest index).  Splitting a row changes no other row's count and only lowers column
+// counts, so while rows are being chosen the rows come in (count descending, index ascending) order
+// and every row whose count is at least the top column count at the start of the run is chosen
+// before any column -- unless a split leaves OB entries in the new row (entries with three or more
+// digits), whose count then competes.  Hence:
+//   - if no entry has three or more digits, one batch takes all rows with count >= top column count
+//     (or all columns with count > top row count);
+//   - otherwise a batch takes only the slots that share the top count.
+// A batch is applied by one pass over the edge list.  The order inside a batch only decides the
+// numbers of the appended slots; it is recorded as a sort key (batch, count descending, split slot)
+// and the appended slots are renumbered on the host when the plan is exported.
 __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g) {
+    extern __shared__ int32_t lds_counts[];
     __shared__ int lds[40];
     if (g.hdr->overflow) return;
+    const int E = *g.ecount;
+    if (E > g.ecap) {
+        if (threadIdx.x == 0) flag_overflow(g.hdr, g.whichE, E);
+        return;
+    }
+    int32_t *rc = g.use_lds ? lds_counts : g.rcnt;
+    int32_t *cc = g.use_lds ? lds_counts + g.rows.cap : g.ccnt;
+    for (int x = threadIdx.x; x < g.rows.cap; x += kPlanThreads) rc[x] = 0;
+    for (int x = threadIdx.x; x < g.cols.cap; x += kPlanThreads) cc[x] = 0;
+    __syncthreads();
+    int deep = 0;
+    const int s2 = g.s * g.s;
+    for (int e = threadIdx.x; e < E; e += kPlanThreads) {
+        const int v = g.eV[e];
+        atomicAdd(&rc[g.eR[e]], 1);
+        atomicAdd(&cc[g.eC[e]], 1);
+        if (v >= s2 || v <= -s2) deep = 1;
+    }
+    deep = block_max(deep, lds);
     int nr = *g.nr_io, nc = *g.nc_io;
-    uint32_t T = 0;
-    // every batch retires at least one digit of one OB entry, and an entry has at most 32 digits
-    const long long max_batches = 32ll * (long long)(*g.ecount) + 64;
-    for (long long it = 0;; ++it) {
-        if (it > max_batches) {
-            if (threadIdx.x == 0) atomicMin(&g.hdr->err, IMUNPACK_EHIP);
+    const long long max_batches = 32ll * (long long)E + 64;  // every batch retires >= one digit of one entry
+    for (long long bid = 0;; ++bid) {
+        if (bid > max_batches || bid >= 65535) {
+            if (threadIdx.x == 0) atomicMin(&g.hdr->err, bid >= 65535 ? IMUNPACK_ERANGE : IMUNPACK_EHIP);
             return;
         }
         int m0 = 0, m1 = 0;
-        for (int x = threadIdx.x; x < nr; x += kPlanThreads) m0 = max(m0, load_agent(&g.rcnt[x]));
-        for (int x = threadIdx.x; x < nc; x += kPlanThreads) m1 = max(m1, load_agent(&g.ccnt[x]));
+        for (int x = threadIdx.x; x < nr; x += kPlanThreads) m0 = max(m0, load_agent(&rc[x]));
+        for (int x = threadIdx.x; x < nc; x += kPlanThreads) m1 = max(m1, load_agent(&cc[x]));
         const int c0 = block_max(m0, lds), c1 = block_max(m1, lds);
         if (c0 == 0 && c1 == 0) break;
         const bool isrow = c0 >= c1;  // rows win ties (Alg. 4: "else if c0 >= c1")
-        const int32_t *cnt = isrow ? g.rcnt : g.ccnt;
-        const int N = isrow ? nr : nc, target = isrow ? c0 : c1;
-        const int cap = isrow ? g.rows.cap : g.cols.cap;
+        int32_t *cnt = isrow ? rc : cc, *other = isrow ? cc : rc;
+        int32_t *epos = isrow ? g.eR : g.eC, *ecross = isrow ? g.eC : g.eR;
+        const SlotSet &mine = isrow ? g.rows : g.cols;
+        const int N = isrow ? nr : nc;
+        // slots with lo <= count <= hi are split in this batch
+        const int hi = isrow ? c0 : c1;
+        const int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
         int nb = 0;
         for (int x0 = 0; x0 < N; x0 += kPlanThreads) {
             const int x = x0 + threadIdx.x;
-            const int flag = (x < N && load_agent(&cnt[x]) == target) ? 1 : 0;
+            const int c = x < N ? load_agent(&cnt[x]) : 0;
+            const int flag = (c >= lo && c <= hi) ? 1 : 0;
             int total;
             const int rank = nb + block_excl_scan(flag, total, lds);
-            if (flag && rank < g.batch_cap) g.batch[rank] = x;
+            if (flag && rank < g.batch_cap) {
+                g.batch[rank] = x;
+                g.bcnt[rank] = c;
+                g.rank_of[x] = rank;
+            }
             nb += total;
         }
-        if (N + nb > cap || nb > g.batch_cap) {
+        if (N + nb > mine.cap || nb > g.batch_cap) {
             if (threadIdx.x == 0) flag_overflow(g.hdr, isrow ? g.whichR : g.whichC, 2 * (N + nb));
             return;
         }
+        for (int r = threadIdx.x; r < nb; r += kPlanThreads) {
+            const int X = g.batch[r], newX = N + r;
+            mine.time[X] = (uint32_t)bid;
+            mine.child[X] = newX;
+            mine.root[newX] = mine.root[X];
+            mine.exp[newX] = mine.exp[X] + 1;
+            mine.time[newX] = kNever;
+            mine.child[newX] = -1;
+            mine.key[newX] = ((unsigned long long)bid << 48) |
+                             ((unsigned long long)(0xFFFFFF - min(g.bcnt[r], 0xFFFFFF)) << 24) | (unsigned)X;
+        }
         __syncthreads();
-        split_batch(g, isrow, N, nb, T);
+        // one pass over the edges: an edge in a split slot keeps digit 0 there and moves floor(v / s)
+        // to the new slot (Alg. 4 lines 7-9 / 11-14); if that is In-Bound the edge is finished and
+        // leaves the count of the crossing slot
+        for (int e = threadIdx.x; e < E; e += kPlanThreads) {
+            const int v = g.eV[e];
+            const int av = v < 0 ? -v : v;
+            if (av < g.s) continue;
+            const int X = epos[e];
+            if (X >= N) continue;  // created in this batch
+            const int c = load_agent(&cnt[X]);
+            if (c < lo || c > hi) continue;
+            const int av2 = av >> g.sh;
+            g.eV[e] = v < 0 ? -av2 : av2;
+            if (av2 >= g.s) {
+                const int newX = N + g.rank_of[X];
+                epos[e] = newX;
+                atomicAdd(&cnt[newX], 1);
+            } else {
+                atomicSub(&other[ecross[e]], 1);
+            }
+        }
+        __syncthreads();
+        for (int r = threadIdx.x; r < nb; r += kPlanThreads)
+            __hip_atomic_store(&cnt[g.batch[r]], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
         if (isrow) nr += nb; else nc += nb;
-        T += (uint32_t)nb;
     }
     if (threadIdx.x == 0) {
         *g.nr_io = nr;
@@ -585,6 +528,7 @@ static void carve_slots(Carver &cv, SlotSet &s, int cap) {
     s.exp = cv.take<int32_t>(cap);
     s.time = cv.take<uint32_t>(cap);
     s.child = cv.take<int32_t>(cap);
+    s.key = cv.take<unsigned long long>(cap);
     s.cap = cap;
 }
 
@@ -623,6 +567,9 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->cols.colB_e = cv.take<int32_t>(kc);
         p->cols.col_sexp = cv.take<int32_t>(kc);
     }
+    p->canon_rowphysA = cv.take<int32_t>(p->cap[CAP_ROWA]);
+    p->canon_rowphysB = cv.take<int32_t>(p->cap[CAP_ROWB]);
+    p->canon_colphys = cv.take<int32_t>(p->cap[CAP_C2]);
     if (own_statsA) {
         p->statsA[0] = cv.take<int32_t>(n); p->statsA[1] = cv.take<int32_t>(d);
         p->statsA[2] = cv.take<int32_t>(n); p->statsA[3] = cv.take<int32_t>(d);
@@ -639,16 +586,11 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         const int ecap = std::max(p->sA == IMUNPACK_BOTH ? p->cap[CAP_EDGEA] : 0,
                                   p->sB == IMUNPACK_BOTH ? p->cap[CAP_EDGEB] : 0);
         p->eR = cv.take<int32_t>(ecap); p->eC = cv.take<int32_t>(ecap); p->eV = cv.take<int32_t>(ecap);
-        p->redge = cv.take<int32_t>(ecap); p->cedge = cv.take<int32_t>(ecap);
         const int rcap = std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), ccap = std::max(p->cap[CAP_C1], p->cap[CAP_C2]);
-        p->rcnt = cv.take<int32_t>(rcap); p->rstart = cv.take<int32_t>(rcap); p->rlen = cv.take<int32_t>(rcap);
-        p->ccnt = cv.take<int32_t>(ccap); p->cstart = cv.take<int32_t>(ccap); p->clen = cv.take<int32_t>(ccap);
+        p->rcnt = cv.take<int32_t>(rcap);
+        p->ccnt = cv.take<int32_t>(ccap);
         p->batch = cv.take<int32_t>(std::max(rcap, ccap));
-        if (p->sB == IMUNPACK_BOTH) {
-            p->rawJ = cv.take<int32_t>(p->cap[CAP_RAWB]);
-            p->rawK = cv.take<int32_t>(p->cap[CAP_RAWB]);
-            p->rawV = cv.take<int32_t>(p->cap[CAP_RAWB]);
-        }
+        p->ob = cv.take<int32_t>((size_t)3 * p->cap[CAP_OB]);
     }
     return cv.off + 256;
 }
@@ -660,59 +602,67 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
     return (int)b;
 }
 
-static int run_greedy(Plan *p, int phase, hipStream_t st) {
+static constexpr int kGreedyLdsMax = 150 * 1024;  // dynamic LDS the greedy may use for the two count vectors
+
+// ob: the operand's OB entry list ([3][ob_cap], count on the device)
+static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const int32_t *ob_count,
+                      int which_list, hipStream_t st) {
     PlanHeader *hdr = p->d_hdr;
     const bool first = phase == 1;
     SlotSet &rows = first ? p->rowA : p->rowB;
     SlotSet &cols = first ? p->c1 : p->c2;
-    int32_t *nr = first ? &hdr->n_u : &hdr->h_u;
-    int32_t *nc = first ? &hdr->d1 : &hdr->d_u;
     int32_t *ecount = first ? &hdr->edgesA : &hdr->edgesB;
     const int ecap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];
-    // live counts start at zero for every slot that may ever exist
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(rows.cap, 256)), dim3(256), 0, st, p->rcnt,
-                       (int64_t)rows.cap, 0);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(cols.cap, 256)), dim3(256), 0, st, p->ccnt,
-                       (int64_t)cols.cap, 0);
-    hipLaunchKernelGGL(check_count_kernel, dim3(1), dim3(64), 0, st, ecount, ecap, hdr,
-                       first ? CAP_EDGEA : CAP_EDGEB);
-    hipLaunchKernelGGL(edge_count_kernel, dim3(grid_for(ecap, 256, 1024)), dim3(256), 0, st, p->eR, p->eC,
-                       ecount, p->rcnt, p->ccnt, hdr);
-    hipLaunchKernelGGL(edge_scan_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rcnt, p->ccnt, nr, nc,
-                       p->rstart, p->rlen, p->cstart, p->clen, hdr);
-    hipLaunchKernelGGL(edge_fill_kernel, dim3(grid_for(ecap, 256, 1024)), dim3(256), 0, st, p->eR, p->eC,
-                       ecount, p->rstart, p->rlen, p->cstart, p->clen, p->redge, p->cedge, hdr);
+    hipLaunchKernelGGL(expand_edges_kernel, dim3(grid_for(ob_cap, 256, 1024)), dim3(256), 0, st, ob, ob_cap,
+                       ob_count, p->c1, p->eR, p->eC, p->eV, ecap, ecount, hdr, which_list,
+                       first ? (int)CAP_EDGEA : (int)CAP_EDGEB);
     GreedyArgs g;
     g.rows = rows; g.cols = cols;
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
-    g.rstart = p->rstart; g.rlen = p->rlen; g.cstart = p->cstart; g.clen = p->clen;
-    g.redge = p->redge; g.cedge = p->cedge;
     g.eR = p->eR; g.eC = p->eC; g.eV = p->eV;
-    g.batch = p->batch;
+    g.ecount = ecount; g.ecap = ecap;
+    g.batch = p->batch; g.bcnt = p->tmpL; g.rank_of = p->tmpCur;
     g.batch_cap = std::max(std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), std::max(p->cap[CAP_C1], p->cap[CAP_C2]));
-    g.nr_io = nr; g.nc_io = nc;
-    g.ecount = ecount;
+    g.nr_io = first ? &hdr->n_u : &hdr->h_u;
+    g.nc_io = first ? &hdr->d1 : &hdr->d_u;
     g.hdr = hdr;
     g.whichR = first ? CAP_ROWA : CAP_ROWB;
     g.whichC = first ? CAP_C1 : CAP_C2;
+    g.whichE = first ? CAP_EDGEA : CAP_EDGEB;
     g.s = p->s; g.sh = p->sh;
-    hipLaunchKernelGGL(greedy_both_kernel, dim3(1), dim3(kPlanThreads), 0, st, g);
+    const size_t lds_bytes = ((size_t)rows.cap + (size_t)cols.cap) * sizeof(int32_t);
+    g.use_lds = lds_bytes <= (size_t)kGreedyLdsMax;
+    static int opted_in = 0;
+    if (!opted_in) {
+        IMU_HIP(hipFuncSetAttribute((const void *)greedy_both_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kGreedyLdsMax));
+        opted_in = 1;
+    }
+    hipLaunchKernelGGL(greedy_both_kernel, dim3(1), dim3(kPlanThreads), g.use_lds ? lds_bytes : 0, st, g);
     return launch_status();
 }
 
 static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B, int64_t ldb,
-                        bool own_statsA, bool own_statsB, hipStream_t st) {
+                        const imunpack_stats_t *stA, const imunpack_stats_t *stB, bool own_statsA,
+                        bool own_statsB, hipStream_t st) {
     PlanHeader *hdr = p->d_hdr;
     const int n = (int)p->n, d = (int)p->d, h = (int)p->h;
     hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr);
-    if (own_statsA) {
-        imunpack_stats_t s{p->statsA[0], p->statsA[1], p->statsA[2], p->statsA[3]};
-        IMU_TRY(scan_i32(A, n, d, lda, p->b, &s, st));
-    }
-    if (own_statsB) {
-        imunpack_stats_t s{p->statsB[0], p->statsB[1], p->statsB[2], p->statsB[3]};
-        IMU_TRY(scan_i32(B, h, d, ldb, p->b, &s, st));
-    }
+    // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
+    // this call's own scan produces one.  The two operands are planned one after the other, so one
+    // own buffer serves both.
+    const bool listA = p->sA == IMUNPACK_BOTH, listB = p->sB == IMUNPACK_BOTH;
+    const bool callerA = listA && stA && stA->ob && stA->ob_count && stA->ob_cap > 0 && !p->ignore_listA;
+    const bool callerB = listB && stB && stB->ob && stB->ob_count && stB->ob_cap > 0 && !p->ignore_listB;
+    const bool scanA = own_statsA || (listA && !callerA), scanB = own_statsB || (listB && !callerB);
+    auto scan_operand = [&](const int32_t *M, int rows, int64_t ld, int32_t **own, bool own_stats, bool list) {
+        imunpack_stats_t sx;
+        memset(&sx, 0, sizeof(sx));
+        if (own_stats) { sx.rowcnt = own[0]; sx.colcnt = own[1]; sx.rowmax = own[2]; sx.colmax = own[3]; }
+        if (list) { sx.ob = p->ob; sx.ob_cap = p->cap[CAP_OB]; sx.ob_count = &hdr->obcount; }
+        return scan_i32(M, rows, d, ld, p->b, &sx, st);
+    };
+    if (scanA) IMU_TRY(scan_operand(A, n, lda, p->statsA, own_statsA, listA && !callerA));
     // ---- phase 1: Unpack(A, B, I, b, strategy_A)
     if (p->sA == IMUNPACK_ROW) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowA, p->statsA[2],
@@ -731,11 +681,10 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                            (const int32_t *)nullptr, &hdr->n_u, hdr, (int)CAP_ROWA);
         hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(d, 256, 64)), dim3(256), 0, st, p->c1, d,
                            (const int32_t *)nullptr, &hdr->d1, hdr, (int)CAP_C1);
-        hipLaunchKernelGGL(coo_extract_kernel, dim3(grid_for((int64_t)n * ((d + 63) / 64) * 64, 256, 4096)),
-                           dim3(256), 0, st, A, (int64_t)n, (int64_t)d, lda, p->s, p->eR, p->eC, p->eV,
-                           p->cap[CAP_EDGEA], &hdr->edgesA, hdr);
-        IMU_TRY(run_greedy(p, 1, st));
+        if (callerA) IMU_TRY(run_greedy(p, 1, stA->ob, (int)stA->ob_cap, stA->ob_count, CAP_LISTA, st));
+        else IMU_TRY(run_greedy(p, 1, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
+    if (scanB) IMU_TRY(scan_operand(B, h, ldb, p->statsB, own_statsB, listB && !callerB));
     // ---- phase 2: Unpack(B_e, A_u, S_u, b, strategy_B); B_e has d1 columns
     if (p->sB == IMUNPACK_ROW) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowB, p->statsB[2],
@@ -754,15 +703,8 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                            (const int32_t *)nullptr, &hdr->h_u, hdr, (int)CAP_ROWB);
         hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(p->cap[CAP_C2], 256, 64)), dim3(256), 0, st,
                            p->c2, 0, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2);
-        hipLaunchKernelGGL(coo_extract_kernel, dim3(grid_for((int64_t)h * ((d + 63) / 64) * 64, 256, 4096)),
-                           dim3(256), 0, st, B, (int64_t)h, (int64_t)d, ldb, p->s, p->rawJ, p->rawK, p->rawV,
-                           p->cap[CAP_RAWB], &hdr->rawB, hdr);
-        hipLaunchKernelGGL(check_count_kernel, dim3(1), dim3(64), 0, st, &hdr->rawB, p->cap[CAP_RAWB], hdr,
-                           (int)CAP_RAWB);
-        hipLaunchKernelGGL(expand_edges_kernel, dim3(grid_for(p->cap[CAP_RAWB], 256, 1024)), dim3(256), 0, st,
-                           p->rawJ, p->rawK, p->rawV, &hdr->rawB, p->cap[CAP_RAWB], p->c1, p->eR, p->eC,
-                           p->eV, p->cap[CAP_EDGEB], &hdr->edgesB, hdr);
-        IMU_TRY(run_greedy(p, 2, st));
+        if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st));
+        else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
     // ---- physical layouts
     hipLaunchKernelGGL(rows_layout_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowA, n, &hdr->n_u, p->layA,
@@ -810,7 +752,8 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         p->cap[CAP_C2] = std::max(p->cap[CAP_C2], (int)(2 * d + 512));
         p->cap[CAP_EDGEA] = std::max(p->cap[CAP_EDGEA], (int)std::min<int64_t>(n * d, std::max<int64_t>(n * d / 64, 4096)));
         p->cap[CAP_EDGEB] = std::max(p->cap[CAP_EDGEB], (int)std::min<int64_t>(2 * h * d, std::max<int64_t>(h * d / 64, 4096)));
-        p->cap[CAP_RAWB] = std::max(p->cap[CAP_RAWB], (int)std::min<int64_t>(h * d, std::max<int64_t>(h * d / 64, 4096)));
+        p->cap[CAP_OB] = std::max(p->cap[CAP_OB], (int)std::min<int64_t>(std::max(n, h) * d, std::max<int64_t>(std::max(n, h) * d / 64, 4096)));
+        p->ignore_listA = p->ignore_listB = 0;
     }
     const bool ownA = !(stats_A && stats_A->rowcnt && stats_A->colcnt && stats_A->rowmax && stats_A->colmax);
     const bool ownB = !(stats_B && stats_B->rowcnt && stats_B->colcnt && stats_B->rowmax && stats_B->colmax);
@@ -832,14 +775,22 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         carve(p, p->arena, ownA, ownB);
         if (!ownA) { p->statsA[0] = stats_A->rowcnt; p->statsA[1] = stats_A->colcnt; p->statsA[2] = stats_A->rowmax; p->statsA[3] = stats_A->colmax; }
         if (!ownB) { p->statsB[0] = stats_B->rowcnt; p->statsB[1] = stats_B->colcnt; p->statsB[2] = stats_B->rowmax; p->statsB[3] = stats_B->colmax; }
-        rc = enqueue_plan(p, A, lda, B, ldb, ownA, ownB, st);
+        rc = enqueue_plan(p, A, lda, B, ldb, stats_A, stats_B, ownA, ownB, st);
         if (rc != IMUNPACK_OK) break;
         hipError_t e = hipMemcpyAsync(&p->hdr, p->d_hdr, sizeof(PlanHeader), hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; break; }
         if (p->hdr.err) { rc = p->hdr.err; break; }
-        if (!p->hdr.overflow) { p->valid = 1; break; }
-        for (int c = 0; c < 8; ++c)
+        if (!p->hdr.overflow) {
+            p->valid = 1;
+            p->canon_valid = 0;
+            p->bothA = strategy_A == IMUNPACK_BOTH;
+            p->bothB = strategy_B == IMUNPACK_BOTH;
+            break;
+        }
+        if (p->hdr.overflow & (1 << CAP_LISTA)) p->ignore_listA = 1;
+        if (p->hdr.overflow & (1 << CAP_LISTB)) p->ignore_listB = 1;
+        for (int c = 0; c <= CAP_OB; ++c)
             if (p->hdr.overflow & (1 << c)) {
                 int64_t nv = std::max<int64_t>((int64_t)p->hdr.need[c] + p->hdr.need[c] / 8 + 256, (int64_t)p->cap[c] * 2);
                 if (nv > (1ll << 30)) { rc = IMUNPACK_ENOMEM; break; }
@@ -867,35 +818,129 @@ extern "C" int imunpack_plan_dims(const imunpack_plan_t *p, int64_t *n_u, int64_
 }
 
 namespace imu {
-__global__ void export_cols_kernel(SlotSet c1, SlotSet c2, int D, int32_t *col_src, int32_t *col_exp) {
-    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x) {
-        const int root = c2.root[c];
-        col_src[c] = c1.root[root];
-        col_exp[c] = c1.exp[root] + c2.exp[c];
+
+// Canonical (paper-order) numbering of the slots of one set.  Slots are appended in runs: a level of
+// the closed-form UnpackRow / UnpackColumn, or a batch of UnpackBoth.  Inside a run the paper's
+// order is (count at the split descending, index of the split slot ascending), the index being the
+// canonical one.  key = run << 48 | (0xFFFFFF - count) << 24 | split slot (internal numbering).
+static int canonical_order(const SlotSet &set, int nbase, int count, const std::vector<int> *base_canon,
+                           hipStream_t st, std::vector<int> &canon_of) {
+    canon_of.assign((size_t)count, 0);
+    for (int x = 0; x < nbase && x < count; ++x) canon_of[x] = base_canon ? (*base_canon)[x] : x;
+    const int extra = count - nbase;
+    if (extra <= 0) return IMUNPACK_OK;
+    std::vector<unsigned long long> key((size_t)extra);
+    IMU_HIP(hipMemcpyAsync(key.data(), set.key + nbase, (size_t)extra * sizeof(unsigned long long),
+                           hipMemcpyDeviceToHost, st));
+    IMU_HIP(hipStreamSynchronize(st));
+    std::vector<int> order((size_t)extra);
+    std::vector<char> assigned((size_t)count, 0);
+    for (int x = 0; x < nbase && x < count; ++x) assigned[x] = 1;
+    for (int t = 0; t < extra; ++t) order[t] = t;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return (key[a] >> 48) < (key[b] >> 48); });
+    int next = nbase;
+    for (size_t lo = 0; lo < order.size();) {
+        size_t hi = lo;
+        const unsigned long long run = key[order[lo]] >> 48;
+        while (hi < order.size() && (key[order[hi]] >> 48) == run) ++hi;
+        auto minor = [&](int t) { return (unsigned)((key[t] >> 24) & 0xFFFFFF); };
+        auto parent = [&](int t) { return (int)(key[t] & 0xFFFFFF); };
+        for (size_t q = lo; q < hi; ++q) {  // the split slot must come from an earlier run
+            const int par = parent(order[q]);
+            if (par < 0 || par >= count || !assigned[par]) return IMUNPACK_EHIP;
+        }
+        std::sort(order.begin() + lo, order.begin() + hi, [&](int a, int b) {
+            if (minor(a) != minor(b)) return minor(a) < minor(b);
+            return canon_of[parent(a)] < canon_of[parent(b)];
+        });
+        for (size_t q = lo; q < hi; ++q) {
+            canon_of[nbase + order[q]] = next++;
+            assigned[nbase + order[q]] = 1;
+        }
+        lo = hi;
     }
+    return IMUNPACK_OK;
 }
+
+struct CanonHost {
+    std::vector<int> rowA, rowB, c1, c2;  // internal slot -> canonical slot
+};
+
+static int fetch_i32(std::vector<int32_t> &dst, const int32_t *src, size_t count, hipStream_t st) {
+    dst.resize(count);
+    if (count) IMU_HIP(hipMemcpyAsync(dst.data(), src, count * 4, hipMemcpyDeviceToHost, st));
+    return IMUNPACK_OK;
+}
+
+static int build_canonical(Plan *p, CanonHost &c) {
+    hipStream_t st = p->stream;
+    const PlanHeader &h = p->hdr;
+    IMU_TRY(canonical_order(p->rowA, (int)p->n, h.n_u, nullptr, st, c.rowA));
+    IMU_TRY(canonical_order(p->rowB, (int)p->h, h.h_u, nullptr, st, c.rowB));
+    IMU_TRY(canonical_order(p->c1, (int)p->d, h.d1, nullptr, st, c.c1));
+    IMU_TRY(canonical_order(p->c2, h.d1, h.d_u, &c.c1, st, c.c2));
+    if (!p->canon_valid) {
+        // physical row / column of every canonical slot, for imunpack_unpack_canonical
+        std::vector<int32_t> phys, out;
+        auto upload = [&](const int32_t *dev_phys, const std::vector<int> &canon, int32_t *dev_out) -> int {
+            IMU_TRY(fetch_i32(phys, dev_phys, canon.size(), st));
+            IMU_HIP(hipStreamSynchronize(st));
+            out.assign(canon.size(), 0);
+            for (size_t x = 0; x < canon.size(); ++x) out[(size_t)canon[x]] = phys[x];
+            if (!out.empty()) IMU_HIP(hipMemcpy(dev_out, out.data(), out.size() * 4, hipMemcpyHostToDevice));
+            return IMUNPACK_OK;
+        };
+        IMU_TRY(upload(p->layA.row_phys, c.rowA, p->canon_rowphysA));
+        IMU_TRY(upload(p->layB.row_phys, c.rowB, p->canon_rowphysB));
+        IMU_TRY(upload(p->cols.col_phys, c.c2, p->canon_colphys));
+        p->canon_valid = 1;
+    }
+    return IMUNPACK_OK;
+}
+
+int ensure_canonical(Plan *p) {
+    if (p->canon_valid) return IMUNPACK_OK;
+    CanonHost c;
+    return build_canonical(p, c);
+}
+
 }  // namespace imu
 
-extern "C" int imunpack_plan_export(const imunpack_plan_t *p, int32_t *rowA_src, int32_t *rowA_exp,
+extern "C" int imunpack_plan_export(const imunpack_plan_t *cp, int32_t *rowA_src, int32_t *rowA_exp,
                                     int32_t *rowB_src, int32_t *rowB_exp, int32_t *col_src,
                                     int32_t *col_exp) {
-    if (!p || !p->valid) return IMUNPACK_EINVAL;
+    if (!cp || !cp->valid) return IMUNPACK_EINVAL;
+    Plan *p = const_cast<Plan *>(cp);
     hipStream_t st = p->stream;
-    const size_t nA = (size_t)p->hdr.n_u * 4, nB = (size_t)p->hdr.h_u * 4, nC = (size_t)p->hdr.d_u * 4;
-    if (rowA_src) IMU_HIP(hipMemcpyAsync(rowA_src, p->rowA.root, nA, hipMemcpyDeviceToHost, st));
-    if (rowA_exp) IMU_HIP(hipMemcpyAsync(rowA_exp, p->rowA.exp, nA, hipMemcpyDeviceToHost, st));
-    if (rowB_src) IMU_HIP(hipMemcpyAsync(rowB_src, p->rowB.root, nB, hipMemcpyDeviceToHost, st));
-    if (rowB_exp) IMU_HIP(hipMemcpyAsync(rowB_exp, p->rowB.exp, nB, hipMemcpyDeviceToHost, st));
+    const PlanHeader &h = p->hdr;
+    CanonHost c;
+    IMU_TRY(build_canonical(p, c));
+    std::vector<int32_t> root, ex, root1, ex1;
+    auto rows_out = [&](const SlotSet &set, const std::vector<int> &canon, int32_t *o_src, int32_t *o_exp) -> int {
+        if (!o_src && !o_exp) return IMUNPACK_OK;
+        IMU_TRY(fetch_i32(root, set.root, canon.size(), st));
+        IMU_TRY(fetch_i32(ex, set.exp, canon.size(), st));
+        IMU_HIP(hipStreamSynchronize(st));
+        for (size_t x = 0; x < canon.size(); ++x) {
+            if (o_src) o_src[canon[x]] = root[x];
+            if (o_exp) o_exp[canon[x]] = ex[x];
+        }
+        return IMUNPACK_OK;
+    };
+    IMU_TRY(rows_out(p->rowA, c.rowA, rowA_src, rowA_exp));
+    IMU_TRY(rows_out(p->rowB, c.rowB, rowB_src, rowB_exp));
     if (col_src || col_exp) {
-        // scratch: the level temporaries are free once planning has finished
-        int32_t *t_src = p->tmpL, *t_exp = p->tmpCur;
-        hipLaunchKernelGGL(export_cols_kernel, dim3(grid_for(p->hdr.d_u, 256, 256)), dim3(256), 0, st, p->c1,
-                           p->c2, p->hdr.d_u, t_src, t_exp);
-        IMU_TRY(launch_status());
-        if (col_src) IMU_HIP(hipMemcpyAsync(col_src, t_src, nC, hipMemcpyDeviceToHost, st));
-        if (col_exp) IMU_HIP(hipMemcpyAsync(col_exp, t_exp, nC, hipMemcpyDeviceToHost, st));
+        IMU_TRY(fetch_i32(root, p->c2.root, (size_t)h.d_u, st));
+        IMU_TRY(fetch_i32(ex, p->c2.exp, (size_t)h.d_u, st));
+        IMU_TRY(fetch_i32(root1, p->c1.root, (size_t)h.d1, st));
+        IMU_TRY(fetch_i32(ex1, p->c1.exp, (size_t)h.d1, st));
+        IMU_HIP(hipStreamSynchronize(st));
+        for (int x = 0; x < h.d_u; ++x) {
+            const int r1 = root[x];  // column slot after unpacking A that this column descends from
+            if (col_src) col_src[c.c2[x]] = root1[r1];
+            if (col_exp) col_exp[c.c2[x]] = ex1[r1] + ex[x];
+        }
     }
-    IMU_HIP(hipStreamSynchronize(st));
     return IMUNPACK_OK;
 }
 

@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
                                                         int32_t *__restrict__ Q, int64_t ldq,
                                                         int32_t *rowcnt, int32_t *colcnt,
                                                         int32_t *rowmax, int32_t *colmax,
-                                                        int32_t *status) {
+                                                        int32_t *status, int32_t *ob, int ob_cap,
+                                                        int32_t *ob_count) {
     __shared__ int lds[2 * 4 * 256];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t c0 = (int64_t)blockIdx.x * 256 + lane * 4;
@@ -107,6 +108,26 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
             if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
             if (rowmax && rm) atomicMax(&rowmax[r], rm);
         }
+        if (ob && rc) {  // rare: append this wave's OB entries (row, column, value) to the list
+            const unsigned long long lt = (1ull << lane) - 1ull;
+            const unsigned long long b0 = __ballot(o0), b1 = __ballot(o1), b2 = __ballot(o2), b3 = __ballot(o3);
+            int base = 0;
+            if (lane == 0) base = atomicAdd(ob_count, rc);
+            base = __shfl(base, 0, 64);
+            int pos = base + __popcll(b0 & lt) + __popcll(b1 & lt) + __popcll(b2 & lt) + __popcll(b3 & lt);
+            const int qv[4] = {q.x, q.y, q.z, q.w};
+            const int ov[4] = {o0, o1, o2, o3};
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ov[u]) {
+                    if (pos < ob_cap) {
+                        ob[pos] = (int32_t)r;
+                        ob[ob_cap + pos] = (int32_t)(c0 + u);
+                        ob[2 * ob_cap + pos] = qv[u];
+                    }
+                    ++pos;
+                }
+        }
     }
     if (colcnt || colmax)
         flush_columns<4>(ccnt, cmax, (int64_t)blockIdx.x * 256, cols, colcnt, colmax, lds);
@@ -121,7 +142,8 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
                                                          float scale, int s, int32_t *__restrict__ Q,
                                                          int64_t ldq, int32_t *rowcnt, int32_t *colcnt,
                                                          int32_t *rowmax, int32_t *colmax,
-                                                         int32_t *status) {
+                                                         int32_t *status, int32_t *ob, int ob_cap,
+                                                         int32_t *ob_count) {
     __shared__ int32_t tile[64][65];
     __shared__ int lds[2 * 4 * 64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -154,11 +176,23 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
         const int o = a >= s;
         ccnt[0] += o;
         cmax[0] = max(cmax[0], a);
-        const int rc = __popcll(__ballot(o));
+        const unsigned long long bo = __ballot(o);
+        const int rc = __popcll(bo);
         const int rm = wave_max_i32(a);
         if (lane == 0 && r < rows) {
             if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
             if (rowmax && rm) atomicMax(&rowmax[r], rm);
+        }
+        if (ob && rc) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(ob_count, rc);
+            base = __shfl(base, 0, 64);
+            const int pos = base + __popcll(bo & ((1ull << lane) - 1ull));
+            if (o && pos < ob_cap) {
+                ob[pos] = (int32_t)r;
+                ob[ob_cap + pos] = (int32_t)c;
+                ob[2 * ob_cap + pos] = q;
+            }
         }
     }
     if (colcnt || colmax) flush_columns<1>(ccnt, cmax, c0, cols, colcnt, colmax, lds);
@@ -178,6 +212,8 @@ static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, in
             }
     }
     if (status) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, status, (int64_t)1, 0);
+    if (st && st->ob && st->ob_count)
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, st->ob_count, (int64_t)1, 0);
     return launch_status();
 }
 
@@ -186,24 +222,28 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
                      int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status,
                      hipStream_t stream) {
     if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
-    if (FROM_FLOAT && (!Q || ldq < cols || !(scale > 0.0f) || !(scale < INFINITY))) return IMUNPACK_EINVAL;
+    if (FROM_FLOAT && (!Q || ldq < cols || !(scale > 0.0f) || !(scale < 3.0e38f))) return IMUNPACK_EINVAL;
     IMU_TRY(zero_stats(st, rows, cols, FROM_FLOAT ? status : nullptr, stream));
     if (rows == 0 || cols == 0) return IMUNPACK_OK;
     const int s = 1 << (b - 1);
     int32_t *rowcnt = st ? st->rowcnt : nullptr, *colcnt = st ? st->colcnt : nullptr;
     int32_t *rowmax = st ? st->rowmax : nullptr, *colmax = st ? st->colmax : nullptr;
-    if (!FROM_FLOAT && !rowcnt && !colcnt && !rowmax && !colmax) return IMUNPACK_OK;
+    int32_t *ob = (st && st->ob && st->ob_count && st->ob_cap > 0) ? st->ob : nullptr;
+    int32_t *ob_count = ob ? st->ob_count : nullptr;
+    if (st && st->ob_cap > 0x7fffffff / 3) return IMUNPACK_EINVAL;
+    const int ob_cap = ob ? (int)st->ob_cap : 0;
+    if (!FROM_FLOAT && !rowcnt && !colcnt && !rowmax && !colmax && !ob) return IMUNPACK_OK;
     const bool vec = sx_c == 1 && (cols % 4) == 0 && (sx_r % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
                      (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0));
     if (vec) {
         dim3 grid((unsigned)((cols + 255) / 256), (unsigned)((rows + 63) / 64));
-        if (grid.y > 65535u * 16u) return IMUNPACK_EINVAL;
+        if (grid.y > 65535u) return IMUNPACK_EINVAL;
         hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status);
+                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     } else {
         dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
         hipLaunchKernelGGL(qscan_tile_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           sx_c, scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status);
+                           sx_c, scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     }
     return launch_status();
 }

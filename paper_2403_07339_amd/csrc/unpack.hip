@@ -158,16 +158,20 @@ extern "C" int imunpack_plan_fusable(const imunpack_plan_t *p) {
     return p->fusable;
 }
 
-extern "C" int imunpack_unpack_canonical(const imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
+namespace imu { int ensure_canonical(Plan *p); }
+
+extern "C" int imunpack_unpack_canonical(const imunpack_plan_t *cp, const int8_t *A_ue, const int8_t *B_eu,
                                          int8_t *A_canon, int8_t *B_canon, imunpack_stream_t stream) {
-    if (!p || !p->valid) return IMUNPACK_EINVAL;
+    if (!cp || !cp->valid) return IMUNPACK_EINVAL;
+    Plan *p = const_cast<Plan *>(cp);
+    IMU_TRY(ensure_canonical(p));  // host-side renumbering into the paper's order (synchronises)
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (A_ue && A_canon && h.n_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, h.Kp, p->layA.row_phys,
-                           p->cols.col_phys, h.n_u, h.d_u, A_canon);
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, h.Kp, p->canon_rowphysA,
+                           p->canon_colphys, h.n_u, h.d_u, A_canon);
     if (B_eu && B_canon && h.h_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, h.Kp, p->layB.row_phys,
-                           p->cols.col_phys, h.h_u, h.d_u, B_canon);
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, h.Kp, p->canon_rowphysB,
+                           p->canon_colphys, h.h_u, h.d_u, B_canon);
     return launch_status();
 }
