@@ -297,6 +297,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             if (threadIdx.x == 0) flag_overflow(g.hdr, isrow ? g.whichR : g.whichC, 2 * (N + nb));
             return;
         }
+        __syncthreads();  // the batch list of the last chunk is written after the scan's barrier
         for (int r = threadIdx.x; r < nb; r += kPlanThreads) {
             const int X = g.batch[r], newX = N + r;
             mine.time[X] = (uint32_t)bid;

@@ -60,6 +60,49 @@ __device__ __forceinline__ void flush_columns(int (&ccnt)[COLS_PER_LANE], int (&
     }
 }
 
+
+// OB entries found by a workgroup are staged in LDS and appended to the global list with a single
+// atomic per workgroup (one atomic per wave-row would serialise on the list's counter).
+constexpr int kObStage = 1024;
+struct ObStage {
+    int count;
+    int base;
+    int32_t row[kObStage], col[kObStage], val[kObStage];
+};
+
+__device__ __forceinline__ void ob_push(ObStage *sg, int pos, int32_t r, int32_t c, int32_t v, int32_t *ob,
+                                        int ob_cap, int32_t *ob_count) {
+    if (pos < kObStage) {
+        sg->row[pos] = r;
+        sg->col[pos] = c;
+        sg->val[pos] = v;
+    } else {  // stage full (an almost entirely OB tile): append directly
+        const int g = atomicAdd(ob_count, 1);
+        if (g < ob_cap) {
+            ob[g] = r;
+            ob[ob_cap + g] = c;
+            ob[2 * ob_cap + g] = v;
+        }
+    }
+}
+
+__device__ __forceinline__ void ob_flush(ObStage *sg, int32_t *ob, int ob_cap, int32_t *ob_count) {
+    __syncthreads();
+    const int n = min(sg->count, kObStage);
+    if (n == 0) return;  // uniform
+    if (threadIdx.x == 0) sg->base = atomicAdd(ob_count, n);
+    __syncthreads();
+    const int base = sg->base;
+    for (int t = threadIdx.x; t < n; t += blockDim.x) {
+        const int g = base + t;
+        if (g < ob_cap) {
+            ob[g] = sg->row[t];
+            ob[ob_cap + g] = sg->col[t];
+            ob[2 * ob_cap + g] = sg->val[t];
+        }
+    }
+}
+
 // Fast path: unit column stride, 16-byte aligned rows.  Workgroup = 64 rows x 256 columns;
 // a wave reads one 1 KiB row segment per instruction (float4 per lane).
 template <bool FROM_FLOAT>
@@ -71,6 +114,11 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
                                                         int32_t *status, int32_t *ob, int ob_cap,
                                                         int32_t *ob_count) {
     __shared__ int lds[2 * 4 * 256];
+    __shared__ ObStage stage;
+    if (ob) {
+        if (threadIdx.x == 0) stage.count = 0;
+        __syncthreads();
+    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t c0 = (int64_t)blockIdx.x * 256 + lane * 4;
     const int64_t r_base = (int64_t)blockIdx.y * 64;
@@ -112,7 +160,7 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
             const unsigned long long lt = (1ull << lane) - 1ull;
             const unsigned long long b0 = __ballot(o0), b1 = __ballot(o1), b2 = __ballot(o2), b3 = __ballot(o3);
             int base = 0;
-            if (lane == 0) base = atomicAdd(ob_count, rc);
+            if (lane == 0) base = atomicAdd(&stage.count, rc);
             base = __shfl(base, 0, 64);
             int pos = base + __popcll(b0 & lt) + __popcll(b1 & lt) + __popcll(b2 & lt) + __popcll(b3 & lt);
             const int qv[4] = {q.x, q.y, q.z, q.w};
@@ -120,15 +168,12 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 if (ov[u]) {
-                    if (pos < ob_cap) {
-                        ob[pos] = (int32_t)r;
-                        ob[ob_cap + pos] = (int32_t)(c0 + u);
-                        ob[2 * ob_cap + pos] = qv[u];
-                    }
+                    ob_push(&stage, pos, (int32_t)r, (int32_t)(c0 + u), qv[u], ob, ob_cap, ob_count);
                     ++pos;
                 }
         }
     }
+    if (ob) ob_flush(&stage, ob, ob_cap, ob_count);
     if (colcnt || colmax)
         flush_columns<4>(ccnt, cmax, (int64_t)blockIdx.x * 256, cols, colcnt, colmax, lds);
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
@@ -146,6 +191,8 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
                                                          int32_t *ob_count) {
     __shared__ int32_t tile[64][65];
     __shared__ int lds[2 * 4 * 64];
+    __shared__ ObStage stage;
+    if (ob && threadIdx.x == 0) stage.count = 0;  // published by the barrier after the tile is filled
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
     int bad = 0;
@@ -185,16 +232,13 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
         }
         if (ob && rc) {
             int base = 0;
-            if (lane == 0) base = atomicAdd(ob_count, rc);
+            if (lane == 0) base = atomicAdd(&stage.count, rc);
             base = __shfl(base, 0, 64);
             const int pos = base + __popcll(bo & ((1ull << lane) - 1ull));
-            if (o && pos < ob_cap) {
-                ob[pos] = (int32_t)r;
-                ob[ob_cap + pos] = (int32_t)c;
-                ob[2 * ob_cap + pos] = q;
-            }
+            if (o) ob_push(&stage, pos, (int32_t)r, (int32_t)c, q, ob, ob_cap, ob_count);
         }
     }
+    if (ob) ob_flush(&stage, ob, ob_cap, ob_count);
     if (colcnt || colmax) flush_columns<1>(ccnt, cmax, c0, cols, colcnt, colmax, lds);
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
 }

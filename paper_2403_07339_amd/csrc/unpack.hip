@@ -40,67 +40,124 @@ __device__ __forceinline__ bool on_chain(const SlotSet &rows, const SlotSet &col
     return true;
 }
 
-// One workgroup per physical row.  OPERAND 0 writes A_ue: rows from Pi_A, column chain inside the
-// unpacking of A, then copied along the columns that unpacking B appended.  OPERAND 1 writes B_eu:
-// rows from Pi_B, column chain inside the unpacking of B_e, whose column c copies B[:, k(c)].
+// One workgroup handles kScatterRows consecutive physical rows over the whole padded width, 16 output
+// bytes per thread and step, so that the column descriptors are fetched once per row block, the
+// source rows (all digit levels of a source row are adjacent) are read from HBM once, and stores are
+// 16 bytes wide.  OPERAND 0 writes A_ue: rows from Pi_A, column chain inside the unpacking of A, then
+// copied along the columns that unpacking B appended.  OPERAND 1 writes B_eu: rows from Pi_B, column
+// chain inside the unpacking of B_e, whose column c copies B[:, k(c)].
+constexpr int kScatterRows = 8;
+
 template <int OPERAND>
 __global__ __launch_bounds__(256) void scatter_kernel(const int32_t *__restrict__ M, int64_t ld,
                                                       RowLayout lay, ColLayout cols, SlotSet rows,
-                                                      SlotSet cset, int Kp, int s, int sh,
+                                                      SlotSet cset, int Mp, int Kp, int s, int sh,
                                                       int8_t *__restrict__ out,
                                                       unsigned long long *bound) {
-    __shared__ unsigned long long red[4];
-    const int p = blockIdx.x;
-    const int R = lay.prow_slot[p];
-    char4 *orow = reinterpret_cast<char4 *>(out + (int64_t)p * Kp);
-    if (R < 0) {
-        for (int q4 = threadIdx.x; q4 < Kp / 4; q4 += 256) orow[q4] = make_char4(0, 0, 0, 0);
-        return;
+    __shared__ unsigned long long red[4][kScatterRows];
+    const int p0 = blockIdx.x * kScatterRows;
+    int slotR[kScatterRows], srcI[kScatterRows], expR[kScatterRows];
+#pragma unroll
+    for (int r = 0; r < kScatterRows; ++r) {
+        const int p = p0 + r;
+        slotR[r] = p < Mp ? lay.prow_slot[p] : -2;
+        srcI[r] = p < Mp ? lay.prow_src[p] : 0;
+        expR[r] = p < Mp ? lay.prow_exp[p] : 0;
     }
-    const int i = lay.prow_src[p];
-    const int er = lay.prow_exp[p];
-    const int32_t *src = M + (int64_t)i * ld;
-    unsigned long long wsum = 0;
-    for (int q4 = threadIdx.x; q4 < Kp / 4; q4 += 256) {
-        int dg[4];
+    unsigned long long wsum[kScatterRows];
+#pragma unroll
+    for (int r = 0; r < kScatterRows; ++r) wsum[r] = 0;
+    const bool ld_vec = (ld % 4) == 0 && ((uintptr_t)M % 16) == 0;
+    for (int q0 = threadIdx.x * 16; q0 < Kp; q0 += 256 * 16) {
+        int k[16], ec[16], sx[16];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int q = q4 * 4 + u;
-            const int k = cols.colA_k[q];
-            int val = 0;
-            if (k >= 0) {
-                const int32_t v = src[k];
-                const int ec = OPERAND == 0 ? cols.colA_e[q] : cols.colB_e[q];
-                const int t = er + ec;
-                if (t == 0) {
-                    val = digit_of(v, 0, sh, s);
-                } else {
-                    val = digit_of(v, t, sh, s);
-                    if (val != 0) {
-                        const int croot = OPERAND == 0 ? k : cols.colA_c1[q];
-                        if (!on_chain(rows, cset, i, croot, er, ec)) val = 0;
-                    }
+            const int4 kk = *reinterpret_cast<const int4 *>(cols.colA_k + q0 + 4 * u);
+            const int4 ee = *reinterpret_cast<const int4 *>((OPERAND == 0 ? cols.colA_e : cols.colB_e) + q0 + 4 * u);
+            const int4 ss = *reinterpret_cast<const int4 *>(cols.col_sexp + q0 + 4 * u);
+            k[4 * u] = kk.x; k[4 * u + 1] = kk.y; k[4 * u + 2] = kk.z; k[4 * u + 3] = kk.w;
+            ec[4 * u] = ee.x; ec[4 * u + 1] = ee.y; ec[4 * u + 2] = ee.z; ec[4 * u + 3] = ee.w;
+            sx[4 * u] = ss.x; sx[4 * u + 1] = ss.y; sx[4 * u + 2] = ss.z; sx[4 * u + 3] = ss.w;
+        }
+        bool run = k[0] >= 0 && (k[0] % 4) == 0 && ld_vec;  // 16 consecutive source columns?
+        int ecany = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            run = run && k[j] == k[0] + j;
+            ecany |= ec[j];
+        }
+#pragma unroll
+        for (int r = 0; r < kScatterRows; ++r) {
+            if (slotR[r] == -2) continue;  // past the last physical row (uniform)
+            int4 *dst = reinterpret_cast<int4 *>(out + (int64_t)(p0 + r) * Kp + q0);
+            if (slotR[r] < 0) {  // padding row
+                *dst = make_int4(0, 0, 0, 0);
+                continue;
+            }
+            const int32_t *src = M + (int64_t)srcI[r] * ld;
+            int32_t v[16];
+            if (run) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int4 x = *reinterpret_cast<const int4 *>(src + k[0] + 4 * u);
+                    v[4 * u] = x.x; v[4 * u + 1] = x.y; v[4 * u + 2] = x.z; v[4 * u + 3] = x.w;
                 }
-                if (val != 0) {
-                    const unsigned sft = (unsigned)(sh * cols.col_sexp[q]);
-                    const unsigned long long mag = (unsigned long long)(val < 0 ? -val : val);
-                    wsum += sft >= 40u ? (1ull << 50) : (mag << sft);
-                    if (wsum > (1ull << 50)) wsum = 1ull << 50;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) v[j] = k[j] >= 0 ? src[k[j]] : 0;
+            }
+            int dg[16];
+            const int er = expR[r];
+            if (er == 0 && ecany == 0) {  // the common case: digit 0 of every entry
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dg[j] = digit_of(v[j], 0, sh, s);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int t = er + ec[j];
+                    int val = digit_of(v[j], t, sh, s);
+                    if (t != 0 && val != 0) {
+                        const int croot = OPERAND == 0 ? k[j] : cols.colA_c1[q0 + j];
+                        if (!on_chain(rows, cset, srcI[r], croot, er, ec[j])) val = 0;
+                    }
+                    dg[j] = val;
                 }
             }
-            dg[u] = val;
-        }
-        orow[q4] = make_char4((signed char)dg[0], (signed char)dg[1], (signed char)dg[2], (signed char)dg[3]);
-    }
-    // weighted L1 norm of the row (saturating), largest over all rows
+            int pk[4];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) wsum += __shfl_xor(wsum, off, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = wsum;
+            for (int u = 0; u < 4; ++u)
+                pk[u] = (dg[4 * u] & 0xFF) | ((dg[4 * u + 1] & 0xFF) << 8) | ((dg[4 * u + 2] & 0xFF) << 16) |
+                        ((dg[4 * u + 3] & 0xFF) << 24);
+            *dst = make_int4(pk[0], pk[1], pk[2], pk[3]);
+            // weighted L1 norm of the row (saturating): sum_c s^e(c) |digit|
+            unsigned long long acc = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const unsigned sft = (unsigned)(sh * sx[j]);
+                const unsigned long long mag = (unsigned long long)(dg[j] < 0 ? -dg[j] : dg[j]);
+                acc += (mag == 0) ? 0ull : (sft >= 40u ? (1ull << 50) : (mag << sft));
+            }
+            wsum[r] += acc;
+            if (wsum[r] > (1ull << 52)) wsum[r] = 1ull << 52;
+        }
+    }
+    // largest row norm of this block -> global maximum
+#pragma unroll
+    for (int r = 0; r < kScatterRows; ++r) {
+        unsigned long long w = wsum[r];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) w += __shfl_xor(w, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][r] = w;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned long long t = red[0] + red[1] + red[2] + red[3];
-        if (t > (1ull << 60)) t = 1ull << 60;
-        if (t) atomicMax(bound, t);
+        unsigned long long best = 0;
+        for (int r = 0; r < kScatterRows; ++r) {
+            unsigned long long t = red[0][r] + red[1][r] + red[2][r] + red[3][r];
+            if (t > (1ull << 60)) t = 1ull << 60;
+            best = best > t ? best : t;
+        }
+        if (best) atomicMax(bound, best);
     }
 }
 
@@ -137,11 +194,13 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     const PlanHeader &h = p->hdr;
     hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
     if (h.Mp > 0 && h.Kp > 0)
-        hipLaunchKernelGGL(scatter_kernel<0>, dim3(h.Mp), dim3(256), 0, st, A, lda, p->layA, p->cols, p->rowA,
-                           p->c1, h.Kp, p->s, p->sh, A_ue, &p->d_hdr->bound[0]);
+        hipLaunchKernelGGL(scatter_kernel<0>, dim3((h.Mp + kScatterRows - 1) / kScatterRows), dim3(256), 0, st, A,
+                           lda, p->layA, p->cols, p->rowA, p->c1, h.Mp, h.Kp, p->s, p->sh, A_ue,
+                           &p->d_hdr->bound[0]);
     if (h.Np > 0 && h.Kp > 0)
-        hipLaunchKernelGGL(scatter_kernel<1>, dim3(h.Np), dim3(256), 0, st, B, ldb, p->layB, p->cols, p->rowB,
-                           p->c2, h.Kp, p->s, p->sh, B_eu, &p->d_hdr->bound[1]);
+        hipLaunchKernelGGL(scatter_kernel<1>, dim3((h.Np + kScatterRows - 1) / kScatterRows), dim3(256), 0, st, B,
+                           ldb, p->layB, p->cols, p->rowB, p->c2, h.Np, h.Kp, p->s, p->sh, B_eu,
+                           &p->d_hdr->bound[1]);
     IMU_TRY(launch_status());
     IMU_HIP(hipMemcpyAsync(p->hdr.bound, p->d_hdr->bound, sizeof(p->hdr.bound), hipMemcpyDeviceToHost, st));
     IMU_HIP(hipStreamSynchronize(st));

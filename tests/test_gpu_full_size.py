@@ -1,0 +1,96 @@
+"""Full-size parity on the benchmark workloads (2-5; workload 1 is covered element by element in
+test_gpu_parity.py), in the launch configuration bench.py times: caller-provided statistics and OB
+lists from the fused quantize pass, fused GEMM epilogue.
+
+Compared in full: the quantized integers, the unpack plan and both unpacked int8 operands in the
+paper's order (the CPU oracle unpacks the full operands in seconds).  The int64 product is compared
+at sampled positions the oracle computes one by one, and in full through an identity that holds at
+any size: sum_ij C[i,j] = sum_k (sum_i A[i,k]) (sum_j B[j,k])."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_07339_amd import workloads
+
+pytestmark = pytest.mark.gpu
+REL_TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def imu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2403_07339_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("index", [2, 3, 4, 5])
+def test_workload_full_size(imu, index):
+    w = workloads.make(index)
+    s = 1 << (w.b - 1)
+    print(f"workload {index}: {w.name}", flush=True)
+    Aq, sta = oracle.rtn_quantize(w.A.contiguous().numpy(), w.scale_a)
+    Bq, stb = oracle.rtn_quantize(w.B.contiguous().numpy(), w.scale_b)
+    assert sta == 0 and stb == 0
+    A_d, B_d = w.A.to("cuda"), w.B.to("cuda")          # workload 4 keeps its transposed strides
+    Qa, st_a, fa = imu.imunpack_quantize(A_d, w.scale_a, w.b, want_ob_list=w.strategy_a == imu.BOTH)
+    Qb, st_b, fb = imu.imunpack_quantize(B_d, w.scale_b, w.b, want_ob_list=w.strategy_b == imu.BOTH)
+    assert int(fa.item()) == 0 and int(fb.item()) == 0
+    assert np.array_equal(Qa.cpu().numpy(), Aq) and np.array_equal(Qb.cpu().numpy(), Bq)
+    for st, q in ((st_a, Aq), (st_b, Bq)):
+        a = np.abs(q.astype(np.int64))
+        assert np.array_equal(st.rowcnt.cpu().numpy(), (a >= s).sum(1))
+        assert np.array_equal(st.colcnt.cpu().numpy(), (a >= s).sum(0))
+        assert np.array_equal(st.rowmax.cpu().numpy(), a.max(1))
+        assert np.array_equal(st.colmax.cpu().numpy(), a.max(0))
+        if st.ob is not None:
+            cnt = int(st.ob_count.item())
+            assert cnt == int((a >= s).sum()) and cnt <= st.ob.shape[1]
+            ob = st.ob[:, :cnt].cpu().numpy()
+            assert np.array_equal(q[ob[0], ob[1]], ob[2])
+            assert len(np.unique(ob[0].astype(np.int64) * q.shape[1] + ob[1])) == cnt
+
+    hnd = oracle.unpack_pair_handle(Aq, Bq, w.b, w.strategy_a, w.strategy_b)
+    assert hnd.max_abs() <= s - 1
+    plan = imu.imunpack_plan(Qa, Qb, w.b, w.strategy_a, w.strategy_b, st_a, st_b)
+    n_u, d_u, h_u, ng = plan.dims()
+    assert (n_u, d_u, h_u) == (hnd.n_u, hnd.d_u, hnd.h_u)
+    S, pas, paw, pbs, pbw = hnd.meta()
+    ra_s, ra_e, rb_s, rb_e, c_s, c_e = [t.numpy().astype(np.int64) for t in plan.export()]
+    assert np.array_equal(ra_s, pas) and np.array_equal(s ** ra_e.astype(object), paw.astype(object))
+    assert np.array_equal(rb_s, pbs) and np.array_equal(s ** rb_e.astype(object), pbw.astype(object))
+    assert np.array_equal(s ** c_e.astype(object), S.astype(object))
+    assert ng == len(np.unique(S))
+
+    A_ue, B_eu = imu.imunpack_unpack(plan, Qa, Qb)
+    Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
+    oa, ob_ = hnd.operands_i8()
+    assert np.array_equal(Ac.cpu().numpy(), oa)
+    assert np.array_equal(Bc.cpu().numpy(), ob_)
+    del Ac, Bc, oa, ob_
+
+    assert plan.fusable(), "the benchmark workloads are expected to take the fused path"
+    C_int = torch.empty((w.n, w.h), dtype=torch.int64, device="cuda")
+    C_fp = torch.empty((w.n, w.h), dtype=torch.float32, device="cuda")
+    imu.imunpack_gemm(plan, A_ue, B_eu, w.scale_a, w.scale_b, C_int, C_fp, None, fuse=True)
+    rng = np.random.default_rng(index)
+    rows, cols = rng.integers(0, w.n, 4096), rng.integers(0, w.h, 4096)
+    want = oracle.int_gemm_at(Aq, Bq, rows, cols)
+    ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    assert np.array_equal(C_int[ri, ci].cpu().numpy(), want)
+    want_fp = oracle.dequantize(want, w.scale_a, w.scale_b)
+    got_fp = C_fp[ri, ci].cpu().numpy().astype(np.float64)
+    assert (np.abs(got_fp - want_fp) <= REL_TOL * np.abs(want_fp)).all()
+    # the product identity through the oracle's own unpacked operands, at a few positions
+    assert np.array_equal(hnd.product_at(rows[:64], cols[:64]), want[:64])
+    # whole-output identity
+    total = int(C_int.sum().item())
+    col_a = Aq.astype(np.int64).sum(0)
+    col_b = Bq.astype(np.int64).sum(0)
+    assert total == int((col_a.astype(object) * col_b.astype(object)).sum())
+    # every fp32 output is the rounded dequantisation of its own int64 (checked on the device in fp64)
+    ref = C_int.to(torch.float64) * (float(np.float32(w.scale_a)) * float(np.float32(w.scale_b)))
+    err = (C_fp.to(torch.float64) - ref).abs()
+    assert bool((err <= REL_TOL * ref.abs()).all())
+    hnd.close()

@@ -228,3 +228,33 @@ def test_end_to_end_config1(imu):
     assert np.array_equal(C_int.cpu().numpy(), want)
     ref = oracle.dequantize(want, w.scale_a, w.scale_b)
     assert (np.abs(C_fp.cpu().numpy().astype(np.float64) - ref) <= REL_TOL * np.abs(ref)).all()
+
+
+def test_run_to_run_determinism(imu):
+    """All outputs are integers (the fp32 one is a function of an integer), atomics only add
+    integers, so every stage must reproduce itself bit for bit, whatever the thread timing."""
+    g = torch.Generator().manual_seed(3)
+    A = torch.randn(600, 1100, generator=g) * 2
+    B = torch.randn(520, 1100, generator=g)
+    B[torch.randperm(520, generator=g)[:6], :] *= 60          # heavy-hitter rows: one big row batch
+    A[torch.rand(A.shape, generator=g) < 0.004] *= 90         # scattered heavy hitters
+    sa, sb = workloads.rtn_scale(A), workloads.rtn_scale(B)
+    A_d, B_d = dev(A), dev(B)
+    plan = imu.Plan()
+    first = None
+    for _ in range(12):
+        Qa, st_a, _ = imu.imunpack_quantize(A_d, sa, 8, want_ob_list=True)
+        Qb, st_b, _ = imu.imunpack_quantize(B_d, sb, 8, want_ob_list=True)
+        imu.imunpack_plan(Qa, Qb, 8, BOTH, BOTH, st_a, st_b, plan)
+        A_ue, B_eu = imu.imunpack_unpack(plan, Qa, Qb)
+        C_int = torch.empty((600, 520), dtype=torch.int64, device="cuda")
+        ws = None if plan.fusable() else torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        imu.imunpack_gemm(plan, A_ue, B_eu, sa, sb, C_int, None, ws, fuse=True)
+        cur = [Qa, Qb, torch.tensor(plan.dims()), torch.cat(plan.export()), A_ue.clone(), B_eu.clone(), C_int]
+        if first is None:
+            first = [t.clone() for t in cur]
+            want = oracle.int_gemm(oracle_quant(A, sa), oracle_quant(B, sb))
+            assert np.array_equal(C_int.cpu().numpy(), want)
+        else:
+            for a, b in zip(first, cur):
+                assert a.shape == b.shape and torch.equal(a, b)
