@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-int64", action="store_true", help="also write the int64 product (parity output)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB), five times: the "
+                         "known-size kernel that hardware traffic counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -67,6 +70,14 @@ def main():
     from paper_2403_07339_amd import workloads
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": dst.numel() * 4}))
+        return
     w = workloads.make(args.workload)
     A, B = w.A.to("cuda"), w.B.to("cuda")          # strided views keep their strides
     n, d, h = w.n, w.d, w.h

@@ -117,10 +117,11 @@ struct imunpack_plan {
     imu::ColLayout cols;
     int32_t *statsA[4], *statsB[4];   // rowcnt, colcnt, rowmax, colmax actually used
     // greedy scratch
-    int32_t *eR, *eC, *eV;
+    unsigned long long *edges;        // two lists of edge_cap packed edges each
+    int edge_cap;
     int32_t *rcnt, *ccnt, *batch;
     int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
-    int32_t *tmpL, *tmpCur, *tmpP;
+    int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB;
     int ignore_listA, ignore_listB;   // a caller's OB list overflowed: scan the operand ourselves
     int bothA, bothB;                 // slot numbering of the set needs the export-time sort
     // canonical (paper-order) numbering, built lazily by the export / test paths

@@ -29,34 +29,6 @@ constexpr int kPlanWaves = kPlanThreads / 64;
 // ---------------------------------------------------------------------------------------------
 // workgroup-wide helpers (kPlanThreads threads)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int block_excl_scan(int v, int &total, int *lds /* >= 40 ints */) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += t;
-    }
-    if (lane == 63) lds[wave] = incl;
-    __syncthreads();
-    if (wave == 0) {
-        int w = lane < kPlanWaves ? lds[lane] : 0;
-        int wi = w;
-#pragma unroll
-        for (int off = 1; off < kPlanWaves; off <<= 1) {
-            int t = __shfl_up(wi, off, 64);
-            if (lane >= off) wi += t;
-        }
-        if (lane < kPlanWaves) lds[lane] = wi - w;
-        if (lane == kPlanWaves - 1) lds[32] = wi;
-    }
-    __syncthreads();
-    const int res = lds[wave] + incl - v;
-    total = lds[32];
-    __syncthreads();
-    return res;
-}
-
 __device__ __forceinline__ int block_max(int v, int *lds /* >= 40 ints */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -90,32 +62,118 @@ __device__ __forceinline__ void flag_overflow(PlanHeader *hdr, int which, int ne
     atomicMax(&hdr->need[which], need);
 }
 
+// Calls emit(x, rank) for every x in [0, N) with flag(x), rank = base + the number of flagged x' < x;
+// returns the number of flagged items.  Every wave owns one contiguous segment and ranks its items
+// by ballot, so the whole selection costs two workgroup barriers.
+template <class F, class E>
+__device__ __forceinline__ int ordered_select(int N, int base, F flag, E emit, int *lds /* >= 40 ints */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int seg = ((N + kPlanWaves - 1) / kPlanWaves + 63) & ~63;
+    const int lo = wave * seg, hi = min(N, lo + seg);
+    int cnt = 0;
+    for (int x0 = lo; x0 < hi; x0 += 64) {
+        const int x = x0 + lane;
+        const bool f = x < hi && flag(x);
+        cnt += __popcll(__ballot(f));
+    }
+    if (lane == 0) lds[wave] = cnt;
+    __syncthreads();
+    int run = base, total = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+        const int c = lds[w];
+        if (w < wave) run += c;
+        total += c;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int x0 = lo; x0 < hi; x0 += 64) {
+        const int x = x0 + lane;
+        const bool f = x < hi && flag(x);
+        const unsigned long long mask = __ballot(f);
+        if (f) emit(x, run + __popcll(mask & below));
+        run += __popcll(mask);
+    }
+    __syncthreads();
+    return total;
+}
+
+// Calls emit(x, prefix) for every x in [0, N), prefix = base + sum of value(x') over x' < x; returns
+// the sum of all values.
+template <class V, class E>
+__device__ __forceinline__ int ordered_scan(int N, int base, V value, E emit, int *lds /* >= 40 ints */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int seg = ((N + kPlanWaves - 1) / kPlanWaves + 63) & ~63;
+    const int lo = wave * seg, hi = min(N, lo + seg);
+    int sum = 0;
+    for (int x0 = lo; x0 < hi; x0 += 64) {
+        const int x = x0 + lane;
+        if (x < hi) sum += value(x);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) lds[wave] = sum;
+    __syncthreads();
+    int run = base, total = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+        const int c = lds[w];
+        if (w < wave) run += c;
+        total += c;
+    }
+    for (int x0 = lo; x0 < hi; x0 += 64) {
+        const int x = x0 + lane;
+        const int v = x < hi ? value(x) : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        if (x < hi) emit(x, run + incl - v);
+        run += __shfl(incl, 63, 64);
+    }
+    __syncthreads();
+    return total;
+}
+
 // ---------------------------------------------------------------------------------------------
 // header / identity
 // ---------------------------------------------------------------------------------------------
-__global__ void init_header_kernel(PlanHeader *hdr) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
+__device__ __forceinline__ void identity_slot(const SlotSet &set, int x) {
+    set.root[x] = x;
+    set.exp[x] = 0;
+    set.time[x] = kNever;
+    set.child[x] = -1;
+}
+
+// Clears the header and makes the first na / nb / nc slots of three sets unsplit originals (a count
+// of 0 skips a set).  The counts are known to the host, which has sized the sets for them.
+__global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_a, SlotSet b, int nb,
+                             int32_t *count_b, SlotSet c, int nc, int32_t *count_c) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         PlanHeader z;
         memset(&z, 0, sizeof(z));
         *hdr = z;
+        if (na) *count_a = na;
+        if (nb) *count_b = nb;
+        if (nc) *count_c = nc;
     }
+    const int stride = gridDim.x * blockDim.x;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < na; x += stride) identity_slot(a, x);
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nb; x += stride) identity_slot(b, x);
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nc; x += stride) identity_slot(c, x);
 }
 
-// slots 0..N-1 become unsplit originals; N comes from the host or from a header field
-__global__ void identity_slots_kernel(SlotSet set, int n_host, const int32_t *n_dev, int32_t *count_out,
-                                      PlanHeader *hdr, int which) {
+// slots 0..N-1 become unsplit originals, N read from the device
+__global__ void identity_slots_kernel(SlotSet set, const int32_t *n_dev, int32_t *count_out, PlanHeader *hdr,
+                                      int which) {
     if (hdr->overflow) return;
-    const int N = n_dev ? *n_dev : n_host;
+    const int N = *n_dev;
     if (N > set.cap) {
         if (blockIdx.x == 0 && threadIdx.x == 0) flag_overflow(hdr, which, N);
         return;
     }
-    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < N; x += gridDim.x * blockDim.x) {
-        set.root[x] = x;
-        set.exp[x] = 0;
-        set.time[x] = kNever;
-        set.child[x] = -1;
-    }
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < N; x += gridDim.x * blockDim.x) identity_slot(set, x);
     if (count_out && blockIdx.x == 0 && threadIdx.x == 0) *count_out = N;
 }
 
@@ -139,21 +197,16 @@ __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
         const int L = digit_levels(maxabs[via ? via[x] : x], sh);
         tmpL[x] = L;
         tmpCur[x] = x;
-        set.root[x] = x;
-        set.exp[x] = 0;
-        set.time[x] = kNever;
-        set.child[x] = -1;
+        identity_slot(set, x);
         lm = max(lm, L);
     }
     const int lmax = block_max(lm, lds);
     int base = N;
     for (int l = 1; l < lmax; ++l) {
-        for (int x0 = 0; x0 < N; x0 += kPlanThreads) {
-            const int x = x0 + threadIdx.x;
-            const int flag = (x < N && tmpL[x] > l) ? 1 : 0;
-            int total;
-            const int slot = base + block_excl_scan(flag, total, lds);
-            if (flag && slot < set.cap) {
+        base += ordered_select(
+            N, base, [&](int x) { return tmpL[x] > l; },
+            [&](int x, int slot) {
+                if (slot >= set.cap) return;
                 set.root[slot] = x;
                 set.exp[slot] = l;
                 set.time[slot] = kNever;
@@ -163,9 +216,8 @@ __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
                 set.child[prev] = slot;
                 set.time[prev] = 0;  // split (only this axis splits in this phase, any finite time will do)
                 tmpCur[x] = slot;
-            }
-            base += total;
-        }
+            },
+            lds);
     }
     if (threadIdx.x == 0) {
         *count_out = base;
@@ -174,55 +226,43 @@ __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// UnpackBoth (Alg. 4): OB entry lists
-// ---------------------------------------------------------------------------------------------
-// Turns the list of OB entries (row, column k, value) of an operand into the edge list the greedy
-// works on.  For the first operand every entry is one edge.  After UnpackA the matrix B_e repeats
-// column k of B once per column slot that descends from k (Alg. 2 line 6 / Alg. 4 line 13), so each
-// OB entry (j, k) of B becomes one edge per such slot.
-__global__ void expand_edges_kernel(const int32_t *ob, int ob_cap, const int32_t *ob_count, SlotSet c1,
-                                    int32_t *eR, int32_t *eC, int32_t *eV, int cap, int32_t *counter,
-                                    PlanHeader *hdr, int which_list, int which_edges) {
-    if (hdr->overflow) return;
-    const int N = *ob_count;
-    if (N > ob_cap) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) flag_overflow(hdr, which_list, N);
-        return;
-    }
-    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < N; t += gridDim.x * blockDim.x) {
-        const int j = ob[t], k = ob[ob_cap + t], v = ob[2 * ob_cap + t];
-        int len = 0;
-        for (int c = k; c >= 0 && len < 64; c = c1.child[c]) ++len;
-        int pos = atomicAdd(counter, len);
-        int left = len;
-        for (int c = k; c >= 0 && left > 0; c = c1.child[c], ++pos, --left) {
-            if (pos < cap) {
-                eR[pos] = j;
-                eC[pos] = c;
-                eV[pos] = v;
-            }
-        }
-    }
-    (void)which_edges;
-}
-
-// ---------------------------------------------------------------------------------------------
 // UnpackBoth (Alg. 4): the greedy
 // ---------------------------------------------------------------------------------------------
 struct GreedyArgs {
     SlotSet rows, cols;
-    int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
-    int32_t *eR, *eC, *eV;         // current row slot, column slot and remaining value of each edge
-    const int32_t *ecount;
+    const int32_t *cols_init;      // second operand: number of column slots to start from (columns after
+                                   // unpacking A), made unsplit originals here; nullptr for the first
+    const int32_t *chain_child;    // second operand: child links of the column slots of A's unpacking
+    const int32_t *chain_root;     // second operand: original column of each of those slots
+    const int32_t *rowcnt, *colcnt, *rowmax;  // the operand's heavy-hitter statistics
+    const int32_t *ob;             // OB entries of the operand: [3][ob_cap] rows | columns | values
+    int ob_cap;
+    const int32_t *ob_count;
+    int which_list;
+    unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
-    int32_t *batch, *bcnt, *rank_of;
+    int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
+    int32_t *batch, *bcnt;
     int batch_cap;
-    int32_t *nr_io, *nc_io;        // slot counts (header fields), read at entry, written at exit
+    int32_t *nr_io, *nc_io;        // slot counts (header fields)
+    int32_t *ecount_out;
     PlanHeader *hdr;
     int whichR, whichC, whichE;
     int s, sh;
-    int use_lds;
 };
+
+// An edge of the greedy: an OB entry's current row slot, column slot and the number of base-s digits
+// it still has there (>= 2 while it is OB).  Only that number matters: a split moves floor(v / s) on.
+constexpr int kEdgeSlotBits = 29;
+__device__ __forceinline__ unsigned long long pack_edge(int row, int col, int levels) {
+    return (unsigned long long)(unsigned)row | ((unsigned long long)(unsigned)col << kEdgeSlotBits) |
+           ((unsigned long long)(unsigned)levels << (2 * kEdgeSlotBits));
+}
+__device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int &col, int &levels) {
+    row = (int)(e & ((1u << kEdgeSlotBits) - 1));
+    col = (int)((e >> kEdgeSlotBits) & ((1u << kEdgeSlotBits) - 1));
+    levels = (int)(e >> (2 * kEdgeSlotBits));
+}
 
 // The sequential algorithm splits, at every step, the row or column with the top OB count (rows win
 // ties, then the lowest index).  Splitting a row changes no other row's count and only lowers column
@@ -233,71 +273,159 @@ struct GreedyArgs {
 //   - if no entry has three or more digits, one batch takes all rows with count >= top column count
 //     (or all columns with count > top row count);
 //   - otherwise a batch takes only the slots that share the top count.
-// A batch is applied by one pass over the edge list.  The order inside a batch only decides the
-// numbers of the appended slots; it is recorded as a sort key (batch, count descending, split slot)
-// and the appended slots are renumbered on the host when the plan is exported.
+// The starting counts are the operand's scan statistics.  After UnpackA the matrix B_e repeats column
+// k of B once per column slot that descends from k (Alg. 2 line 6 / Alg. 4 line 13): such a slot
+// starts with the count of column k, and every OB entry (j, k) adds one to row j per extra slot.
+// A batch is one pass over the live entries: an entry in a split slot keeps digit 0 there and moves
+// floor(v / s) to the new slot (Alg. 4 lines 7-9 / 11-14); if that is In-Bound the entry is finished:
+// it leaves the count of the crossing slot and the list.  The first pass reads the operand's OB list
+// itself; its survivors and those of every later pass are written, compacted, to a list of packed
+// edges.  The order inside a batch only decides the numbers of the appended slots; it is recorded as
+// a sort key (batch, count descending, split slot) and the appended slots are renumbered on the host
+// when the plan is exported.
+template <bool LDS>
 __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g) {
-    extern __shared__ int32_t lds_counts[];
+    extern __shared__ __attribute__((aligned(16))) int32_t lds_counts[];
     __shared__ int lds[40];
-    if (g.hdr->overflow) return;
-    const int E = *g.ecount;
-    if (E > g.ecap) {
-        if (threadIdx.x == 0) flag_overflow(g.hdr, g.whichE, E);
+    __shared__ int s_count;
+    PlanHeader *hdr = g.hdr;
+    if (hdr->overflow) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int nr = *g.nr_io, nc;
+    if (g.cols_init) {
+        nc = *g.cols_init;
+        if (nc > g.cols.cap) {
+            if (threadIdx.x == 0) flag_overflow(hdr, g.whichC, nc);
+            return;
+        }
+        for (int x = threadIdx.x; x < nc; x += kPlanThreads) identity_slot(g.cols, x);
+    } else {
+        nc = *g.nc_io;
+    }
+    const int nob = *g.ob_count;
+    if (nob > g.ob_cap) {
+        if (threadIdx.x == 0) flag_overflow(hdr, g.which_list, nob);
         return;
     }
-    int32_t *rc = g.use_lds ? lds_counts : g.rcnt;
-    int32_t *cc = g.use_lds ? lds_counts + g.rows.cap : g.ccnt;
-    for (int x = threadIdx.x; x < g.rows.cap; x += kPlanThreads) rc[x] = 0;
-    for (int x = threadIdx.x; x < g.cols.cap; x += kPlanThreads) cc[x] = 0;
-    __syncthreads();
+    const int rpad = (g.rows.cap + 7) & ~3, cpad = (g.cols.cap + 7) & ~3;  // int4 reads may run past the last slot
+    int32_t *rc = LDS ? lds_counts : g.rcnt;
+    int32_t *cc = LDS ? lds_counts + rpad : g.ccnt;
+    // ---- starting counts
     int deep = 0;
     const int s2 = g.s * g.s;
-    for (int e = threadIdx.x; e < E; e += kPlanThreads) {
-        const int v = g.eV[e];
-        atomicAdd(&rc[g.eR[e]], 1);
-        atomicAdd(&cc[g.eC[e]], 1);
-        if (v >= s2 || v <= -s2) deep = 1;
+    for (int x = threadIdx.x; x < rpad; x += kPlanThreads) {
+        rc[x] = x < nr ? g.rowcnt[x] : 0;
+        if (x < nr && g.rowmax[x] >= s2) deep = 1;
+    }
+    for (int x = threadIdx.x; x < cpad; x += kPlanThreads)
+        cc[x] = x < nc ? g.colcnt[g.chain_root ? g.chain_root[x] : x] : 0;
+    if (threadIdx.x == 0) s_count = 0;
+    __syncthreads();
+    // ---- the extra edges of repeated columns (second operand only)
+    unsigned long long *list0 = g.edges, *list1 = g.edges + g.ecap;
+    if (g.chain_child) {
+        for (int t = threadIdx.x; t < nob; t += kPlanThreads) {
+            const int k = g.ob[g.ob_cap + t];
+            int c = g.chain_child[k];
+            if (c < 0) continue;
+            const int j = g.ob[t], v = g.ob[2 * (size_t)g.ob_cap + t];
+            const int L = digit_levels(v < 0 ? -v : v, g.sh);
+            for (int hop = 0; c >= 0 && hop < 64; c = g.chain_child[c], ++hop) {
+                const int pos = atomicAdd(&s_count, 1);
+                if (pos < g.ecap) list0[pos] = pack_edge(j, c, L);
+                atomicAdd(&rc[j], 1);
+            }
+        }
     }
     deep = block_max(deep, lds);
-    int nr = *g.nr_io, nc = *g.nc_io;
-    const long long max_batches = 32ll * (long long)E + 64;  // every batch retires >= one digit of one entry
+    const int extras = s_count;
+    long long Etotal = (long long)nob + extras;
+    if (threadIdx.x == 0) *g.ecount_out = (int)min(Etotal, 2147483647ll);
+    if (Etotal > g.ecap) {
+        if (threadIdx.x == 0) flag_overflow(hdr, g.whichE, (int)min(Etotal, 1ll << 30));
+        return;
+    }
+    int E = extras, cur = 0;
+    const long long max_batches = 32ll * Etotal + 64;  // every batch retires >= one digit of one entry
     for (long long bid = 0;; ++bid) {
         if (bid > max_batches || bid >= 65535) {
-            if (threadIdx.x == 0) atomicMin(&g.hdr->err, bid >= 65535 ? IMUNPACK_ERANGE : IMUNPACK_EHIP);
+            if (threadIdx.x == 0) atomicMin(&hdr->err, bid >= 65535 ? IMUNPACK_ERANGE : IMUNPACK_EHIP);
             return;
         }
         int m0 = 0, m1 = 0;
-        for (int x = threadIdx.x; x < nr; x += kPlanThreads) m0 = max(m0, load_agent(&rc[x]));
-        for (int x = threadIdx.x; x < nc; x += kPlanThreads) m1 = max(m1, load_agent(&cc[x]));
+        for (int x = threadIdx.x * 4; x < nr; x += kPlanThreads * 4) {
+            const int4 c = *reinterpret_cast<const int4 *>(&rc[x]);
+            m0 = max(max(m0, max(c.x, c.y)), max(c.z, c.w));
+        }
+        for (int x = threadIdx.x * 4; x < nc; x += kPlanThreads * 4) {
+            const int4 c = *reinterpret_cast<const int4 *>(&cc[x]);
+            m1 = max(max(m1, max(c.x, c.y)), max(c.z, c.w));
+        }
         const int c0 = block_max(m0, lds), c1 = block_max(m1, lds);
-        if (c0 == 0 && c1 == 0) break;
+        if (c0 <= 0 && c1 <= 0) break;
         const bool isrow = c0 >= c1;  // rows win ties (Alg. 4: "else if c0 >= c1")
         int32_t *cnt = isrow ? rc : cc, *other = isrow ? cc : rc;
-        int32_t *epos = isrow ? g.eR : g.eC, *ecross = isrow ? g.eC : g.eR;
         const SlotSet &mine = isrow ? g.rows : g.cols;
         const int N = isrow ? nr : nc;
-        // slots with lo <= count <= hi are split in this batch
+        // slots with lo <= count <= hi are split in this batch, numbered in index order: every wave
+        // owns one contiguous segment, four slots per lane
         const int hi = isrow ? c0 : c1;
         const int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
-        int nb = 0;
-        for (int x0 = 0; x0 < N; x0 += kPlanThreads) {
-            const int x = x0 + threadIdx.x;
-            const int c = x < N ? load_agent(&cnt[x]) : 0;
-            const int flag = (c >= lo && c <= hi) ? 1 : 0;
-            int total;
-            const int rank = nb + block_excl_scan(flag, total, lds);
-            if (flag && rank < g.batch_cap) {
-                g.batch[rank] = x;
-                g.bcnt[rank] = c;
-                g.rank_of[x] = rank;
-            }
-            nb += total;
+        const int seg = ((N + kPlanWaves - 1) / kPlanWaves + 255) & ~255;
+        const int wlo = wave * seg, whi = min(N, wlo + seg);
+        int found = 0;
+        for (int x0 = wlo; x0 < whi; x0 += 256) {
+            const int x = x0 + lane * 4;  // counts past slot N-1 (within the padding) are 0 < lo
+            const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
+            found += __popcll(__ballot(c.x >= lo && c.x <= hi)) + __popcll(__ballot(c.y >= lo && c.y <= hi)) +
+                     __popcll(__ballot(c.z >= lo && c.z <= hi)) + __popcll(__ballot(c.w >= lo && c.w <= hi));
         }
-        if (N + nb > mine.cap || nb > g.batch_cap) {
-            if (threadIdx.x == 0) flag_overflow(g.hdr, isrow ? g.whichR : g.whichC, 2 * (N + nb));
+        if (lane == 0) lds[wave] = found;
+        __syncthreads();
+        int run = 0, nb = 0;
+#pragma unroll
+        for (int w = 0; w < kPlanWaves; ++w) {
+            const int c = lds[w];
+            if (w < wave) run += c;
+            nb += c;
+        }
+        for (int x0 = wlo; x0 < whi; x0 += 256) {
+            const int x = x0 + lane * 4;
+            const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
+            const int cv[4] = {c.x, c.y, c.z, c.w};
+            bool f[4];
+            unsigned long long m[4];
+            int before = 0, all = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                f[i] = cv[i] >= lo && cv[i] <= hi;
+                m[i] = __ballot(f[i]);
+                before += __popcll(m[i] & below);
+                all += __popcll(m[i]);
+            }
+            int rank = run + before;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (f[i]) {
+                    if (rank < g.batch_cap) {
+                        g.batch[rank] = x + i;
+                        g.bcnt[rank] = cv[i];
+                    }
+                    ++rank;
+                }
+            }
+            run += all;
+        }
+        if (threadIdx.x == 0) s_count = 0;
+        __syncthreads();
+        if (N + nb > mine.cap || nb > g.batch_cap || N + nb >= (1 << kEdgeSlotBits)) {
+            if (threadIdx.x == 0) {
+                if (N + nb >= (1 << kEdgeSlotBits)) atomicMin(&hdr->err, IMUNPACK_ERANGE);
+                else flag_overflow(hdr, isrow ? g.whichR : g.whichC, 2 * (N + nb));
+            }
             return;
         }
-        __syncthreads();  // the batch list of the last chunk is written after the scan's barrier
         for (int r = threadIdx.x; r < nb; r += kPlanThreads) {
             const int X = g.batch[r], newX = N + r;
             mine.time[X] = (uint32_t)bid;
@@ -308,32 +436,89 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             mine.child[newX] = -1;
             mine.key[newX] = ((unsigned long long)bid << 48) |
                              ((unsigned long long)(0xFFFFFF - min(g.bcnt[r], 0xFFFFFF)) << 24) | (unsigned)X;
+            cnt[X] = -(r + 1);  // marks the slot as split in this batch and names its new slot
         }
         __syncthreads();
-        // one pass over the edges: an edge in a split slot keeps digit 0 there and moves floor(v / s)
-        // to the new slot (Alg. 4 lines 7-9 / 11-14); if that is In-Bound the edge is finished and
-        // leaves the count of the crossing slot
-        for (int e = threadIdx.x; e < E; e += kPlanThreads) {
-            const int v = g.eV[e];
-            const int av = v < 0 ? -v : v;
-            if (av < g.s) continue;
-            const int X = epos[e];
-            if (X >= N) continue;  // created in this batch
-            const int c = load_agent(&cnt[X]);
-            if (c < lo || c > hi) continue;
-            const int av2 = av >> g.sh;
-            g.eV[e] = v < 0 ? -av2 : av2;
-            if (av2 >= g.s) {
-                const int newX = N + g.rank_of[X];
-                epos[e] = newX;
-                atomicAdd(&cnt[newX], 1);
-            } else {
-                atomicSub(&other[ecross[e]], 1);
+        // ---- the pass
+        // one entry: returns the packed survivor, 0 if the entry is finished (or absent: levels 0)
+        auto visit = [&](int row, int col, int levels) -> unsigned long long {
+            if (levels < 2) return 0ull;
+            const int c = cnt[isrow ? row : col];
+            if (c < 0 && -c - 1 < nb) {
+                if (levels > 2) {
+                    const int newX = N + (-c - 1);
+                    if (isrow) row = newX; else col = newX;
+                    --levels;
+                    atomicAdd(&cnt[newX], 1);
+                } else {
+                    atomicSub(&other[isrow ? col : row], 1);
+                    return 0ull;
+                }
+            }
+            return pack_edge(row, col, levels);
+        };
+        constexpr int U = 4;
+        unsigned long long *dst = bid == 0 ? list1 : (cur ? list0 : list1);
+        auto emit = [&](const unsigned long long (&out)[U]) {
+            unsigned long long m[U];
+            int before = 0, all = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                m[u] = __ballot(out[u] != 0ull);
+                before += __popcll(m[u] & below);
+                all += __popcll(m[u]);
+            }
+            int base = 0;
+            if (lane == 0 && all) base = atomicAdd(&s_count, all);
+            base = __shfl(base, 0, 64) + before;
+            // order inside the wave's block: lane-major, then u (any order is fine)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (out[u] != 0ull) dst[base++] = out[u];
+        };
+        if (bid == 0) {
+            for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
+                int j[U], k[U], v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
+                    j[u] = k[u] = v[u] = 0;
+                    if (t < nob) {
+                        j[u] = g.ob[t];
+                        k[u] = g.ob[g.ob_cap + t];
+                        v[u] = g.ob[2 * (size_t)g.ob_cap + t];
+                    }
+                }
+                unsigned long long out[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    out[u] = visit(j[u], k[u], v[u] == 0 ? 0 : digit_levels(v[u] < 0 ? -v[u] : v[u], g.sh));
+                emit(out);
+            }
+        }
+        {
+            const unsigned long long *src = (bid == 0 || cur == 0) ? list0 : list1;
+            for (int e0 = 0; e0 < E; e0 += kPlanThreads * U) {
+                unsigned long long ed[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int idx = e0 + u * kPlanThreads + (int)threadIdx.x;
+                    ed[u] = idx < E ? src[idx] : 0ull;
+                }
+                unsigned long long out[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    int row, col, levels;
+                    unpack_edge(ed[u], row, col, levels);
+                    out[u] = visit(row, col, levels);
+                }
+                emit(out);
             }
         }
         __syncthreads();
-        for (int r = threadIdx.x; r < nb; r += kPlanThreads)
-            __hip_atomic_store(&cnt[g.batch[r]], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        E = s_count;
+        cur = bid == 0 ? 1 : (cur ^ 1);
+        for (int r = threadIdx.x; r < nb; r += kPlanThreads) cnt[g.batch[r]] = 0;
         __syncthreads();
         if (isrow) nr += nb; else nc += nb;
     }
@@ -350,32 +535,19 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
 // row straddles a GEMM tile, so that Pi can be applied inside one tile's epilogue.  Source row i
 // with unpadded start P_i goes to tile floor(P_i / (kTile - (Lmax-1))): a closed form, and the
 // rows of a tile never exceed kTile.
-__global__ __launch_bounds__(kPlanThreads) void rows_layout_kernel(SlotSet rows, int nbase,
-                                                                   const int32_t *count_dev, RowLayout lay,
-                                                                   int cap_phys, int cap_tiles,
-                                                                   int32_t *tmpL, int32_t *tmpP,
-                                                                   PlanHeader *hdr, int operand) {
-    __shared__ int lds[40];
-    __shared__ int s_ntiles;
-    if (hdr->overflow) return;
+__device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count_dev, const RowLayout &lay,
+                            int cap_phys, int cap_tiles, int32_t *tmpP, PlanHeader *hdr, int operand, int *lds) {
+    int32_t *nlev = lay.src_nlev;
     int lm = 1;
     for (int i = threadIdx.x; i < nbase; i += kPlanThreads) {
         int L = 1;
         for (int R = rows.child[i]; R >= 0 && L < 64; R = rows.child[R]) ++L;
-        tmpL[i] = L;
+        nlev[i] = L;
         lm = max(lm, L);
     }
     const int lmax = block_max(lm, lds);
-    int base = 0;
-    for (int x0 = 0; x0 < nbase; x0 += kPlanThreads) {
-        const int x = x0 + threadIdx.x;
-        const int v = x < nbase ? tmpL[x] : 0;
-        int total;
-        const int ex = block_excl_scan(v, total, lds);
-        if (x < nbase) tmpP[x] = base + ex;
-        base += total;
-    }
-    __syncthreads();
+    const int base = ordered_scan(
+        nbase, 0, [&](int x) { return nlev[x]; }, [&](int x, int pre) { tmpP[x] = pre; }, lds);
     const int Tp = kTile - (lmax - 1);
     const int ntiles = nbase > 0 ? tmpP[nbase - 1] / Tp + 1 : 0;
     const int Mp = ntiles * kTile;
@@ -413,9 +585,9 @@ __global__ __launch_bounds__(kPlanThreads) void rows_layout_kernel(SlotSet rows,
         const int i0 = lay.tile_src0[t];
         const int pst = t * kTile + (tmpP[i] - tmpP[i0]);
         lay.src_pstart[i] = pst;
-        lay.src_nlev[i] = tmpL[i];
+        const int L = nlev[i];
         int l = 0;
-        for (int R = i; R >= 0 && l < tmpL[i]; R = rows.child[R], ++l) {
+        for (int R = i; R >= 0 && l < L; R = rows.child[R], ++l) {
             lay.prow_slot[pst + l] = R;
             lay.prow_src[pst + l] = i;
             lay.prow_exp[pst + l] = l;
@@ -429,22 +601,36 @@ __global__ __launch_bounds__(kPlanThreads) void rows_layout_kernel(SlotSet rows,
 }
 
 // Columns: grouped by the exponent of the diagonal entry of S (Alg. 3 runs one GEMM per distinct
-// entry), highest exponent first, canonical order inside a group, each group zero-padded to a
-// multiple of kKPad.
-__global__ __launch_bounds__(kPlanThreads) void cols_layout_kernel(SlotSet c1, SlotSet c2, ColLayout cols,
-                                                                   int cap_phys, int s, int sh,
-                                                                   PlanHeader *hdr) {
-    __shared__ int lds[40];
+// entry), highest exponent first, each group zero-padded to a multiple of kKPad.  Inside a group the
+// columns are ordered by the original column they copy, so that a run of physical columns reads a
+// run of source columns.  The slots that descend from original column k are the column slots r of
+// A's unpacking with root k (a chain) and, for each r, the chain of slots of the second unpacking
+// that starts at r.
+template <class Fn>
+__device__ __forceinline__ void for_slots_of_column(const SlotSet &c1, const SlotSet &c2, int k, Fn fn) {
+    int hops = 0;
+    for (int r = k; r >= 0 && hops < 4096; r = c1.child[r]) {
+        const int ea = c1.exp[r];
+        for (int c = r; c >= 0 && hops < 4096; c = c2.child[c], ++hops) fn(r, ea, c, c2.exp[c]);
+    }
+}
+
+__device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayout &cols, int d, int cap_phys,
+                            int s, int sh, PlanHeader *hdr, int *lds) {
     __shared__ int hist[kMaxGroups];
-    __shared__ int s_ng, s_kp;
-    if (hdr->overflow) return;
-    const int D = hdr->d_u;
+    __shared__ int s_ng, s_kp, s_total;
     for (int e = threadIdx.x; e < kMaxGroups; e += kPlanThreads) hist[e] = 0;
+    if (threadIdx.x == 0) s_total = 0;
     __syncthreads();
-    for (int c = threadIdx.x; c < D; c += kPlanThreads) {
-        const int e = c1.exp[c2.root[c]] + c2.exp[c];
-        if (e < kMaxGroups) atomicAdd(&hist[e], 1);
-        else atomicMin(&hdr->err, IMUNPACK_ERANGE);
+    for (int k = threadIdx.x; k < d; k += kPlanThreads) {
+        int mine = 0;
+        for_slots_of_column(c1, c2, k, [&](int, int ea, int, int eb) {
+            const int e = ea + eb;
+            ++mine;
+            if (e < kMaxGroups) atomicAdd(&hist[e], 1);
+            else atomicMin(&hdr->err, IMUNPACK_ERANGE);
+        });
+        atomicAdd(&s_total, mine);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -463,7 +649,8 @@ __global__ __launch_bounds__(kPlanThreads) void cols_layout_kernel(SlotSet c1, S
         hdr->Kp = k0;
         s_ng = ng;
         s_kp = k0;
-        if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
+        if (s_total != hdr->d_u) atomicMin(&hdr->err, IMUNPACK_EHIP);  // a slot no column chain reaches
+        if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * hdr->d_u);
     }
     __syncthreads();
     const int ng = s_ng, Kp = s_kp;
@@ -479,30 +666,40 @@ __global__ __launch_bounds__(kPlanThreads) void cols_layout_kernel(SlotSet c1, S
     __syncthreads();
     for (int g = 0; g < ng; ++g) {
         const int ge = hdr->grp_exp[g];
-        int base = hdr->grp_k0[g];
-        for (int x0 = 0; x0 < D; x0 += kPlanThreads) {
-            const int c = x0 + threadIdx.x;
-            int flag = 0, root = 0, ea = 0, eb = 0;
-            if (c < D) {
-                root = c2.root[c];
-                ea = c1.exp[root];
-                eb = c2.exp[c];
-                flag = (ea + eb == ge) ? 1 : 0;
-            }
-            int total;
-            const int q = base + block_excl_scan(flag, total, lds);
-            if (flag) {
-                cols.pcol_slot[q] = c;
-                cols.col_phys[c] = q;
-                cols.colA_k[q] = c1.root[root];
-                cols.colA_c1[q] = root;
-                cols.colA_e[q] = ea;
-                cols.colB_e[q] = eb;
-                cols.col_sexp[q] = ge;
-            }
-            base += total;
-        }
+        ordered_scan(
+            d, hdr->grp_k0[g],
+            [&](int k) {
+                int m = 0;
+                for_slots_of_column(c1, c2, k, [&](int, int ea, int, int eb) { m += (ea + eb == ge) ? 1 : 0; });
+                return m;
+            },
+            [&](int k, int q) {
+                for_slots_of_column(c1, c2, k, [&](int r, int ea, int c, int eb) {
+                    if (ea + eb != ge) return;
+                    cols.pcol_slot[q] = c;
+                    cols.col_phys[c] = q;
+                    cols.colA_k[q] = k;
+                    cols.colA_c1[q] = r;
+                    cols.colA_e[q] = ea;
+                    cols.colB_e[q] = eb;
+                    cols.col_sexp[q] = ge;
+                    ++q;
+                });
+            },
+            lds);
     }
+}
+
+// One workgroup per layout: rows of A, rows of B, columns.
+__global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
+    SlotSet rowA, int n, RowLayout layA, int cap_physA, int32_t *tmpPA, SlotSet rowB, int h, RowLayout layB,
+    int cap_physB, int32_t *tmpPB, SlotSet c1, SlotSet c2, ColLayout cols, int d, int cap_physC, int s, int sh,
+    PlanHeader *hdr) {
+    __shared__ int lds[40];
+    if (hdr->overflow) return;
+    if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, lds);
+    else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, lds);
+    else cols_layout(c1, c2, cols, d, cap_physC, s, sh, hdr, lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -582,14 +779,16 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
     const int maxslots = std::max(std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), std::max(p->cap[CAP_C1], p->cap[CAP_C2]));
     p->tmpL = cv.take<int32_t>(maxslots);
     p->tmpCur = cv.take<int32_t>(maxslots);
-    p->tmpP = cv.take<int32_t>(maxslots);
+    p->tmpPA = cv.take<int32_t>(n + 1);
+    p->tmpPB = cv.take<int32_t>(h + 1);
     if (p->sA == IMUNPACK_BOTH || p->sB == IMUNPACK_BOTH) {
         const int ecap = std::max(p->sA == IMUNPACK_BOTH ? p->cap[CAP_EDGEA] : 0,
                                   p->sB == IMUNPACK_BOTH ? p->cap[CAP_EDGEB] : 0);
-        p->eR = cv.take<int32_t>(ecap); p->eC = cv.take<int32_t>(ecap); p->eV = cv.take<int32_t>(ecap);
+        p->edges = cv.take<unsigned long long>((size_t)2 * ecap);
+        p->edge_cap = ecap;
         const int rcap = std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), ccap = std::max(p->cap[CAP_C1], p->cap[CAP_C2]);
-        p->rcnt = cv.take<int32_t>(rcap);
-        p->ccnt = cv.take<int32_t>(ccap);
+        p->rcnt = cv.take<int32_t>(rcap + 8);
+        p->ccnt = cv.take<int32_t>(ccap + 8);
         p->batch = cv.take<int32_t>(std::max(rcap, ccap));
         p->ob = cv.take<int32_t>((size_t)3 * p->cap[CAP_OB]);
     }
@@ -612,34 +811,38 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     const bool first = phase == 1;
     SlotSet &rows = first ? p->rowA : p->rowB;
     SlotSet &cols = first ? p->c1 : p->c2;
-    int32_t *ecount = first ? &hdr->edgesA : &hdr->edgesB;
-    const int ecap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];
-    hipLaunchKernelGGL(expand_edges_kernel, dim3(grid_for(ob_cap, 256, 1024)), dim3(256), 0, st, ob, ob_cap,
-                       ob_count, p->c1, p->eR, p->eC, p->eV, ecap, ecount, hdr, which_list,
-                       first ? (int)CAP_EDGEA : (int)CAP_EDGEB);
     GreedyArgs g;
     g.rows = rows; g.cols = cols;
+    g.cols_init = first ? nullptr : &hdr->d1;
+    g.chain_child = first ? nullptr : p->c1.child;
+    g.chain_root = first ? nullptr : p->c1.root;
+    int32_t **stats = first ? p->statsA : p->statsB;
+    g.rowcnt = stats[0]; g.colcnt = stats[1]; g.rowmax = stats[2];
+    g.ob = ob; g.ob_cap = ob_cap; g.ob_count = ob_count; g.which_list = which_list;
+    g.edges = p->edges;
+    g.ecap = std::min(p->cap[first ? CAP_EDGEA : CAP_EDGEB], p->edge_cap);
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
-    g.eR = p->eR; g.eC = p->eC; g.eV = p->eV;
-    g.ecount = ecount; g.ecap = ecap;
-    g.batch = p->batch; g.bcnt = p->tmpL; g.rank_of = p->tmpCur;
+    g.batch = p->batch; g.bcnt = p->tmpL;
     g.batch_cap = std::max(std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), std::max(p->cap[CAP_C1], p->cap[CAP_C2]));
     g.nr_io = first ? &hdr->n_u : &hdr->h_u;
     g.nc_io = first ? &hdr->d1 : &hdr->d_u;
+    g.ecount_out = first ? &hdr->edgesA : &hdr->edgesB;
     g.hdr = hdr;
     g.whichR = first ? CAP_ROWA : CAP_ROWB;
     g.whichC = first ? CAP_C1 : CAP_C2;
     g.whichE = first ? CAP_EDGEA : CAP_EDGEB;
     g.s = p->s; g.sh = p->sh;
-    const size_t lds_bytes = ((size_t)rows.cap + (size_t)cols.cap) * sizeof(int32_t);
-    g.use_lds = lds_bytes <= (size_t)kGreedyLdsMax;
+    const size_t lds_bytes = ((size_t)((rows.cap + 7) & ~3) + (size_t)((cols.cap + 7) & ~3)) * sizeof(int32_t);
     static int opted_in = 0;
     if (!opted_in) {
-        IMU_HIP(hipFuncSetAttribute((const void *)greedy_both_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kGreedyLdsMax));
+        IMU_HIP(hipFuncSetAttribute((const void *)greedy_both_kernel<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGreedyLdsMax));
         opted_in = 1;
     }
-    hipLaunchKernelGGL(greedy_both_kernel, dim3(1), dim3(kPlanThreads), g.use_lds ? lds_bytes : 0, st, g);
+    if (lds_bytes <= (size_t)kGreedyLdsMax)
+        hipLaunchKernelGGL(greedy_both_kernel<true>, dim3(1), dim3(kPlanThreads), lds_bytes, st, g);
+    else
+        hipLaunchKernelGGL(greedy_both_kernel<false>, dim3(1), dim3(kPlanThreads), 0, st, g);
     return launch_status();
 }
 
@@ -648,7 +851,13 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                         bool own_statsB, hipStream_t st) {
     PlanHeader *hdr = p->d_hdr;
     const int n = (int)p->n, d = (int)p->d, h = (int)p->h;
-    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr);
+    // header cleared; the sets that start as unsplit originals with a size the host knows
+    const int idA = p->sA != IMUNPACK_ROW ? n : 0, idC1 = p->sA != IMUNPACK_COL ? d : 0,
+              idB = p->sB != IMUNPACK_ROW ? h : 0;
+    if (idA > p->rowA.cap || idC1 > p->c1.cap || idB > p->rowB.cap) return IMUNPACK_EINVAL;
+    hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, 1)), 256, 64)),
+                       dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, idB,
+                       &hdr->h_u);
     // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
     // this call's own scan produces one.  The two operands are planned one after the other, so one
     // own buffer serves both.
@@ -669,19 +878,11 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowA, p->statsA[2],
                            (const int32_t *)nullptr, n, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
                            &hdr->n_u, hdr, (int)CAP_ROWA);
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(d, 256, 64)), dim3(256), 0, st, p->c1, d,
-                           (const int32_t *)nullptr, &hdr->d1, hdr, (int)CAP_C1);
     } else if (p->sA == IMUNPACK_COL) {
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(n, 256, 64)), dim3(256), 0, st, p->rowA, n,
-                           (const int32_t *)nullptr, &hdr->n_u, hdr, (int)CAP_ROWA);
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c1, p->statsA[3],
                            (const int32_t *)nullptr, d, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
                            &hdr->d1, hdr, (int)CAP_C1);
     } else {
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(n, 256, 64)), dim3(256), 0, st, p->rowA, n,
-                           (const int32_t *)nullptr, &hdr->n_u, hdr, (int)CAP_ROWA);
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(d, 256, 64)), dim3(256), 0, st, p->c1, d,
-                           (const int32_t *)nullptr, &hdr->d1, hdr, (int)CAP_C1);
         if (callerA) IMU_TRY(run_greedy(p, 1, stA->ob, (int)stA->ob_cap, stA->ob_count, CAP_LISTA, st));
         else IMU_TRY(run_greedy(p, 1, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
@@ -692,29 +893,19 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                            (const int32_t *)nullptr, h, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
                            &hdr->h_u, hdr, (int)CAP_ROWB);
         hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(p->cap[CAP_C2], 256, 64)), dim3(256), 0, st,
-                           p->c2, 0, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2);
+                           p->c2, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2);
     } else if (p->sB == IMUNPACK_COL) {
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(h, 256, 64)), dim3(256), 0, st, p->rowB, h,
-                           (const int32_t *)nullptr, &hdr->h_u, hdr, (int)CAP_ROWB);
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c2, p->statsB[3],
                            (const int32_t *)p->c1.root, 0, (const int32_t *)&hdr->d1, p->sh, p->tmpL,
                            p->tmpCur, &hdr->d_u, hdr, (int)CAP_C2);
     } else {
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(h, 256, 64)), dim3(256), 0, st, p->rowB, h,
-                           (const int32_t *)nullptr, &hdr->h_u, hdr, (int)CAP_ROWB);
-        hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(p->cap[CAP_C2], 256, 64)), dim3(256), 0, st,
-                           p->c2, 0, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2);
         if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st));
         else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
     // ---- physical layouts
-    hipLaunchKernelGGL(rows_layout_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowA, n, &hdr->n_u, p->layA,
-                       phys_cap_rows(p->cap[CAP_ROWA]), phys_cap_rows(p->cap[CAP_ROWA]) / kTile + 2, p->tmpL,
-                       p->tmpP, hdr, 0);
-    hipLaunchKernelGGL(rows_layout_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowB, h, &hdr->h_u, p->layB,
-                       phys_cap_rows(p->cap[CAP_ROWB]), phys_cap_rows(p->cap[CAP_ROWB]) / kTile + 2, p->tmpL,
-                       p->tmpP, hdr, 1);
-    hipLaunchKernelGGL(cols_layout_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c1, p->c2, p->cols,
+    hipLaunchKernelGGL(layouts_kernel, dim3(3), dim3(kPlanThreads), 0, st, p->rowA, n, p->layA,
+                       phys_cap_rows(p->cap[CAP_ROWA]), p->tmpPA, p->rowB, h, p->layB,
+                       phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
                        phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, hdr);
     return launch_status();
 }
