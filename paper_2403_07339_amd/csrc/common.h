@@ -119,7 +119,7 @@ struct imunpack_plan {
     // greedy scratch
     unsigned long long *edges;        // two lists of edge_cap packed edges each
     int edge_cap;
-    int32_t *rcnt, *ccnt, *batch;
+    int32_t *rcnt, *ccnt;
     int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
     int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB;
     int ignore_listA, ignore_listB;   // a caller's OB list overflowed: scan the operand ourselves

@@ -151,9 +151,8 @@ __device__ __forceinline__ void identity_slot(const SlotSet &set, int x) {
 __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_a, SlotSet b, int nb,
                              int32_t *count_b, SlotSet c, int nc, int32_t *count_c) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        PlanHeader z;
-        memset(&z, 0, sizeof(z));
-        *hdr = z;
+        static_assert(sizeof(PlanHeader) % sizeof(int32_t) == 0, "header is cleared word by word");
+        for (size_t i = 0; i < sizeof(PlanHeader) / sizeof(int32_t); ++i) reinterpret_cast<int32_t *>(hdr)[i] = 0;
         if (na) *count_a = na;
         if (nb) *count_b = nb;
         if (nc) *count_c = nc;
@@ -242,8 +241,6 @@ struct GreedyArgs {
     unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
     int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
-    int32_t *batch, *bcnt;
-    int batch_cap;
     int32_t *nr_io, *nc_io;        // slot counts (header fields)
     int32_t *ecount_out;
     PlanHeader *hdr;
@@ -286,12 +283,15 @@ __device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int 
 template <bool LDS>
 __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g) {
     extern __shared__ __attribute__((aligned(16))) int32_t lds_counts[];
+    __shared__ int s_max[2 * kPlanWaves];
+    __shared__ int s_found[kPlanWaves];
     __shared__ int lds[40];
     __shared__ int s_count;
     PlanHeader *hdr = g.hdr;
     if (hdr->overflow) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned long long below = (1ull << lane) - 1ull;
+    const int32_t *__restrict__ ob = g.ob;
     int nr = *g.nr_io, nc;
     if (g.cols_init) {
         nc = *g.cols_init;
@@ -311,6 +311,14 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     const int rpad = (g.rows.cap + 7) & ~3, cpad = (g.cols.cap + 7) & ~3;  // int4 reads may run past the last slot
     int32_t *rc = LDS ? lds_counts : g.rcnt;
     int32_t *cc = LDS ? lds_counts + rpad : g.ccnt;
+    // number of base-s digits of a magnitude: ceil(bits / sh), the division as a multiplication
+    const unsigned inv_sh = (65536u + (unsigned)g.sh - 1u) / (unsigned)g.sh;
+    auto levels_of = [&](int v) -> int {
+        if (v == 0) return 0;
+        const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
+        const unsigned bits = 32u - (unsigned)__clz(av);
+        return (int)(((bits + (unsigned)g.sh - 1u) * inv_sh) >> 16);
+    };
     // ---- starting counts
     int deep = 0;
     const int s2 = g.s * g.s;
@@ -323,24 +331,35 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     if (threadIdx.x == 0) s_count = 0;
     __syncthreads();
     // ---- the extra edges of repeated columns (second operand only)
-    unsigned long long *list0 = g.edges, *list1 = g.edges + g.ecap;
+    unsigned long long *list0 = g.edges, *list1 = g.edges + ((g.ecap + 1) & ~1);  // both 16-byte aligned
+    constexpr int U = 4;
     if (g.chain_child) {
-        for (int t = threadIdx.x; t < nob; t += kPlanThreads) {
-            const int k = g.ob[g.ob_cap + t];
-            int c = g.chain_child[k];
-            if (c < 0) continue;
-            const int j = g.ob[t], v = g.ob[2 * (size_t)g.ob_cap + t];
-            const int L = digit_levels(v < 0 ? -v : v, g.sh);
-            for (int hop = 0; c >= 0 && hop < 64; c = g.chain_child[c], ++hop) {
-                const int pos = atomicAdd(&s_count, 1);
-                if (pos < g.ecap) list0[pos] = pack_edge(j, c, L);
-                atomicAdd(&rc[j], 1);
+        for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
+            int ch[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
+                ch[u] = t < nob ? ob[g.ob_cap + t] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) ch[u] = ch[u] >= 0 ? g.chain_child[ch[u]] : -1;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (ch[u] < 0) continue;
+                const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
+                const int j = ob[t], L = levels_of(ob[2 * (size_t)g.ob_cap + t]);
+                int c = ch[u];
+                for (int hop = 0; c >= 0 && hop < 64; c = g.chain_child[c], ++hop) {
+                    const int pos = atomicAdd(&s_count, 1);
+                    if (pos < g.ecap) list0[pos] = pack_edge(j, c, L);
+                    atomicAdd(&rc[j], 1);
+                }
             }
         }
     }
     deep = block_max(deep, lds);
     const int extras = s_count;
-    long long Etotal = (long long)nob + extras;
+    const long long Etotal = (long long)nob + extras;
     if (threadIdx.x == 0) *g.ecount_out = (int)min(Etotal, 2147483647ll);
     if (Etotal > g.ecap) {
         if (threadIdx.x == 0) flag_overflow(hdr, g.whichE, (int)min(Etotal, 1ll << 30));
@@ -353,26 +372,57 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             if (threadIdx.x == 0) atomicMin(&hdr->err, bid >= 65535 ? IMUNPACK_ERANGE : IMUNPACK_EHIP);
             return;
         }
+        // Every wave owns one contiguous segment of the row slots and one of the column slots, four
+        // slots per lane.  (1) top counts; the marks the previous batch left in split slots (negative
+        // values) are cleared on the way -- a split slot never holds an OB entry again.
+        const int segR = ((nr + kPlanWaves - 1) / kPlanWaves + 255) & ~255;
+        const int segC = ((nc + kPlanWaves - 1) / kPlanWaves + 255) & ~255;
         int m0 = 0, m1 = 0;
-        for (int x = threadIdx.x * 4; x < nr; x += kPlanThreads * 4) {
-            const int4 c = *reinterpret_cast<const int4 *>(&rc[x]);
+        for (int x0 = wave * segR; x0 < min(nr, (wave + 1) * segR); x0 += 256) {
+            const int x = x0 + lane * 4;
+            if (x >= nr) continue;
+            int4 c = *reinterpret_cast<const int4 *>(&rc[x]);
+            if ((c.x | c.y | c.z | c.w) < 0) {
+                c = make_int4(max(c.x, 0), max(c.y, 0), max(c.z, 0), max(c.w, 0));
+                *reinterpret_cast<int4 *>(&rc[x]) = c;
+            }
             m0 = max(max(m0, max(c.x, c.y)), max(c.z, c.w));
         }
-        for (int x = threadIdx.x * 4; x < nc; x += kPlanThreads * 4) {
-            const int4 c = *reinterpret_cast<const int4 *>(&cc[x]);
+        for (int x0 = wave * segC; x0 < min(nc, (wave + 1) * segC); x0 += 256) {
+            const int x = x0 + lane * 4;
+            if (x >= nc) continue;
+            int4 c = *reinterpret_cast<const int4 *>(&cc[x]);
+            if ((c.x | c.y | c.z | c.w) < 0) {
+                c = make_int4(max(c.x, 0), max(c.y, 0), max(c.z, 0), max(c.w, 0));
+                *reinterpret_cast<int4 *>(&cc[x]) = c;
+            }
             m1 = max(max(m1, max(c.x, c.y)), max(c.z, c.w));
         }
-        const int c0 = block_max(m0, lds), c1 = block_max(m1, lds);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            m0 = max(m0, __shfl_xor(m0, off, 64));
+            m1 = max(m1, __shfl_xor(m1, off, 64));
+        }
+        if (lane == 0) {
+            s_max[wave] = m0;
+            s_max[kPlanWaves + wave] = m1;
+        }
+        __syncthreads();
+        int c0 = 0, c1 = 0;
+#pragma unroll
+        for (int w = 0; w < kPlanWaves; ++w) {
+            c0 = max(c0, s_max[w]);
+            c1 = max(c1, s_max[kPlanWaves + w]);
+        }
         if (c0 <= 0 && c1 <= 0) break;
         const bool isrow = c0 >= c1;  // rows win ties (Alg. 4: "else if c0 >= c1")
         int32_t *cnt = isrow ? rc : cc, *other = isrow ? cc : rc;
         const SlotSet &mine = isrow ? g.rows : g.cols;
         const int N = isrow ? nr : nc;
-        // slots with lo <= count <= hi are split in this batch, numbered in index order: every wave
-        // owns one contiguous segment, four slots per lane
+        // (2) slots with lo <= count <= hi are split in this batch, numbered in index order
         const int hi = isrow ? c0 : c1;
         const int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
-        const int seg = ((N + kPlanWaves - 1) / kPlanWaves + 255) & ~255;
+        const int seg = isrow ? segR : segC;
         const int wlo = wave * seg, whi = min(N, wlo + seg);
         int found = 0;
         for (int x0 = wlo; x0 < whi; x0 += 256) {
@@ -381,145 +431,160 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             found += __popcll(__ballot(c.x >= lo && c.x <= hi)) + __popcll(__ballot(c.y >= lo && c.y <= hi)) +
                      __popcll(__ballot(c.z >= lo && c.z <= hi)) + __popcll(__ballot(c.w >= lo && c.w <= hi));
         }
-        if (lane == 0) lds[wave] = found;
+        if (lane == 0) s_found[wave] = found;
         __syncthreads();
         int run = 0, nb = 0;
 #pragma unroll
         for (int w = 0; w < kPlanWaves; ++w) {
-            const int c = lds[w];
+            const int c = s_found[w];
             if (w < wave) run += c;
             nb += c;
         }
-        for (int x0 = wlo; x0 < whi; x0 += 256) {
-            const int x = x0 + lane * 4;
-            const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
-            const int cv[4] = {c.x, c.y, c.z, c.w};
-            bool f[4];
-            unsigned long long m[4];
-            int before = 0, all = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                f[i] = cv[i] >= lo && cv[i] <= hi;
-                m[i] = __ballot(f[i]);
-                before += __popcll(m[i] & below);
-                all += __popcll(m[i]);
-            }
-            int rank = run + before;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (f[i]) {
-                    if (rank < g.batch_cap) {
-                        g.batch[rank] = x + i;
-                        g.bcnt[rank] = cv[i];
-                    }
-                    ++rank;
-                }
-            }
-            run += all;
-        }
-        if (threadIdx.x == 0) s_count = 0;
-        __syncthreads();
-        if (N + nb > mine.cap || nb > g.batch_cap || N + nb >= (1 << kEdgeSlotBits)) {
+        if (N + nb > mine.cap || N + nb >= (1 << kEdgeSlotBits)) {
             if (threadIdx.x == 0) {
                 if (N + nb >= (1 << kEdgeSlotBits)) atomicMin(&hdr->err, IMUNPACK_ERANGE);
                 else flag_overflow(hdr, isrow ? g.whichR : g.whichC, 2 * (N + nb));
             }
             return;
         }
-        for (int r = threadIdx.x; r < nb; r += kPlanThreads) {
-            const int X = g.batch[r], newX = N + r;
-            mine.time[X] = (uint32_t)bid;
-            mine.child[X] = newX;
-            mine.root[newX] = mine.root[X];
-            mine.exp[newX] = mine.exp[X] + 1;
-            mine.time[newX] = kNever;
-            mine.child[newX] = -1;
-            mine.key[newX] = ((unsigned long long)bid << 48) |
-                             ((unsigned long long)(0xFFFFFF - min(g.bcnt[r], 0xFFFFFF)) << 24) | (unsigned)X;
-            cnt[X] = -(r + 1);  // marks the slot as split in this batch and names its new slot
-        }
-        __syncthreads();
-        // ---- the pass
-        // one entry: returns the packed survivor, 0 if the entry is finished (or absent: levels 0)
-        auto visit = [&](int row, int col, int levels) -> unsigned long long {
-            if (levels < 2) return 0ull;
-            const int c = cnt[isrow ? row : col];
-            if (c < 0 && -c - 1 < nb) {
-                if (levels > 2) {
-                    const int newX = N + (-c - 1);
-                    if (isrow) row = newX; else col = newX;
-                    --levels;
-                    atomicAdd(&cnt[newX], 1);
-                } else {
-                    atomicSub(&other[isrow ? col : row], 1);
-                    return 0ull;
-                }
+        // (3) the new slots; a split slot's count is replaced by a mark that names its new slot (only
+        // the lane that owns a slot reads its count in steps 1-3)
+        for (int x0 = wlo; x0 < whi; x0 += 256) {
+            const int x = x0 + lane * 4;
+            const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
+            const int cv[4] = {c.x, c.y, c.z, c.w};
+            bool f[4];
+            int before = 0, all = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                f[i] = cv[i] >= lo && cv[i] <= hi;
+                const unsigned long long m = __ballot(f[i]);
+                before += __popcll(m & below);
+                all += __popcll(m);
             }
-            return pack_edge(row, col, levels);
-        };
-        constexpr int U = 4;
+            int rank = run + before;
+            int root[4], ex[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                root[i] = f[i] ? mine.root[x + i] : 0;
+                ex[i] = f[i] ? mine.exp[x + i] : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (!f[i]) continue;
+                const int X = x + i, newX = N + rank;
+                mine.time[X] = (uint32_t)bid;
+                mine.child[X] = newX;
+                mine.root[newX] = root[i];
+                mine.exp[newX] = ex[i] + 1;
+                mine.time[newX] = kNever;
+                mine.child[newX] = -1;
+                mine.key[newX] = ((unsigned long long)bid << 48) |
+                                 ((unsigned long long)(0xFFFFFF - min(cv[i], 0xFFFFFF)) << 24) | (unsigned)X;
+                cnt[X] = -(rank + 1);
+                ++rank;
+            }
+            run += all;
+        }
+        if (threadIdx.x == 0) s_count = 0;
+        __syncthreads();
+        // (4) the pass.  The survivors of U entries per lane are appended with one counter update per wave.
         unsigned long long *dst = bid == 0 ? list1 : (cur ? list0 : list1);
-        auto emit = [&](const unsigned long long (&out)[U]) {
-            unsigned long long m[U];
+        auto process = [&](auto &row, auto &col, auto &lev) {
+            constexpr int U = sizeof(lev) / sizeof(int);
+            int c[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) c[u] = lev[u] >= 2 ? cnt[isrow ? row[u] : col[u]] : 0;  // marks do not change during a pass
+            unsigned long long out[U];
             int before = 0, all = 0;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                m[u] = __ballot(out[u] != 0ull);
-                before += __popcll(m[u] & below);
-                all += __popcll(m[u]);
+                out[u] = 0ull;
+                if (lev[u] >= 2) {
+                    if (c[u] < 0 && -c[u] - 1 < nb) {
+                        if (lev[u] > 2) {
+                            const int newX = N + (-c[u] - 1);
+                            if (isrow) row[u] = newX; else col[u] = newX;
+                            atomicAdd(&cnt[newX], 1);
+                            out[u] = pack_edge(row[u], col[u], lev[u] - 1);
+                        } else {
+                            atomicSub(&other[isrow ? col[u] : row[u]], 1);
+                        }
+                    } else {
+                        out[u] = pack_edge(row[u], col[u], lev[u]);
+                    }
+                }
+                const unsigned long long m = __ballot(out[u] != 0ull);
+                before += __popcll(m & below);
+                all += __popcll(m);
             }
+            if (!all) return;
             int base = 0;
-            if (lane == 0 && all) base = atomicAdd(&s_count, all);
+            if (lane == 0) base = atomicAdd(&s_count, all);
             base = __shfl(base, 0, 64) + before;
-            // order inside the wave's block: lane-major, then u (any order is fine)
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (out[u] != 0ull) dst[base++] = out[u];
         };
-        if (bid == 0) {
-            for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
-                int j[U], k[U], v[U];
+        if (bid == 0) {  // the operand's OB list itself
+            int j[U], k[U], v[U];
+            auto fetch = [&](int t0, int (&fj)[U], int (&fk)[U], int (&fv)[U]) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
-                    j[u] = k[u] = v[u] = 0;
+                    fj[u] = fk[u] = fv[u] = 0;
                     if (t < nob) {
-                        j[u] = g.ob[t];
-                        k[u] = g.ob[g.ob_cap + t];
-                        v[u] = g.ob[2 * (size_t)g.ob_cap + t];
+                        fj[u] = ob[t];
+                        fk[u] = ob[g.ob_cap + t];
+                        fv[u] = ob[2 * (size_t)g.ob_cap + t];
                     }
                 }
-                unsigned long long out[U];
+            };
+            fetch(0, j, k, v);
+            for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
+                int j2[U], k2[U], v2[U];
+                fetch(t0 + kPlanThreads * U, j2, k2, v2);  // past the end: all absent
+                int lev[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    out[u] = visit(j[u], k[u], v[u] == 0 ? 0 : digit_levels(v[u] < 0 ? -v[u] : v[u], g.sh));
-                emit(out);
+                for (int u = 0; u < U; ++u) lev[u] = levels_of(v[u]);
+                process(j, k, lev);
+#pragma unroll
+                for (int u = 0; u < U; ++u) { j[u] = j2[u]; k[u] = k2[u]; v[u] = v2[u]; }
             }
         }
-        {
-            const unsigned long long *src = (bid == 0 || cur == 0) ? list0 : list1;
-            for (int e0 = 0; e0 < E; e0 += kPlanThreads * U) {
-                unsigned long long ed[U];
+        {  // the list of packed edges, two per load
+            constexpr int U2 = 8;
+            const unsigned long long *__restrict__ src = (bid == 0 || cur == 0) ? list0 : list1;
+            unsigned long long ed[U2];
+            auto fetch = [&](int e0, unsigned long long (&fe)[U2]) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int idx = e0 + u * kPlanThreads + (int)threadIdx.x;
-                    ed[u] = idx < E ? src[idx] : 0ull;
+                for (int u = 0; u < U2; u += 2) {
+                    const int idx = e0 + (u * kPlanThreads + (int)threadIdx.x * 2);
+                    if (idx + 1 < E) {
+                        const ulonglong2 t = *reinterpret_cast<const ulonglong2 *>(src + idx);
+                        fe[u] = t.x;
+                        fe[u + 1] = t.y;
+                    } else {
+                        fe[u] = idx < E ? src[idx] : 0ull;
+                        fe[u + 1] = 0ull;
+                    }
                 }
-                unsigned long long out[U];
+            };
+            fetch(0, ed);
+            for (int e0 = 0; e0 < E; e0 += kPlanThreads * U2) {
+                unsigned long long ed2[U2];
+                fetch(e0 + kPlanThreads * U2, ed2);
+                int row[U2], col[U2], lev[U2];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    int row, col, levels;
-                    unpack_edge(ed[u], row, col, levels);
-                    out[u] = visit(row, col, levels);
-                }
-                emit(out);
+                for (int u = 0; u < U2; ++u) unpack_edge(ed[u], row[u], col[u], lev[u]);
+                process(row, col, lev);
+#pragma unroll
+                for (int u = 0; u < U2; ++u) ed[u] = ed2[u];
             }
         }
         __syncthreads();
         E = s_count;
         cur = bid == 0 ? 1 : (cur ^ 1);
-        for (int r = threadIdx.x; r < nb; r += kPlanThreads) cnt[g.batch[r]] = 0;
-        __syncthreads();
         if (isrow) nr += nb; else nc += nb;
     }
     if (threadIdx.x == 0) {
@@ -784,12 +849,11 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
     if (p->sA == IMUNPACK_BOTH || p->sB == IMUNPACK_BOTH) {
         const int ecap = std::max(p->sA == IMUNPACK_BOTH ? p->cap[CAP_EDGEA] : 0,
                                   p->sB == IMUNPACK_BOTH ? p->cap[CAP_EDGEB] : 0);
-        p->edges = cv.take<unsigned long long>((size_t)2 * ecap);
+        p->edges = cv.take<unsigned long long>((size_t)2 * ecap + 2);
         p->edge_cap = ecap;
         const int rcap = std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), ccap = std::max(p->cap[CAP_C1], p->cap[CAP_C2]);
         p->rcnt = cv.take<int32_t>(rcap + 8);
         p->ccnt = cv.take<int32_t>(ccap + 8);
-        p->batch = cv.take<int32_t>(std::max(rcap, ccap));
         p->ob = cv.take<int32_t>((size_t)3 * p->cap[CAP_OB]);
     }
     return cv.off + 256;
@@ -822,8 +886,6 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.edges = p->edges;
     g.ecap = std::min(p->cap[first ? CAP_EDGEA : CAP_EDGEB], p->edge_cap);
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
-    g.batch = p->batch; g.bcnt = p->tmpL;
-    g.batch_cap = std::max(std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), std::max(p->cap[CAP_C1], p->cap[CAP_C2]));
     g.nr_io = first ? &hdr->n_u : &hdr->h_u;
     g.nc_io = first ? &hdr->d1 : &hdr->d_u;
     g.ecount_out = first ? &hdr->edgesA : &hdr->edgesB;
