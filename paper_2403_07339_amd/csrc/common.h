@@ -39,6 +39,7 @@ static inline int launch_status() {
 constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both operands)
 constexpr int kKPad = 128;       // every exponent group is padded to a multiple of this many columns
 constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
+constexpr int kScatterWin = 1024;  // source columns per window of the scatter kernel
 constexpr uint32_t kNever = 0xFFFFFFFFu;  // split time of a row/column that is never split
 
 // One set of growing row (or column) slots: what Pi (or S) needs per slot, plus the split
@@ -63,6 +64,7 @@ struct PlanHeader {
     int32_t grp_k0[kMaxGroups];      // first physical column
     int32_t grp_len[kMaxGroups];     // real columns (without padding)
     int32_t edgesA, edgesB, obcount; // OB entry lists built for UnpackBoth
+    int32_t nobA, nobB;              // OB entries of A / B kept for the scatter (UnpackBoth operands)
     int32_t overflow;                // bit set: which capacity was too small
     int32_t need[10];                // size that would have been needed, per capacity
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
@@ -93,6 +95,10 @@ struct ColLayout {
     int32_t *colA_e;      // [Kp] its digit level along the columns of A
     int32_t *colB_e;      // [Kp] digit level along the columns of B_e
     int32_t *col_sexp;    // [Kp] exponent of the diagonal entry of S
+    int4 *unit_desc;      // [Kp/16] per 16-column unit: lowest and highest source column (-1: all padding),
+                          // bit 0 of z: 16 consecutive source columns from a multiple of 4, bit 1: one digit
+                          // level pair for all its columns; w: level along A | along B << 8 | exponent of S << 16
+    int32_t *win_unit;    // [groups][windows+1] first 16-column unit of a group at or past a source window
 };
 
 }  // namespace imu
@@ -120,8 +126,10 @@ struct imunpack_plan {
     unsigned long long *edges;        // two lists of edge_cap packed edges each
     int edge_cap;
     int32_t *rcnt, *ccnt;
+    int32_t *obcopyA, *obcopyB;       // OB entries of an UnpackBoth operand, kept for the scatter: [3][cap[CAP_EDGEx]]
+    unsigned long long *rowsumA, *rowsumB;  // weighted L1 norm per physical row, written by the scatter
     int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
-    int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB;
+    int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB, *tmpE, *tmpK, *tmpR, *tmpOff;
     int ignore_listA, ignore_listB;   // a caller's OB list overflowed: scan the operand ourselves
     int bothA, bothB;                 // slot numbering of the set needs the export-time sort
     // canonical (paper-order) numbering, built lazily by the export / test paths

@@ -240,6 +240,8 @@ struct GreedyArgs {
     int which_list;
     unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
+    int32_t *ob_keep;              // [3][ecap]: the OB entries, kept for the scatter
+    int32_t *ob_keep_count;
     int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
     int32_t *nr_io, *nc_io;        // slot counts (header fields)
     int32_t *ecount_out;
@@ -360,7 +362,10 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     deep = block_max(deep, lds);
     const int extras = s_count;
     const long long Etotal = (long long)nob + extras;
-    if (threadIdx.x == 0) *g.ecount_out = (int)min(Etotal, 2147483647ll);
+    if (threadIdx.x == 0) {
+        *g.ecount_out = (int)min(Etotal, 2147483647ll);
+        *g.ob_keep_count = nob;
+    }
     if (Etotal > g.ecap) {
         if (threadIdx.x == 0) flag_overflow(hdr, g.whichE, (int)min(Etotal, 1ll << 30));
         return;
@@ -546,7 +551,15 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                 fetch(t0 + kPlanThreads * U, j2, k2, v2);  // past the end: all absent
                 int lev[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) lev[u] = levels_of(v[u]);
+                for (int u = 0; u < U; ++u) {
+                    lev[u] = levels_of(v[u]);
+                    const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
+                    if (t < nob) {
+                        g.ob_keep[t] = j[u];
+                        g.ob_keep[g.ecap + t] = k[u];
+                        g.ob_keep[2 * (size_t)g.ecap + t] = v[u];
+                    }
+                }
                 process(j, k, lev);
 #pragma unroll
                 for (int u = 0; u < U; ++u) { j[u] = j2[u]; k[u] = k2[u]; v[u] = v2[u]; }
@@ -667,35 +680,35 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
 
 // Columns: grouped by the exponent of the diagonal entry of S (Alg. 3 runs one GEMM per distinct
 // entry), highest exponent first, each group zero-padded to a multiple of kKPad.  Inside a group the
-// columns are ordered by the original column they copy, so that a run of physical columns reads a
-// run of source columns.  The slots that descend from original column k are the column slots r of
-// A's unpacking with root k (a chain) and, for each r, the chain of slots of the second unpacking
-// that starts at r.
-template <class Fn>
-__device__ __forceinline__ void for_slots_of_column(const SlotSet &c1, const SlotSet &c2, int k, Fn fn) {
-    int hops = 0;
-    for (int r = k; r >= 0 && hops < 4096; r = c1.child[r]) {
-        const int ea = c1.exp[r];
-        for (int c = r; c >= 0 && hops < 4096; c = c2.child[c], ++hops) fn(r, ea, c, c2.exp[c]);
-    }
-}
-
+// columns are ordered by the original column k they copy (ties: by the digit level along A's
+// unpacking), so that a run of physical columns reads a run of source columns.  A column slot c of
+// the second unpacking descends from slot r = c2.root[c] of the first, which descends from original
+// column k = c1.root[r]; its exponent is c1.exp[r] + c2.exp[c].
+// Also written: for every group and every window of kScatterWin source columns, the first 16-column
+// unit whose first column copies a source column at or past the window's start (the scatter kernel
+// walks the source in such windows).
 __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayout &cols, int d, int cap_phys,
-                            int s, int sh, PlanHeader *hdr, int *lds) {
+                            int s, int sh, int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff,
+                            PlanHeader *hdr, int *lds) {
     __shared__ int hist[kMaxGroups];
-    __shared__ int s_ng, s_kp, s_total;
+    __shared__ int s_ng, s_kp, s_bad;
+    const int D = hdr->d_u;
     for (int e = threadIdx.x; e < kMaxGroups; e += kPlanThreads) hist[e] = 0;
-    if (threadIdx.x == 0) s_total = 0;
+    if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
-    for (int k = threadIdx.x; k < d; k += kPlanThreads) {
-        int mine = 0;
-        for_slots_of_column(c1, c2, k, [&](int, int ea, int, int eb) {
-            const int e = ea + eb;
-            ++mine;
-            if (e < kMaxGroups) atomicAdd(&hist[e], 1);
-            else atomicMin(&hdr->err, IMUNPACK_ERANGE);
-        });
-        atomicAdd(&s_total, mine);
+    for (int c = threadIdx.x; c < D; c += kPlanThreads) {
+        const int r = c2.root[c], eb = c2.exp[c];
+        const int ea = c1.exp[r], k = c1.root[r];
+        const int e = ea + eb;
+        tmpE[c] = e | (ea << 8) | (eb << 16);
+        tmpK[c] = k;
+        tmpR[c] = r;
+        if (e < kMaxGroups && ea < 256 && eb < 256) {
+            atomicAdd(&hist[e], 1);
+        } else {
+            atomicMin(&hdr->err, IMUNPACK_ERANGE);
+            s_bad = 1;
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -714,12 +727,11 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         hdr->Kp = k0;
         s_ng = ng;
         s_kp = k0;
-        if (s_total != hdr->d_u) atomicMin(&hdr->err, IMUNPACK_EHIP);  // a slot no column chain reaches
-        if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * hdr->d_u);
+        if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
     }
     __syncthreads();
     const int ng = s_ng, Kp = s_kp;
-    if (Kp > cap_phys) return;
+    if (Kp > cap_phys || s_bad) return;
     for (int q = threadIdx.x; q < Kp; q += kPlanThreads) {
         cols.pcol_slot[q] = -1;
         cols.colA_k[q] = -1;
@@ -728,30 +740,95 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         cols.colB_e[q] = 0;
         cols.col_sexp[q] = 0;
     }
-    __syncthreads();
     for (int g = 0; g < ng; ++g) {
-        const int ge = hdr->grp_exp[g];
+        const int ge = hdr->grp_exp[g], q0 = hdr->grp_k0[g];
+        for (int k = threadIdx.x; k < d; k += kPlanThreads) tmpOff[k] = 0;
+        __syncthreads();
+        for (int c = threadIdx.x; c < D; c += kPlanThreads)
+            if ((tmpE[c] & 0xFF) == ge) atomicAdd(&tmpOff[tmpK[c]], 1);
+        __syncthreads();
         ordered_scan(
-            d, hdr->grp_k0[g],
-            [&](int k) {
-                int m = 0;
-                for_slots_of_column(c1, c2, k, [&](int, int ea, int, int eb) { m += (ea + eb == ge) ? 1 : 0; });
-                return m;
-            },
-            [&](int k, int q) {
-                for_slots_of_column(c1, c2, k, [&](int r, int ea, int c, int eb) {
-                    if (ea + eb != ge) return;
-                    cols.pcol_slot[q] = c;
-                    cols.col_phys[c] = q;
-                    cols.colA_k[q] = k;
-                    cols.colA_c1[q] = r;
-                    cols.colA_e[q] = ea;
-                    cols.colB_e[q] = eb;
-                    cols.col_sexp[q] = ge;
-                    ++q;
-                });
-            },
-            lds);
+            d, q0, [&](int k) { return tmpOff[k]; }, [&](int k, int pre) { tmpOff[k] = pre; }, lds);
+        for (int c = threadIdx.x; c < D; c += kPlanThreads) {
+            const int pe = tmpE[c];
+            if ((pe & 0xFF) != ge) continue;
+            const int k = tmpK[c];
+            const int q = atomicAdd(&tmpOff[k], 1);
+            cols.pcol_slot[q] = c;
+            cols.colA_k[q] = k;
+            cols.colA_c1[q] = tmpR[c];
+            cols.colA_e[q] = (pe >> 8) & 0xFF;
+            cols.colB_e[q] = (pe >> 16) & 0xFF;
+            cols.col_sexp[q] = ge;
+        }
+        __syncthreads();
+        // columns of one group that copy the same source column: order them by their level along A
+        for (int k = threadIdx.x; k < d; k += kPlanThreads) {
+            const int end = tmpOff[k], beg = k ? tmpOff[k - 1] : q0;
+            for (int i = beg + 1; i < end; ++i) {
+                const int slot = cols.pcol_slot[i], c1s = cols.colA_c1[i], ea = cols.colA_e[i], eb = cols.colB_e[i];
+                int j = i - 1;
+                while (j >= beg && cols.colA_e[j] > ea) {
+                    cols.pcol_slot[j + 1] = cols.pcol_slot[j];
+                    cols.colA_c1[j + 1] = cols.colA_c1[j];
+                    cols.colA_e[j + 1] = cols.colA_e[j];
+                    cols.colB_e[j + 1] = cols.colB_e[j];
+                    --j;
+                }
+                cols.pcol_slot[j + 1] = slot;
+                cols.colA_c1[j + 1] = c1s;
+                cols.colA_e[j + 1] = ea;
+                cols.colB_e[j + 1] = eb;
+            }
+        }
+        __syncthreads();
+    }
+    for (int q = threadIdx.x; q < Kp; q += kPlanThreads) {
+        const int c = cols.pcol_slot[q];
+        if (c >= 0) cols.col_phys[c] = q;
+    }
+    __syncthreads();
+    // per 16-column unit: what the scatter kernel needs to pick its path without the per-column arrays
+    for (int u = threadIdx.x; u < Kp / 16; u += kPlanThreads) {
+        const int q0 = 16 * u;
+        const int k0 = cols.colA_k[q0], ea0 = cols.colA_e[q0], eb0 = cols.colB_e[q0];
+        int kmin = 0x7fffffff, kmax = -1, sexp = 0;
+        bool run = k0 >= 0 && (k0 % 4) == 0, uniform = true;
+        for (int j = 0; j < 16; ++j) {
+            const int k = cols.colA_k[q0 + j];
+            run = run && k == k0 + j;
+            if (k >= 0) {
+                kmin = min(kmin, k);
+                kmax = max(kmax, k);
+                sexp = cols.col_sexp[q0 + j];
+                uniform = uniform && cols.colA_e[q0 + j] == ea0 && cols.colB_e[q0 + j] == eb0;
+            }
+        }
+        int4 ud;
+        ud.x = kmax < 0 ? -1 : kmin;
+        ud.y = kmax;
+        ud.z = (run ? 1 : 0) | (uniform ? 2 : 0);
+        ud.w = (ea0 & 0xFF) | ((eb0 & 0xFF) << 8) | ((sexp & 0xFF) << 16);
+        cols.unit_desc[u] = ud;
+    }
+    // window table
+    const int nwin = (d + kScatterWin - 1) / kScatterWin;
+    for (int t = threadIdx.x; t < ng * (nwin + 1); t += kPlanThreads) {
+        const int g = t / (nwin + 1), w = t % (nwin + 1);
+        const int u0 = hdr->grp_k0[g] / 16;
+        const int u1 = (g + 1 < ng ? hdr->grp_k0[g + 1] : Kp) / 16;
+        int lo = u0, hi = u1;
+        if (w < nwin) {
+            const int want = w * kScatterWin;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                const int kk = cols.colA_k[16 * mid];
+                if (kk < 0 || kk >= want) hi = mid; else lo = mid + 1;  // padding sorts last
+            }
+        } else {
+            lo = u1;
+        }
+        cols.win_unit[g * (nwin + 1) + w] = lo;
     }
 }
 
@@ -759,12 +836,15 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
 __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     SlotSet rowA, int n, RowLayout layA, int cap_physA, int32_t *tmpPA, SlotSet rowB, int h, RowLayout layB,
     int cap_physB, int32_t *tmpPB, SlotSet c1, SlotSet c2, ColLayout cols, int d, int cap_physC, int s, int sh,
-    PlanHeader *hdr) {
+    int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr) {
     __shared__ int lds[40];
     if (hdr->overflow) return;
     if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, lds);
     else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, lds);
-    else cols_layout(c1, c2, cols, d, cap_physC, s, sh, hdr, lds);
+    else {
+        cols_layout(c1, c2, cols, d, cap_physC, s, sh, tmpE, tmpK, tmpR, tmpOff, hdr, lds);
+        if (threadIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -829,7 +909,15 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->cols.colA_e = cv.take<int32_t>(kc);
         p->cols.colB_e = cv.take<int32_t>(kc);
         p->cols.col_sexp = cv.take<int32_t>(kc);
+        p->cols.unit_desc = cv.take<int4>(kc / 16 + 1);
+        p->cols.win_unit = cv.take<int32_t>((size_t)kMaxGroups * ((d + kScatterWin - 1) / kScatterWin + 1));
+        p->tmpE = cv.take<int32_t>(p->cap[CAP_C2]);
+        p->tmpK = cv.take<int32_t>(p->cap[CAP_C2]);
+        p->tmpR = cv.take<int32_t>(p->cap[CAP_C2]);
+        p->tmpOff = cv.take<int32_t>(d + 1);
     }
+    p->rowsumA = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWA]));
+    p->rowsumB = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWB]));
     p->canon_rowphysA = cv.take<int32_t>(p->cap[CAP_ROWA]);
     p->canon_rowphysB = cv.take<int32_t>(p->cap[CAP_ROWB]);
     p->canon_colphys = cv.take<int32_t>(p->cap[CAP_C2]);
@@ -850,6 +938,8 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         const int ecap = std::max(p->sA == IMUNPACK_BOTH ? p->cap[CAP_EDGEA] : 0,
                                   p->sB == IMUNPACK_BOTH ? p->cap[CAP_EDGEB] : 0);
         p->edges = cv.take<unsigned long long>((size_t)2 * ecap + 2);
+        p->obcopyA = cv.take<int32_t>(p->sA == IMUNPACK_BOTH ? (size_t)3 * p->cap[CAP_EDGEA] : 0);
+        p->obcopyB = cv.take<int32_t>(p->sB == IMUNPACK_BOTH ? (size_t)3 * p->cap[CAP_EDGEB] : 0);
         p->edge_cap = ecap;
         const int rcap = std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), ccap = std::max(p->cap[CAP_C1], p->cap[CAP_C2]);
         p->rcnt = cv.take<int32_t>(rcap + 8);
@@ -886,6 +976,8 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.edges = p->edges;
     g.ecap = std::min(p->cap[first ? CAP_EDGEA : CAP_EDGEB], p->edge_cap);
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
+    g.ob_keep = first ? p->obcopyA : p->obcopyB;
+    g.ob_keep_count = first ? &hdr->nobA : &hdr->nobB;
     g.nr_io = first ? &hdr->n_u : &hdr->h_u;
     g.nc_io = first ? &hdr->d1 : &hdr->d_u;
     g.ecount_out = first ? &hdr->edgesA : &hdr->edgesB;
@@ -968,7 +1060,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     hipLaunchKernelGGL(layouts_kernel, dim3(3), dim3(kPlanThreads), 0, st, p->rowA, n, p->layA,
                        phys_cap_rows(p->cap[CAP_ROWA]), p->tmpPA, p->rowB, h, p->layB,
                        phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
-                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, hdr);
+                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr);
     return launch_status();
 }
 

@@ -243,21 +243,39 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
 }
 
+// Clears up to six int32 arrays in one launch.
+struct ZeroList {
+    int32_t *p[6];
+    int64_t len[6];
+};
+__global__ void zero_lists_kernel(ZeroList z) {
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        int32_t *p = z.p[i];
+        const int64_t len = z.len[i];
+        if (!p) continue;
+        for (int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; x < len; x += (int64_t)gridDim.x * blockDim.x)
+            p[x] = 0;
+    }
+}
+
 static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, int32_t *status,
                       hipStream_t stream) {
+    ZeroList z;
+    int64_t longest = 0;
+    for (int i = 0; i < 6; ++i) { z.p[i] = nullptr; z.len[i] = 0; }
     if (st) {
         int32_t *p[4] = {st->rowcnt, st->colcnt, st->rowmax, st->colmax};
-        int64_t len[4] = {rows, cols, rows, cols};
+        const int64_t len[4] = {rows, cols, rows, cols};
         for (int i = 0; i < 4; ++i)
-            if (p[i] && len[i] > 0) {
-                int blocks = (int)((len[i] + 255) / 256);
-                if (blocks > 1024) blocks = 1024;
-                hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks), dim3(256), 0, stream, p[i], len[i], 0);
-            }
+            if (p[i] && len[i] > 0) { z.p[i] = p[i]; z.len[i] = len[i]; longest = len[i] > longest ? len[i] : longest; }
+        if (st->ob && st->ob_count) { z.p[4] = st->ob_count; z.len[4] = 1; longest = longest > 1 ? longest : 1; }
     }
-    if (status) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, status, (int64_t)1, 0);
-    if (st && st->ob && st->ob_count)
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, st->ob_count, (int64_t)1, 0);
+    if (status) { z.p[5] = status; z.len[5] = 1; longest = longest > 1 ? longest : 1; }
+    if (longest == 0) return IMUNPACK_OK;
+    int blocks = (int)((longest + 255) / 256);
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(zero_lists_kernel, dim3(blocks), dim3(256), 0, stream, z);
     return launch_status();
 }
 

@@ -6,158 +6,277 @@
 // (column) in place and moves floor(v / s) to the appended row (column); a row or column is split
 // at most once.  So the digits of the original entry (i, k) lie on a chain of positions: the
 // remainder sitting at (R, C) moves to the child of R if R was split before C, to the child of C
-// otherwise, and every other descendant position holds 0.  Position (R, C) with row level eR and
-// column level eC therefore holds digit eR + eC of the entry if the chain passes through it, else 0.
+// otherwise, and every other descendant position holds 0.
+//   - An operand unpacked by UnpackRow or UnpackColumn splits along one axis only: position (R, C)
+//     with row level eR and column level eC holds digit eR + eC of its entry.  scatter_kernel<true>
+//     writes all of it.
+//   - An operand unpacked by UnpackBoth holds digit 0 at the level-(0, 0) position of every entry and
+//     0 elsewhere, except along the chains of its OB entries.  scatter_kernel<false> writes the
+//     former, fixup_kernel then places the higher digits of the listed OB entries.
 #include "common.h"
 
 namespace imu {
 
-// sign(v) * ((|v| >> (sh * t)) & (s - 1)); a shift of 32 or more gives 0
-__device__ __forceinline__ int digit_of(int32_t v, int t, int sh, int s) {
-    const unsigned sft = (unsigned)(sh * t);
-    if (sft >= 32u) return 0;
-    const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
-    const int dg = (int)((av >> sft) & (unsigned)(s - 1));
-    return v < 0 ? -dg : dg;
-}
-
-// Does the chain of the entry at (row root, column root) pass through (level er, level ec)?
-__device__ __forceinline__ bool on_chain(const SlotSet &rows, const SlotSet &cols, int rroot, int croot,
-                                         int er, int ec) {
-    int r = rroot, c = croot, a = 0, b = 0;
-    while (a < er || b < ec) {
-        const uint32_t tr = rows.time[r], tc = cols.time[c];
-        if (tr < tc) {
-            if (a == er) return false;
-            r = rows.child[r];
-            ++a;
-        } else {
-            if (b == ec || tc == kNever) return false;
-            c = cols.child[c];
-            ++b;
-        }
-    }
-    return true;
-}
-
-// One workgroup handles kScatterRows consecutive physical rows over the whole padded width, 16 output
-// bytes per thread and step, so that the column descriptors are fetched once per row block, the
-// source rows (all digit levels of a source row are adjacent) are read from HBM once, and stores are
-// 16 bytes wide.  OPERAND 0 writes A_ue: rows from Pi_A, column chain inside the unpacking of A, then
-// copied along the columns that unpacking B appended.  OPERAND 1 writes B_eu: rows from Pi_B, column
-// chain inside the unpacking of B_e, whose column c copies B[:, k(c)].
+// One workgroup handles kScatterRows consecutive physical rows and walks the source in windows of
+// kScatterWin columns.  A window of the block's source rows (all digit levels of a source row are
+// adjacent, so the block has few distinct ones) is staged in LDS once; every 16-column output unit
+// whose first column copies a source column of the window is then produced from LDS -- the columns of
+// a group are ordered by source column, so the units of every group advance with the window and
+// each source element is read from HBM once.  A column that copies a source column outside the
+// window (the tail of a unit that straddles two windows, or a sparse group) is read from global
+// memory instead.  Stores are 16 bytes wide.  The kernel also leaves, per physical row, the weighted
+// L1 norm sum_c s^e(c) |digit| of what it wrote, and raises *bound to the largest of them.
 constexpr int kScatterRows = 8;
+constexpr int kScatterThreads = 256;
+static_assert(kScatterWin == 4 * kScatterThreads, "one int4 per thread and staged row");
 
-template <int OPERAND>
-__global__ __launch_bounds__(256) void scatter_kernel(const int32_t *__restrict__ M, int64_t ld,
-                                                      RowLayout lay, ColLayout cols, SlotSet rows,
-                                                      SlotSet cset, int Mp, int Kp, int s, int sh,
-                                                      int8_t *__restrict__ out,
-                                                      unsigned long long *bound) {
-    __shared__ unsigned long long red[4][kScatterRows];
+struct ScatterArgs {
+    const int32_t *M;            // the int32 operand, row-major
+    int64_t ld;
+    const int32_t *prow_slot, *prow_src, *prow_exp;  // per physical row
+    const int32_t *col_k;        // per physical column: source column, -1 = padding
+    const int32_t *col_e;        // per physical column: digit level along this operand's column axis
+    const int4 *unit_desc;
+    int lev_shift;               // where this operand's level sits in unit_desc.w
+    const int32_t *win_unit;
+    int Mp, Kp, d, ngroups, s, sh;
+    int8_t *out;
+    unsigned long long *rowsum, *bound;
+};
+
+template <bool DENSE>
+__global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a) {
+    __shared__ __attribute__((aligned(16))) int32_t tile[kScatterRows][kScatterWin];
+    __shared__ int s_slot[kScatterRows], s_src[kScatterRows], s_er[kScatterRows], s_trow[kScatterRows];
+    __shared__ unsigned long long s_wsum[kScatterRows];
+    __shared__ int s_u0[kMaxGroups + 1], s_ucount[kMaxGroups + 1], s_total;
     const int p0 = blockIdx.x * kScatterRows;
-    int slotR[kScatterRows], srcI[kScatterRows], expR[kScatterRows];
-#pragma unroll
-    for (int r = 0; r < kScatterRows; ++r) {
-        const int p = p0 + r;
-        slotR[r] = p < Mp ? lay.prow_slot[p] : -2;
-        srcI[r] = p < Mp ? lay.prow_src[p] : 0;
-        expR[r] = p < Mp ? lay.prow_exp[p] : 0;
-    }
-    unsigned long long wsum[kScatterRows];
-#pragma unroll
-    for (int r = 0; r < kScatterRows; ++r) wsum[r] = 0;
-    const bool ld_vec = (ld % 4) == 0 && ((uintptr_t)M % 16) == 0;
-    for (int q0 = threadIdx.x * 16; q0 < Kp; q0 += 256 * 16) {
-        int k[16], ec[16], sx[16];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int4 kk = *reinterpret_cast<const int4 *>(cols.colA_k + q0 + 4 * u);
-            const int4 ee = *reinterpret_cast<const int4 *>((OPERAND == 0 ? cols.colA_e : cols.colB_e) + q0 + 4 * u);
-            const int4 ss = *reinterpret_cast<const int4 *>(cols.col_sexp + q0 + 4 * u);
-            k[4 * u] = kk.x; k[4 * u + 1] = kk.y; k[4 * u + 2] = kk.z; k[4 * u + 3] = kk.w;
-            ec[4 * u] = ee.x; ec[4 * u + 1] = ee.y; ec[4 * u + 2] = ee.z; ec[4 * u + 3] = ee.w;
-            sx[4 * u] = ss.x; sx[4 * u + 1] = ss.y; sx[4 * u + 2] = ss.z; sx[4 * u + 3] = ss.w;
-        }
-        bool run = k[0] >= 0 && (k[0] % 4) == 0 && ld_vec;  // 16 consecutive source columns?
-        int ecany = 0;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            run = run && k[j] == k[0] + j;
-            ecany |= ec[j];
-        }
-#pragma unroll
-        for (int r = 0; r < kScatterRows; ++r) {
-            if (slotR[r] == -2) continue;  // past the last physical row (uniform)
-            int4 *dst = reinterpret_cast<int4 *>(out + (int64_t)(p0 + r) * Kp + q0);
-            if (slotR[r] < 0) {  // padding row
-                *dst = make_int4(0, 0, 0, 0);
-                continue;
-            }
-            const int32_t *src = M + (int64_t)srcI[r] * ld;
-            int32_t v[16];
-            if (run) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int4 x = *reinterpret_cast<const int4 *>(src + k[0] + 4 * u);
-                    v[4 * u] = x.x; v[4 * u + 1] = x.y; v[4 * u + 2] = x.z; v[4 * u + 3] = x.w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) v[j] = k[j] >= 0 ? src[k[j]] : 0;
-            }
-            int dg[16];
-            const int er = expR[r];
-            if (er == 0 && ecany == 0) {  // the common case: digit 0 of every entry
-#pragma unroll
-                for (int j = 0; j < 16; ++j) dg[j] = digit_of(v[j], 0, sh, s);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int t = er + ec[j];
-                    int val = digit_of(v[j], t, sh, s);
-                    if (t != 0 && val != 0) {
-                        const int croot = OPERAND == 0 ? k[j] : cols.colA_c1[q0 + j];
-                        if (!on_chain(rows, cset, srcI[r], croot, er, ec[j])) val = 0;
-                    }
-                    dg[j] = val;
-                }
-            }
-            int pk[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                pk[u] = (dg[4 * u] & 0xFF) | ((dg[4 * u + 1] & 0xFF) << 8) | ((dg[4 * u + 2] & 0xFF) << 16) |
-                        ((dg[4 * u + 3] & 0xFF) << 24);
-            *dst = make_int4(pk[0], pk[1], pk[2], pk[3]);
-            // weighted L1 norm of the row (saturating): sum_c s^e(c) |digit|
-            unsigned long long acc = 0;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const unsigned sft = (unsigned)(sh * sx[j]);
-                const unsigned long long mag = (unsigned long long)(dg[j] < 0 ? -dg[j] : dg[j]);
-                acc += (mag == 0) ? 0ull : (sft >= 40u ? (1ull << 50) : (mag << sft));
-            }
-            wsum[r] += acc;
-            if (wsum[r] > (1ull << 52)) wsum[r] = 1ull << 52;
-        }
-    }
-    // largest row norm of this block -> global maximum
-#pragma unroll
-    for (int r = 0; r < kScatterRows; ++r) {
-        unsigned long long w = wsum[r];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) w += __shfl_xor(w, off, 64);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][r] = w;
+    const int nwin = (a.d + kScatterWin - 1) / kScatterWin;
+    const int s = a.s, sh = a.sh, Kp = a.Kp, d = a.d;
+    if (threadIdx.x < kScatterRows) {
+        const int p = p0 + threadIdx.x;
+        s_slot[threadIdx.x] = p < a.Mp ? a.prow_slot[p] : -2;
+        s_src[threadIdx.x] = p < a.Mp ? a.prow_src[p] : -1;
+        s_er[threadIdx.x] = p < a.Mp ? a.prow_exp[p] : 0;
+        s_wsum[threadIdx.x] = 0;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long best = 0;
+    // s_trow[r]: which staged row holds the source row of physical row r
+    if (threadIdx.x < kScatterRows) {
+        int r = threadIdx.x;
+        while (r > 0 && s_src[r] >= 0 && s_src[r - 1] == s_src[r]) --r;
+        s_trow[threadIdx.x] = r;
+    }
+    __syncthreads();
+    const bool ld_vec = (a.ld % 4) == 0 && ((uintptr_t)a.M % 16) == 0;
+    auto fetch = [&](int w, int4 (&pre)[kScatterRows]) {
+        const int k = w * kScatterWin + (int)threadIdx.x * 4;
+#pragma unroll
         for (int r = 0; r < kScatterRows; ++r) {
-            unsigned long long t = red[0][r] + red[1][r] + red[2][r] + red[3][r];
-            if (t > (1ull << 60)) t = 1ull << 60;
-            best = best > t ? best : t;
+            pre[r] = make_int4(0, 0, 0, 0);
+            const int si = s_src[r];
+            if (s_trow[r] != r || si < 0 || w >= nwin) continue;
+            const int32_t *src = a.M + (int64_t)si * a.ld;
+            if (ld_vec && k + 3 < d) {
+                pre[r] = *reinterpret_cast<const int4 *>(src + k);
+            } else {
+                if (k < d) pre[r].x = src[k];
+                if (k + 1 < d) pre[r].y = src[k + 1];
+                if (k + 2 < d) pre[r].z = src[k + 2];
+                if (k + 3 < d) pre[r].w = src[k + 3];
+            }
         }
-        if (best) atomicMax(bound, best);
+    };
+    int4 pre[kScatterRows];
+    fetch(0, pre);
+    const int mask = s - 1;
+    for (int w = 0; w < nwin; ++w) {
+        if (w > 0) __syncthreads();  // the previous window has been consumed
+#pragma unroll
+        for (int r = 0; r < kScatterRows; ++r)
+            *reinterpret_cast<int4 *>(&tile[r][threadIdx.x * 4]) = pre[r];
+        if ((int)threadIdx.x < a.ngroups) {
+            const int g = threadIdx.x;
+            const int u0 = a.win_unit[g * (nwin + 1) + w], u1 = a.win_unit[g * (nwin + 1) + w + 1];
+            s_u0[g] = u0;
+            s_ucount[g] = u1 - u0;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int total = 0;
+            for (int g = 0; g < a.ngroups; ++g) total += s_ucount[g];
+            s_total = total;
+        }
+        fetch(w + 1, pre);  // in flight while this window is processed
+        __syncthreads();
+        const int kbase = w * kScatterWin;
+        const int total = s_total;
+        // work items: (unit, half of the block's rows), flattened over the groups
+        for (int item = threadIdx.x; item < 2 * total; item += kScatterThreads) {
+            int ui = item >> 1, g = 0;
+            while (ui >= s_ucount[g]) ui -= s_ucount[g++];
+            const int unit = s_u0[g] + ui, q0 = unit * 16;
+            const int rbeg = (item & 1) * (kScatterRows / 2);
+            const int4 ud = a.unit_desc[unit];
+            const int kmin = ud.x, kmax = ud.y;
+            const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
+            const int ecu = (ud.w >> a.lev_shift) & 0xFF;
+            const unsigned nsft = (unsigned)(sh * ((ud.w >> 16) & 0xFF));  // weight of the unit's columns in the row norm
+            const bool staged = kmin >= kbase && kmax < kbase + kScatterWin;
+            int k[16], ec[16];
+            if (kmax >= 0 && !run) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int4 kk = *reinterpret_cast<const int4 *>(a.col_k + q0 + 4 * u);
+                    k[4 * u] = kk.x; k[4 * u + 1] = kk.y; k[4 * u + 2] = kk.z; k[4 * u + 3] = kk.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) k[j] = kmin + j;
+            }
+            if (kmax >= 0 && !uniform) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int4 ee = *reinterpret_cast<const int4 *>(a.col_e + q0 + 4 * u);
+                    ec[4 * u] = ee.x; ec[4 * u + 1] = ee.y; ec[4 * u + 2] = ee.z; ec[4 * u + 3] = ee.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) ec[j] = ecu;
+            }
+#pragma unroll 1
+            for (int rr = 0; rr < kScatterRows / 2; ++rr) {
+                const int r = rbeg + rr;
+                const int slot = s_slot[r];
+                if (slot == -2) break;  // past the last physical row
+                int4 *dst = reinterpret_cast<int4 *>(a.out + (int64_t)(p0 + r) * Kp + q0);
+                const int er = s_er[r];
+                if (slot < 0 || kmax < 0 || (!DENSE && uniform && er + ecu != 0)) {
+                    // padding row, padding columns, or a unit that holds no level-0 position
+                    *dst = make_int4(0, 0, 0, 0);
+                    continue;
+                }
+                // ---- the source values
+                const int32_t *trow = tile[s_trow[r]];
+                int32_t v[16];
+                if (run && staged) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int4 x = *reinterpret_cast<const int4 *>(trow + (kmin - kbase) + 4 * u);
+                        v[4 * u] = x.x; v[4 * u + 1] = x.y; v[4 * u + 2] = x.z; v[4 * u + 3] = x.w;
+                    }
+                } else {
+                    bool miss = false;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const unsigned off = (unsigned)(k[j] - kbase);
+                        const bool in = off < (unsigned)kScatterWin;
+                        v[j] = trow[in ? off : 0u];
+                        if (!in) v[j] = 0;
+                        miss = miss || (!in && k[j] >= 0);
+                    }
+                    if (miss) {  // rare: a source column outside the staged window
+                        const int32_t *src = a.M + (int64_t)s_src[r] * a.ld;
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const unsigned off = (unsigned)(k[j] - kbase);
+                            if (k[j] >= 0 && off >= (unsigned)kScatterWin) v[j] = src[k[j]];
+                        }
+                    }
+                }
+                // ---- digits (sign-magnitude)
+                int pk[4];
+                unsigned mag = 0;  // sum of |digit| over the unit
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    int dg[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int x = v[4 * u + i];
+                        const int t = er + ec[4 * u + i];
+                        if (DENSE) {
+                            const unsigned sft = (unsigned)(sh * t);
+                            const unsigned av = x < 0 ? 0u - (unsigned)x : (unsigned)x;
+                            const int m = sft >= 32u ? 0 : (int)((av >> sft) & (unsigned)mask);
+                            dg[i] = x < 0 ? -m : m;
+                        } else {
+                            // digit 0: x - s * trunc(x / s)
+                            const int d0 = x - ((x + ((x >> 31) & mask)) & ~mask);
+                            dg[i] = t == 0 ? d0 : 0;
+                        }
+                    }
+                    pk[u] = (int)(__builtin_amdgcn_perm((unsigned)dg[1], (unsigned)dg[0], 0x0c0c0400u) |
+                                  __builtin_amdgcn_perm((unsigned)dg[3], (unsigned)dg[2], 0x04000c0cu));
+                    mag = __builtin_amdgcn_sad_u8((unsigned)pk[u] ^ 0x80808080u, 0x80808080u, mag);
+                }
+                *dst = make_int4(pk[0], pk[1], pk[2], pk[3]);
+                if (mag)  // one exponent of S per unit; saturating
+                    atomicAdd(&s_wsum[r], nsft >= 40u ? (1ull << 50) : ((unsigned long long)mag << nsft));
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < kScatterRows && p0 + (int)threadIdx.x < a.Mp) {
+        unsigned long long t = s_wsum[threadIdx.x];
+        if (t > (1ull << 60)) t = 1ull << 60;
+        a.rowsum[p0 + threadIdx.x] = t;
+        if (t) atomicMax(a.bound, t);
+    }
+}
+
+// Places the digits above digit 0 of the listed OB entries of an operand unpacked by UnpackBoth.
+// The remainder floor(|v| / s) of an entry at (R, C) moves to the child of whichever of R and C was
+// split first (Alg. 4 lines 7-9 / 11-14) and leaves its own digit 0 there.
+//   second == 0 (A): the entry's column chain lives in the column slots of A's unpacking; A_ue then
+//     repeats column r of A_u in every column slot of the second unpacking that descends from r
+//     (Alg. 2 line 6 / Alg. 4 line 13), so every digit is written once per such slot.
+//   second == 1 (B): B_e holds a copy of column k of B in every column slot r of A's unpacking that
+//     descends from k, and each copy is unpacked on its own.
+struct FixupArgs {
+    const int32_t *ob;          // [3][ob_cap] rows | columns | values
+    int ob_cap;
+    const int32_t *ob_count;
+    int second;
+    SlotSet rows, cset;         // the operand's row slots and the column slots of its own unpacking
+    const int32_t *c1_child;    // second == 1: child links among the column slots of A's unpacking
+    const int32_t *c2_child;    // second == 0: child links among the column slots of the second unpacking
+    const int32_t *row_phys, *col_phys, *col_sexp;
+    int Kp, s, sh;
+    int8_t *out;
+    unsigned long long *rowsum, *bound;
+};
+
+__global__ void fixup_kernel(FixupArgs f) {
+    const int n = min(*f.ob_count, f.ob_cap);
+    const unsigned mask = (unsigned)(f.s - 1);
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < n; t += gridDim.x * blockDim.x) {
+        const int i = f.ob[t], k = f.ob[f.ob_cap + t], v = f.ob[2 * (size_t)f.ob_cap + t];
+        const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
+        for (int croot = k, copies = 0; croot >= 0 && copies < 64; croot = f.second ? f.c1_child[croot] : -1, ++copies) {
+            int R = i, C = croot;
+            unsigned rem = av;
+            for (int step = 0; step < 40; ++step) {
+                rem >>= f.sh;
+                if (rem == 0) break;
+                const uint32_t tr = f.rows.time[R], tc = f.cset.time[C];
+                if (tr < tc) R = f.rows.child[R];
+                else if (tc != kNever) C = f.cset.child[C];
+                else break;  // an OB remainder nothing splits: not a complete plan
+                if (R < 0 || C < 0) break;
+                const int m = (int)(rem & mask);
+                if (m == 0) continue;
+                const int p = f.row_phys[R];
+                const int8_t dg = (int8_t)(v < 0 ? -m : m);
+                for (int c = C, hops = 0; c >= 0 && hops < 4096; c = f.second ? -1 : f.c2_child[c], ++hops) {
+                    const int q = f.col_phys[c];
+                    f.out[(int64_t)p * f.Kp + q] = dg;
+                    const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
+                    const unsigned long long term = nsft >= 40u ? (1ull << 50) : ((unsigned long long)m << nsft);
+                    const unsigned long long now = atomicAdd(&f.rowsum[p], term) + term;
+                    atomicMax(f.bound, now > (1ull << 60) ? (1ull << 60) : now);
+                }
+            }
+        }
     }
 }
 
@@ -192,15 +311,46 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     if (!p || !p->valid || !A || !B || !A_ue || !B_eu || lda < p->d || ldb < p->d) return IMUNPACK_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
-    hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
-    if (h.Mp > 0 && h.Kp > 0)
-        hipLaunchKernelGGL(scatter_kernel<0>, dim3((h.Mp + kScatterRows - 1) / kScatterRows), dim3(256), 0, st, A,
-                           lda, p->layA, p->cols, p->rowA, p->c1, h.Mp, h.Kp, p->s, p->sh, A_ue,
-                           &p->d_hdr->bound[0]);
-    if (h.Np > 0 && h.Kp > 0)
-        hipLaunchKernelGGL(scatter_kernel<1>, dim3((h.Np + kScatterRows - 1) / kScatterRows), dim3(256), 0, st, B,
-                           ldb, p->layB, p->cols, p->rowB, p->c2, h.Np, h.Kp, p->s, p->sh, B_eu,
-                           &p->d_hdr->bound[1]);
+    // the planner leaves the bounds cleared; a repeated unpack of the same plan clears them again
+    if (p->unpacked) hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
+    for (int op = 0; op < 2; ++op) {
+        const int rowsP = op ? h.Np : h.Mp;
+        if (rowsP <= 0 || h.Kp <= 0) continue;
+        const RowLayout &lay = op ? p->layB : p->layA;
+        const bool both = (op ? p->sB : p->sA) == IMUNPACK_BOTH;
+        ScatterArgs a;
+        a.M = op ? B : A; a.ld = op ? ldb : lda;
+        a.prow_slot = lay.prow_slot; a.prow_src = lay.prow_src; a.prow_exp = lay.prow_exp;
+        a.col_k = p->cols.colA_k;
+        a.col_e = op ? p->cols.colB_e : p->cols.colA_e;
+        a.unit_desc = p->cols.unit_desc;
+        a.lev_shift = op ? 8 : 0;
+        a.win_unit = p->cols.win_unit;
+        a.Mp = rowsP; a.Kp = h.Kp; a.d = (int)p->d; a.ngroups = h.ngroups; a.s = p->s; a.sh = p->sh;
+        a.out = op ? B_eu : A_ue;
+        a.rowsum = op ? p->rowsumB : p->rowsumA;
+        a.bound = &p->d_hdr->bound[op];
+        const dim3 grid((rowsP + kScatterRows - 1) / kScatterRows);
+        if (both) hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, a);
+        else hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, a);
+        if (both) {
+            FixupArgs f;
+            f.ob = op ? p->obcopyB : p->obcopyA;
+            f.ob_cap = p->cap[op ? CAP_EDGEB : CAP_EDGEA];
+            f.ob_count = op ? &p->d_hdr->nobB : &p->d_hdr->nobA;
+            f.second = op;
+            f.rows = op ? p->rowB : p->rowA;
+            f.cset = op ? p->c2 : p->c1;
+            f.c1_child = p->c1.child;
+            f.c2_child = p->c2.child;
+            f.row_phys = lay.row_phys; f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
+            f.Kp = h.Kp; f.s = p->s; f.sh = p->sh;
+            f.out = a.out; f.rowsum = a.rowsum; f.bound = a.bound;
+            const int nob = op ? h.nobB : h.nobA;
+            if (nob > 0)
+                hipLaunchKernelGGL(fixup_kernel, dim3((nob + 255) / 256), dim3(256), 0, st, f);
+        }
+    }
     IMU_TRY(launch_status());
     IMU_HIP(hipMemcpyAsync(p->hdr.bound, p->d_hdr->bound, sizeof(p->hdr.bound), hipMemcpyDeviceToHost, st));
     IMU_HIP(hipStreamSynchronize(st));
