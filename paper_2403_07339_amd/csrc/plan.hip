@@ -617,11 +617,35 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
                             int cap_phys, int cap_tiles, int32_t *tmpP, PlanHeader *hdr, int operand, int *lds) {
     int32_t *nlev = lay.src_nlev;
     int lm = 1;
-    for (int i = threadIdx.x; i < nbase; i += kPlanThreads) {
-        int L = 1;
-        for (int R = rows.child[i]; R >= 0 && L < 64; R = rows.child[R]) ++L;
-        nlev[i] = L;
-        lm = max(lm, L);
+    constexpr int V = 4;  // source rows per thread and step: their chains are walked side by side
+    for (int i0 = threadIdx.x; i0 < nbase; i0 += kPlanThreads * V) {
+        int R[V], L[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int i = i0 + u * kPlanThreads;
+            R[u] = i < nbase ? rows.child[i] : -1;
+            L[u] = 1;
+        }
+        for (int hop = 0; hop < 64; ++hop) {
+            bool more = false;
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                if (R[u] >= 0) {
+                    ++L[u];
+                    R[u] = rows.child[R[u]];
+                    more = true;
+                }
+            }
+            if (!more) break;
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int i = i0 + u * kPlanThreads;
+            if (i < nbase) {
+                nlev[i] = L[u];
+                lm = max(lm, L[u]);
+            }
+        }
     }
     const int lmax = block_max(lm, lds);
     const int base = ordered_scan(
@@ -658,18 +682,37 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
         lay.prow_exp[p] = 0;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nbase; i += kPlanThreads) {
-        const int t = tmpP[i] / Tp;
-        const int i0 = lay.tile_src0[t];
-        const int pst = t * kTile + (tmpP[i] - tmpP[i0]);
-        lay.src_pstart[i] = pst;
-        const int L = nlev[i];
-        int l = 0;
-        for (int R = i; R >= 0 && l < L; R = rows.child[R], ++l) {
-            lay.prow_slot[pst + l] = R;
-            lay.prow_src[pst + l] = i;
-            lay.prow_exp[pst + l] = l;
-            lay.row_phys[R] = pst + l;
+    for (int i0 = threadIdx.x; i0 < nbase; i0 += kPlanThreads * V) {
+        int R[V], pst[V], L[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int i = i0 + u * kPlanThreads;
+            R[u] = -1;
+            pst[u] = 0;
+            L[u] = 0;
+            if (i < nbase) {
+                const int P = tmpP[i], t = P / Tp;
+                pst[u] = t * kTile + (P - tmpP[lay.tile_src0[t]]);
+                L[u] = nlev[i];
+                R[u] = i;
+                lay.src_pstart[i] = pst[u];
+            }
+        }
+        for (int l = 0; l < 64; ++l) {
+            bool more = false;
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                if (R[u] >= 0 && l < L[u]) {
+                    const int Rc = R[u];
+                    R[u] = rows.child[Rc];
+                    lay.prow_slot[pst[u] + l] = Rc;
+                    lay.prow_src[pst[u] + l] = i0 + u * kPlanThreads;
+                    lay.prow_exp[pst[u] + l] = l;
+                    lay.row_phys[Rc] = pst[u] + l;
+                    more = true;
+                }
+            }
+            if (!more) break;
         }
     }
     if (threadIdx.x == 0) {
@@ -696,18 +739,34 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
     for (int e = threadIdx.x; e < kMaxGroups; e += kPlanThreads) hist[e] = 0;
     if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
-    for (int c = threadIdx.x; c < D; c += kPlanThreads) {
-        const int r = c2.root[c], eb = c2.exp[c];
-        const int ea = c1.exp[r], k = c1.root[r];
-        const int e = ea + eb;
-        tmpE[c] = e | (ea << 8) | (eb << 16);
-        tmpK[c] = k;
-        tmpR[c] = r;
-        if (e < kMaxGroups && ea < 256 && eb < 256) {
-            atomicAdd(&hist[e], 1);
-        } else {
-            atomicMin(&hdr->err, IMUNPACK_ERANGE);
-            s_bad = 1;
+    constexpr int V = 8;  // column slots per thread and step, loaded side by side
+    for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
+        int r[V], eb[V], ea[V], k[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int c = c0 + u * kPlanThreads;
+            r[u] = c < D ? c2.root[c] : 0;
+            eb[u] = c < D ? c2.exp[c] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            ea[u] = c1.exp[r[u]];
+            k[u] = c1.root[r[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int c = c0 + u * kPlanThreads;
+            if (c >= D) continue;
+            const int e = ea[u] + eb[u];
+            tmpE[c] = e | (ea[u] << 8) | (eb[u] << 16);
+            tmpK[c] = k[u];
+            tmpR[c] = r[u];
+            if (e < kMaxGroups && ea[u] < 256 && eb[u] < 256) {
+                atomicAdd(&hist[e], 1);
+            } else {
+                atomicMin(&hdr->err, IMUNPACK_ERANGE);
+                s_bad = 1;
+            }
         }
     }
     __syncthreads();
@@ -744,22 +803,45 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         const int ge = hdr->grp_exp[g], q0 = hdr->grp_k0[g];
         for (int k = threadIdx.x; k < d; k += kPlanThreads) tmpOff[k] = 0;
         __syncthreads();
-        for (int c = threadIdx.x; c < D; c += kPlanThreads)
-            if ((tmpE[c] & 0xFF) == ge) atomicAdd(&tmpOff[tmpK[c]], 1);
+        for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
+            int pe[V], k[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const int c = c0 + u * kPlanThreads;
+                pe[u] = c < D ? tmpE[c] : -1;
+                k[u] = c < D ? tmpK[c] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u)
+                if (pe[u] >= 0 && (pe[u] & 0xFF) == ge) atomicAdd(&tmpOff[k[u]], 1);
+        }
         __syncthreads();
         ordered_scan(
             d, q0, [&](int k) { return tmpOff[k]; }, [&](int k, int pre) { tmpOff[k] = pre; }, lds);
-        for (int c = threadIdx.x; c < D; c += kPlanThreads) {
-            const int pe = tmpE[c];
-            if ((pe & 0xFF) != ge) continue;
-            const int k = tmpK[c];
-            const int q = atomicAdd(&tmpOff[k], 1);
-            cols.pcol_slot[q] = c;
-            cols.colA_k[q] = k;
-            cols.colA_c1[q] = tmpR[c];
-            cols.colA_e[q] = (pe >> 8) & 0xFF;
-            cols.colB_e[q] = (pe >> 16) & 0xFF;
-            cols.col_sexp[q] = ge;
+        for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
+            int pe[V], k[V], rr[V], q[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const int c = c0 + u * kPlanThreads;
+                pe[u] = c < D ? tmpE[c] : -1;
+                k[u] = c < D ? tmpK[c] : 0;
+                rr[u] = c < D ? tmpR[c] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                if (pe[u] < 0 || (pe[u] & 0xFF) != ge) pe[u] = -1;
+                q[u] = pe[u] >= 0 ? atomicAdd(&tmpOff[k[u]], 1) : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                if (pe[u] < 0) continue;
+                cols.pcol_slot[q[u]] = c0 + u * kPlanThreads;
+                cols.colA_k[q[u]] = k[u];
+                cols.colA_c1[q[u]] = rr[u];
+                cols.colA_e[q[u]] = (pe[u] >> 8) & 0xFF;
+                cols.colB_e[q[u]] = (pe[u] >> 16) & 0xFF;
+                cols.col_sexp[q[u]] = ge;
+            }
         }
         __syncthreads();
         // columns of one group that copy the same source column: order them by their level along A
