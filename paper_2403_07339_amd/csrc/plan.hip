@@ -934,7 +934,6 @@ __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
 // ---------------------------------------------------------------------------------------------
 int scan_i32(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
              const imunpack_stats_t *st, hipStream_t stream);
-__global__ void fill_i32_kernel(int32_t *p, int64_t count, int32_t value);
 
 struct Carver {
     char *base;

@@ -5,6 +5,8 @@
 // HBM-bound: 4 B read + 4 B written per element (4 B read for the stand-alone scan).
 #include "common.h"
 
+#include <algorithm>
+
 namespace imu {
 
 __device__ __forceinline__ int wave_max_i32(int v) {
@@ -24,12 +26,6 @@ __device__ __forceinline__ int32_t rtn_one(float x, float scale, int &bad) {
 }
 
 __device__ __forceinline__ int iabs_sat(int32_t v) { return v < 0 ? (v == INT32_MIN ? INT32_MAX : -v) : v; }
-
-__global__ void fill_i32_kernel(int32_t *p, int64_t count, int32_t value) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t step = (int64_t)gridDim.x * blockDim.x;
-    for (; i < count; i += step) p[i] = value;
-}
 
 // Column partials of one workgroup: wave w holds, per lane, the statistics of its own columns over
 // the rows that wave visited; they are combined through LDS and one atomic per column is issued.
@@ -103,7 +99,7 @@ __device__ __forceinline__ void ob_flush(ObStage *sg, int32_t *ob, int ob_cap, i
     }
 }
 
-// Fast path: unit column stride, 16-byte aligned rows.  Workgroup = 64 rows x 256 columns;
+// Fast path: unit column stride, 16-byte aligned rows.  Workgroup = rows_per_wg rows x 256 columns;
 // a wave reads one 1 KiB row segment per instruction (float4 per lane).
 template <bool FROM_FLOAT>
 __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__ Xv, int64_t rows,
@@ -112,7 +108,7 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
                                                         int32_t *rowcnt, int32_t *colcnt,
                                                         int32_t *rowmax, int32_t *colmax,
                                                         int32_t *status, int32_t *ob, int ob_cap,
-                                                        int32_t *ob_count) {
+                                                        int32_t *ob_count, int rows_per_wg) {
     __shared__ int lds[2 * 4 * 256];
     __shared__ ObStage stage;
     if (ob) {
@@ -120,62 +116,67 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
         __syncthreads();
     }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t c0 = (int64_t)blockIdx.x * 256 + lane * 4;
-    const int64_t r_base = (int64_t)blockIdx.y * 64;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; rotating the column block with the row block
+    // lets every XCD touch every column block (and so every memory channel) while the workgroups that
+    // run together still cover whole rows.
+    const int cbx = (blockIdx.x + blockIdx.y) % gridDim.x;
+    const int64_t c0 = (int64_t)cbx * 256 + lane * 4;
+    const int64_t r_base = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t r_end = min(rows, r_base + rows_per_wg);
     int ccnt[4] = {0, 0, 0, 0}, cmax[4] = {0, 0, 0, 0};
     int bad = 0;
     const bool in_cols = c0 < cols;  // cols % 4 == 0 on this path
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-        const int64_t r = r_base + wave + 4 * it;
-        if (r >= rows) break;  // uniform per wave
-        int4 q = make_int4(0, 0, 0, 0);
-        if (in_cols) {
-            if (FROM_FLOAT) {
-                const float4 x = *reinterpret_cast<const float4 *>(
-                    reinterpret_cast<const float *>(Xv) + r * ldx + c0);
-                q.x = rtn_one(x.x, scale, bad);
-                q.y = rtn_one(x.y, scale, bad);
-                q.z = rtn_one(x.z, scale, bad);
-                q.w = rtn_one(x.w, scale, bad);
-                *reinterpret_cast<int4 *>(Q + r * ldq + c0) = q;
-            } else {
-                q = *reinterpret_cast<const int4 *>(reinterpret_cast<const int32_t *>(Xv) + r * ldx + c0);
-            }
-        }
-        const int a0 = iabs_sat(q.x), a1 = iabs_sat(q.y), a2 = iabs_sat(q.z), a3 = iabs_sat(q.w);
-        const int o0 = a0 >= s, o1 = a1 >= s, o2 = a2 >= s, o3 = a3 >= s;
-        ccnt[0] += o0; ccnt[1] += o1; ccnt[2] += o2; ccnt[3] += o3;
-        cmax[0] = max(cmax[0], a0); cmax[1] = max(cmax[1], a1);
-        cmax[2] = max(cmax[2], a2); cmax[3] = max(cmax[3], a3);
-        // row statistics: popcount of the wave's ballots, wave-wide max
-        const int rc = __popcll(__ballot(o0)) + __popcll(__ballot(o1)) + __popcll(__ballot(o2)) +
-                       __popcll(__ballot(o3));
-        const int rm = wave_max_i32(max(max(a0, a1), max(a2, a3)));
-        if (lane == 0) {
-            if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
-            if (rowmax && rm) atomicMax(&rowmax[r], rm);
-        }
-        if (ob && rc) {  // rare: append this wave's OB entries (row, column, value) to the list
-            const unsigned long long lt = (1ull << lane) - 1ull;
-            const unsigned long long b0 = __ballot(o0), b1 = __ballot(o1), b2 = __ballot(o2), b3 = __ballot(o3);
-            int base = 0;
-            if (lane == 0) base = atomicAdd(&stage.count, rc);
-            base = __shfl(base, 0, 64);
-            int pos = base + __popcll(b0 & lt) + __popcll(b1 & lt) + __popcll(b2 & lt) + __popcll(b3 & lt);
-            const int qv[4] = {q.x, q.y, q.z, q.w};
-            const int ov[4] = {o0, o1, o2, o3};
+    // four rows per step: their loads are issued together, before any of them is used
+    for (int64_t rb = r_base + wave; rb < r_end; rb += 16) {  // uniform per wave
+        int4 raw[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (ov[u]) {
-                    ob_push(&stage, pos, (int32_t)r, (int32_t)(c0 + u), qv[u], ob, ob_cap, ob_count);
-                    ++pos;
+        for (int v = 0; v < 4; ++v) {
+            const int64_t r = rb + 4 * v;
+            raw[v] = make_int4(0, 0, 0, 0);
+            if (in_cols && r < r_end)
+                raw[v] = *reinterpret_cast<const int4 *>(reinterpret_cast<const int32_t *>(Xv) + r * ldx + c0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int64_t r = rb + 4 * v;
+            if (r >= r_end) break;  // uniform per wave
+            int4 q = raw[v];
+            if (FROM_FLOAT && in_cols) {
+                q.x = rtn_one(__int_as_float(raw[v].x), scale, bad);
+                q.y = rtn_one(__int_as_float(raw[v].y), scale, bad);
+                q.z = rtn_one(__int_as_float(raw[v].z), scale, bad);
+                q.w = rtn_one(__int_as_float(raw[v].w), scale, bad);
+                *reinterpret_cast<int4 *>(Q + r * ldq + c0) = q;
+            }
+            const int a0 = iabs_sat(q.x), a1 = iabs_sat(q.y), a2 = iabs_sat(q.z), a3 = iabs_sat(q.w);
+            const int o0 = a0 >= s, o1 = a1 >= s, o2 = a2 >= s, o3 = a3 >= s;
+            ccnt[0] += o0; ccnt[1] += o1; ccnt[2] += o2; ccnt[3] += o3;
+            cmax[0] = max(cmax[0], a0); cmax[1] = max(cmax[1], a1);
+            cmax[2] = max(cmax[2], a2); cmax[3] = max(cmax[3], a3);
+            // row statistics: popcount of the wave's ballots, wave-wide max
+            if (rowcnt || rowmax) {
+                const int rc = __popcll(__ballot(o0)) + __popcll(__ballot(o1)) + __popcll(__ballot(o2)) +
+                               __popcll(__ballot(o3));
+                const int rm = wave_max_i32(max(max(a0, a1), max(a2, a3)));
+                if (lane == 0) {
+                    if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
+                    if (rowmax && rm) atomicMax(&rowmax[r], rm);
                 }
+            }
+            if (ob) {  // rare, lane by lane: append the OB entries (row, column, value) to the staged list
+                const int qv[4] = {q.x, q.y, q.z, q.w};
+                const int ov[4] = {o0, o1, o2, o3};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ov[u])
+                        ob_push(&stage, atomicAdd(&stage.count, 1), (int32_t)r, (int32_t)(c0 + u), qv[u], ob,
+                                ob_cap, ob_count);
+            }
         }
     }
     if (ob) ob_flush(&stage, ob, ob_cap, ob_count);
     if (colcnt || colmax)
-        flush_columns<4>(ccnt, cmax, (int64_t)blockIdx.x * 256, cols, colcnt, colmax, lds);
+        flush_columns<4>(ccnt, cmax, (int64_t)cbx * 256, cols, colcnt, colmax, lds);
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
 }
 
@@ -298,10 +299,13 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
     const bool vec = sx_c == 1 && (cols % 4) == 0 && (sx_r % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
                      (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0));
     if (vec) {
-        dim3 grid((unsigned)((cols + 255) / 256), (unsigned)((rows + 63) / 64));
-        if (grid.y > 65535u) return IMUNPACK_EINVAL;
+        const int64_t cblocks = (cols + 255) / 256;
+        int64_t rpw = 64;
+        if ((rows + rpw - 1) / rpw > 65535) rpw = ((rows + 65534) / 65535 + 3) / 4 * 4;
+        dim3 grid((unsigned)cblocks, (unsigned)((rows + rpw - 1) / rpw));
         hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
+                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count,
+                           (int)rpw);
     } else {
         dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
         hipLaunchKernelGGL(qscan_tile_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
