@@ -730,15 +730,21 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
 // Also written: for every group and every window of kScatterWin source columns, the first 16-column
 // unit whose first column copies a source column at or past the window's start (the scatter kernel
 // walks the source in such windows).
+constexpr int kColBlocks = 8;  // workgroups that share the column layout, one exponent group at a time each
+
 __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayout &cols, int d, int cap_phys,
-                            int s, int sh, int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff,
-                            PlanHeader *hdr, int *lds) {
+                            int s, int sh, int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOffAll,
+                            PlanHeader *hdr, int *lds, int part) {
     __shared__ int hist[kMaxGroups];
+    __shared__ int s_gexp[kMaxGroups], s_gk0[kMaxGroups];
     __shared__ int s_ng, s_kp, s_bad;
     const int D = hdr->d_u;
+    int32_t *tmpOff = tmpOffAll + (size_t)part * (d + 1);
     for (int e = threadIdx.x; e < kMaxGroups; e += kPlanThreads) hist[e] = 0;
     if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
+    // every part computes the same per-slot values and the same group table (the stores of the
+    // parts coincide); a part then lays out the groups part, part + kColBlocks, ...
     constexpr int V = 8;  // column slots per thread and step, loaded side by side
     for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
         int r[V], eb[V], ea[V], k[V];
@@ -776,31 +782,38 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         for (int e = kMaxGroups - 1; e >= 0; --e) {
             if (!hist[e]) continue;
             if (e * sh > 62 || hist[e] > lim) atomicMin(&hdr->err, IMUNPACK_ERANGE);
-            hdr->grp_exp[ng] = e;
-            hdr->grp_k0[ng] = k0;
-            hdr->grp_len[ng] = hist[e];
+            s_gexp[ng] = e;
+            s_gk0[ng] = k0;
+            if (part == 0) {
+                hdr->grp_exp[ng] = e;
+                hdr->grp_k0[ng] = k0;
+                hdr->grp_len[ng] = hist[e];
+            }
             k0 += (hist[e] + kKPad - 1) / kKPad * kKPad;
             ++ng;
         }
-        hdr->ngroups = ng;
-        hdr->Kp = k0;
+        if (part == 0) {
+            hdr->ngroups = ng;
+            hdr->Kp = k0;
+            if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
+        }
         s_ng = ng;
         s_kp = k0;
-        if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
     }
     __syncthreads();
     const int ng = s_ng, Kp = s_kp;
     if (Kp > cap_phys || s_bad) return;
-    for (int q = threadIdx.x; q < Kp; q += kPlanThreads) {
-        cols.pcol_slot[q] = -1;
-        cols.colA_k[q] = -1;
-        cols.colA_c1[q] = 0;
-        cols.colA_e[q] = 0;
-        cols.colB_e[q] = 0;
-        cols.col_sexp[q] = 0;
-    }
-    for (int g = 0; g < ng; ++g) {
-        const int ge = hdr->grp_exp[g], q0 = hdr->grp_k0[g];
+    const int nwin = (d + kScatterWin - 1) / kScatterWin;
+    for (int g = part; g < ng; g += kColBlocks) {
+        const int ge = s_gexp[g], q0 = s_gk0[g], q1 = g + 1 < ng ? s_gk0[g + 1] : Kp;
+        for (int q = q0 + threadIdx.x; q < q1; q += kPlanThreads) {
+            cols.pcol_slot[q] = -1;
+            cols.colA_k[q] = -1;
+            cols.colA_c1[q] = 0;
+            cols.colA_e[q] = 0;
+            cols.colB_e[q] = 0;
+            cols.col_sexp[q] = 0;
+        }
         for (int k = threadIdx.x; k < d; k += kPlanThreads) tmpOff[k] = 0;
         __syncthreads();
         for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
@@ -864,57 +877,53 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             }
         }
         __syncthreads();
-    }
-    for (int q = threadIdx.x; q < Kp; q += kPlanThreads) {
-        const int c = cols.pcol_slot[q];
-        if (c >= 0) cols.col_phys[c] = q;
-    }
-    __syncthreads();
-    // per 16-column unit: what the scatter kernel needs to pick its path without the per-column arrays
-    for (int u = threadIdx.x; u < Kp / 16; u += kPlanThreads) {
-        const int q0 = 16 * u;
-        const int k0 = cols.colA_k[q0], ea0 = cols.colA_e[q0], eb0 = cols.colB_e[q0];
-        int kmin = 0x7fffffff, kmax = -1, sexp = 0;
-        bool run = k0 >= 0 && (k0 % 4) == 0, uniform = true;
-        for (int j = 0; j < 16; ++j) {
-            const int k = cols.colA_k[q0 + j];
-            run = run && k == k0 + j;
-            if (k >= 0) {
-                kmin = min(kmin, k);
-                kmax = max(kmax, k);
-                sexp = cols.col_sexp[q0 + j];
-                uniform = uniform && cols.colA_e[q0 + j] == ea0 && cols.colB_e[q0 + j] == eb0;
-            }
+        for (int q = q0 + threadIdx.x; q < q1; q += kPlanThreads) {
+            const int c = cols.pcol_slot[q];
+            if (c >= 0) cols.col_phys[c] = q;
         }
-        int4 ud;
-        ud.x = kmax < 0 ? -1 : kmin;
-        ud.y = kmax;
-        ud.z = (run ? 1 : 0) | (uniform ? 2 : 0);
-        ud.w = (ea0 & 0xFF) | ((eb0 & 0xFF) << 8) | ((sexp & 0xFF) << 16);
-        cols.unit_desc[u] = ud;
-    }
-    // window table
-    const int nwin = (d + kScatterWin - 1) / kScatterWin;
-    for (int t = threadIdx.x; t < ng * (nwin + 1); t += kPlanThreads) {
-        const int g = t / (nwin + 1), w = t % (nwin + 1);
-        const int u0 = hdr->grp_k0[g] / 16;
-        const int u1 = (g + 1 < ng ? hdr->grp_k0[g + 1] : Kp) / 16;
-        int lo = u0, hi = u1;
-        if (w < nwin) {
-            const int want = w * kScatterWin;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                const int kk = cols.colA_k[16 * mid];
-                if (kk < 0 || kk >= want) hi = mid; else lo = mid + 1;  // padding sorts last
+        // per 16-column unit: what the scatter kernel needs to pick its path without the per-column arrays
+        for (int u = q0 / 16 + threadIdx.x; u < q1 / 16; u += kPlanThreads) {
+            const int qq = 16 * u;
+            const int k0 = cols.colA_k[qq], ea0 = cols.colA_e[qq], eb0 = cols.colB_e[qq];
+            int kmin = 0x7fffffff, kmax = -1;
+            bool run = k0 >= 0 && (k0 % 4) == 0, uniform = true;
+            for (int j = 0; j < 16; ++j) {
+                const int k = cols.colA_k[qq + j];
+                run = run && k == k0 + j;
+                if (k >= 0) {
+                    kmin = min(kmin, k);
+                    kmax = max(kmax, k);
+                    uniform = uniform && cols.colA_e[qq + j] == ea0 && cols.colB_e[qq + j] == eb0;
+                }
             }
-        } else {
-            lo = u1;
+            int4 ud;
+            ud.x = kmax < 0 ? -1 : kmin;
+            ud.y = kmax;
+            ud.z = (run ? 1 : 0) | (uniform ? 2 : 0);
+            ud.w = (ea0 & 0xFF) | ((eb0 & 0xFF) << 8) | ((ge & 0xFF) << 16);
+            cols.unit_desc[u] = ud;
         }
-        cols.win_unit[g * (nwin + 1) + w] = lo;
+        // window table of the group
+        for (int w = threadIdx.x; w <= nwin; w += kPlanThreads) {
+            const int u0 = q0 / 16, u1 = q1 / 16;
+            int lo = u0, hi = u1;
+            if (w < nwin) {
+                const int want = w * kScatterWin;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    const int kk = cols.colA_k[16 * mid];
+                    if (kk < 0 || kk >= want) hi = mid; else lo = mid + 1;  // padding sorts last
+                }
+            } else {
+                lo = u1;
+            }
+            cols.win_unit[g * (nwin + 1) + w] = lo;
+        }
+        __syncthreads();
     }
 }
 
-// One workgroup per layout: rows of A, rows of B, columns.
+// One workgroup for the rows of A, one for the rows of B, kColBlocks for the columns.
 __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     SlotSet rowA, int n, RowLayout layA, int cap_physA, int32_t *tmpPA, SlotSet rowB, int h, RowLayout layB,
     int cap_physB, int32_t *tmpPB, SlotSet c1, SlotSet c2, ColLayout cols, int d, int cap_physC, int s, int sh,
@@ -924,8 +933,8 @@ __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, lds);
     else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, lds);
     else {
-        cols_layout(c1, c2, cols, d, cap_physC, s, sh, tmpE, tmpK, tmpR, tmpOff, hdr, lds);
-        if (threadIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
+        cols_layout(c1, c2, cols, d, cap_physC, s, sh, tmpE, tmpK, tmpR, tmpOff, hdr, lds, (int)blockIdx.x - 2);
+        if (blockIdx.x == 2 && threadIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
     }
 }
 
@@ -995,7 +1004,7 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->tmpE = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpK = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpR = cv.take<int32_t>(p->cap[CAP_C2]);
-        p->tmpOff = cv.take<int32_t>(d + 1);
+        p->tmpOff = cv.take<int32_t>((size_t)kColBlocks * (d + 1));
     }
     p->rowsumA = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWA]));
     p->rowsumB = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWB]));
@@ -1138,7 +1147,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
         else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
     // ---- physical layouts
-    hipLaunchKernelGGL(layouts_kernel, dim3(3), dim3(kPlanThreads), 0, st, p->rowA, n, p->layA,
+    hipLaunchKernelGGL(layouts_kernel, dim3(2 + kColBlocks), dim3(kPlanThreads), 0, st, p->rowA, n, p->layA,
                        phys_cap_rows(p->cap[CAP_ROWA]), p->tmpPA, p->rowB, h, p->layB,
                        phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
                        phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr);

@@ -246,10 +246,15 @@ struct FixupArgs {
     unsigned long long *rowsum, *bound;
 };
 
-__global__ void fixup_kernel(FixupArgs f) {
+// Both operands in one launch: blocks [0, blocks_a) serve fa, the rest fb.
+__global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a) {
+    const bool first = (int)blockIdx.x < blocks_a;
+    const FixupArgs &f = first ? fa : fb;
+    const int block = first ? blockIdx.x : blockIdx.x - blocks_a;
+    const int nblocks = first ? blocks_a : gridDim.x - blocks_a;
     const int n = min(*f.ob_count, f.ob_cap);
     const unsigned mask = (unsigned)(f.s - 1);
-    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < n; t += gridDim.x * blockDim.x) {
+    for (int t = block * blockDim.x + threadIdx.x; t < n; t += nblocks * blockDim.x) {
         const int i = f.ob[t], k = f.ob[f.ob_cap + t], v = f.ob[2 * (size_t)f.ob_cap + t];
         const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
         for (int croot = k, copies = 0; croot >= 0 && copies < 64; croot = f.second ? f.c1_child[croot] : -1, ++copies) {
@@ -272,8 +277,11 @@ __global__ void fixup_kernel(FixupArgs f) {
                     f.out[(int64_t)p * f.Kp + q] = dg;
                     const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
                     const unsigned long long term = nsft >= 40u ? (1ull << 50) : ((unsigned long long)m << nsft);
-                    const unsigned long long now = atomicAdd(&f.rowsum[p], term) + term;
-                    atomicMax(f.bound, now > (1ull << 60) ? (1ull << 60) : now);
+                    unsigned long long now = atomicAdd(&f.rowsum[p], term) + term;
+                    if (now > (1ull << 60)) now = 1ull << 60;
+                    // the bound only grows: a plain (possibly stale) read filters most of the updates
+                    if (now > __hip_atomic_load(f.bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                        atomicMax(f.bound, now);
                 }
             }
         }
@@ -313,6 +321,8 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     const PlanHeader &h = p->hdr;
     // the planner leaves the bounds cleared; a repeated unpack of the same plan clears them again
     if (p->unpacked) hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
+    FixupArgs fx[2] = {};
+    int fblocks[2] = {0, 0};
     for (int op = 0; op < 2; ++op) {
         const int rowsP = op ? h.Np : h.Mp;
         if (rowsP <= 0 || h.Kp <= 0) continue;
@@ -333,8 +343,9 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         const dim3 grid((rowsP + kScatterRows - 1) / kScatterRows);
         if (both) hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, a);
         else hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, a);
-        if (both) {
-            FixupArgs f;
+        const int nob = op ? h.nobB : h.nobA;
+        if (both && nob > 0) {
+            FixupArgs &f = fx[op];
             f.ob = op ? p->obcopyB : p->obcopyA;
             f.ob_cap = p->cap[op ? CAP_EDGEB : CAP_EDGEA];
             f.ob_count = op ? &p->d_hdr->nobB : &p->d_hdr->nobA;
@@ -346,10 +357,13 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.row_phys = lay.row_phys; f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
             f.Kp = h.Kp; f.s = p->s; f.sh = p->sh;
             f.out = a.out; f.rowsum = a.rowsum; f.bound = a.bound;
-            const int nob = op ? h.nobB : h.nobA;
-            if (nob > 0)
-                hipLaunchKernelGGL(fixup_kernel, dim3((nob + 255) / 256), dim3(256), 0, st, f);
+            fblocks[op] = (nob + 255) / 256;
         }
+    }
+    if (fblocks[0] + fblocks[1] > 0) {  // after both scatters: the fix-up overwrites zeros they wrote
+        if (!fblocks[0]) fx[0] = fx[1];  // never dereferenced, but keep the argument well-formed
+        if (!fblocks[1]) fx[1] = fx[0];
+        hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1]), dim3(256), 0, st, fx[0], fx[1], fblocks[0]);
     }
     IMU_TRY(launch_status());
     IMU_HIP(hipMemcpyAsync(p->hdr.bound, p->d_hdr->bound, sizeof(p->hdr.bound), hipMemcpyDeviceToHost, st));
