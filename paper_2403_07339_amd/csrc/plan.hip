@@ -285,7 +285,8 @@ __device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int 
 template <bool LDS>
 __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g) {
     extern __shared__ __attribute__((aligned(16))) int32_t lds_counts[];
-    __shared__ int s_max[2 * kPlanWaves];
+    __shared__ int s_top[2];
+    __shared__ int s_pick[kPlanWaves][256];  // per wave: the slots picked in one 256-slot step
     __shared__ int s_found[kPlanWaves];
     __shared__ int lds[40];
     __shared__ int s_count;
@@ -330,7 +331,10 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     }
     for (int x = threadIdx.x; x < cpad; x += kPlanThreads)
         cc[x] = x < nc ? g.colcnt[g.chain_root ? g.chain_root[x] : x] : 0;
-    if (threadIdx.x == 0) s_count = 0;
+    if (threadIdx.x == 0) {
+        s_count = 0;
+        s_top[0] = s_top[1] = 0;
+    }
     __syncthreads();
     // ---- the extra edges of repeated columns (second operand only)
     unsigned long long *list0 = g.edges, *list1 = g.edges + ((g.ecap + 1) & ~1);  // both 16-byte aligned
@@ -409,16 +413,11 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             m1 = max(m1, __shfl_xor(m1, off, 64));
         }
         if (lane == 0) {
-            s_max[wave] = m0;
-            s_max[kPlanWaves + wave] = m1;
+            atomicMax(&s_top[0], m0);
+            atomicMax(&s_top[1], m1);
         }
         __syncthreads();
-        int c0 = 0, c1 = 0;
-#pragma unroll
-        for (int w = 0; w < kPlanWaves; ++w) {
-            c0 = max(c0, s_max[w]);
-            c1 = max(c1, s_max[kPlanWaves + w]);
-        }
+        const int c0 = s_top[0], c1 = s_top[1];  // cleared again in step 3, past the next barrier
         if (c0 <= 0 && c1 <= 0) break;
         const bool isrow = c0 >= c1;  // rows win ties (Alg. 4: "else if c0 >= c1")
         int32_t *cnt = isrow ? rc : cc, *other = isrow ? cc : rc;
@@ -453,7 +452,8 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             return;
         }
         // (3) the new slots; a split slot's count is replaced by a mark that names its new slot (only
-        // the lane that owns a slot reads its count in steps 1-3)
+        // the lane that owns a slot reads its count in steps 1-3).  The picked slots of a step are
+        // first compacted into the wave's LDS list, so that the stores run over them densely.
         for (int x0 = wlo; x0 < whi; x0 += 256) {
             const int x = x0 + lane * 4;
             const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
@@ -467,59 +467,60 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                 before += __popcll(m & below);
                 all += __popcll(m);
             }
-            int rank = run + before;
-            int root[4], ex[4];
+            if (all == 0) continue;  // uniform per wave
+            int pos = before;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                root[i] = f[i] ? mine.root[x + i] : 0;
-                ex[i] = f[i] ? mine.exp[x + i] : 0;
+                if (f[i]) {
+                    s_pick[wave][pos] = (min(cv[i], 0xFFFFFF) << 8) | (lane * 4 + i);
+                    cnt[x + i] = -(run + pos + 1);
+                    ++pos;
+                }
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (!f[i]) continue;
-                const int X = x + i, newX = N + rank;
+            for (int j = lane; j < all; j += 64) {
+                const int pk = s_pick[wave][j];
+                const int X = x0 + (pk & 0xFF), newX = N + run + j;
+                const int root = mine.root[X], ex = mine.exp[X];
                 mine.time[X] = (uint32_t)bid;
                 mine.child[X] = newX;
-                mine.root[newX] = root[i];
-                mine.exp[newX] = ex[i] + 1;
+                mine.root[newX] = root;
+                mine.exp[newX] = ex + 1;
                 mine.time[newX] = kNever;
                 mine.child[newX] = -1;
                 mine.key[newX] = ((unsigned long long)bid << 48) |
-                                 ((unsigned long long)(0xFFFFFF - min(cv[i], 0xFFFFFF)) << 24) | (unsigned)X;
-                cnt[X] = -(rank + 1);
-                ++rank;
+                                 ((unsigned long long)(0xFFFFFF - (pk >> 8)) << 24) | (unsigned)X;
             }
             run += all;
         }
-        if (threadIdx.x == 0) s_count = 0;
+        if (threadIdx.x == 0) {
+            s_count = 0;
+            s_top[0] = s_top[1] = 0;
+        }
         __syncthreads();
         // (4) the pass.  The survivors of U entries per lane are appended with one counter update per wave.
         unsigned long long *dst = bid == 0 ? list1 : (cur ? list0 : list1);
-        auto process = [&](auto &row, auto &col, auto &lev) {
-            constexpr int U = sizeof(lev) / sizeof(int);
+        constexpr unsigned long long kSlotMask = (1ull << kEdgeSlotBits) - 1ull;
+        const int xshift = isrow ? 0 : kEdgeSlotBits, oshift = isrow ? kEdgeSlotBits : 0;
+        auto process = [&](auto &e) {  // e[u]: packed edge, 0 if absent
+            constexpr int U = sizeof(e) / sizeof(unsigned long long);
             int c[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) c[u] = lev[u] >= 2 ? cnt[isrow ? row[u] : col[u]] : 0;  // marks do not change during a pass
-            unsigned long long out[U];
+            for (int u = 0; u < U; ++u)  // marks do not change during a pass; slot 0's count is harmless for absent edges
+                c[u] = cnt[(int)((e[u] >> xshift) & kSlotMask)];
             int before = 0, all = 0;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                out[u] = 0ull;
-                if (lev[u] >= 2) {
-                    if (c[u] < 0 && -c[u] - 1 < nb) {
-                        if (lev[u] > 2) {
-                            const int newX = N + (-c[u] - 1);
-                            if (isrow) row[u] = newX; else col[u] = newX;
-                            atomicAdd(&cnt[newX], 1);
-                            out[u] = pack_edge(row[u], col[u], lev[u] - 1);
-                        } else {
-                            atomicSub(&other[isrow ? col[u] : row[u]], 1);
-                        }
+                if (e[u] != 0ull && c[u] < 0 && -c[u] - 1 < nb) {
+                    if ((e[u] >> (2 * kEdgeSlotBits)) > 2ull) {  // still OB in the new slot: move on
+                        const unsigned long long newX = (unsigned long long)(N + (-c[u] - 1));
+                        atomicAdd(&cnt[(int)newX], 1);
+                        e[u] = ((e[u] & ~(kSlotMask << xshift)) | (newX << xshift)) - (1ull << (2 * kEdgeSlotBits));
                     } else {
-                        out[u] = pack_edge(row[u], col[u], lev[u]);
+                        atomicSub(&other[(int)((e[u] >> oshift) & kSlotMask)], 1);
+                        e[u] = 0ull;
                     }
                 }
-                const unsigned long long m = __ballot(out[u] != 0ull);
+                const unsigned long long m = __ballot(e[u] != 0ull);
                 before += __popcll(m & below);
                 all += __popcll(m);
             }
@@ -529,7 +530,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             base = __shfl(base, 0, 64) + before;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (out[u] != 0ull) dst[base++] = out[u];
+                if (e[u] != 0ull) dst[base++] = e[u];
         };
         if (bid == 0) {  // the operand's OB list itself
             int j[U], k[U], v[U];
@@ -549,10 +550,11 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
                 int j2[U], k2[U], v2[U];
                 fetch(t0 + kPlanThreads * U, j2, k2, v2);  // past the end: all absent
-                int lev[U];
+                unsigned long long e[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    lev[u] = levels_of(v[u]);
+                    const int lev = levels_of(v[u]);
+                    e[u] = lev >= 2 ? pack_edge(j[u], k[u], lev) : 0ull;
                     const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
                     if (t < nob) {
                         g.ob_keep[t] = j[u];
@@ -560,7 +562,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                         g.ob_keep[2 * (size_t)g.ecap + t] = v[u];
                     }
                 }
-                process(j, k, lev);
+                process(e);
 #pragma unroll
                 for (int u = 0; u < U; ++u) { j[u] = j2[u]; k[u] = k2[u]; v[u] = v2[u]; }
             }
@@ -587,10 +589,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             for (int e0 = 0; e0 < E; e0 += kPlanThreads * U2) {
                 unsigned long long ed2[U2];
                 fetch(e0 + kPlanThreads * U2, ed2);
-                int row[U2], col[U2], lev[U2];
-#pragma unroll
-                for (int u = 0; u < U2; ++u) unpack_edge(ed[u], row[u], col[u], lev[u]);
-                process(row, col, lev);
+                process(ed);
 #pragma unroll
                 for (int u = 0; u < U2; ++u) ed[u] = ed2[u];
             }
@@ -1046,7 +1045,7 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
     return (int)b;
 }
 
-static constexpr int kGreedyLdsMax = 150 * 1024;  // dynamic LDS the greedy may use for the two count vectors
+static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
 
 // ob: the operand's OB entry list ([3][ob_cap], count on the device)
 static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const int32_t *ob_count,
