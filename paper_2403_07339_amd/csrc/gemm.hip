@@ -14,6 +14,9 @@
 #include <cstring>
 #include <type_traits>
 
+// first register of every aligned quad of the 256 accumulation registers
+#define IMU_ACC_QUADS "0,4,8,12,16,20,24,28,32,36,40,44,48,52,56,60,64,68,72,76,80,84,88,92,96,100,104,108,112,116,120,124,128,132,136,140,144,148,152,156,160,164,168,172,176,180,184,188,192,196,200,204,208,212,216,220,224,228,232,236,240,244,248,252"
+
 namespace imu {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -205,6 +208,35 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // kt+1 and stream B(kt+2) into the slot of A(kt).
     int kt = kt0;
     for (int seg = 0; seg <= g.nbound; ++seg) {
+        if (seg > 0) {  // start of the next exponent group: Horner step
+            // The accumulators fill the whole accumulation register file (a0..a255), so shifting every
+            // one of those registers shifts every accumulator, whichever block sits where.  Written
+            // out by hand: left to the compiler, this step spills three blocks to scratch memory.
+            const int shv = g.bound_sh[seg - 1];
+            int t0, t1, t2, t3;
+            asm volatile(
+                "s_nop 15\n\ts_nop 7\n\t"  // the last MFMA results must have landed
+                ".irp n," IMU_ACC_QUADS "\n\t"
+                "v_accvgpr_read_b32 %[t0], a[\\n]\n\t"
+                "v_accvgpr_read_b32 %[t1], a[\\n+1]\n\t"
+                "v_accvgpr_read_b32 %[t2], a[\\n+2]\n\t"
+                "v_accvgpr_read_b32 %[t3], a[\\n+3]\n\t"
+                "v_lshlrev_b32 %[t0], %[sh], %[t0]\n\t"
+                "v_lshlrev_b32 %[t1], %[sh], %[t1]\n\t"
+                "v_lshlrev_b32 %[t2], %[sh], %[t2]\n\t"
+                "v_lshlrev_b32 %[t3], %[sh], %[t3]\n\t"
+                "v_accvgpr_write_b32 a[\\n], %[t0]\n\t"
+                "v_accvgpr_write_b32 a[\\n+1], %[t1]\n\t"
+                "v_accvgpr_write_b32 a[\\n+2], %[t2]\n\t"
+                "v_accvgpr_write_b32 a[\\n+3], %[t3]\n\t"
+                ".endr\n\t"
+                "s_nop 7"
+                : [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3), "+a"(acc[0][0]), "+a"(acc[0][1]),
+                  "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]),
+                  "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                  "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
+                : [sh] "s"(shv));
+        }
         const int kend = seg < g.nbound ? g.bound_kt[seg] + 1 : kt1;
         for (; kt < kend; ++kt) {
             const int8_t *stA = smem + sa * kHalfBytes, *stB = smem + ring(sa, 1) * kHalfBytes;
@@ -224,15 +256,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             __builtin_amdgcn_sched_barrier(0);
             step(1, stA1, stB1, 0, 0, 8);
             sa = ring(sa, 2);
-        }
-        if (seg < g.nbound) {  // end of an exponent group: Horner step
-            const int shv = g.bound_sh[seg];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] <<= shv;
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before LDS is reused
