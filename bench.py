@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
+# HBM bytes per launch of the GEMM kernel (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this
+# file, each scaled by what the counter reads for a plain copy of known size; the summary of those runs
+# is profiles/bench_workload3_hbm_traffic.md).  Only measured for the default workload.
+GEMM_TRAFFIC_BYTES = {3: 848.0e6}
 
 
 def cpu_baseline(w, budget_rows: int = 4096):
@@ -154,7 +158,9 @@ def main():
         "prepass_GBps": {"quantize+scan": q_bytes / stage_ms[0] / 1e6, "scatter": u_bytes / stage_ms[2] / 1e6,
                          "hbm_peak": HBM_PEAK_GBS},
         "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "traffic": None},
+                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES.get(args.workload),
+                     "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
