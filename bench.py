@@ -52,6 +52,45 @@ def cpu_baseline(w, budget_rows: int = 4096):
                       f"fp64 dequantise of the first {rows} of {w.n} rows of A against all of B {t3 - t2:.1f} s"}
 
 
+def measure_extras(torch, imu, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args):
+    """Untimed side measurements reported beside the headline: the two quantize calls on their own, this
+    library's GEMM on the original shape with operands clipped to int8 (what one pays without
+    exactness), and the measured peaks of the matrix cores and of a device-to-device copy."""
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    res = {}
+    res["quant_a_ms"] = timed(lambda: imu.imunpack_quantize(A, w.scale_a, w.b, Qa, st_a, status[0:1]), 10)
+    res["quant_b_ms"] = timed(lambda: imu.imunpack_quantize(B, w.scale_b, w.b, Qb, st_b, status[1:2]), 10)
+    lim = (1 << (w.b - 1)) - 1
+    Qa_c, Qb_c = Qa.clamp(-lim, lim), Qb.clamp(-lim, lim)
+    plain = imu.imunpack_plan(Qa_c, Qb_c, w.b, imu.ROW, imu.ROW)
+    A8, B8 = imu.imunpack_unpack(plain, Qa_c, Qb_c)
+    assert plain.unpack_ratio() == 1.0 and plain.fusable()
+    res["plain_gemm_ms"] = timed(lambda: imu.imunpack_gemm(plain, A8, B8, w.scale_a, w.scale_b, None, C_fp, None,
+                                                           fuse=True), 10)
+    del plain, A8, B8, Qa_c, Qb_c
+    ops = [0]
+    def peak():
+        ops[0] = imu.imunpack_diag_mfma_peak(256 * 4, 4000)
+    ms = timed(peak, 3)
+    res["mfma_peak_tops"] = ops[0] / ms / 1e9
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ms = timed(lambda: dst.copy_(src), 5)
+    res["copy_gbps"] = 2 * src.numel() * 4 / ms / 1e6
+    del src, dst
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +173,7 @@ def main():
 
     ms_step = dt * 1e3 / args.steps
     stage_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / args.steps for i in range(5)]
+    extra = measure_extras(torch, imu, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
     n_u, d_u, h_u, ng = plan.dims()
     ba, bb, _ = plan.unpacked_bytes()
     gemm_ms = stage_ms[4]
@@ -162,6 +202,17 @@ def main():
                      "traffic": GEMM_TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
     }
+    out["unpack"]["time_ratio_vs_plain_int8_gemm"] = ms_step / extra["plain_gemm_ms"]
+    out["plain_int8_gemm"] = {"ms": extra["plain_gemm_ms"], "TOPS": w.ops / extra["plain_gemm_ms"] / 1e9,
+                              "note": "this library's GEMM on the original shape, operands clipped to int8 (not exact)"}
+    out["stage_ms"]["quantize+scan A"] = extra["quant_a_ms"]
+    out["stage_ms"]["quantize+scan B"] = extra["quant_b_ms"]
+    out["measured_peaks"] = {"int8_mfma_TOPS": extra["mfma_peak_tops"], "copy_GBps": extra["copy_gbps"],
+                             "gemm_frac_of_measured_mfma": achieved / extra["mfma_peak_tops"],
+                             "note": "register-resident v_mfma_i32_32x32x32_i8 loop, 4 waves per SIMD; device-to-device "
+                                     "copy of 1 GiB (read + written bytes)"}
+    out["prepass_GBps"]["quantize+scan_frac_of_copy"] = out["prepass_GBps"]["quantize+scan"] / extra["copy_gbps"]
+    out["prepass_GBps"]["scatter_frac_of_copy"] = out["prepass_GBps"]["scatter"] / extra["copy_gbps"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -175,6 +175,12 @@ int imunpack_last_hip_error(void);
  * 0 = the shifted group sum may exceed int32 and the un-fused path is required. */
 int imunpack_plan_fusable(const imunpack_plan_t *plan);
 
+/* Measured matrix-core peak (benchmark reporting only, not part of the method): launches
+ * `workgroups` workgroups of 4 waves that each issue 8 * iters register-resident
+ * v_mfma_i32_32x32x32_i8 with no memory traffic, and writes the number of integer operations
+ * (2 per multiply-add) the launch performs to *ops.  The caller times the stream. */
+int imunpack_diag_mfma_peak(int workgroups, int iters, int64_t *ops, imunpack_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = [
     "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
-    "imunpack_plan_fusable",
+    "imunpack_plan_fusable", "imunpack_diag_mfma_peak",
 ]
 
 
@@ -51,6 +51,7 @@ _lib.imunpack_recombine.argtypes = [_vp, _vp, _f32, _f32, _vp, _vp, _i64, _vp]
 _lib.imunpack_strerror.argtypes = [_i32]
 _lib.imunpack_strerror.restype = C.c_char_p
 _lib.imunpack_plan_fusable.argtypes = [_vp]
+_lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 for _name in EXPORTS:
     if _name != "imunpack_strerror":
         getattr(_lib, _name).restype = C.c_int
@@ -277,3 +278,11 @@ def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale
     if int(st_a.item()) or int(st_b.item()):
         raise ImunpackError(ERANGE, "imunpack_quantize status")
     return C_int, C_fp, plan
+
+
+def imunpack_diag_mfma_peak(workgroups: int, iters: int) -> int:
+    """Launches the register-resident int8 MFMA loop on the current stream; returns the integer
+    operations it performs (the caller times the stream)."""
+    ops = _i64(0)
+    _check(_lib.imunpack_diag_mfma_peak(int(workgroups), int(iters), C.byref(ops), _stream()), "imunpack_diag_mfma_peak")
+    return int(ops.value)

@@ -409,6 +409,32 @@ __global__ __launch_bounds__(256) void recombine_kernel(const int64_t *__restric
     if (C_fp) C_fp[o] = (float)((double)acc * scale);
 }
 
+// Register-resident back-to-back int8 MFMAs (no memory traffic): what the matrix cores sustain on
+// this chip, for the measured-peak line of the benchmark.  Eight independent accumulators per wave.
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int *sink) {
+    v4i a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = (int)threadIdx.x + i;
+        b[i] = (int)blockIdx.x + i;
+    }
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int x = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x ^= acc[i][r];
+    if (x == 0x7fffffff && sink) *sink = x;  // keeps the accumulators live
+}
+
 }  // namespace imu
 
 using namespace imu;
@@ -495,4 +521,12 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
     if (fuse != 0)  // the caller asked for final outputs: finish the job here
         return imunpack_recombine(p, workspace, scale_A, scale_B, C_int, C_fp, ldc, stream);
     return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_diag_mfma_peak(int workgroups, int iters, int64_t *ops, imunpack_stream_t stream) {
+    if (workgroups <= 0 || workgroups > 65535 || iters <= 0 || iters > (1 << 24)) return IMUNPACK_EINVAL;
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, iters, (int *)nullptr);
+    // 4 waves per workgroup, 8 MFMAs per iteration, 2 * 32 * 32 * 32 operations each
+    if (ops) *ops = (int64_t)workgroups * 4 * (int64_t)iters * 8 * 65536;
+    return launch_status();
 }
