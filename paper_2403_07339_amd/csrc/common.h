@@ -37,6 +37,7 @@ static inline int launch_status() {
 
 // ---- geometry shared by planner, scatter and GEMM ----------------------------------------------
 constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both operands)
+constexpr int kChunk = 64;       // physical rows the GEMM epilogue holds at a time; no source row straddles a chunk
 constexpr int kKPad = 128;       // every exponent group is padded to a multiple of this many columns
 constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
 constexpr int kScatterWin = 1024;  // source columns per window of the scatter kernel
@@ -84,6 +85,7 @@ struct RowLayout {
     int32_t *src_pstart;  // [n]   first physical row of source row i
     int32_t *src_nlev;    // [n]   number of levels of source row i
     int32_t *tile_src0;   // [tiles+1] first source row of each tile
+    int32_t *chunk_src0;  // [4 tiles+1] first source row of each chunk of kChunk physical rows
     int32_t *tile_flat;   // [tiles]   1 if every source row of the tile has a single level
 };
 
@@ -118,6 +120,8 @@ struct imunpack_plan {
     // views into the arena (valid after a successful imunpack_plan)
     imu::PlanHeader *d_hdr;
     imu::PlanHeader hdr;          // host mirror
+    imu::PlanHeader *pin_hdr;     // pinned staging copy of the header (device-to-host copies land here)
+    hipEvent_t ready;             // recorded after such a copy; the host polls it
     imu::SlotSet rowA, rowB, c1, c2;
     imu::RowLayout layA, layB;
     imu::ColLayout cols;
@@ -142,4 +146,9 @@ struct imunpack_plan {
 
 namespace imu {
 using Plan = struct ::imunpack_plan;  // the C function imunpack_plan() hides the bare struct name
+
+// Copies bytes [offset, offset + bytes) of the device header into the host mirror and waits for it.
+// The wait polls an event instead of blocking in the driver: the wake-up of a blocking wait costs
+// tens of microseconds during which the GPU idles between two stages of the path.
+int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st);
 }

@@ -295,27 +295,81 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
         return;
     }
 
-    // ---- fused epilogue.  The accumulators leave the registers through LDS, 64 physical rows of the
-    // tile at a time ([64][256] int32, rows padded to 260), so that global stores are row-contiguous
-    // and the digit levels of a source row / column (which the planner keeps inside one tile) can be
-    // added up: C_int[i,j] = sum_{levels a of i, c of j} s^(a+c) * acc[row(i,a)][col(j,c)].
+    // ---- fused epilogue.  The accumulators leave the registers through LDS, one chunk of 64 physical
+    // rows of the tile at a time ([64][256] int32, rows padded to 260), so that global stores are
+    // row-contiguous and the digit levels of a source row (which the planner keeps inside one chunk)
+    // and of a source column (inside one tile) can be added up:
+    // C_int[i,j] = sum_{levels a of i, c of j} s^(a+c) * acc[row(i,a)][col(j,c)].
 #ifdef IMU_GEMM_DIAG
     if constexpr ((g_diag & 32) != 0) { if (acc[0][0][0] == 0x12345) g.C_fp[0] = 1.0f; return; }
 #endif
-    const int isrc0 = g.layA.tile_src0[tm], nsrcA = g.layA.tile_src0[tm + 1] - isrc0;
     const int jsrc0 = g.layB.tile_src0[tn], nsrcB = g.layB.tile_src0[tn + 1] - jsrc0;
-    const bool flat = g.flatA[tm] && g.flatB[tn];
+    const bool flatA = g.flatA[tm] != 0, flatB = g.flatB[tn] != 0;
     constexpr int FLD = 260;
     int32_t *fold = reinterpret_cast<int32_t *>(smem);
+    // behind the staging buffer: per source row of the tile its first physical row (relative to the
+    // tile) | levels << 16; the same per source column; the first source row of each chunk
+    int32_t *rowmeta = fold + kChunk * FLD, *colmeta = rowmeta + kTile, *chunk0 = colmeta + kTile;
     // scale * 2^final_shift is exact: one multiplication in binary64, one rounding to fp32
     const double scale2 = g.scale * (double)(1ull << g.final_shift);
-    const bool vec_ok = flat && (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (nsrcB % 4) == 0 &&
+    const bool vec_ok = flatB && (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (nsrcB % 4) == 0 &&
                         (!g.C_fp || ((uintptr_t)g.C_fp % 16) == 0) && (!g.C_int || ((uintptr_t)g.C_int % 16) == 0);
-    const int jf = jsrc0 + tid;
-    const bool have_col = !flat && tid < nsrcB;
-    const int q0 = have_col ? g.layB.src_pstart[jf] - n0 : 0;
-    const int lj = have_col ? g.layB.src_nlev[jf] : 0;
-    int64_t run = 0;
+    {
+        const int isrc0 = g.layA.tile_src0[tm], nsrcA = g.layA.tile_src0[tm + 1] - isrc0;
+        if (!flatA && tid < nsrcA)
+            rowmeta[tid] = (g.layA.src_pstart[isrc0 + tid] - m0) | (g.layA.src_nlev[isrc0 + tid] << 16);
+        if (!flatB && tid < nsrcB)
+            colmeta[tid] = (g.layB.src_pstart[jsrc0 + tid] - n0) | (g.layB.src_nlev[jsrc0 + tid] << 16);
+        if (tid <= kTile / kChunk) chunk0[tid] = g.layA.chunk_src0[tm * (kTile / kChunk) + tid];
+    }  // published by the first barrier below
+    auto store4_32 = [&](int64_t o, int cols_left, const v4i &v) {  // a single level: the int32 sums as they are
+        if (vec_ok) {
+            if (g.C_fp) {
+                v4f f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
+                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+            }
+            if (g.C_int) {
+                v2l lo, hi;
+                lo[0] = (int64_t)v[0] << g.final_shift; lo[1] = (int64_t)v[1] << g.final_shift;
+                hi[0] = (int64_t)v[2] << g.final_shift; hi[1] = (int64_t)v[3] << g.final_shift;
+                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
+                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < cols_left) {
+                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
+                    if (g.C_int) g.C_int[o + k] = (int64_t)v[k] << g.final_shift;
+                }
+        }
+    };
+    auto store4 = [&](int64_t o, int cols_left, const int64_t (&v)[4]) {  // v: before the final shift
+        if (vec_ok) {
+            if (g.C_fp) {
+                v4f f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
+                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+            }
+            if (g.C_int) {
+                v2l lo, hi;
+                lo[0] = v[0] << g.final_shift; lo[1] = v[1] << g.final_shift;
+                hi[0] = v[2] << g.final_shift; hi[1] = v[3] << g.final_shift;
+                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
+                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < cols_left) {
+                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
+                    if (g.C_int) g.C_int[o + k] = v[k] << g.final_shift;
+                }
+        }
+    };
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         __syncthreads();
@@ -330,62 +384,59 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                             acc[(c & 1) * 2 + ii][jj][r];
         }
         __syncthreads();
-        if (flat) {
-            // physical order = source order: thread t streams rows (t>>6) + 4*it, columns 4*(t&63)..+3
+        // source rows of this chunk: cs0 .. cs0 + ns - 1; no source row straddles a chunk
+        const int cs0 = chunk0[c], ns = chunk0[c + 1] - cs0;
+        const int rs0 = cs0 - chunk0[0];  // index of the chunk's first source row in rowmeta
+        if (flatB) {
+            // source columns = physical columns: work items are (source row, four columns)
             const int col4 = (tid & 63) * 4;
-            for (int it = 0; it < 16; ++it) {
-                const int row = (tid >> 6) + 4 * it;
-                const int pi = c * 64 + row;
-                if (pi >= nsrcA) break;
-                const v4i v = *reinterpret_cast<const v4i *>(fold + row * FLD + col4);
-                const int64_t o = (int64_t)(isrc0 + pi) * g.ldc + jsrc0 + col4;
+            if (col4 < nsrcB && flatA) {  // physical order = source order inside the chunk
+                for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                    const v4i x = *reinterpret_cast<const v4i *>(fold + r * FLD + col4);
 #ifdef IMU_GEMM_DIAG
-                if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[o] = 1.0f; continue; }
+                    if constexpr ((g_diag & 16) != 0) { if (x[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
 #endif
-                if (vec_ok) {
-                    if (col4 < nsrcB) {
-                        if (g.C_fp) {
-                            v4f f;
-#pragma unroll
-                            for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
-                            __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
-                        }
-                        if (g.C_int) {
-                            v2l lo, hi;
-                            lo[0] = (int64_t)v[0] << g.final_shift; lo[1] = (int64_t)v[1] << g.final_shift;
-                            hi[0] = (int64_t)v[2] << g.final_shift; hi[1] = (int64_t)v[3] << g.final_shift;
-                            __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
-                            __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
-                        }
+                    store4_32((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x);
+                }
+            } else if (col4 < nsrcB) {
+                for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                    int prel = r, nl = 1;
+                    if (!flatA) {
+                        const int m = rowmeta[rs0 + r];
+                        prel = (m & 0xFFFF) - c * kChunk;
+                        nl = m >> 16;
                     }
-                } else {
+                    int64_t v[4] = {0, 0, 0, 0};
+                    for (int l = 0; l < nl; ++l) {
+                        const v4i x = *reinterpret_cast<const v4i *>(fold + (prel + l) * FLD + col4);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        if (col4 + k < nsrcB) {
-                            if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
-                            if (g.C_int) g.C_int[o + k] = (int64_t)v[k] << g.final_shift;
-                        }
+                        for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * l);
+                    }
+#ifdef IMU_GEMM_DIAG
+                    if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
+#endif
+                    store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v);
                 }
             }
         } else {
-            for (int row = 0; row < 64; ++row) {
-                const int p = m0 + c * 64 + row;
-                const int i = g.layA.prow_src[p];
-                if (i < 0) continue;  // padding row (uniform)
-                const int lvl = g.layA.prow_exp[p];
-                const bool last = lvl == g.layA.src_nlev[i] - 1;
-                if (have_col) {
-                    int64_t v = 0;
-                    for (int l = 0; l < lj; ++l) v += (int64_t)fold[row * FLD + q0 + l] << (g.sh * l);
-                    run += v << (g.sh * lvl);
-                    if (last) {
-                        const int64_t outv = run << g.final_shift;
-                        const int64_t o = (int64_t)i * g.ldc + jf;
-                        if (g.C_int) g.C_int[o] = outv;
-                        if (g.C_fp) g.C_fp[o] = (float)((double)run * scale2);
-                        run = 0;
-                    }
+            // split source columns: work items are (source row, source column)
+            for (int it = tid; it < ns * nsrcB; it += kGemmThreads) {
+                const int r = it / nsrcB, jc = it - r * nsrcB;
+                int prel = r, nl = 1;
+                if (!flatA) {
+                    const int m = rowmeta[rs0 + r];
+                    prel = (m & 0xFFFF) - c * kChunk;
+                    nl = m >> 16;
                 }
+                const int cm = colmeta[jc];
+                const int q0 = cm & 0xFFFF, lj = cm >> 16;
+                int64_t v = 0;
+                for (int a = 0; a < nl; ++a)
+                    for (int l = 0; l < lj; ++l)
+                        v += (int64_t)fold[(prel + a) * FLD + q0 + l] << (g.sh * (a + l));
+                const int64_t o = (int64_t)(cs0 + r) * g.ldc + jsrc0 + jc;
+                if (g.C_int) g.C_int[o] = v << g.final_shift;
+                if (g.C_fp) g.C_fp[o] = (float)((double)v * scale2);
             }
         }
     }

@@ -609,11 +609,14 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
 // physical layouts
 // ---------------------------------------------------------------------------------------------
 // Rows: source-major (all digit levels of a source row adjacent, level ascending), and no source
-// row straddles a GEMM tile, so that Pi can be applied inside one tile's epilogue.  Source row i
-// with unpadded start P_i goes to tile floor(P_i / (kTile - (Lmax-1))): a closed form, and the
-// rows of a tile never exceed kTile.
+// row straddles a chunk of `chunk` physical rows: kChunk for A (four chunks per GEMM tile), so that Pi_A
+// can be applied on the 64 rows the tile's epilogue holds in LDS at a time; kTile for B, whose levels
+// are folded along the columns of a tile.  Source row i with unpadded start P_i
+// goes to chunk floor(P_i / (kChunk - (Lmax-1))): a closed form, and the rows of a chunk never exceed
+// kChunk.
 __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count_dev, const RowLayout &lay,
-                            int cap_phys, int cap_tiles, int32_t *tmpP, PlanHeader *hdr, int operand, int *lds) {
+                            int cap_phys, int cap_tiles, int32_t *tmpP, PlanHeader *hdr, int operand, int chunk,
+                            int *lds) {
     int32_t *nlev = lay.src_nlev;
     int lm = 1;
     constexpr int V = 4;  // source rows per thread and step: their chains are walked side by side
@@ -649,8 +652,15 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
     const int lmax = block_max(lm, lds);
     const int base = ordered_scan(
         nbase, 0, [&](int x) { return nlev[x]; }, [&](int x, int pre) { tmpP[x] = pre; }, lds);
-    const int Tp = kTile - (lmax - 1);
-    const int ntiles = nbase > 0 ? tmpP[nbase - 1] / Tp + 1 : 0;
+    // chunks of `chunk` physical rows (a divisor of kTile); source row i goes to chunk floor(P_i / Cp)
+    const int Cp = chunk - (lmax - 1);
+    if (Cp < 1) {
+        if (threadIdx.x == 0) atomicMin(&hdr->err, IMUNPACK_ERANGE);
+        return;
+    }
+    const int nchunks = nbase > 0 ? tmpP[nbase - 1] / Cp + 1 : 0;
+    const int kPerTile = kTile / chunk;
+    const int ntiles = (nchunks + kPerTile - 1) / kPerTile;
     const int Mp = ntiles * kTile;
     if (Mp > cap_phys || ntiles + 1 > cap_tiles || base != *count_dev) {
         if (threadIdx.x == 0) {
@@ -659,15 +669,16 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
         }
         return;
     }
-    for (int t = threadIdx.x; t <= ntiles; t += kPlanThreads) {
-        // first i with P_i >= t * Tp
+    for (int ch = threadIdx.x; ch <= ntiles * kPerTile; ch += kPlanThreads) {
+        // first i with P_i >= ch * Cp
         int lo = 0, hi = nbase;
-        const int want = t * Tp;
+        const int want = ch * Cp;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
             if (tmpP[mid] >= want) hi = mid; else lo = mid + 1;
         }
-        lay.tile_src0[t] = (t == ntiles) ? nbase : lo;
+        lay.chunk_src0[ch] = lo;
+        if (ch % kPerTile == 0) lay.tile_src0[ch / kPerTile] = lo;
     }
     __syncthreads();
     for (int t = threadIdx.x; t < ntiles; t += kPlanThreads) {
@@ -690,8 +701,8 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
             pst[u] = 0;
             L[u] = 0;
             if (i < nbase) {
-                const int P = tmpP[i], t = P / Tp;
-                pst[u] = t * kTile + (P - tmpP[lay.tile_src0[t]]);
+                const int P = tmpP[i], ch = P / Cp;
+                pst[u] = ch * chunk + (P - tmpP[lay.chunk_src0[ch]]);
                 L[u] = nlev[i];
                 R[u] = i;
                 lay.src_pstart[i] = pst[u];
@@ -929,8 +940,9 @@ __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr) {
     __shared__ int lds[40];
     if (hdr->overflow) return;
-    if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, lds);
-    else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, lds);
+    // rows of A: the GEMM epilogue folds them chunk by chunk; rows of B (columns of C): tile by tile
+    if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, kChunk, lds);
+    else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, kTile, lds);
     else {
         cols_layout(c1, c2, cols, d, cap_physC, s, sh, tmpE, tmpK, tmpR, tmpOff, hdr, lds, (int)blockIdx.x - 2);
         if (blockIdx.x == 2 && threadIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
@@ -964,7 +976,7 @@ static void carve_slots(Carver &cv, SlotSet &s, int cap) {
     s.cap = cap;
 }
 
-static inline int phys_cap_rows(int cap) { return (int)((int64_t)cap * kTile / (kTile - 32) + 2 * kTile); }
+static inline int phys_cap_rows(int cap) { return (int)((int64_t)cap * kChunk / (kChunk - 8) + 2 * kTile); }
 static inline int phys_cap_cols(int cap) { return cap + kMaxGroups * kKPad; }
 
 // Lays every device array out in the arena for the current capacities; returns the bytes needed.
@@ -987,6 +999,7 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         l.src_pstart = cv.take<int32_t>(nb + 1);
         l.src_nlev = cv.take<int32_t>(nb + 1);
         l.tile_src0 = cv.take<int32_t>(pc / kTile + 2);
+        l.chunk_src0 = cv.take<int32_t>(pc / kChunk + 8);
         l.tile_flat = cv.take<int32_t>(pc / kTile + 2);
     }
     {
@@ -1153,6 +1166,26 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     return launch_status();
 }
 
+int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st) {
+    if (!p->pin_hdr || offset + bytes > sizeof(PlanHeader)) return IMUNPACK_EINVAL;
+    char *pin = reinterpret_cast<char *>(p->pin_hdr) + offset;
+    IMU_HIP(hipMemcpyAsync(pin, reinterpret_cast<const char *>(p->d_hdr) + offset, bytes, hipMemcpyDeviceToHost, st));
+    IMU_HIP(hipEventRecord(p->ready, st));
+    hipError_t e = hipErrorNotReady;
+    for (long spin = 0; spin < 20000000 && e == hipErrorNotReady; ++spin) e = hipEventQuery(p->ready);
+    if (e == hipErrorNotReady) {  // a very long plan: stop burning the core
+        (void)hipGetLastError();
+        e = hipEventSynchronize(p->ready);
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return IMUNPACK_EHIP;
+    }
+    memcpy(reinterpret_cast<char *>(&p->hdr) + offset, pin, bytes);
+    return IMUNPACK_OK;
+}
+
 }  // namespace imu
 
 using namespace imu;
@@ -1171,6 +1204,13 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         p = new (std::nothrow) Plan();
         if (!p) return IMUNPACK_ENOMEM;
         memset(p, 0, sizeof(*p));
+        if (hipHostMalloc((void **)&p->pin_hdr, sizeof(PlanHeader), hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&p->ready, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            if (p->pin_hdr) (void)hipHostFree(p->pin_hdr);
+            delete p;
+            return IMUNPACK_ENOMEM;
+        }
     }
     const bool same = p->valid && p->n == n && p->d == d && p->h == h && p->b == b && p->sA == strategy_A &&
                       p->sB == strategy_B;
@@ -1212,9 +1252,8 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         if (!ownB) { p->statsB[0] = stats_B->rowcnt; p->statsB[1] = stats_B->colcnt; p->statsB[2] = stats_B->rowmax; p->statsB[3] = stats_B->colmax; }
         rc = enqueue_plan(p, A, lda, B, ldb, stats_A, stats_B, ownA, ownB, st);
         if (rc != IMUNPACK_OK) break;
-        hipError_t e = hipMemcpyAsync(&p->hdr, p->d_hdr, sizeof(PlanHeader), hipMemcpyDeviceToHost, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);
-        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; break; }
+        rc = fetch_header(p, 0, sizeof(PlanHeader), st);
+        if (rc != IMUNPACK_OK) break;
         if (p->hdr.err) { rc = p->hdr.err; break; }
         if (!p->hdr.overflow) {
             p->valid = 1;
@@ -1235,7 +1274,12 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         rc = IMUNPACK_ENOMEM;  // stays if the attempts run out
     }
     if (rc != IMUNPACK_OK && !p->valid) {
-        if (!*plan) { if (p->arena) (void)hipFree(p->arena); delete p; }
+        if (!*plan) {
+            if (p->arena) (void)hipFree(p->arena);
+            (void)hipEventDestroy(p->ready);
+            (void)hipHostFree(p->pin_hdr);
+            delete p;
+        }
         return rc;
     }
     *plan = p;
@@ -1386,6 +1430,8 @@ extern "C" int imunpack_plan_destroy(imunpack_plan_t *p) {
         hipError_t e = hipFree(p->arena);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; }
     }
+    if (p->ready) (void)hipEventDestroy(p->ready);
+    if (p->pin_hdr) (void)hipHostFree(p->pin_hdr);
     delete p;
     return rc;
 }

@@ -15,6 +15,8 @@
 //     former, fixup_kernel then places the higher digits of the listed OB entries.
 #include "common.h"
 
+#include <cstddef>
+
 namespace imu {
 
 // One workgroup handles kScatterRows consecutive physical rows and walks the source in windows of
@@ -366,8 +368,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1]), dim3(256), 0, st, fx[0], fx[1], fblocks[0]);
     }
     IMU_TRY(launch_status());
-    IMU_HIP(hipMemcpyAsync(p->hdr.bound, p->d_hdr->bound, sizeof(p->hdr.bound), hipMemcpyDeviceToHost, st));
-    IMU_HIP(hipStreamSynchronize(st));
+    IMU_TRY(fetch_header(p, offsetof(PlanHeader, bound), sizeof(p->hdr.bound), st));
     // |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound_A, bound_B): the shifted sum of all groups
     // fits int32 iff that is below 2^31.
     const unsigned long long m = p->hdr.bound[0] < p->hdr.bound[1] ? p->hdr.bound[0] : p->hdr.bound[1];
