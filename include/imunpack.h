@@ -96,7 +96,9 @@ int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int
  * Decides every row / column split for A (with B as partner) and then for B (with A_u as partner
  * and S_u carried over) without moving the operands.  A: n x d, B: h x d, int32, device.
  * stats_A / stats_B: statistics of A / B for this b as written by imunpack_quantize or
- * imunpack_scan; NULL lets the call scan the operand itself.
+ * imunpack_scan; NULL lets the call scan the operand itself.  For an UnpackBoth operand the OB
+ * entry list of its statistics is used if it is complete, and copied: nothing of stats_A / stats_B
+ * is read after the call returns.
  * *plan == NULL creates a plan object; a non-NULL *plan is re-planned in place and its device
  * buffers are reused (they only grow), so that steady-state calls allocate nothing.
  * Synchronises the stream (the sizes n', d', h' are needed on the host).
@@ -126,7 +128,8 @@ int imunpack_plan_destroy(imunpack_plan_t *plan);
 
 /* ---- (4) digit scatter (Eq. (mod); Alg. 1 l.4-5, Alg. 2 l.4-6, Alg. 4 l.7-8, 11-13) -----------
  * Writes A_ue and B_eu as int8 in the plan's *physical* layout: rows grouped by source row (all
- * digit levels of a row inside one GEMM tile), columns grouped by diagonal entry of S_uu, both
+ * digit levels of a row of A inside one 64-row chunk of a GEMM tile, of a row of B inside one tile),
+ * columns grouped by diagonal entry of S_uu and ordered by source column inside a group, both
  * zero-padded to tile multiples.  The partner's columns are duplicated where a column was split.
  * imunpack_unpacked_bytes gives the buffer sizes and the workspace an un-fused GEMM needs.
  * A, B: the int32 operands the plan was made from.  A_ue, B_eu: device, caller-allocated.
