@@ -48,7 +48,8 @@ struct ScatterArgs {
 
 template <bool DENSE>
 __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a) {
-    __shared__ __attribute__((aligned(16))) int32_t tile[kScatterRows][kScatterWin];
+    // rows padded by 16 bytes: lanes that read the same columns of different rows hit different banks
+    __shared__ __attribute__((aligned(16))) int32_t tile[kScatterRows][kScatterWin + 4];
     __shared__ int s_slot[kScatterRows], s_src[kScatterRows], s_er[kScatterRows], s_trow[kScatterRows];
     __shared__ unsigned long long s_wsum[kScatterRows];
     __shared__ int s_u0[kMaxGroups + 1], s_ucount[kMaxGroups + 1], s_total;
@@ -113,12 +114,25 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
         __syncthreads();
         const int kbase = w * kScatterWin;
         const int total = s_total;
-        // work items: (unit, half of the block's rows), flattened over the groups
-        for (int item = threadIdx.x; item < 2 * total; item += kScatterThreads) {
-            int ui = item >> 1, g = 0;
+        // work items: (unit, half of the block's rows), flattened over the groups; the last, partial
+        // round of such items is dealt out row by row instead, so that it costs one row per thread
+        // rather than four
+        const int n4 = 2 * total, full = n4 / kScatterThreads * kScatterThreads;
+        const int nitems = full + (n4 - full) * (kScatterRows / 2);
+        for (int item = threadIdx.x; item < nitems; item += kScatterThreads) {
+            int it4 = item, rbeg, rcount;
+            if (item < full) {
+                rbeg = (item & 1) * (kScatterRows / 2);
+                rcount = kScatterRows / 2;
+            } else {
+                const int t = item - full;
+                it4 = full + t / (kScatterRows / 2);
+                rbeg = (it4 & 1) * (kScatterRows / 2) + t % (kScatterRows / 2);
+                rcount = 1;
+            }
+            int ui = it4 >> 1, g = 0;
             while (ui >= s_ucount[g]) ui -= s_ucount[g++];
             const int unit = s_u0[g] + ui, q0 = unit * 16;
-            const int rbeg = (item & 1) * (kScatterRows / 2);
             const int4 ud = a.unit_desc[unit];
             const int kmin = ud.x, kmax = ud.y;
             const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
@@ -147,7 +161,7 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
                 for (int j = 0; j < 16; ++j) ec[j] = ecu;
             }
 #pragma unroll 1
-            for (int rr = 0; rr < kScatterRows / 2; ++rr) {
+            for (int rr = 0; rr < rcount; ++rr) {
                 const int r = rbeg + rr;
                 const int slot = s_slot[r];
                 if (slot == -2) break;  // past the last physical row
