@@ -155,10 +155,16 @@ def main():
             bufs["B"] = torch.empty(bb, dtype=torch.int8, device=dev)
         imu.imunpack_unpack(plan, Qa, Qb, bufs["A"], bufs["B"])
         mark(3)
-        if not plan.fusable() and (bufs["ws"] is None or bufs["ws"].numel() * 8 < bw):
-            bufs["ws"] = torch.empty(bw // 8, dtype=torch.int64, device=dev)
         mark(4)
-        imu.imunpack_gemm(plan, bufs["A"], bufs["B"], w.scale_a, w.scale_b, C_int, C_fp, bufs["ws"], fuse=True)
+        # The fused launch goes out before the host knows whether it is exact; only if it was not (and
+        # no workspace was at hand for the fallback) does the call report ERANGE.
+        try:
+            imu.imunpack_gemm(plan, bufs["A"], bufs["B"], w.scale_a, w.scale_b, C_int, C_fp, bufs["ws"], fuse=True)
+        except imu.ImunpackError as e:
+            if e.code != imu.ERANGE:
+                raise
+            bufs["ws"] = torch.empty(bw // 8, dtype=torch.int64, device=dev)
+            imu.imunpack_gemm(plan, bufs["A"], bufs["B"], w.scale_a, w.scale_b, C_int, C_fp, bufs["ws"], fuse=True)
         mark(5)
 
     for _ in range(args.warmup):

@@ -133,8 +133,8 @@ int imunpack_plan_destroy(imunpack_plan_t *plan);
  * zero-padded to tile multiples.  The partner's columns are duplicated where a column was split.
  * imunpack_unpacked_bytes gives the buffer sizes and the workspace an un-fused GEMM needs.
  * A, B: the int32 operands the plan was made from.  A_ue, B_eu: device, caller-allocated.
- * imunpack_unpack synchronises the stream once at its end (it returns the accumulator bound that
- * selects the GEMM path to the host). */
+ * imunpack_unpack does not wait for the device: the accumulator bounds that select the GEMM path
+ * reach the host later, and imunpack_gemm / imunpack_plan_fusable wait for them. */
 int imunpack_unpacked_bytes(const imunpack_plan_t *plan, size_t *bytes_A, size_t *bytes_B,
                             size_t *bytes_workspace);
 int imunpack_unpack(imunpack_plan_t *plan, const int32_t *A, int64_t lda,
@@ -175,7 +175,8 @@ const char *imunpack_strerror(int code);
 int imunpack_last_hip_error(void);
 
 /* Which GEMM path the plan's last imunpack_unpack selected: 1 = single fused launch is exact,
- * 0 = the shifted group sum may exceed int32 and the un-fused path is required. */
+ * 0 = the shifted group sum may exceed int32 and the un-fused path is required.  Waits for that
+ * unpack to finish on the device. */
 int imunpack_plan_fusable(const imunpack_plan_t *plan);
 
 /* Measured matrix-core peak (benchmark reporting only, not part of the method): launches

@@ -122,6 +122,11 @@ struct imunpack_plan {
     imu::PlanHeader hdr;          // host mirror
     imu::PlanHeader *pin_hdr;     // pinned staging copy of the header (device-to-host copies land here)
     hipEvent_t ready;             // recorded after such a copy; the host polls it
+    hipStream_t side;             // carries the copy of the accumulator bounds, so that the caller's stream
+                                  // can already hold the GEMM while the host waits for them
+    hipEvent_t scattered;         // recorded on the caller's stream after the scatter; `side` waits for it
+    int bound_pending;            // the bounds of the last imunpack_unpack have not been read back yet
+    int guess_fusable;            // whether the fused GEMM was exact for this plan object the last time
     imu::SlotSet rowA, rowB, c1, c2;
     imu::RowLayout layA, layB;
     imu::ColLayout cols;
@@ -151,4 +156,6 @@ using Plan = struct ::imunpack_plan;  // the C function imunpack_plan() hides th
 // The wait polls an event instead of blocking in the driver: the wake-up of a blocking wait costs
 // tens of microseconds during which the GPU idles between two stages of the path.
 int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st);
+// Waits for the bounds that imunpack_unpack left in flight and sets p->fusable.
+int resolve_bound(Plan *p);
 }

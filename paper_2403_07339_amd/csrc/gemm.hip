@@ -49,6 +49,10 @@ struct GemmArgs {
     int64_t *C_u;
     int Np;
     int seg_shift, seg_first;
+    // fused launch made before the host knows the accumulator bounds: the kernel checks them itself
+    // and writes nothing if the shifted group sum could leave int32
+    const unsigned long long *guard;
+    int guard_mul;            // s - 1
 };
 
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2,
@@ -94,6 +98,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #ifdef IMU_GEMM_DIAG
     constexpr int g_diag = IMU_GEMM_DIAG;  // diagnostics build only (wrong results by design)
 #endif
+    if (MODE == 0 && g.guard) {
+        const unsigned long long b0 = g.guard[0], b1 = g.guard[1];
+        const unsigned long long m = b0 < b1 ? b0 : b1;
+        if (!(m < (1ull << 40) && m * (unsigned long long)g.guard_mul < (1ull << 31))) return;
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -520,10 +529,11 @@ extern "C" int imunpack_recombine(const imunpack_plan_t *p, const void *workspac
     return launch_status();
 }
 
-extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
+extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, const int8_t *B_eu,
                              void *workspace, int64_t *C_int, float *C_fp, int64_t ldc, float scale_A,
                              float scale_B, int fuse, imunpack_stream_t stream) {
-    if (!p || !p->valid || !p->unpacked || !A_ue || !B_eu) return IMUNPACK_EINVAL;
+    if (!cp || !cp->valid || !cp->unpacked || !A_ue || !B_eu) return IMUNPACK_EINVAL;
+    Plan *p = const_cast<Plan *>(cp);
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (h.mtiles <= 0 || h.ntiles <= 0) return IMUNPACK_OK;
@@ -539,12 +549,22 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
     g.Np = h.Np;
     const int grid = h.mtiles * h.ntiles;
     bool fused = fuse != 0;
-    if (fused && !p->fusable) {
-        if (!workspace) return IMUNPACK_ERANGE;
-        fused = false;
+    // The bounds of the last imunpack_unpack may still be on their way to the host.  If the fused
+    // launch was exact for this plan object the last time, it goes out now with a guard (the kernel
+    // checks the bounds on the device and writes nothing if they are too large), and only then does
+    // the host wait: the GPU does not idle while the answer travels.
+    const bool speculate = fused && p->bound_pending && p->guess_fusable;
+    if (!speculate) {
+        IMU_TRY(resolve_bound(p));
+        if (fused && !p->fusable) {
+            if (!workspace) return IMUNPACK_ERANGE;
+            fused = false;
+        }
     }
     if (fused) {
         if ((!C_int && !C_fp) || ldc < p->h) return IMUNPACK_EINVAL;
+        g.guard = speculate ? p->d_hdr->bound : nullptr;
+        g.guard_mul = p->s - 1;
         g.kt0 = 0; g.kt1 = h.Kp / BK;
         g.nbound = 0;
         for (int q = 0; q + 1 < h.ngroups; ++q) {
@@ -556,7 +576,12 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *p, const int8_t *A_ue, const
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
         hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
-        return launch_status();
+        IMU_TRY(launch_status());
+        if (!speculate) return IMUNPACK_OK;
+        IMU_TRY(resolve_bound(p));
+        if (p->fusable) return IMUNPACK_OK;
+        if (!workspace) return IMUNPACK_ERANGE;  // the guarded launch wrote nothing
+        g.guard = nullptr;
     }
     if (!workspace) return IMUNPACK_EINVAL;
     g.C_u = (int64_t *)workspace;

@@ -1166,11 +1166,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     return launch_status();
 }
 
-int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st) {
-    if (!p->pin_hdr || offset + bytes > sizeof(PlanHeader)) return IMUNPACK_EINVAL;
-    char *pin = reinterpret_cast<char *>(p->pin_hdr) + offset;
-    IMU_HIP(hipMemcpyAsync(pin, reinterpret_cast<const char *>(p->d_hdr) + offset, bytes, hipMemcpyDeviceToHost, st));
-    IMU_HIP(hipEventRecord(p->ready, st));
+int poll_ready(Plan *p) {
     hipError_t e = hipErrorNotReady;
     for (long spin = 0; spin < 20000000 && e == hipErrorNotReady; ++spin) e = hipEventQuery(p->ready);
     if (e == hipErrorNotReady) {  // a very long plan: stop burning the core
@@ -1182,6 +1178,15 @@ int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st) {
         (void)hipGetLastError();
         return IMUNPACK_EHIP;
     }
+    return IMUNPACK_OK;
+}
+
+int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st) {
+    if (!p->pin_hdr || offset + bytes > sizeof(PlanHeader)) return IMUNPACK_EINVAL;
+    char *pin = reinterpret_cast<char *>(p->pin_hdr) + offset;
+    IMU_HIP(hipMemcpyAsync(pin, reinterpret_cast<const char *>(p->d_hdr) + offset, bytes, hipMemcpyDeviceToHost, st));
+    IMU_HIP(hipEventRecord(p->ready, st));
+    IMU_TRY(poll_ready(p));
     memcpy(reinterpret_cast<char *>(&p->hdr) + offset, pin, bytes);
     return IMUNPACK_OK;
 }
@@ -1205,13 +1210,20 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         if (!p) return IMUNPACK_ENOMEM;
         memset(p, 0, sizeof(*p));
         if (hipHostMalloc((void **)&p->pin_hdr, sizeof(PlanHeader), hipHostMallocDefault) != hipSuccess ||
-            hipEventCreateWithFlags(&p->ready, hipEventDisableTiming) != hipSuccess) {
+            hipEventCreateWithFlags(&p->ready, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&p->scattered, hipEventDisableTiming) != hipSuccess ||
+            hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking) != hipSuccess) {
             (void)hipGetLastError();
+            if (p->side) (void)hipStreamDestroy(p->side);
+            if (p->scattered) (void)hipEventDestroy(p->scattered);
+            if (p->ready) (void)hipEventDestroy(p->ready);
             if (p->pin_hdr) (void)hipHostFree(p->pin_hdr);
             delete p;
             return IMUNPACK_ENOMEM;
         }
+        p->guess_fusable = 1;
     }
+    if (p->bound_pending) (void)resolve_bound(p);  // a copy into the header mirror is still in flight
     const bool same = p->valid && p->n == n && p->d == d && p->h == h && p->b == b && p->sA == strategy_A &&
                       p->sB == strategy_B;
     p->valid = 0;
@@ -1276,6 +1288,8 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
     if (rc != IMUNPACK_OK && !p->valid) {
         if (!*plan) {
             if (p->arena) (void)hipFree(p->arena);
+            (void)hipStreamDestroy(p->side);
+            (void)hipEventDestroy(p->scattered);
             (void)hipEventDestroy(p->ready);
             (void)hipHostFree(p->pin_hdr);
             delete p;
@@ -1430,6 +1444,9 @@ extern "C" int imunpack_plan_destroy(imunpack_plan_t *p) {
         hipError_t e = hipFree(p->arena);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; }
     }
+    if (p->bound_pending) (void)resolve_bound(p);
+    if (p->side) (void)hipStreamDestroy(p->side);
+    if (p->scattered) (void)hipEventDestroy(p->scattered);
     if (p->ready) (void)hipEventDestroy(p->ready);
     if (p->pin_hdr) (void)hipHostFree(p->pin_hdr);
     delete p;

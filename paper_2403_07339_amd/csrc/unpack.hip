@@ -15,7 +15,10 @@
 //     former, fixup_kernel then places the higher digits of the listed OB entries.
 #include "common.h"
 
+namespace imu { int poll_ready(Plan *p); }
+
 #include <cstddef>
+#include <cstring>
 
 namespace imu {
 
@@ -335,6 +338,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     if (!p || !p->valid || !A || !B || !A_ue || !B_eu || lda < p->d || ldb < p->d) return IMUNPACK_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
+    if (p->bound_pending) IMU_TRY(resolve_bound(p));  // of an earlier unpack of this plan
     // the planner leaves the bounds cleared; a repeated unpack of the same plan clears them again
     if (p->unpacked) hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
     FixupArgs fx[2] = {};
@@ -382,17 +386,38 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1]), dim3(256), 0, st, fx[0], fx[1], fblocks[0]);
     }
     IMU_TRY(launch_status());
-    IMU_TRY(fetch_header(p, offsetof(PlanHeader, bound), sizeof(p->hdr.bound), st));
-    // |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound_A, bound_B): the shifted sum of all groups
-    // fits int32 iff that is below 2^31.
-    const unsigned long long m = p->hdr.bound[0] < p->hdr.bound[1] ? p->hdr.bound[0] : p->hdr.bound[1];
-    p->fusable = (m < (1ull << 40)) && (m * (unsigned long long)(p->s - 1) < (1ull << 31));
+    // The bounds travel to the host on the plan's side stream, behind the scatter: the caller's stream is
+    // free to take the GEMM at once (imunpack_gemm launches it guarded and then waits for the bounds).
+    IMU_HIP(hipEventRecord(p->scattered, st));
+    IMU_HIP(hipStreamWaitEvent(p->side, p->scattered, 0));
+    IMU_HIP(hipMemcpyAsync(reinterpret_cast<char *>(p->pin_hdr) + offsetof(PlanHeader, bound),
+                           reinterpret_cast<const char *>(p->d_hdr) + offsetof(PlanHeader, bound),
+                           sizeof(p->hdr.bound), hipMemcpyDeviceToHost, p->side));
+    IMU_HIP(hipEventRecord(p->ready, p->side));
+    p->bound_pending = 1;
     p->unpacked = 1;
     return IMUNPACK_OK;
 }
 
-extern "C" int imunpack_plan_fusable(const imunpack_plan_t *p) {
-    if (!p || !p->valid || !p->unpacked) return 0;
+namespace imu {
+int resolve_bound(Plan *p) {
+    if (!p->bound_pending) return IMUNPACK_OK;
+    p->bound_pending = 0;
+    IMU_TRY(poll_ready(p));
+    memcpy(p->hdr.bound, p->pin_hdr->bound, sizeof(p->hdr.bound));
+    // |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound_A, bound_B): the shifted sum of all groups
+    // fits int32 iff that is below 2^31.
+    const unsigned long long m = p->hdr.bound[0] < p->hdr.bound[1] ? p->hdr.bound[0] : p->hdr.bound[1];
+    p->fusable = (m < (1ull << 40)) && (m * (unsigned long long)(p->s - 1) < (1ull << 31));
+    p->guess_fusable = p->fusable;
+    return IMUNPACK_OK;
+}
+}  // namespace imu
+
+extern "C" int imunpack_plan_fusable(const imunpack_plan_t *cp) {
+    if (!cp || !cp->valid || !cp->unpacked) return 0;
+    Plan *p = const_cast<Plan *>(cp);
+    if (resolve_bound(p) != IMUNPACK_OK) return 0;
     return p->fusable;
 }
 

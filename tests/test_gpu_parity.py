@@ -258,3 +258,28 @@ def test_run_to_run_determinism(imu):
         else:
             for a, b in zip(first, cur):
                 assert a.shape == b.shape and torch.equal(a, b)
+
+
+def test_fused_launch_before_the_bounds_are_known(imu):
+    """imunpack_unpack leaves the accumulator bounds in flight and a fused imunpack_gemm goes out
+    guarded before the host has them.  On data whose shifted group sum does not fit int32 the guarded
+    launch must write nothing: without a workspace the call reports ERANGE, with one it falls back to
+    the un-fused path and the result is exact."""
+    rng = np.random.default_rng(5)
+    Aq = rng.integers(-(1 << 22), 1 << 22, size=(96, 320)).astype(np.int32)
+    Bq = rng.integers(-(1 << 22), 1 << 22, size=(80, 320)).astype(np.int32)
+    want = oracle.int_gemm(Aq, Bq)
+    Qa, Qb = torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda()
+    plan = imu.imunpack_plan(Qa, Qb, 8, ROW, COL)   # a new plan object guesses "fused"
+    A_ue, B_eu = imu.imunpack_unpack(plan, Qa, Qb)
+    C_int = torch.full(want.shape, -7, dtype=torch.int64, device="cuda")
+    with pytest.raises(imu.ImunpackError) as err:
+        imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C_int, None, None, fuse=True)
+    assert err.value.code == imu.ERANGE
+    assert not plan.fusable()
+    assert bool((C_int == -7).all()), "the guarded launch must not have written anything"
+    plan2 = imu.imunpack_plan(Qa, Qb, 8, ROW, COL)
+    A2, B2 = imu.imunpack_unpack(plan2, Qa, Qb)
+    ws = torch.empty(plan2.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+    imu.imunpack_gemm(plan2, A2, B2, 1.0, 1.0, C_int, None, ws, fuse=True)   # guarded launch, then the fallback
+    assert np.array_equal(C_int.cpu().numpy(), want)
