@@ -244,6 +244,114 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
 }
 
+// Transposed input (unit stride down the rows of the operand, as for a weight-gradient GEMM that
+// contracts over tokens).  Workgroup = 128 x 128 tile: it is read along the input's contiguous axis
+// (512 bytes per column and instruction), quantised, staged in LDS column-major, and then written
+// and scanned row by row exactly as on the fast path (512 bytes of Q per row).
+constexpr int kTrTile = 128, kTrPitch = kTrTile + 1;
+
+template <bool FROM_FLOAT>
+__global__ __launch_bounds__(256) void qscan_tr_kernel(const void *__restrict__ Xv, int64_t rows, int64_t cols,
+                                                       int64_t sx_c, float scale, int s,
+                                                       int32_t *__restrict__ Q, int64_t ldq, int32_t *rowcnt,
+                                                       int32_t *colcnt, int32_t *rowmax, int32_t *colmax,
+                                                       int32_t *status, int32_t *ob, int ob_cap,
+                                                       int32_t *ob_count) {
+    __shared__ int32_t tile[kTrTile * kTrPitch];  // [column][row]
+    __shared__ ObStage stage;
+    if (ob && threadIdx.x == 0) stage.count = 0;  // published by the barrier after the tile is filled
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int64_t r0 = (int64_t)blockIdx.x * kTrTile, c0 = (int64_t)blockIdx.y * kTrTile;
+    int bad = 0;
+    // ---- read: wave w takes columns [32w, 32w+32), two per instruction, four rows per lane
+    const int64_t rl = r0 + 4 * l32;  // rows % 4 == 0 on this path
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const int cc = 32 * wave + 2 * it + half;
+        const int64_t c = c0 + cc;
+        int4 raw = make_int4(0, 0, 0, 0);
+        const bool ok = c < cols && rl < rows;
+        if (ok) raw = *reinterpret_cast<const int4 *>(reinterpret_cast<const int32_t *>(Xv) + c * sx_c + rl);
+        int q[4] = {raw.x, raw.y, raw.z, raw.w};
+        if (FROM_FLOAT && ok) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q[i] = rtn_one(__int_as_float(q[i]), scale, bad);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[cc * kTrPitch + 4 * l32 + i] = q[i];
+    }
+    __syncthreads();
+    // ---- write and scan: wave w takes rows [32w, 32w+32), two per instruction, four columns per lane
+    int ccnt[4] = {0, 0, 0, 0}, cmax[4] = {0, 0, 0, 0};
+    const int64_t cl = c0 + 4 * l32;  // cols % 4 == 0 on this path
+    const unsigned long long mine = half ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull;
+    for (int it = 0; it < 16; ++it) {
+        const int rr = 32 * wave + 2 * it + half;
+        const int64_t r = r0 + rr;
+        const bool ok = r < rows && cl < cols;
+        int q[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = tile[(4 * l32 + i) * kTrPitch + rr];
+        if (FROM_FLOAT && ok) *reinterpret_cast<int4 *>(Q + r * ldq + cl) = make_int4(q[0], q[1], q[2], q[3]);
+        int a[4], o[4];
+        int rm = 0, any = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = ok ? iabs_sat(q[i]) : 0;
+            o[i] = a[i] >= s;
+            ccnt[i] += o[i];
+            cmax[i] = max(cmax[i], a[i]);
+            rm = max(rm, a[i]);
+            any |= o[i];
+        }
+        if (rowcnt || rowmax) {
+            int rc = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rc += __popcll(__ballot(o[i]) & mine);
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) rm = max(rm, __shfl_xor(rm, off, 64));  // inside the half-wave
+            if (l32 == 0 && r < rows) {
+                if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
+                if (rowmax && rm) atomicMax(&rowmax[r], rm);
+            }
+        }
+        if (ob && any) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (o[i])
+                    ob_push(&stage, atomicAdd(&stage.count, 1), (int32_t)r, (int32_t)(cl + i), q[i], ob, ob_cap,
+                            ob_count);
+        }
+    }
+    if (ob) ob_flush(&stage, ob, ob_cap, ob_count);
+    if (colcnt || colmax) {
+        __syncthreads();  // the tile has been consumed: its memory takes the column partials
+        int32_t *part = tile;  // [2][8 half-waves][128 columns]
+        const int hw = 2 * wave + half;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            part[(0 * 8 + hw) * kTrTile + 4 * l32 + i] = ccnt[i];
+            part[(1 * 8 + hw) * kTrTile + 4 * l32 + i] = cmax[i];
+        }
+        __syncthreads();
+        if (threadIdx.x < kTrTile) {
+            int cnt = 0, mx = 0;
+#pragma unroll
+            for (int w8 = 0; w8 < 8; ++w8) {
+                cnt += part[(0 * 8 + w8) * kTrTile + threadIdx.x];
+                mx = max(mx, part[(1 * 8 + w8) * kTrTile + threadIdx.x]);
+            }
+            const int64_t col = c0 + threadIdx.x;
+            if (col < cols) {
+                if (colcnt && cnt) atomicAdd(&colcnt[col], cnt);
+                if (colmax && mx) atomicMax(&colmax[col], mx);
+            }
+        }
+    }
+    if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
+}
+
 // Clears up to six int32 arrays in one launch.
 struct ZeroList {
     int32_t *p[6];
@@ -306,6 +414,11 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
         hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
                            scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count,
                            (int)rpw);
+    } else if (sx_r == 1 && (rows % 4) == 0 && (cols % 4) == 0 && (sx_c % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
+               (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0)) && (cols + kTrTile - 1) / kTrTile <= 65535) {
+        dim3 grid((unsigned)((rows + kTrTile - 1) / kTrTile), (unsigned)((cols + kTrTile - 1) / kTrTile));
+        hipLaunchKernelGGL(qscan_tr_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_c, scale, s, Q,
+                           ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     } else {
         dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
         hipLaunchKernelGGL(qscan_tile_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
