@@ -52,7 +52,7 @@ def cpu_baseline(w, budget_rows: int = 4096):
                       f"fp64 dequantise of the first {rows} of {w.n} rows of A against all of B {t3 - t2:.1f} s"}
 
 
-def measure_extras(torch, imu, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args):
+def measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args):
     """Untimed side measurements reported beside the headline: the two quantize calls on their own, this
     library's GEMM on the original shape with operands clipped to int8 (what one pays without
     exactness), and the measured peaks of the matrix cores and of a device-to-device copy."""
@@ -82,6 +82,10 @@ def measure_extras(torch, imu, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args):
         ops[0] = imu.imunpack_diag_mfma_peak(256 * 4, 4000)
     ms = timed(peak, 3)
     res["mfma_peak_tops"] = ops[0] / ms / 1e9
+    _, ratios, best = imu.imunpack_price(st_a, w.n, st_b, w.h, w.d, w.b)
+    names = workloads.STRATEGY_NAMES
+    res["priced_r"] = {f"{names[p[0]]}/{names[p[1]]}": r for p, r in ratios.items()}
+    res["priced_best"] = f"{names[best[0]]}/{names[best[1]]}"
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
     dst = torch.empty_like(src)
     ms = timed(lambda: dst.copy_(src), 5)
@@ -179,7 +183,7 @@ def main():
 
     ms_step = dt * 1e3 / args.steps
     stage_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / args.steps for i in range(5)]
-    extra = measure_extras(torch, imu, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
+    extra = measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
     n_u, d_u, h_u, ng = plan.dims()
     ba, bb, _ = plan.unpacked_bytes()
     gemm_ms = stage_ms[4]
@@ -209,6 +213,8 @@ def main():
                      "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
     }
     out["unpack"]["time_ratio_vs_plain_int8_gemm"] = ms_step / extra["plain_gemm_ms"]
+    out["unpack"]["priced_r_one_axis_pairs"] = extra["priced_r"]   # from the scan statistics alone (Sec. 4.2, "Mix")
+    out["unpack"]["priced_best_one_axis_pair"] = extra["priced_best"]
     out["plain_int8_gemm"] = {"ms": extra["plain_gemm_ms"], "TOPS": w.ops / extra["plain_gemm_ms"] / 1e9,
                               "note": "this library's GEMM on the original shape, operands clipped to int8 (not exact)"}
     out["stage_ms"]["quantize+scan A"] = extra["quant_a_ms"]

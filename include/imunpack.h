@@ -92,6 +92,21 @@ int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int64_t sx_r, 
 int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
                   const imunpack_stats_t *stats, imunpack_stream_t stream);
 
+/* ---- strategy choice (Sec. 4.2, unpack ratio r = n'd'h' / (ndh); the "Mix" rows of its tables) -
+ * Prices the four pairs of the one-axis strategies from the scan statistics alone, without
+ * unpacking: UnpackRow / UnpackColumn append one slot per further digit of the largest magnitude of
+ * a row / column, so n', d', h' follow from rowmax / colmax (for UnpackColumn on both operands a
+ * column k of A with LA digits meets LB digits of column k of B: LA * LB columns).
+ * stats_A, stats_B: device, rowmax and colmax required.  dims_out (host, may be NULL):
+ * [pair][3] = n', d', h' for the pairs (strategy_A, strategy_B) = (ROW,ROW), (ROW,COL), (COL,ROW),
+ * (COL,COL); ratio_out (host, may be NULL): their r.  best_A / best_B (host, may be NULL): the
+ * pair with the smallest r (first in that order on ties).  UnpackBoth is priced by planning with
+ * it (imunpack_plan + imunpack_plan_dims).  Synchronises the stream.
+ * Errors: EINVAL, ERANGE (a size does not fit int64), EHIP. */
+int imunpack_price(const imunpack_stats_t *stats_A, int64_t n, const imunpack_stats_t *stats_B,
+                   int64_t h, int64_t d, int b, int64_t *dims_out, double *ratio_out,
+                   int *best_A, int *best_B, imunpack_stream_t stream);
+
 /* ---- (3) unpack plan (Alg. 1, 2, 4, 5 and the two-operand composition of Sec. 4) -------------
  * Decides every row / column split for A (with B as partner) and then for B (with A_u as partner
  * and S_u carried over) without moving the operands.  A: n x d, B: h x d, int32, device.

@@ -26,7 +26,7 @@ EXPORTS = [
     "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
-    "imunpack_plan_fusable", "imunpack_diag_mfma_peak",
+    "imunpack_plan_fusable", "imunpack_diag_mfma_peak", "imunpack_price",
 ]
 
 
@@ -52,6 +52,8 @@ _lib.imunpack_strerror.argtypes = [_i32]
 _lib.imunpack_strerror.restype = C.c_char_p
 _lib.imunpack_plan_fusable.argtypes = [_vp]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
+_lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
+                                C.POINTER(C.c_double), C.POINTER(_i32), C.POINTER(_i32), _vp]
 for _name in EXPORTS:
     if _name != "imunpack_strerror":
         getattr(_lib, _name).restype = C.c_int
@@ -286,3 +288,18 @@ def imunpack_diag_mfma_peak(workgroups: int, iters: int) -> int:
     ops = _i64(0)
     _check(_lib.imunpack_diag_mfma_peak(int(workgroups), int(iters), C.byref(ops), _stream()), "imunpack_diag_mfma_peak")
     return int(ops.value)
+
+
+def imunpack_price(stats_a: Stats, n: int, stats_b: Stats, h: int, d: int, b: int):
+    """Prices the four pairs of one-axis strategies from the scan statistics (no unpacking).  Returns
+    (dims, ratios, best): dims[(sA, sB)] = (n', d', h'), ratios[(sA, sB)] = r, best = the pair with
+    the smallest r."""
+    dims = (_i64 * 12)()
+    ratios = (C.c_double * 4)()
+    ba, bb = _i32(0), _i32(0)
+    ca, cb = stats_a._c(), stats_b._c()
+    _check(_lib.imunpack_price(C.byref(ca), n, C.byref(cb), h, d, b, dims, ratios, C.byref(ba), C.byref(bb),
+                               _stream()), "imunpack_price")
+    pairs = [(ROW, ROW), (ROW, COL), (COL, ROW), (COL, COL)]
+    return ({p: tuple(int(dims[3 * q + c]) for c in range(3)) for q, p in enumerate(pairs)},
+            {p: float(ratios[q]) for q, p in enumerate(pairs)}, (int(ba.value), int(bb.value)))

@@ -950,6 +950,33 @@ __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// strategy pricing (Sec. 4.2)
+// ---------------------------------------------------------------------------------------------
+// out[0] = sum_i L(rowmaxA_i), out[1] = sum_j L(rowmaxB_j), out[2] = sum_k L(colmaxA_k),
+// out[3] = sum_k L(colmaxB_k), out[4] = sum_k L(colmaxA_k) * L(colmaxB_k); L = number of base-s digits.
+__global__ __launch_bounds__(256) void price_kernel(const int32_t *rowmaxA, int64_t n, const int32_t *rowmaxB,
+                                                    int64_t h, const int32_t *colmaxA, const int32_t *colmaxB,
+                                                    int64_t d, int sh, unsigned long long *out) {
+    unsigned long long acc[5] = {0, 0, 0, 0, 0};
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t0; i < n; i += stride) acc[0] += digit_levels(rowmaxA[i], sh);
+    for (int64_t j = t0; j < h; j += stride) acc[1] += digit_levels(rowmaxB[j], sh);
+    for (int64_t k = t0; k < d; k += stride) {
+        const int la = digit_levels(colmaxA[k], sh), lb = digit_levels(colmaxB[k], sh);
+        acc[2] += la;
+        acc[3] += lb;
+        acc[4] += (unsigned long long)la * lb;
+    }
+#pragma unroll
+    for (int q = 0; q < 5; ++q) {
+        unsigned long long v = acc[q];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if ((threadIdx.x & 63) == 0 && v) atomicAdd(&out[q], v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 int scan_i32(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
@@ -1451,4 +1478,48 @@ extern "C" int imunpack_plan_destroy(imunpack_plan_t *p) {
     if (p->pin_hdr) (void)hipHostFree(p->pin_hdr);
     delete p;
     return rc;
+}
+
+extern "C" int imunpack_price(const imunpack_stats_t *stA, int64_t n, const imunpack_stats_t *stB, int64_t h,
+                              int64_t d, int b, int64_t *dims_out, double *ratio_out, int *best_A, int *best_B,
+                              imunpack_stream_t stream) {
+    if (!stA || !stB || !stA->rowmax || !stA->colmax || !stB->rowmax || !stB->colmax || n <= 0 || h <= 0 ||
+        d <= 0 || b < 2 || b > 8)
+        return IMUNPACK_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned long long *sums = nullptr, host[5];
+    IMU_HIP(hipMalloc((void **)&sums, sizeof(host)));
+    int rc = IMUNPACK_OK;
+    hipError_t e = hipMemsetAsync(sums, 0, sizeof(host), st);
+    if (e == hipSuccess) {
+        const int64_t longest = std::max(std::max(n, h), d);
+        hipLaunchKernelGGL(price_kernel, dim3(grid_for(longest, 256, 1024)), dim3(256), 0, st, stA->rowmax, n,
+                           stB->rowmax, h, stA->colmax, stB->colmax, d, b - 1, sums);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; }
+    (void)hipFree(sums);
+    if (rc != IMUNPACK_OK) return rc;
+    // (strategy_A, strategy_B): (ROW,ROW), (ROW,COL), (COL,ROW), (COL,COL)
+    const unsigned long long dims[4][3] = {{host[0], (unsigned long long)d, host[1]},
+                                            {host[0], host[3], (unsigned long long)h},
+                                            {(unsigned long long)n, host[2], host[1]},
+                                            {(unsigned long long)n, host[4], (unsigned long long)h}};
+    double best = 0.0;
+    int bi = -1;
+    for (int q = 0; q < 4; ++q) {
+        for (int c = 0; c < 3; ++c) {
+            if (dims[q][c] > (1ull << 62)) return IMUNPACK_ERANGE;
+            if (dims_out) dims_out[3 * q + c] = (int64_t)dims[q][c];
+        }
+        const double r = ((double)dims[q][0] / (double)n) * ((double)dims[q][1] / (double)d) *
+                         ((double)dims[q][2] / (double)h);
+        if (ratio_out) ratio_out[q] = r;
+        if (bi < 0 || r < best) { best = r; bi = q; }
+    }
+    if (best_A) *best_A = (bi & 2) ? IMUNPACK_COL : IMUNPACK_ROW;
+    if (best_B) *best_B = (bi & 1) ? IMUNPACK_COL : IMUNPACK_ROW;
+    return IMUNPACK_OK;
 }

@@ -283,3 +283,27 @@ def test_fused_launch_before_the_bounds_are_known(imu):
     ws = torch.empty(plan2.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
     imu.imunpack_gemm(plan2, A2, B2, 1.0, 1.0, C_int, None, ws, fuse=True)   # guarded launch, then the fallback
     assert np.array_equal(C_int.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("kind,b", [("scattered", 8), ("channels", 8), ("heavy", 4), ("deep", 8), ("clean", 8), ("rows", 3)])
+def test_price_matches_unpacked_sizes(imu, kind, b):
+    """Sec. 4.2: the sizes n', d', h' (and so the unpack ratio r) that imunpack_price reads off the scan
+    statistics equal those of the oracle's literal UnpackRow / UnpackColumn for all four pairs, and
+    the pair it picks has the smallest r."""
+    w = workloads.small(seed=21, n=150, d=260, h=90, kind=kind, b=b)
+    Aq, _ = oracle.rtn_quantize(w.A.numpy(), w.scale_a)
+    Bq, _ = oracle.rtn_quantize(w.B.numpy(), w.scale_b)
+    Qa, Qb = torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda()
+    st_a, st_b = imu.imunpack_scan(Qa, b), imu.imunpack_scan(Qb, b)
+    dims, ratios, best = imu.imunpack_price(st_a, w.n, st_b, w.h, w.d, b)
+    want_r = {}
+    for pair in dims:
+        hnd = oracle.unpack_pair_handle(Aq, Bq, b, pair[0], pair[1])
+        assert dims[pair] == (hnd.n_u, hnd.d_u, hnd.h_u), pair
+        want_r[pair] = hnd.n_u * hnd.d_u * hnd.h_u / (w.n * w.d * w.h)
+        assert abs(ratios[pair] - want_r[pair]) <= 1e-12 * want_r[pair]
+        hnd.close()
+    assert want_r[best] == min(want_r.values())
+    # and the planner agrees with the price of the chosen pair
+    plan = imu.imunpack_plan(Qa, Qb, b, best[0], best[1], st_a, st_b)
+    assert plan.dims()[:3] == (dims[best][0], dims[best][1], dims[best][2])
