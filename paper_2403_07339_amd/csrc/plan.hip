@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     extern __shared__ __attribute__((aligned(16))) int32_t lds_counts[];
     __shared__ int s_top[2];
     __shared__ int s_pick[kPlanWaves][256];  // per wave: the slots picked in one 256-slot step
-    __shared__ int s_found[kPlanWaves];
+    __shared__ int s_found[kPlanWaves], s_positive[kPlanWaves];
     __shared__ int lds[40];
     __shared__ int s_count;
     PlanHeader *hdr = g.hdr;
@@ -428,22 +428,31 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         const int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
         const int seg = isrow ? segR : segC;
         const int wlo = wave * seg, whi = min(N, wlo + seg);
-        int found = 0;
+        int found = 0, positive = 0;
         for (int x0 = wlo; x0 < whi; x0 += 256) {
             const int x = x0 + lane * 4;  // counts past slot N-1 (within the padding) are 0 < lo
             const int4 c = x < N ? *reinterpret_cast<const int4 *>(&cnt[x]) : make_int4(0, 0, 0, 0);
             found += __popcll(__ballot(c.x >= lo && c.x <= hi)) + __popcll(__ballot(c.y >= lo && c.y <= hi)) +
                      __popcll(__ballot(c.z >= lo && c.z <= hi)) + __popcll(__ballot(c.w >= lo && c.w <= hi));
+            positive += __popcll(__ballot(c.x > 0)) + __popcll(__ballot(c.y > 0)) + __popcll(__ballot(c.z > 0)) +
+                        __popcll(__ballot(c.w > 0));
         }
-        if (lane == 0) s_found[wave] = found;
+        if (lane == 0) {
+            s_found[wave] = found;
+            s_positive[wave] = positive;
+        }
         __syncthreads();
-        int run = 0, nb = 0;
+        int run = 0, nb = 0, npos = 0;
 #pragma unroll
         for (int w = 0; w < kPlanWaves; ++w) {
             const int c = s_found[w];
             if (w < wave) run += c;
             nb += c;
+            npos += s_positive[w];
         }
+        // If no entry has three or more digits and the batch takes every slot of its side that still
+        // holds an OB entry, every live entry is finished by it: nothing is left to count.
+        const bool finishes = !deep && nb == npos;
         if (N + nb > mine.cap || N + nb >= (1 << kEdgeSlotBits)) {
             if (threadIdx.x == 0) {
                 if (N + nb >= (1 << kEdgeSlotBits)) atomicMin(&hdr->err, IMUNPACK_ERANGE);
@@ -497,6 +506,34 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             s_top[0] = s_top[1] = 0;
         }
         __syncthreads();
+        if (finishes) {
+            if (bid == 0) {  // the scatter still wants the operand's OB entries
+                constexpr int V = 8;  // entries per thread and step, loaded side by side
+                for (int t0 = threadIdx.x; t0 < nob; t0 += kPlanThreads * V) {
+                    int j[V], k[V], v[V];
+#pragma unroll
+                    for (int u = 0; u < V; ++u) {
+                        const int t = t0 + u * kPlanThreads;
+                        j[u] = t < nob ? ob[t] : 0;
+                        k[u] = t < nob ? ob[g.ob_cap + t] : 0;
+                        v[u] = t < nob ? ob[2 * (size_t)g.ob_cap + t] : 0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < V; ++u) {
+                        const int t = t0 + u * kPlanThreads;
+                        if (t < nob) {
+                            g.ob_keep[t] = j[u];
+                            g.ob_keep[g.ecap + t] = k[u];
+                            g.ob_keep[2 * (size_t)g.ecap + t] = v[u];
+                        }
+                    }
+                }
+            }
+            for (int x = threadIdx.x; x < rpad; x += kPlanThreads) rc[x] = 0;
+            for (int x = threadIdx.x; x < cpad; x += kPlanThreads) cc[x] = 0;
+            if (isrow) nr += nb; else nc += nb;
+            break;
+        }
         // (4) the pass.  The survivors of U entries per lane are appended with one counter update per wave.
         unsigned long long *dst = bid == 0 ? list1 : (cur ? list0 : list1);
         constexpr unsigned long long kSlotMask = (1ull << kEdgeSlotBits) - 1ull;
