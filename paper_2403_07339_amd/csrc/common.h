@@ -40,7 +40,6 @@ constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both
 constexpr int kChunk = 64;       // physical rows the GEMM epilogue holds at a time; no source row straddles a chunk
 constexpr int kKPad = 128;       // every exponent group is padded to a multiple of this many columns
 constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
-constexpr int kScatterWin = 1024;  // source columns per window of the scatter kernel
 constexpr uint32_t kNever = 0xFFFFFFFFu;  // split time of a row/column that is never split
 
 // One set of growing row (or column) slots: what Pi (or S) needs per slot, plus the split
@@ -69,7 +68,7 @@ struct PlanHeader {
     int32_t overflow;                // bit set: which capacity was too small
     int32_t need[10];                // size that would have been needed, per capacity
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
-    uint32_t pad_;
+    uint32_t cols_done;              // column-layout workgroups that have finished (the last one orders the units)
     unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
 };
 
@@ -87,6 +86,10 @@ struct RowLayout {
     int32_t *tile_src0;   // [tiles+1] first source row of each tile
     int32_t *chunk_src0;  // [4 tiles+1] first source row of each chunk of kChunk physical rows
     int32_t *tile_flat;   // [tiles]   1 if every source row of the tile has a single level
+    // weighted L1 norm  sum_c s^e(c) |digit|  per physical row, in pieces: what the fix-up pass placed
+    // (cleared by the planner) and one partial sum per wave of the scatter kernel
+    unsigned long long *rowsum;   // [Mp]
+    unsigned long long *wavesum;  // [Mp][waves per row]
 };
 
 struct ColLayout {
@@ -98,9 +101,10 @@ struct ColLayout {
     int32_t *colB_e;      // [Kp] digit level along the columns of B_e
     int32_t *col_sexp;    // [Kp] exponent of the diagonal entry of S
     int4 *unit_desc;      // [Kp/16] per 16-column unit: lowest and highest source column (-1: all padding),
-                          // bit 0 of z: 16 consecutive source columns from a multiple of 4, bit 1: one digit
-                          // level pair for all its columns; w: level along A | along B << 8 | exponent of S << 16
-    int32_t *win_unit;    // [groups][windows+1] first 16-column unit of a group at or past a source window
+                          // bit 0 of z: 16 consecutive source columns, bit 1: one digit level pair for all
+                          // its columns; w: level along A | along B << 8 | exponent of S << 16
+    int4 *unit_sorted;    // [Kp/16] the same descriptors with the unit's index in z >> 8, the units with both
+                          // bits set first: the order in which the scatter kernel deals them to its lanes
 };
 
 }  // namespace imu
@@ -136,7 +140,6 @@ struct imunpack_plan {
     int edge_cap;
     int32_t *rcnt, *ccnt;
     int32_t *obcopyA, *obcopyB;       // OB entries of an UnpackBoth operand, kept for the scatter: [3][cap[CAP_EDGEx]]
-    unsigned long long *rowsumA, *rowsumB;  // weighted L1 norm per physical row, written by the scatter
     int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
     int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB, *tmpE, *tmpK, *tmpR, *tmpOff;
     int ignore_listA, ignore_listB;   // a caller's OB list overflowed: scan the operand ourselves

@@ -727,6 +727,7 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
         lay.prow_slot[p] = -1;
         lay.prow_src[p] = -1;
         lay.prow_exp[p] = 0;
+        lay.rowsum[p] = 0;
     }
     __syncthreads();
     for (int i0 = threadIdx.x; i0 < nbase; i0 += kPlanThreads * V) {
@@ -774,9 +775,8 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
 // unpacking), so that a run of physical columns reads a run of source columns.  A column slot c of
 // the second unpacking descends from slot r = c2.root[c] of the first, which descends from original
 // column k = c1.root[r]; its exponent is c1.exp[r] + c2.exp[c].
-// Also written: for every group and every window of kScatterWin source columns, the first 16-column
-// unit whose first column copies a source column at or past the window's start (the scatter kernel
-// walks the source in such windows).
+// Also written: a descriptor per 16-column unit, which lets the scatter kernel pick its path without
+// the per-column arrays.
 constexpr int kColBlocks = 8;  // workgroups that share the column layout, one exponent group at a time each
 
 __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayout &cols, int d, int cap_phys,
@@ -850,7 +850,6 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
     __syncthreads();
     const int ng = s_ng, Kp = s_kp;
     if (Kp > cap_phys || s_bad) return;
-    const int nwin = (d + kScatterWin - 1) / kScatterWin;
     for (int g = part; g < ng; g += kColBlocks) {
         const int ge = s_gexp[g], q0 = s_gk0[g], q1 = g + 1 < ng ? s_gk0[g + 1] : Kp;
         for (int q = q0 + threadIdx.x; q < q1; q += kPlanThreads) {
@@ -933,7 +932,7 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             const int qq = 16 * u;
             const int k0 = cols.colA_k[qq], ea0 = cols.colA_e[qq], eb0 = cols.colB_e[qq];
             int kmin = 0x7fffffff, kmax = -1;
-            bool run = k0 >= 0 && (k0 % 4) == 0, uniform = true;
+            bool run = k0 >= 0, uniform = true;
             for (int j = 0; j < 16; ++j) {
                 const int k = cols.colA_k[qq + j];
                 run = run && k == k0 + j;
@@ -950,24 +949,27 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             ud.w = (ea0 & 0xFF) | ((eb0 & 0xFF) << 8) | ((ge & 0xFF) << 16);
             cols.unit_desc[u] = ud;
         }
-        // window table of the group
-        for (int w = threadIdx.x; w <= nwin; w += kPlanThreads) {
-            const int u0 = q0 / 16, u1 = q1 / 16;
-            int lo = u0, hi = u1;
-            if (w < nwin) {
-                const int want = w * kScatterWin;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    const int kk = cols.colA_k[16 * mid];
-                    if (kk < 0 || kk >= want) hi = mid; else lo = mid + 1;  // padding sorts last
-                }
-            } else {
-                lo = u1;
-            }
-            cols.win_unit[g * (nwin + 1) + w] = lo;
-        }
         __syncthreads();
     }
+    // The workgroup that finishes last deals the units out: those that copy 16 consecutive source
+    // columns at one digit level first (in order), the others behind them, so that the lanes of a
+    // wave of the scatter kernel nearly always take the same path.
+    __shared__ int s_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&hdr->cols_done, 1u) == (unsigned)(kColBlocks - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();  // what the other workgroups wrote before their increment is visible past this fence
+    const int nunits = Kp / 16;
+    auto fast = [&](int u) { return (cols.unit_desc[u].z & 3) == 3; };
+    auto put = [&](int u, int pos) {
+        int4 ud = cols.unit_desc[u];
+        ud.z = (ud.z & 3) | (u << 8);
+        cols.unit_sorted[pos] = ud;
+    };
+    const int nfast = ordered_select(nunits, 0, fast, put, lds);
+    ordered_select(nunits, nfast, [&](int u) { return !fast(u); }, put, lds);
 }
 
 // One workgroup for the rows of A, one for the rows of B, kColBlocks for the columns.
@@ -1065,6 +1067,8 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         l.tile_src0 = cv.take<int32_t>(pc / kTile + 2);
         l.chunk_src0 = cv.take<int32_t>(pc / kChunk + 8);
         l.tile_flat = cv.take<int32_t>(pc / kTile + 2);
+        l.rowsum = cv.take<unsigned long long>(pc);
+        l.wavesum = cv.take<unsigned long long>((size_t)pc * ((phys_cap_cols(p->cap[CAP_C2]) / 16 + 63) / 64));
     }
     {
         const int kc = phys_cap_cols(p->cap[CAP_C2]);
@@ -1076,14 +1080,12 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->cols.colB_e = cv.take<int32_t>(kc);
         p->cols.col_sexp = cv.take<int32_t>(kc);
         p->cols.unit_desc = cv.take<int4>(kc / 16 + 1);
-        p->cols.win_unit = cv.take<int32_t>((size_t)kMaxGroups * ((d + kScatterWin - 1) / kScatterWin + 1));
+        p->cols.unit_sorted = cv.take<int4>(kc / 16 + 1);
         p->tmpE = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpK = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpR = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpOff = cv.take<int32_t>((size_t)kColBlocks * (d + 1));
     }
-    p->rowsumA = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWA]));
-    p->rowsumB = cv.take<unsigned long long>(phys_cap_rows(p->cap[CAP_ROWB]));
     p->canon_rowphysA = cv.take<int32_t>(p->cap[CAP_ROWA]);
     p->canon_rowphysB = cv.take<int32_t>(p->cap[CAP_ROWB]);
     p->canon_colphys = cv.take<int32_t>(p->cap[CAP_C2]);

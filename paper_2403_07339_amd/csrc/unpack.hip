@@ -17,23 +17,21 @@
 
 namespace imu { int poll_ready(Plan *p); }
 
+#include <algorithm>
 #include <cstddef>
 #include <cstring>
 
 namespace imu {
 
-// One workgroup handles kScatterRows consecutive physical rows and walks the source in windows of
-// kScatterWin columns.  A window of the block's source rows (all digit levels of a source row are
-// adjacent, so the block has few distinct ones) is staged in LDS once; every 16-column output unit
-// whose first column copies a source column of the window is then produced from LDS -- the columns of
-// a group are ordered by source column, so the units of every group advance with the window and
-// each source element is read from HBM once.  A column that copies a source column outside the
-// window (the tail of a unit that straddles two windows, or a sparse group) is read from global
-// memory instead.  Stores are 16 bytes wide.  The kernel also leaves, per physical row, the weighted
-// L1 norm sum_c s^e(c) |digit| of what it wrote, and raises *bound to the largest of them.
-constexpr int kScatterRows = 8;
+// One thread per (physical row, 16-column output unit), independent of every other: it reads the 16
+// source values of its unit and writes the unit's 16 bytes; a wave (64 units of one row) also leaves
+// sum_c s^e(c) |digit|  of what it wrote, its part of the row's weighted L1 norm.  The columns of a group are ordered by source column, so
+// nearly every unit copies 16 consecutive source columns (64 contiguous bytes); the planner deals
+// those units out first, the others (which gather through the column table) behind them, so the
+// lanes of a wave nearly always take the same path.  No staging and no barriers: the launch is a
+// stream of short waves, eight to a SIMD, which is what keeps enough loads in flight.
 constexpr int kScatterThreads = 256;
-static_assert(kScatterWin == 4 * kScatterThreads, "one int4 per thread and staged row");
+constexpr int kScatterChunk = 64;  // physical rows per blockIdx.y
 
 struct ScatterArgs {
     const int32_t *M;            // the int32 operand, row-major
@@ -41,206 +39,122 @@ struct ScatterArgs {
     const int32_t *prow_slot, *prow_src, *prow_exp;  // per physical row
     const int32_t *col_k;        // per physical column: source column, -1 = padding
     const int32_t *col_e;        // per physical column: digit level along this operand's column axis
-    const int4 *unit_desc;
+    const int4 *unit_desc;       // in dealing order, the unit's index in z >> 8
     int lev_shift;               // where this operand's level sits in unit_desc.w
-    const int32_t *win_unit;
-    int Mp, Kp, d, ngroups, s, sh;
+    int Mp, Kp, s, sh;
     int8_t *out;
-    unsigned long long *rowsum, *bound;
+    unsigned long long *wavesum; // [Mp][waves per row]: every wave of the launch leaves its part of the row norm
 };
+
+typedef int v4i_u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at any int boundary
+
+// Sign-magnitude digit `level` of four values, one per byte; *mag += the four magnitudes.
+__device__ __forceinline__ int digits4(const int (&x)[4], unsigned sft, int bits, unsigned &mag) {
+    int dg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int sx = x[i] >> 31;
+        const unsigned av = (unsigned)((x[i] ^ sx) - sx);
+        const int m = (int)__builtin_amdgcn_ubfe(av, sft, (unsigned)bits);
+        mag += (unsigned)m;
+        dg[i] = (m ^ sx) - sx;
+    }
+    return (int)(__builtin_amdgcn_perm((unsigned)dg[1], (unsigned)dg[0], 0x0c0c0400u) |
+                 __builtin_amdgcn_perm((unsigned)dg[3], (unsigned)dg[2], 0x04000c0cu));
+}
 
 template <bool DENSE>
 __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a) {
-    // rows padded by 16 bytes: lanes that read the same columns of different rows hit different banks
-    __shared__ __attribute__((aligned(16))) int32_t tile[kScatterRows][kScatterWin + 4];
-    __shared__ int s_slot[kScatterRows], s_src[kScatterRows], s_er[kScatterRows], s_trow[kScatterRows];
-    __shared__ unsigned long long s_wsum[kScatterRows];
-    __shared__ int s_u0[kMaxGroups + 1], s_ucount[kMaxGroups + 1], s_total;
-    const int p0 = blockIdx.x * kScatterRows;
-    const int nwin = (a.d + kScatterWin - 1) / kScatterWin;
-    const int s = a.s, sh = a.sh, Kp = a.Kp, d = a.d;
-    if (threadIdx.x < kScatterRows) {
-        const int p = p0 + threadIdx.x;
-        s_slot[threadIdx.x] = p < a.Mp ? a.prow_slot[p] : -2;
-        s_src[threadIdx.x] = p < a.Mp ? a.prow_src[p] : -1;
-        s_er[threadIdx.x] = p < a.Mp ? a.prow_exp[p] : 0;
-        s_wsum[threadIdx.x] = 0;
-    }
-    __syncthreads();
-    // s_trow[r]: which staged row holds the source row of physical row r
-    if (threadIdx.x < kScatterRows) {
-        int r = threadIdx.x;
-        while (r > 0 && s_src[r] >= 0 && s_src[r - 1] == s_src[r]) --r;
-        s_trow[threadIdx.x] = r;
-    }
-    __syncthreads();
-    const bool ld_vec = (a.ld % 4) == 0 && ((uintptr_t)a.M % 16) == 0;
-    auto fetch = [&](int w, int4 (&pre)[kScatterRows]) {
-        const int k = w * kScatterWin + (int)threadIdx.x * 4;
+    const int nunits = a.Kp >> 4;
+    const int wpr = (nunits + 63) >> 6, upr = wpr << 6;  // waves and lanes per row: a wave never straddles rows
+    const int local = blockIdx.x * kScatterThreads + threadIdx.x;
+    const int rl = local / upr, upos = local - rl * upr;
+    const int p = blockIdx.y * kScatterChunk + rl;
+    if (rl >= kScatterChunk || p >= a.Mp) return;  // whole waves
+    const bool inside = upos < nunits;
+    unsigned mag = 0;   // sum of |digit| over the unit
+    unsigned nsft = 0;  // weight of the unit's columns in the row norm, as a shift
+    if (inside) {
+        const int4 ud = a.unit_desc[upos];
+        const int slot = a.prow_slot[p], er = a.prow_exp[p];
+        const int q0 = (ud.z >> 8) * 16;
+        const int kmin = ud.x, kmax = ud.y;
+        const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
+        const int ecu = (ud.w >> a.lev_shift) & 0xFF;
+        nsft = (unsigned)(a.sh * ((ud.w >> 16) & 0xFF));
+        int4 *dst = reinterpret_cast<int4 *>(a.out + (int64_t)p * a.Kp + q0);
+        // padding row, padding columns, or (UnpackBoth operands hold digit 0 at level (0, 0) only; every
+        // operand: no digit that high) a unit that holds nothing
+        const unsigned usft = (unsigned)(a.sh * (er + ecu));
+        const bool empty = slot < 0 || kmax < 0 || (uniform && (DENSE ? usft >= 32u : er + ecu != 0));
+        int4 o = make_int4(0, 0, 0, 0);
+        if (!empty) {
+            const int32_t *src = a.M + (int64_t)a.prow_src[p] * a.ld;
+            int v[4][4];
+            if (run) {
 #pragma unroll
-        for (int r = 0; r < kScatterRows; ++r) {
-            pre[r] = make_int4(0, 0, 0, 0);
-            const int si = s_src[r];
-            if (s_trow[r] != r || si < 0 || w >= nwin) continue;
-            const int32_t *src = a.M + (int64_t)si * a.ld;
-            if (ld_vec && k + 3 < d) {
-                pre[r] = *reinterpret_cast<const int4 *>(src + k);
-            } else {
-                if (k < d) pre[r].x = src[k];
-                if (k + 1 < d) pre[r].y = src[k + 1];
-                if (k + 2 < d) pre[r].z = src[k + 2];
-                if (k + 3 < d) pre[r].w = src[k + 3];
-            }
-        }
-    };
-    int4 pre[kScatterRows];
-    fetch(0, pre);
-    const int mask = s - 1;
-    for (int w = 0; w < nwin; ++w) {
-        if (w > 0) __syncthreads();  // the previous window has been consumed
-#pragma unroll
-        for (int r = 0; r < kScatterRows; ++r)
-            *reinterpret_cast<int4 *>(&tile[r][threadIdx.x * 4]) = pre[r];
-        if ((int)threadIdx.x < a.ngroups) {
-            const int g = threadIdx.x;
-            const int u0 = a.win_unit[g * (nwin + 1) + w], u1 = a.win_unit[g * (nwin + 1) + w + 1];
-            s_u0[g] = u0;
-            s_ucount[g] = u1 - u0;
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int total = 0;
-            for (int g = 0; g < a.ngroups; ++g) total += s_ucount[g];
-            s_total = total;
-        }
-        fetch(w + 1, pre);  // in flight while this window is processed
-        __syncthreads();
-        const int kbase = w * kScatterWin;
-        const int total = s_total;
-        // work items: (unit, half of the block's rows), flattened over the groups; the last, partial
-        // round of such items is dealt out row by row instead, so that it costs one row per thread
-        // rather than four
-        const int n4 = 2 * total, full = n4 / kScatterThreads * kScatterThreads;
-        const int nitems = full + (n4 - full) * (kScatterRows / 2);
-        for (int item = threadIdx.x; item < nitems; item += kScatterThreads) {
-            int it4 = item, rbeg, rcount;
-            if (item < full) {
-                rbeg = (item & 1) * (kScatterRows / 2);
-                rcount = kScatterRows / 2;
-            } else {
-                const int t = item - full;
-                it4 = full + t / (kScatterRows / 2);
-                rbeg = (it4 & 1) * (kScatterRows / 2) + t % (kScatterRows / 2);
-                rcount = 1;
-            }
-            int ui = it4 >> 1, g = 0;
-            while (ui >= s_ucount[g]) ui -= s_ucount[g++];
-            const int unit = s_u0[g] + ui, q0 = unit * 16;
-            const int4 ud = a.unit_desc[unit];
-            const int kmin = ud.x, kmax = ud.y;
-            const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
-            const int ecu = (ud.w >> a.lev_shift) & 0xFF;
-            const unsigned nsft = (unsigned)(sh * ((ud.w >> 16) & 0xFF));  // weight of the unit's columns in the row norm
-            const bool staged = kmin >= kbase && kmax < kbase + kScatterWin;
-            int k[16], ec[16];
-            if (kmax >= 0 && !run) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int4 kk = *reinterpret_cast<const int4 *>(a.col_k + q0 + 4 * u);
-                    k[4 * u] = kk.x; k[4 * u + 1] = kk.y; k[4 * u + 2] = kk.z; k[4 * u + 3] = kk.w;
+                for (int j = 0; j < 4; ++j) {
+                    const v4i_u x = *reinterpret_cast<const v4i_u *>(src + kmin + 4 * j);
+                    v[j][0] = x.x; v[j][1] = x.y; v[j][2] = x.z; v[j][3] = x.w;
                 }
-            } else {
+            } else {  // gather through the column table
 #pragma unroll
-                for (int j = 0; j < 16; ++j) k[j] = kmin + j;
+                for (int j = 0; j < 4; ++j) {
+                    const int4 kk = *reinterpret_cast<const int4 *>(a.col_k + q0 + 4 * j);
+                    v[j][0] = kk.x >= 0 ? src[kk.x] : 0;
+                    v[j][1] = kk.y >= 0 ? src[kk.y] : 0;
+                    v[j][2] = kk.z >= 0 ? src[kk.z] : 0;
+                    v[j][3] = kk.w >= 0 ? src[kk.w] : 0;
+                }
             }
-            if (kmax >= 0 && !uniform) {
+            int pk[4];
+            if (uniform) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int4 ee = *reinterpret_cast<const int4 *>(a.col_e + q0 + 4 * u);
-                    ec[4 * u] = ee.x; ec[4 * u + 1] = ee.y; ec[4 * u + 2] = ee.z; ec[4 * u + 3] = ee.w;
-                }
-            } else {
+                for (int j = 0; j < 4; ++j) pk[j] = digits4(v[j], usft, a.sh, mag);
+            } else {  // a digit level per column
 #pragma unroll
-                for (int j = 0; j < 16; ++j) ec[j] = ecu;
-            }
-#pragma unroll 1
-            for (int rr = 0; rr < rcount; ++rr) {
-                const int r = rbeg + rr;
-                const int slot = s_slot[r];
-                if (slot == -2) break;  // past the last physical row
-                int4 *dst = reinterpret_cast<int4 *>(a.out + (int64_t)(p0 + r) * Kp + q0);
-                const int er = s_er[r];
-                if (slot < 0 || kmax < 0 || (!DENSE && uniform && er + ecu != 0)) {
-                    // padding row, padding columns, or a unit that holds no level-0 position
-                    *dst = make_int4(0, 0, 0, 0);
-                    continue;
-                }
-                // ---- the source values
-                const int32_t *trow = tile[s_trow[r]];
-                int32_t v[16];
-                if (run && staged) {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int4 x = *reinterpret_cast<const int4 *>(trow + (kmin - kbase) + 4 * u);
-                        v[4 * u] = x.x; v[4 * u + 1] = x.y; v[4 * u + 2] = x.z; v[4 * u + 3] = x.w;
-                    }
-                } else {
-                    bool miss = false;
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const unsigned off = (unsigned)(k[j] - kbase);
-                        const bool in = off < (unsigned)kScatterWin;
-                        v[j] = trow[in ? off : 0u];
-                        if (!in) v[j] = 0;
-                        miss = miss || (!in && k[j] >= 0);
-                    }
-                    if (miss) {  // rare: a source column outside the staged window
-                        const int32_t *src = a.M + (int64_t)s_src[r] * a.ld;
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) {
-                            const unsigned off = (unsigned)(k[j] - kbase);
-                            if (k[j] >= 0 && off >= (unsigned)kScatterWin) v[j] = src[k[j]];
-                        }
-                    }
-                }
-                // ---- digits (sign-magnitude)
-                int pk[4];
-                unsigned mag = 0;  // sum of |digit| over the unit
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int j = 0; j < 4; ++j) {
+                    const int4 ee = *reinterpret_cast<const int4 *>(a.col_e + q0 + 4 * j);
+                    const int ec[4] = {ee.x, ee.y, ee.z, ee.w};
                     int dg[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int x = v[4 * u + i];
-                        const int t = er + ec[4 * u + i];
-                        if (DENSE) {
-                            const unsigned sft = (unsigned)(sh * t);
-                            const unsigned av = x < 0 ? 0u - (unsigned)x : (unsigned)x;
-                            const int m = sft >= 32u ? 0 : (int)((av >> sft) & (unsigned)mask);
-                            dg[i] = x < 0 ? -m : m;
-                        } else {
-                            // digit 0: x - s * trunc(x / s)
-                            const int d0 = x - ((x + ((x >> 31) & mask)) & ~mask);
-                            dg[i] = t == 0 ? d0 : 0;
-                        }
+                        const int t = er + ec[i];
+                        const unsigned sft = (unsigned)(a.sh * t);
+                        const int one[4] = {v[j][i], 0, 0, 0};
+                        unsigned m1 = 0;
+                        const bool holds = DENSE ? sft < 32u : t == 0;
+                        dg[i] = holds ? (digits4(one, sft, a.sh, m1) & 0xFF) : 0;
+                        mag += holds ? m1 : 0u;
                     }
-                    pk[u] = (int)(__builtin_amdgcn_perm((unsigned)dg[1], (unsigned)dg[0], 0x0c0c0400u) |
-                                  __builtin_amdgcn_perm((unsigned)dg[3], (unsigned)dg[2], 0x04000c0cu));
-                    mag = __builtin_amdgcn_sad_u8((unsigned)pk[u] ^ 0x80808080u, 0x80808080u, mag);
+                    pk[j] = dg[0] | (dg[1] << 8) | (dg[2] << 16) | (dg[3] << 24);
                 }
-                *dst = make_int4(pk[0], pk[1], pk[2], pk[3]);
-                if (mag)  // one exponent of S per unit; saturating
-                    atomicAdd(&s_wsum[r], nsft >= 40u ? (1ull << 50) : ((unsigned long long)mag << nsft));
             }
+            o = make_int4(pk[0], pk[1], pk[2], pk[3]);
+        }
+        *dst = o;
+    }
+    // ---- the wave's part of the row norm
+    auto weighted = [](unsigned long long m, unsigned sft) {  // saturating, far above what a fused GEMM tolerates
+        const unsigned long long t = sft >= 40u ? (1ull << 44) : (m << sft);
+        return t < (1ull << 44) ? t : (1ull << 44);
+    };
+    const unsigned long long nz = __ballot(mag != 0);
+    unsigned long long total = 0;
+    if (nz != 0) {
+        const unsigned n1 = (unsigned)__builtin_amdgcn_readlane((int)nsft, __builtin_ctzll(nz));
+        if (__all(mag == 0 || nsft == n1)) {  // one exponent of S: add the magnitudes, weigh once
+            unsigned t = mag;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
+            total = weighted(t, n1);
+        } else {
+            total = weighted(mag, nsft);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
         }
     }
-    __syncthreads();
-    if (threadIdx.x < kScatterRows && p0 + (int)threadIdx.x < a.Mp) {
-        unsigned long long t = s_wsum[threadIdx.x];
-        if (t > (1ull << 60)) t = 1ull << 60;
-        a.rowsum[p0 + threadIdx.x] = t;
-        if (t) atomicMax(a.bound, t);
-    }
+    if ((threadIdx.x & 63) == 0) a.wavesum[(int64_t)p * wpr + (upos >> 6)] = total;
 }
 
 // Places the digits above digit 0 of the listed OB entries of an operand unpacked by UnpackBoth.
@@ -263,14 +177,49 @@ struct FixupArgs {
     int Kp, s, sh;
     int8_t *out;
     unsigned long long *rowsum, *bound;
+    const unsigned long long *wavesum;  // what the scatter kernel left per row and wave
+    int wpr;
 };
 
-// Both operands in one launch: blocks [0, blocks_a) serve fa, the rest fb.
-__global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a) {
+// The whole norm of physical row p as far as it is known: the scatter kernel's parts plus `placed`.
+__device__ __forceinline__ unsigned long long row_norm(const unsigned long long *wavesum, int wpr, int p,
+                                                       unsigned long long placed) {
+    unsigned long long t = placed;
+    for (int w = 0; w < wpr; ++w) t += wavesum[(int64_t)p * wpr + w];
+    return t < (1ull << 60) ? t : (1ull << 60);
+}
+
+// Both operands in one launch: blocks [0, blocks_a) serve fa, the next blocks_b serve fb; the blocks
+// behind them raise the two bounds to the largest row norm.  A row norm that this launch still adds
+// to is covered twice, by whichever partial value the scan reads and by the value that the last
+// addition returns.
+__global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int blocks_b,
+                             const unsigned long long *rowsum_a, const unsigned long long *wavesum_a, int rows_a,
+                             unsigned long long *bound_a, const unsigned long long *rowsum_b,
+                             const unsigned long long *wavesum_b, int rows_b, unsigned long long *bound_b, int wpr) {
+    if ((int)blockIdx.x >= blocks_a + blocks_b) {
+        const int nscan = gridDim.x - blocks_a - blocks_b;
+        unsigned long long ma = 0, mb = 0;
+        for (int t = ((int)blockIdx.x - blocks_a - blocks_b) * blockDim.x + threadIdx.x; t < rows_a + rows_b;
+             t += nscan * blockDim.x) {
+            if (t < rows_a) ma = max(ma, row_norm(wavesum_a, wpr, t, rowsum_a[t]));
+            else mb = max(mb, row_norm(wavesum_b, wpr, t - rows_a, rowsum_b[t - rows_a]));
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            ma = max(ma, (unsigned long long)__shfl_xor((long long)ma, off, 64));
+            mb = max(mb, (unsigned long long)__shfl_xor((long long)mb, off, 64));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            if (ma > __hip_atomic_load(bound_a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_a, ma);
+            if (mb > __hip_atomic_load(bound_b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_b, mb);
+        }
+        return;
+    }
     const bool first = (int)blockIdx.x < blocks_a;
     const FixupArgs &f = first ? fa : fb;
     const int block = first ? blockIdx.x : blockIdx.x - blocks_a;
-    const int nblocks = first ? blocks_a : gridDim.x - blocks_a;
+    const int nblocks = first ? blocks_a : blocks_b;
     const int n = min(*f.ob_count, f.ob_cap);
     const unsigned mask = (unsigned)(f.s - 1);
     for (int t = block * blockDim.x + threadIdx.x; t < n; t += nblocks * blockDim.x) {
@@ -295,9 +244,8 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a) {
                     const int q = f.col_phys[c];
                     f.out[(int64_t)p * f.Kp + q] = dg;
                     const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
-                    const unsigned long long term = nsft >= 40u ? (1ull << 50) : ((unsigned long long)m << nsft);
-                    unsigned long long now = atomicAdd(&f.rowsum[p], term) + term;
-                    if (now > (1ull << 60)) now = 1ull << 60;
+                    const unsigned long long term = nsft >= 40u ? (1ull << 44) : ((unsigned long long)m << nsft);
+                    const unsigned long long now = row_norm(f.wavesum, f.wpr, p, atomicAdd(&f.rowsum[p], term) + term);
                     // the bound only grows: a plain (possibly stale) read filters most of the updates
                     if (now > __hip_atomic_load(f.bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
                         atomicMax(f.bound, now);
@@ -307,8 +255,13 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a) {
     }
 }
 
-__global__ void reset_bound_kernel(PlanHeader *hdr) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
+// A repeated unpack of one plan: clears what the planner left cleared for the first.
+__global__ void reset_bound_kernel(PlanHeader *hdr, unsigned long long *rowsum_a, int rows_a,
+                                   unsigned long long *rowsum_b, int rows_b) {
+    const int t0 = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+    if (t0 == 0) hdr->bound[0] = hdr->bound[1] = 0;
+    for (int t = t0; t < rows_a; t += stride) rowsum_a[t] = 0;
+    for (int t = t0; t < rows_b; t += stride) rowsum_b[t] = 0;
 }
 
 // canon[R][c] = phys[row_phys[R]][col_phys[c]]
@@ -339,10 +292,13 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (p->bound_pending) IMU_TRY(resolve_bound(p));  // of an earlier unpack of this plan
-    // the planner leaves the bounds cleared; a repeated unpack of the same plan clears them again
-    if (p->unpacked) hipLaunchKernelGGL(reset_bound_kernel, dim3(1), dim3(64), 0, st, p->d_hdr);
+    // the planner leaves the bounds and the row norms cleared; a repeated unpack of the same plan clears them again
+    if (p->unpacked)
+        hipLaunchKernelGGL(reset_bound_kernel, dim3(64), dim3(256), 0, st, p->d_hdr, p->layA.rowsum, h.Mp,
+                           p->layB.rowsum, h.Np);
     FixupArgs fx[2] = {};
     int fblocks[2] = {0, 0};
+    const int wpr = (h.Kp / 16 + 63) / 64;  // waves of the scatter kernel per physical row
     for (int op = 0; op < 2; ++op) {
         const int rowsP = op ? h.Np : h.Mp;
         if (rowsP <= 0 || h.Kp <= 0) continue;
@@ -353,14 +309,14 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         a.prow_slot = lay.prow_slot; a.prow_src = lay.prow_src; a.prow_exp = lay.prow_exp;
         a.col_k = p->cols.colA_k;
         a.col_e = op ? p->cols.colB_e : p->cols.colA_e;
-        a.unit_desc = p->cols.unit_desc;
+        a.unit_desc = p->cols.unit_sorted;
         a.lev_shift = op ? 8 : 0;
-        a.win_unit = p->cols.win_unit;
-        a.Mp = rowsP; a.Kp = h.Kp; a.d = (int)p->d; a.ngroups = h.ngroups; a.s = p->s; a.sh = p->sh;
+        a.Mp = rowsP; a.Kp = h.Kp; a.s = p->s; a.sh = p->sh;
         a.out = op ? B_eu : A_ue;
-        a.rowsum = op ? p->rowsumB : p->rowsumA;
-        a.bound = &p->d_hdr->bound[op];
-        const dim3 grid((rowsP + kScatterRows - 1) / kScatterRows);
+        a.wavesum = lay.wavesum;
+        const int64_t per_chunk = (int64_t)kScatterChunk * wpr * 64;
+        const dim3 grid((unsigned)((per_chunk + kScatterThreads - 1) / kScatterThreads),
+                        (unsigned)((rowsP + kScatterChunk - 1) / kScatterChunk));
         if (both) hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, a);
         else hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, a);
         const int nob = op ? h.nobB : h.nobA;
@@ -376,14 +332,19 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.c2_child = p->c2.child;
             f.row_phys = lay.row_phys; f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
             f.Kp = h.Kp; f.s = p->s; f.sh = p->sh;
-            f.out = a.out; f.rowsum = a.rowsum; f.bound = a.bound;
+            f.out = a.out; f.rowsum = lay.rowsum; f.bound = &p->d_hdr->bound[op];
+            f.wavesum = lay.wavesum; f.wpr = wpr;
             fblocks[op] = (nob + 255) / 256;
         }
     }
-    if (fblocks[0] + fblocks[1] > 0) {  // after both scatters: the fix-up overwrites zeros they wrote
+    if (h.Kp > 0 && h.Mp + h.Np > 0) {
+        // after both scatters: the fix-up overwrites zeros they wrote, the scan reads their row norms
         if (!fblocks[0]) fx[0] = fx[1];  // never dereferenced, but keep the argument well-formed
         if (!fblocks[1]) fx[1] = fx[0];
-        hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1]), dim3(256), 0, st, fx[0], fx[1], fblocks[0]);
+        const int nscan = std::min(64, (h.Mp + h.Np + 255) / 256);
+        hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1] + nscan), dim3(256), 0, st, fx[0], fx[1],
+                           fblocks[0], fblocks[1], p->layA.rowsum, p->layA.wavesum, h.Mp, &p->d_hdr->bound[0],
+                           p->layB.rowsum, p->layB.wavesum, h.Np, &p->d_hdr->bound[1], wpr);
     }
     IMU_TRY(launch_status());
     // The bounds travel to the host on the plan's side stream, behind the scatter: the caller's stream is
