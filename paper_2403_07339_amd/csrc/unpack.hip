@@ -23,15 +23,16 @@ namespace imu { int poll_ready(Plan *p); }
 
 namespace imu {
 
-// One thread per (physical row, 16-column output unit), independent of every other: it reads the 16
-// source values of its unit and writes the unit's 16 bytes; a wave (64 units of one row) also leaves
-// sum_c s^e(c) |digit|  of what it wrote, its part of the row's weighted L1 norm.  The columns of a group are ordered by source column, so
-// nearly every unit copies 16 consecutive source columns (64 contiguous bytes); the planner deals
-// those units out first, the others (which gather through the column table) behind them, so the
-// lanes of a wave nearly always take the same path.  No staging and no barriers: the launch is a
-// stream of short waves, eight to a SIMD, which is what keeps enough loads in flight.
+// One thread per (physical row, 16-column output unit), independent of every other thread: it reads
+// the 16 source values of its unit and writes the unit's 16 bytes.  A wave is 64 units of one row (its
+// row data travel in scalar registers) and also leaves  sum_c s^e(c) |digit|  of what it wrote, its
+// part of the row's weighted L1 norm.  The columns of a group are ordered by source column, so nearly
+// every unit copies 16 consecutive source columns (64 contiguous bytes); the planner deals those units
+// out first, the others (which gather through the column table) behind them, so the lanes of a wave
+// nearly always take the same path.  No staging and no barriers: the launch is a stream of short
+// waves, eight to a SIMD, which is what keeps enough loads in flight.
 constexpr int kScatterThreads = 256;
-constexpr int kScatterChunk = 64;  // physical rows per blockIdx.y
+constexpr int kScatterWaves = kScatterThreads / 64;  // = physical rows per workgroup
 
 struct ScatterArgs {
     const int32_t *M;            // the int32 operand, row-major
@@ -48,7 +49,8 @@ struct ScatterArgs {
 
 typedef int v4i_u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at any int boundary
 
-// Sign-magnitude digit `level` of four values, one per byte; *mag += the four magnitudes.
+// Sign-magnitude digit at bit offset sft (`bits` wide) of four values, one per byte; mag += the four
+// magnitudes.
 __device__ __forceinline__ int digits4(const int (&x)[4], unsigned sft, int bits, unsigned &mag) {
     int dg[4];
 #pragma unroll
@@ -63,30 +65,47 @@ __device__ __forceinline__ int digits4(const int (&x)[4], unsigned sft, int bits
                  __builtin_amdgcn_perm((unsigned)dg[3], (unsigned)dg[2], 0x04000c0cu));
 }
 
+// Digit 0 of four values, on the four bytes at once.  With v = x mod s (the low bits of the two's
+// complement), the sign-magnitude digit is v for x >= 0 and, for x < 0, 0 if v = 0 and v - s
+// otherwise, which as a byte is v with the bits above the digit set.  mask4 = (s - 1) in every byte.
+__device__ __forceinline__ int digit0x4(const int (&x)[4], unsigned mask4, unsigned &mag) {
+    const unsigned l01 = __builtin_amdgcn_perm((unsigned)x[1], (unsigned)x[0], 0x07030400u);  // lo0 lo1 hi0 hi1
+    const unsigned l23 = __builtin_amdgcn_perm((unsigned)x[3], (unsigned)x[2], 0x07030400u);
+    const unsigned lo = __builtin_amdgcn_perm(l23, l01, 0x05040100u);  // the four low bytes
+    const unsigned hi = __builtin_amdgcn_perm(l23, l01, 0x07060302u);  // the four high bytes (sign in bit 7)
+    const unsigned v = lo & mask4;
+    const unsigned nz = (v + 0x7f7f7f7fu) & 0x80808080u;              // bit 7: v != 0
+    const unsigned t = hi & nz;                                        // bit 7: negative and v != 0
+    const unsigned full = (t - (t >> 7)) | t;                          // 0xff in those bytes
+    const unsigned r = v | (full & ~mask4);
+    mag = __builtin_amdgcn_sad_u8(r ^ 0x80808080u, 0x80808080u, mag);  // sum of |int8|
+    return (int)r;
+}
+
 template <bool DENSE>
 __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a) {
-    const int nunits = a.Kp >> 4;
-    const int wpr = (nunits + 63) >> 6, upr = wpr << 6;  // waves and lanes per row: a wave never straddles rows
-    const int local = blockIdx.x * kScatterThreads + threadIdx.x;
-    const int rl = local / upr, upos = local - rl * upr;
-    const int p = blockIdx.y * kScatterChunk + rl;
-    if (rl >= kScatterChunk || p >= a.Mp) return;  // whole waves
+    const int nunits = a.Kp >> 4, wpr = (nunits + 63) >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int upos = blockIdx.x * 64 + (int)(threadIdx.x & 63);
     const bool inside = upos < nunits;
-    unsigned mag = 0;   // sum of |digit| over the unit
-    unsigned nsft = 0;  // weight of the unit's columns in the row norm, as a shift
-    if (inside) {
-        const int4 ud = a.unit_desc[upos];
+    const int4 ud = inside ? a.unit_desc[upos] : make_int4(-1, -1, 3, 0);
+    const int q0 = (ud.z >> 8) * 16;
+    const int kmin = ud.x, kmax = ud.y;
+    const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
+    const int ecu = (ud.w >> a.lev_shift) & 0xFF;
+    const unsigned nsft = (unsigned)(a.sh * ((ud.w >> 16) & 0xFF));  // weight of the unit's columns in the row norm
+    const unsigned mask4 = (unsigned)(a.s - 1) * 0x01010101u;
+    auto weighted = [](unsigned long long m, unsigned sft) {  // saturating, far above what a fused GEMM tolerates
+        const unsigned long long t = sft >= 40u ? (1ull << 44) : (m << sft);
+        return t < (1ull << 44) ? t : (1ull << 44);
+    };
+    for (int p = blockIdx.y * kScatterWaves + wave; p < a.Mp; p += gridDim.y * kScatterWaves) {
         const int slot = a.prow_slot[p], er = a.prow_exp[p];
-        const int q0 = (ud.z >> 8) * 16;
-        const int kmin = ud.x, kmax = ud.y;
-        const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
-        const int ecu = (ud.w >> a.lev_shift) & 0xFF;
-        nsft = (unsigned)(a.sh * ((ud.w >> 16) & 0xFF));
-        int4 *dst = reinterpret_cast<int4 *>(a.out + (int64_t)p * a.Kp + q0);
+        unsigned mag = 0;  // sum of |digit| over the unit
         // padding row, padding columns, or (UnpackBoth operands hold digit 0 at level (0, 0) only; every
         // operand: no digit that high) a unit that holds nothing
         const unsigned usft = (unsigned)(a.sh * (er + ecu));
-        const bool empty = slot < 0 || kmax < 0 || (uniform && (DENSE ? usft >= 32u : er + ecu != 0));
+        const bool empty = !inside || slot < 0 || kmax < 0 || (uniform && (DENSE ? usft >= 32u : er + ecu != 0));
         int4 o = make_int4(0, 0, 0, 0);
         if (!empty) {
             const int32_t *src = a.M + (int64_t)a.prow_src[p] * a.ld;
@@ -109,8 +128,13 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
             }
             int pk[4];
             if (uniform) {
+                if (!DENSE || usft == 0u) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) pk[j] = digits4(v[j], usft, a.sh, mag);
+                    for (int j = 0; j < 4; ++j) pk[j] = digit0x4(v[j], mask4, mag);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pk[j] = digits4(v[j], usft, a.sh, mag);
+                }
             } else {  // a digit level per column
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -132,29 +156,25 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
             }
             o = make_int4(pk[0], pk[1], pk[2], pk[3]);
         }
-        *dst = o;
-    }
-    // ---- the wave's part of the row norm
-    auto weighted = [](unsigned long long m, unsigned sft) {  // saturating, far above what a fused GEMM tolerates
-        const unsigned long long t = sft >= 40u ? (1ull << 44) : (m << sft);
-        return t < (1ull << 44) ? t : (1ull << 44);
-    };
-    const unsigned long long nz = __ballot(mag != 0);
-    unsigned long long total = 0;
-    if (nz != 0) {
-        const unsigned n1 = (unsigned)__builtin_amdgcn_readlane((int)nsft, __builtin_ctzll(nz));
-        if (__all(mag == 0 || nsft == n1)) {  // one exponent of S: add the magnitudes, weigh once
-            unsigned t = mag;
+        if (inside) *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.Kp + q0) = o;
+        // ---- the wave's part of the row norm
+        const unsigned long long nz = __ballot(mag != 0);
+        unsigned long long total = 0;
+        if (nz != 0) {
+            const unsigned n1 = (unsigned)__builtin_amdgcn_readlane((int)nsft, __builtin_ctzll(nz));
+            if (__all(mag == 0 || nsft == n1)) {  // one exponent of S: add the magnitudes, weigh once
+                unsigned t = mag;
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
-            total = weighted(t, n1);
-        } else {
-            total = weighted(mag, nsft);
+                for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
+                total = weighted(t, n1);
+            } else {
+                total = weighted(mag, nsft);
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
+                for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
+            }
         }
+        if ((threadIdx.x & 63) == 0) a.wavesum[(int64_t)p * wpr + blockIdx.x] = total;
     }
-    if ((threadIdx.x & 63) == 0) a.wavesum[(int64_t)p * wpr + (upos >> 6)] = total;
 }
 
 // Places the digits above digit 0 of the listed OB entries of an operand unpacked by UnpackBoth.
@@ -314,9 +334,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         a.Mp = rowsP; a.Kp = h.Kp; a.s = p->s; a.sh = p->sh;
         a.out = op ? B_eu : A_ue;
         a.wavesum = lay.wavesum;
-        const int64_t per_chunk = (int64_t)kScatterChunk * wpr * 64;
-        const dim3 grid((unsigned)((per_chunk + kScatterThreads - 1) / kScatterThreads),
-                        (unsigned)((rowsP + kScatterChunk - 1) / kScatterChunk));
+        const dim3 grid((unsigned)wpr, (unsigned)std::min((rowsP + kScatterWaves - 1) / kScatterWaves, 65535));
         if (both) hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, a);
         else hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, a);
         const int nob = op ? h.nobB : h.nobA;
