@@ -961,15 +961,38 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
     __syncthreads();
     if (!s_last) return;
     __threadfence();  // what the other workgroups wrote before their increment is visible past this fence
+    // every wave owns a contiguous segment of the units: count its fast ones, then place all of them
     const int nunits = Kp / 16;
-    auto fast = [&](int u) { return (cols.unit_desc[u].z & 3) == 3; };
-    auto put = [&](int u, int pos) {
-        int4 ud = cols.unit_desc[u];
-        ud.z = (ud.z & 3) | (u << 8);
-        cols.unit_sorted[pos] = ud;
-    };
-    const int nfast = ordered_select(nunits, 0, fast, put, lds);
-    ordered_select(nunits, nfast, [&](int u) { return !fast(u); }, put, lds);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int useg = ((nunits + kPlanWaves - 1) / kPlanWaves + 63) & ~63;
+    const int ulo = wave * useg, uhi = min(nunits, ulo + useg);
+    int cnt = 0;
+    for (int u0 = ulo; u0 < uhi; u0 += 64) {
+        const int u = u0 + lane;
+        cnt += __popcll(__ballot(u < uhi && (cols.unit_desc[u].z & 3) == 3));
+    }
+    if (lane == 0) lds[wave] = cnt;
+    __syncthreads();
+    int before = 0, nfast = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+        const int c = lds[w];
+        if (w < wave) before += c;
+        nfast += c;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int u0 = ulo; u0 < uhi; u0 += 64) {
+        const int u = u0 + lane;
+        int4 ud = u < uhi ? cols.unit_desc[u] : make_int4(0, 0, 0, 0);
+        const bool f = u < uhi && (ud.z & 3) == 3;
+        const unsigned long long m = __ballot(f);
+        const int fast_before = before + __popcll(m & below);  // fast units in front of u
+        if (u < uhi) {
+            ud.z = (ud.z & 3) | (u << 8);
+            cols.unit_sorted[f ? fast_before : nfast + (u - fast_before)] = ud;
+        }
+        before += __popcll(m);
+    }
 }
 
 // One workgroup for the rows of A, one for the rows of B, kColBlocks for the columns.
