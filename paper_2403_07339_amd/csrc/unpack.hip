@@ -101,6 +101,7 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
     };
     for (int p = blockIdx.y * kScatterWaves + wave; p < a.Mp; p += gridDim.y * kScatterWaves) {
         const int slot = a.prow_slot[p], er = a.prow_exp[p];
+        const int si = max(a.prow_src[p], 0);  // asked for together with the other two
         unsigned mag = 0;  // sum of |digit| over the unit
         // padding row, padding columns, or (UnpackBoth operands hold digit 0 at level (0, 0) only; every
         // operand: no digit that high) a unit that holds nothing
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
         const bool empty = !inside || slot < 0 || kmax < 0 || (uniform && (DENSE ? usft >= 32u : er + ecu != 0));
         int4 o = make_int4(0, 0, 0, 0);
         if (!empty) {
-            const int32_t *src = a.M + (int64_t)a.prow_src[p] * a.ld;
+            const int32_t *src = a.M + (int64_t)si * a.ld;
             int v[4][4];
             if (run) {
 #pragma unroll
@@ -209,6 +210,37 @@ __device__ __forceinline__ unsigned long long row_norm(const unsigned long long 
     return t < (1ull << 60) ? t : (1ull << 60);
 }
 
+// rowsum[p] += term for every lane that gets here together.  Atomics on one address are served one
+// after the other, and the OB entries of a heavy row sit side by side in the list: in two rounds, the
+// lanes that name the same row as the first lane still waiting are added up and share one atomic; the
+// lanes left after that issue their own.  Returns the row's sum after the addition in the lanes that
+// issued an atomic (`led`).
+__device__ __forceinline__ unsigned long long add_to_row(unsigned long long *rowsum, int p, unsigned long long term,
+                                                         bool &led) {
+    const int lane = threadIdx.x & 63;
+    const int lo = (int)(unsigned)term, hi = (int)(unsigned)(term >> 32);
+    unsigned long long pending = __ballot(1), sum = term;
+    bool mine = true;  // this lane still has to issue its own atomic
+    for (int round = 0; round < 2 && pending; ++round) {
+        const int lead = __builtin_ctzll(pending);
+        const int pl = __builtin_amdgcn_readlane(p, lead);
+        const unsigned long long same = __ballot(mine && p == pl);
+        if (same != (1ull << lead)) {  // uniform
+            unsigned long long t = 0;
+            for (unsigned long long m = same; m; m &= m - 1) {
+                const int from = __builtin_ctzll(m);
+                t += ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi, from) << 32) |
+                     (unsigned long long)(unsigned)__builtin_amdgcn_readlane(lo, from);
+            }
+            if (lane == lead) sum = t;
+            else if (mine && p == pl) mine = false;  // carried by the leading lane
+        }
+        pending &= ~same;
+    }
+    led = mine;
+    return mine ? atomicAdd(&rowsum[p], sum) + sum : 0ull;
+}
+
 // Both operands in one launch: blocks [0, blocks_a) serve fa, the next blocks_b serve fb; the blocks
 // behind them raise the two bounds to the largest row norm.  A row norm that this launch still adds
 // to is covered twice, by whichever partial value the scan reads and by the value that the last
@@ -265,10 +297,14 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
                     f.out[(int64_t)p * f.Kp + q] = dg;
                     const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
                     const unsigned long long term = nsft >= 40u ? (1ull << 44) : ((unsigned long long)m << nsft);
-                    const unsigned long long now = row_norm(f.wavesum, f.wpr, p, atomicAdd(&f.rowsum[p], term) + term);
-                    // the bound only grows: a plain (possibly stale) read filters most of the updates
-                    if (now > __hip_atomic_load(f.bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                        atomicMax(f.bound, now);
+                    bool led;
+                    const unsigned long long placed = add_to_row(f.rowsum, p, term, led);
+                    if (led) {
+                        const unsigned long long now = row_norm(f.wavesum, f.wpr, p, placed);
+                        // the bound only grows: a plain (possibly stale) read filters most of the updates
+                        if (now > __hip_atomic_load(f.bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                            atomicMax(f.bound, now);
+                    }
                 }
             }
         }
