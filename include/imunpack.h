@@ -194,6 +194,14 @@ int imunpack_last_hip_error(void);
  * unpack to finish on the device. */
 int imunpack_plan_fusable(const imunpack_plan_t *plan);
 
+/* The two numbers that decision rests on, as the plan's last imunpack_unpack measured them:
+ * bound[0] = max over the rows R of A_ue of sum_c s^e(c) |A_ue[R, c]|, bound[1] the same for B_eu,
+ * e(c) the exponent of column c's diagonal entry of S_uu (Alg. 3).  Every entry of the other operand
+ * is at most s - 1 in magnitude, so |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound[0], bound[1]), and
+ * the fused launch is exact when that stays below 2^31.  Values of 2^44 and more are reported
+ * saturated (at least 2^44).  bound: host, two elements.  Waits like imunpack_plan_fusable. */
+int imunpack_plan_bounds(const imunpack_plan_t *plan, uint64_t *bound);
+
 /* Measured matrix-core peak (benchmark reporting only, not part of the method): launches
  * `workgroups` workgroups of 4 waves that each issue 8 * iters register-resident
  * v_mfma_i32_32x32x32_i8 with no memory traffic, and writes the number of integer operations

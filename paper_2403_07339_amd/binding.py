@@ -26,7 +26,7 @@ EXPORTS = [
     "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
-    "imunpack_plan_fusable", "imunpack_diag_mfma_peak", "imunpack_price",
+    "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_price",
 ]
 
 
@@ -51,6 +51,7 @@ _lib.imunpack_recombine.argtypes = [_vp, _vp, _f32, _f32, _vp, _vp, _i64, _vp]
 _lib.imunpack_strerror.argtypes = [_i32]
 _lib.imunpack_strerror.restype = C.c_char_p
 _lib.imunpack_plan_fusable.argtypes = [_vp]
+_lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 _lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
                                 C.POINTER(C.c_double), C.POINTER(_i32), C.POINTER(_i32), _vp]
@@ -188,6 +189,12 @@ class Plan:
 
     def fusable(self) -> bool:
         return bool(_lib.imunpack_plan_fusable(self._h))
+
+    def bounds(self):
+        """(bound_A, bound_B): the largest weighted L1 row norm of A_ue and of B_eu that the last unpack measured."""
+        out = (C.c_uint64 * 2)()
+        _check(_lib.imunpack_plan_bounds(self._h, out), "imunpack_plan_bounds")
+        return int(out[0]), int(out[1])
 
 
 def imunpack_plan(A: torch.Tensor, B: torch.Tensor, b: int, strategy_a: int, strategy_b: int,

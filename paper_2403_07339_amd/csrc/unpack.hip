@@ -436,6 +436,15 @@ extern "C" int imunpack_plan_fusable(const imunpack_plan_t *cp) {
     return p->fusable;
 }
 
+extern "C" int imunpack_plan_bounds(const imunpack_plan_t *cp, uint64_t *bound) {
+    if (!cp || !cp->valid || !cp->unpacked || !bound) return IMUNPACK_EINVAL;
+    Plan *p = const_cast<Plan *>(cp);
+    IMU_TRY(resolve_bound(p));
+    bound[0] = p->hdr.bound[0];
+    bound[1] = p->hdr.bound[1];
+    return IMUNPACK_OK;
+}
+
 namespace imu { int ensure_canonical(Plan *p); }
 
 extern "C" int imunpack_unpack_canonical(const imunpack_plan_t *cp, const int8_t *A_ue, const int8_t *B_eu,

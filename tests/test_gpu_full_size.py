@@ -68,6 +68,12 @@ def test_workload_full_size(imu, index):
     oa, ob_ = hnd.operands_i8()
     assert np.array_equal(Ac.cpu().numpy(), oa)
     assert np.array_equal(Bc.cpu().numpy(), ob_)
+    # the accumulator bounds: max over rows of sum_c S[c] |digit|, on the oracle's operands
+    S64 = S.astype(np.int64)
+    for got, m in zip(plan.bounds(), (oa, ob_)):
+        want_b = max(int((np.abs(m[r0:r0 + 1024].astype(np.int64)) * S64[None, :]).sum(1).max())
+                     for r0 in range(0, m.shape[0], 1024))
+        assert got == want_b
     del Ac, Bc, oa, ob_
 
     assert plan.fusable(), "the benchmark workloads are expected to take the fused path"

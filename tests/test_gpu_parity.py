@@ -117,6 +117,7 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     # padding of the physical layout must be zero: total magnitude is preserved
     assert int(A_ue.to(torch.int64).abs().sum().item()) == int(np.abs(oa.astype(np.int64)).sum())
     assert int(B_eu.to(torch.int64).abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
+    check_bounds(plan, oa, ob, S, s)
     want = oracle.int_gemm(Aq, Bq)
     want_fp = oracle.dequantize(want, scale_a, scale_b)
     ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
@@ -139,6 +140,24 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
         assert (err <= REL_TOL * np.abs(want_fp)).all(), name
     hnd.close()
     return plan
+
+
+def check_bounds(plan, oa, ob, S, s):
+    """The accumulator bounds the scatter measured against their definition, evaluated on the
+    oracle's unpacked operands: max over rows of sum_c S[c] |digit|; and the path they select."""
+    w = np.array([int(x) for x in S], dtype=object)
+    want = []
+    for m in (oa, ob):
+        if m.size == 0:
+            want.append(0)
+            continue
+        rows = (np.abs(m.astype(np.int64)).astype(object) * w[None, :]).sum(1)
+        want.append(int(max(rows)))
+    got = plan.bounds()
+    for g, t in zip(got, want):
+        assert g == t if t < (1 << 44) else g >= (1 << 44), (got, want)
+    m = min(want)
+    assert plan.fusable() == (m < (1 << 40) and m * (s - 1) < (1 << 31))
 
 
 def rand_ints(rng, rows, cols, s, p_ob, depth):
