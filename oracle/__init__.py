@@ -9,6 +9,7 @@ package.  It shares nothing with the HIP library.
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 import subprocess
 from dataclasses import dataclass
@@ -277,3 +278,22 @@ def exact_gemm_via_unpack(A, B, b: int, strategy_a: int, strategy_b: int) -> np.
     u = unpack_pair(A, B, b, strategy_a, strategy_b)
     C_u = scaled_matmul(u.A, u.B, u.S)
     return apply_pi(C_u, u.piA_src, u.piA_w, u.piB_src, u.piB_w, n, h)
+
+
+def percentile_alpha(x: np.ndarray, p: float) -> np.float32:
+    """alpha_p(A) of Sec. 2 (the sentence after Eq. (quantized_A)): the p-th percentile of the
+    magnitudes, i.e. the smallest magnitude a such that at least p % of the entries of A lie in
+    [-a, a].  Written out: sort the magnitudes; with N entries the answer is the k-th smallest,
+    k = ceil(p N / 100) (at least 1).  No interpolation: the paper only asks for a value that
+    p % of the entries fall within, and an order statistic is the smallest such value."""
+    a = np.sort(np.abs(np.asarray(x, dtype=np.float32)).ravel())
+    if a.size == 0 or not (0.0 < p <= 100.0):
+        raise ValueError("empty matrix or p outside (0, 100]")
+    k = min(a.size, max(1, math.ceil(p * float(a.size) / 100.0)))
+    return np.float32(a[k - 1])
+
+
+def rtn_step(alpha, beta) -> np.float32:
+    """Eq. (quantized_A): A_q = round((0.5 beta / alpha_p(A)) A): beta integers cover
+    [-alpha_p, alpha_p], so one RTN step is alpha_p / (0.5 beta) (formed once, in binary32)."""
+    return np.float32(np.float32(alpha) / np.float32(0.5 * float(beta)))

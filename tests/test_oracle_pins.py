@@ -2,6 +2,7 @@
 mathematics fixes (printed values, closed forms, invariants, library routines, brute force),
 never against itself.  No GPU needed."""
 import itertools
+import math
 import os
 
 import numpy as np
@@ -490,3 +491,69 @@ def test_unpack_ratio_definition():
     assert (u.A.shape[0], u.A.shape[1], u.B.shape[0]) == (5, 5, 3)
     u = oracle.unpack_pair(A, B, b, COL, ROW)
     assert (u.A.shape[0], u.A.shape[1], u.B.shape[0]) == (4, 6, 3)
+
+
+# ---------------------------------------------------------------------------------------------
+# alpha_p and the RTN step of Sec. 2 (Eq. (quantized_A))
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N", [1, 2, 7, 100, 1000, 4097])
+@pytest.mark.parametrize("p", [0.01, 1.0, 50.0, 95.0, 99.5, 100.0])
+def test_percentile_is_the_smallest_covering_magnitude(N, p):
+    """Brute force on the definition: at least p % of the entries lie in [-alpha, alpha], and no
+    smaller magnitude of the matrix does that."""
+    rng = np.random.default_rng(N * 1000 + int(p * 100))
+    x = (rng.standard_normal(N) * rng.choice([1.0, 30.0], N, p=[0.97, 0.03])).astype(np.float32)
+    x[rng.integers(0, N, max(1, N // 10))] = x[0]          # ties
+    a = oracle.percentile_alpha(x.reshape(1, -1), p)
+    mags = np.abs(x)
+    need = p * N / 100.0
+    assert (mags <= a).sum() >= need
+    assert a in mags
+    smaller = mags[mags < a]
+    if smaller.size:
+        assert (mags <= smaller.max()).sum() < need
+
+
+def test_percentile_closed_forms():
+    # a permutation of +-1..N: the k-th smallest magnitude is k
+    for N in (10, 100, 1001):
+        rng = np.random.default_rng(N)
+        x = (rng.permutation(N) + 1).astype(np.float32) * rng.choice([-1.0, 1.0], N).astype(np.float32)
+        for p in (10.0, 33.3, 95.0, 100.0):
+            assert oracle.percentile_alpha(x.reshape(-1, 1), p) == np.float32(math.ceil(p * N / 100.0))
+    # p = 100 is the largest magnitude; a tiny p the smallest; the sign and the order do not matter
+    x = np.array([[3.0, -7.5, 0.25], [-0.125, 2.0, 7.0]], dtype=np.float32)
+    assert oracle.percentile_alpha(x, 100.0) == np.float32(7.5)
+    assert oracle.percentile_alpha(x, 1e-9) == np.float32(0.125)
+    assert oracle.percentile_alpha(-x.T[::-1], 50.0) == oracle.percentile_alpha(x, 50.0) == np.float32(2.0)
+    # all equal: that value for every p
+    assert oracle.percentile_alpha(np.full((5, 5), -2.5, np.float32), 37.0) == np.float32(2.5)
+    # large normal sample: the 95th percentile of |N(0, sigma)| is 1.95996 sigma
+    z = np.random.default_rng(0).standard_normal(1 << 20).astype(np.float32) * np.float32(0.02)
+    assert abs(float(oracle.percentile_alpha(z.reshape(1024, -1), 95.0)) / 0.02 - 1.95996) < 0.01
+    with pytest.raises(ValueError):
+        oracle.percentile_alpha(x, 0.0)
+    with pytest.raises(ValueError):
+        oracle.percentile_alpha(x, 100.5)
+
+
+def test_rtn_step_covers_the_percentile_range_with_beta_integers():
+    """Eq. (quantized_A): with the step alpha_p / (0.5 beta), a value of magnitude alpha_p rounds to
+    0.5 beta in magnitude, so [-alpha_p, alpha_p] maps onto the beta integers around zero (beta odd:
+    -(beta-1)/2 .. (beta-1)/2 after rounding half to even at the two ends is not required here, only
+    the range) and p % of the entries round into it."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((64, 257)).astype(np.float32) * np.float32(0.3)
+    for beta in (15, 31, 255):
+        for p in (95.0, 99.0):
+            a = oracle.percentile_alpha(x, p)
+            step = oracle.rtn_step(a, beta)
+            assert step == np.float32(np.float32(a) / np.float32(0.5 * beta))
+            q, st = oracle.rtn_quantize(x, step)
+            assert st == 0
+            lim = math.floor(0.5 * beta + 0.5)   # round(0.5 beta) in magnitude at most
+            inside = (np.abs(q) <= lim).sum()
+            assert inside >= p * x.size / 100.0
+            # the entry that defines alpha_p lands on +-round(0.5 beta) up to the rounding of the step
+            ia = np.argmin(np.abs(np.abs(x) - a))
+            assert abs(abs(int(q.ravel()[ia])) - 0.5 * beta) <= 0.5 + 1e-3
