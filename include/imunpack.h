@@ -74,6 +74,21 @@ typedef struct {
     int32_t *ob_count;
 } imunpack_stats_t;
 
+/* ---- (0) the range estimate that sets the RTN step ----------------------------------------------
+ * Sec. 2, the sentence after Eq. (quantized_A): alpha_p(A), the p-th percentile of the magnitudes of
+ * A: the smallest magnitude a such that at least p % of the entries lie in [-a, a], i.e. the k-th
+ * smallest |x| with k = ceil(p * rows * cols / 100) (an entry of A, no interpolation).  With beta
+ * integers to cover [-alpha_p, alpha_p], Eq. (quantized_A) is imunpack_quantize with
+ * scale = alpha_p / (0.5 * beta).
+ * X: device, element (r, c) at X[r*sx_r + c*sx_c], strides > 0.  0 < p <= 100; rows * cols < 2^32.
+ * alpha: device, one float, written when the stream gets there.  status_flag: device, may be NULL;
+ * set to 1 if X holds a NaN (alpha is then meaningless), else 0.  workspace: device,
+ * IMUNPACK_PERCENTILE_WORKSPACE_BYTES, contents irrelevant before and after.  Errors: EINVAL. */
+#define IMUNPACK_PERCENTILE_WORKSPACE_BYTES 16384
+int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                        double p, float *alpha, int32_t *status_flag, void *workspace,
+                        imunpack_stream_t stream);
+
 /* ---- (1)+(2) RTN quantisation fused with the heavy-hitter scan --------------------------------
  * Sec. 2, Eq. (quantized_A) with the step supplied by the caller:
  *     Q[r*ldq + c] = rint(X[r*sx_r + c*sx_c] / scale)      (int32, no clipping)

@@ -27,6 +27,7 @@ EXPORTS = [
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_price",
+    "imunpack_percentile",
 ]
 
 
@@ -51,6 +52,7 @@ _lib.imunpack_recombine.argtypes = [_vp, _vp, _f32, _f32, _vp, _vp, _i64, _vp]
 _lib.imunpack_strerror.argtypes = [_i32]
 _lib.imunpack_strerror.restype = C.c_char_p
 _lib.imunpack_plan_fusable.argtypes = [_vp]
+_lib.imunpack_percentile.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _vp, _vp, _vp, _vp]
 _lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 _lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
@@ -111,6 +113,27 @@ class Stats:
                       self.ob.data_ptr() if self.ob is not None else None,
                       self.ob.shape[1] if self.ob is not None else 0,
                       self.ob_count.data_ptr() if self.ob_count is not None else None)
+
+
+PERCENTILE_WORKSPACE_BYTES = 16384
+
+
+def imunpack_percentile(X: torch.Tensor, p: float, alpha: torch.Tensor | None = None,
+                        status: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """alpha_p(X): the p-th percentile of the magnitudes of X (the k-th smallest |x|, k = ceil(p N / 100)).
+    X: 2-D fp32 device tensor, any positive strides.  Returns (alpha, status), one-element device tensors."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+    if alpha is None:
+        alpha = torch.empty(1, dtype=torch.float32, device=X.device)
+    if status is None:
+        status = torch.empty(1, dtype=torch.int32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(PERCENTILE_WORKSPACE_BYTES, dtype=torch.uint8, device=X.device)
+    assert workspace.numel() * workspace.element_size() >= PERCENTILE_WORKSPACE_BYTES
+    _check(_lib.imunpack_percentile(X.data_ptr(), X.shape[0], X.shape[1], X.stride(0), X.stride(1), float(p),
+                                    alpha.data_ptr(), status.data_ptr(), workspace.data_ptr(), _stream()),
+           "imunpack_percentile")
+    return alpha, status
 
 
 def imunpack_quantize(X: torch.Tensor, scale: float, b: int, Q: torch.Tensor | None = None,

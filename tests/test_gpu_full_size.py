@@ -100,3 +100,12 @@ def test_workload_full_size(imu, index):
     err = (C_fp.to(torch.float64) - ref).abs()
     assert bool((err <= REL_TOL * ref.abs()).all())
     hnd.close()
+
+
+def test_percentile_full_size(imu):
+    """alpha_95 of the two operands of the benchmark workload, against the sorted magnitudes."""
+    w = workloads.make(3)
+    for X in (w.A, w.B):
+        alpha, status = imu.imunpack_percentile(X.to("cuda"), 95.0)
+        assert int(status.item()) == 0
+        assert alpha.cpu().numpy()[0] == oracle.percentile_alpha(X.numpy(), 95.0)

@@ -326,3 +326,61 @@ def test_price_matches_unpacked_sizes(imu, kind, b):
     # and the planner agrees with the price of the chosen pair
     plan = imu.imunpack_plan(Qa, Qb, b, best[0], best[1], st_a, st_b)
     assert plan.dims()[:3] == (dims[best][0], dims[best][1], dims[best][2])
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 5), (64, 256), (200, 1000), (77, 130), (513, 260), (2048, 2048)])
+@pytest.mark.parametrize("p", [0.5, 50.0, 95.0, 99.9, 100.0])
+def test_percentile_matches_the_order_statistic(imu, shape, p):
+    """alpha_p on the device is the oracle's order statistic, bit for bit (it is an entry of the
+    matrix): heavy-tailed values with ties, infinities and zeros, row-major and transposed views."""
+    g = torch.Generator().manual_seed(shape[0] * 7919 + shape[1] + int(p * 10))
+    x = torch.randn(shape, generator=g) * 0.02
+    x[torch.rand(shape, generator=g) < 0.01] *= 50.0
+    flat = x.view(-1)
+    n = flat.numel()
+    if n > 8:
+        flat[torch.randint(0, n, (max(1, n // 7),), generator=g)] = float(flat[0])      # ties
+        flat[torch.randint(0, n, (max(1, n // 50),), generator=g)] = 0.0
+        flat[1] = float("inf")
+        flat[2] = -float("inf")
+    want = oracle.percentile_alpha(x.numpy(), p)
+    for view in (x.to("cuda"), x.t().contiguous().to("cuda").t()):           # unit column stride / unit row stride
+        alpha, status = imu.imunpack_percentile(view, p)
+        assert int(status.item()) == 0
+        got = alpha.cpu().numpy()[0]
+        assert got == want or (np.isinf(got) and np.isinf(want)), (got, want)
+    # a view with neither stride 1 and an odd row pitch (scalar path)
+    wide = torch.zeros((shape[0], 2 * shape[1] + 1), device="cuda")
+    wide[:, 0:2 * shape[1]:2] = x.to("cuda")
+    alpha, status = imu.imunpack_percentile(wide[:, 0:2 * shape[1]:2], p)
+    assert alpha.cpu().numpy()[0] == want or np.isinf(want)
+
+
+def test_percentile_flags_nan_and_rejects_bad_arguments(imu):
+    x = torch.randn(33, 70, device="cuda")
+    alpha, status = imu.imunpack_percentile(x, 95.0)
+    assert int(status.item()) == 0
+    x[5, 6] = float("nan")
+    alpha, status = imu.imunpack_percentile(x, 95.0)
+    assert int(status.item()) == 1
+    for bad in (0.0, -1.0, 100.5, float("nan")):
+        with pytest.raises(imu.ImunpackError) as err:
+            imu.imunpack_percentile(x, bad)
+        assert err.value.code == imu.EINVAL
+
+
+def test_percentile_step_feeds_the_quantizer(imu):
+    """Eq. (quantized_A) end to end: alpha_95 on the device, the step alpha / (0.5 beta), RTN on the
+    device; equal to the oracle's chain on the same matrix."""
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn((300, 520), generator=g) * 0.05
+    x[:, 17] *= 40.0
+    for beta in (15, 255):
+        alpha, _ = imu.imunpack_percentile(x.to("cuda"), 95.0)
+        a = alpha.cpu().numpy()[0]
+        assert a == oracle.percentile_alpha(x.numpy(), 95.0)
+        step = oracle.rtn_step(a, beta)
+        Q, _, flag = imu.imunpack_quantize(x.to("cuda"), float(step), 8)
+        want, st = oracle.rtn_quantize(x.numpy(), step)
+        assert st == 0 and int(flag.item()) == 0
+        assert np.array_equal(Q.cpu().numpy(), want)
