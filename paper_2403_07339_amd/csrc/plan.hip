@@ -240,7 +240,6 @@ struct GreedyArgs {
     int which_list;
     unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
-    int32_t *ob_keep;              // [3][ecap]: the OB entries, kept for the scatter
     int32_t *ob_keep_count;
     int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
     int32_t *nr_io, *nc_io;        // slot counts (header fields)
@@ -507,28 +506,6 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         }
         __syncthreads();
         if (finishes) {
-            if (bid == 0) {  // the scatter still wants the operand's OB entries
-                constexpr int V = 8;  // entries per thread and step, loaded side by side
-                for (int t0 = threadIdx.x; t0 < nob; t0 += kPlanThreads * V) {
-                    int j[V], k[V], v[V];
-#pragma unroll
-                    for (int u = 0; u < V; ++u) {
-                        const int t = t0 + u * kPlanThreads;
-                        j[u] = t < nob ? ob[t] : 0;
-                        k[u] = t < nob ? ob[g.ob_cap + t] : 0;
-                        v[u] = t < nob ? ob[2 * (size_t)g.ob_cap + t] : 0;
-                    }
-#pragma unroll
-                    for (int u = 0; u < V; ++u) {
-                        const int t = t0 + u * kPlanThreads;
-                        if (t < nob) {
-                            g.ob_keep[t] = j[u];
-                            g.ob_keep[g.ecap + t] = k[u];
-                            g.ob_keep[2 * (size_t)g.ecap + t] = v[u];
-                        }
-                    }
-                }
-            }
             for (int x = threadIdx.x; x < rpad; x += kPlanThreads) rc[x] = 0;
             for (int x = threadIdx.x; x < cpad; x += kPlanThreads) cc[x] = 0;
             if (isrow) nr += nb; else nc += nb;
@@ -592,12 +569,6 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                 for (int u = 0; u < U; ++u) {
                     const int lev = levels_of(v[u]);
                     e[u] = lev >= 2 ? pack_edge(j[u], k[u], lev) : 0ull;
-                    const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
-                    if (t < nob) {
-                        g.ob_keep[t] = j[u];
-                        g.ob_keep[g.ecap + t] = k[u];
-                        g.ob_keep[2 * (size_t)g.ecap + t] = v[u];
-                    }
                 }
                 process(e);
 #pragma unroll
@@ -1147,6 +1118,18 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
     return (int)b;
 }
 
+// The OB entries of an UnpackBoth operand, kept for the scatter's fix-up pass: the caller's list need
+// not outlive the call.  Many workgroups, ahead of the (single-workgroup) greedy.
+__global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict__ ob, int ob_cap,
+                                                      const int32_t *ob_count, int32_t *__restrict__ keep, int keep_cap) {
+    const int n = min(min(*ob_count, ob_cap), keep_cap);
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < n; t += gridDim.x * blockDim.x) {
+        keep[t] = ob[t];
+        keep[keep_cap + t] = ob[ob_cap + t];
+        keep[2 * (size_t)keep_cap + t] = ob[2 * (size_t)ob_cap + t];
+    }
+}
+
 static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
 
 // ob: the operand's OB entry list ([3][ob_cap], count on the device)
@@ -1167,7 +1150,6 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.edges = p->edges;
     g.ecap = std::min(p->cap[first ? CAP_EDGEA : CAP_EDGEB], p->edge_cap);
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
-    g.ob_keep = first ? p->obcopyA : p->obcopyB;
     g.ob_keep_count = first ? &hdr->nobA : &hdr->nobB;
     g.nr_io = first ? &hdr->n_u : &hdr->h_u;
     g.nc_io = first ? &hdr->d1 : &hdr->d_u;
@@ -1184,6 +1166,9 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kGreedyLdsMax));
         opted_in = 1;
     }
+    const int keep_cap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];  // the stride the fix-up pass reads with
+    hipLaunchKernelGGL(ob_copy_kernel, dim3(grid_for(std::min(ob_cap, keep_cap), 256, 128)), dim3(256), 0, st, ob, ob_cap,
+                       ob_count, first ? p->obcopyA : p->obcopyB, keep_cap);
     if (lds_bytes <= (size_t)kGreedyLdsMax)
         hipLaunchKernelGGL(greedy_both_kernel<true>, dim3(1), dim3(kPlanThreads), lds_bytes, st, g);
     else
