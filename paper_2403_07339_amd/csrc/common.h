@@ -69,6 +69,8 @@ struct PlanHeader {
     int32_t need[10];                // size that would have been needed, per capacity
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
     uint32_t cols_done;              // column-layout workgroups that have finished (the last one orders the units)
+    int32_t extras;                  // edges that the repeated columns of B_e add to B's OB entries (UnpackBoth on B)
+    int32_t pad_;
     unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
 };
 
@@ -139,6 +141,7 @@ struct imunpack_plan {
     unsigned long long *edges;        // two lists of edge_cap packed edges each
     int edge_cap;
     int32_t *rcnt, *ccnt;
+    int32_t *extraRows;               // per row of B: how many of those extra edges it has
     int32_t *obcopyA, *obcopyB;       // OB entries of an UnpackBoth operand, kept for the scatter: [3][cap[CAP_EDGEx]]
     int32_t *ob;                      // own OB entry list [3][cap[CAP_OB]] when the caller gave none
     int32_t *tmpL, *tmpCur, *tmpPA, *tmpPB, *tmpE, *tmpK, *tmpR, *tmpOff;

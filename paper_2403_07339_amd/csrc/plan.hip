@@ -149,7 +149,7 @@ __device__ __forceinline__ void identity_slot(const SlotSet &set, int x) {
 // Clears the header and makes the first na / nb / nc slots of three sets unsplit originals (a count
 // of 0 skips a set).  The counts are known to the host, which has sized the sets for them.
 __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_a, SlotSet b, int nb,
-                             int32_t *count_b, SlotSet c, int nc, int32_t *count_c) {
+                             int32_t *count_b, SlotSet c, int nc, int32_t *count_c, int32_t *zeroed, int nzeroed) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         static_assert(sizeof(PlanHeader) % sizeof(int32_t) == 0, "header is cleared word by word");
         for (size_t i = 0; i < sizeof(PlanHeader) / sizeof(int32_t); ++i) reinterpret_cast<int32_t *>(hdr)[i] = 0;
@@ -161,6 +161,7 @@ __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < na; x += stride) identity_slot(a, x);
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nb; x += stride) identity_slot(b, x);
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nc; x += stride) identity_slot(c, x);
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nzeroed; x += stride) zeroed[x] = 0;
 }
 
 // slots 0..N-1 become unsplit originals, N read from the device
@@ -241,6 +242,7 @@ struct GreedyArgs {
     unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
     int32_t *ob_keep_count;
+    const int32_t *extra_rows;     // second operand: extra edges per row (repeated columns), else null
     int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
     int32_t *nr_io, *nc_io;        // slot counts (header fields)
     int32_t *ecount_out;
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     int deep = 0;
     const int s2 = g.s * g.s;
     for (int x = threadIdx.x; x < rpad; x += kPlanThreads) {
-        rc[x] = x < nr ? g.rowcnt[x] : 0;
+        rc[x] = x < nr ? g.rowcnt[x] + (g.extra_rows ? g.extra_rows[x] : 0) : 0;
         if (x < nr && g.rowmax[x] >= s2) deep = 1;
     }
     for (int x = threadIdx.x; x < cpad; x += kPlanThreads)
@@ -335,33 +337,12 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         s_top[0] = s_top[1] = 0;
     }
     __syncthreads();
-    // ---- the extra edges of repeated columns (second operand only)
+    // ---- the extra edges of repeated columns (second operand only) were found by ob_copy_kernel: they
+    // head the first edge list, and the rows they touch start with that many more OB entries
     unsigned long long *list0 = g.edges, *list1 = g.edges + ((g.ecap + 1) & ~1);  // both 16-byte aligned
     constexpr int U = 4;
-    if (g.chain_child) {
-        for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
-            int ch[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
-                ch[u] = t < nob ? ob[g.ob_cap + t] : -1;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) ch[u] = ch[u] >= 0 ? g.chain_child[ch[u]] : -1;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (ch[u] < 0) continue;
-                const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
-                const int j = ob[t], L = levels_of(ob[2 * (size_t)g.ob_cap + t]);
-                int c = ch[u];
-                for (int hop = 0; c >= 0 && hop < 64; c = g.chain_child[c], ++hop) {
-                    const int pos = atomicAdd(&s_count, 1);
-                    if (pos < g.ecap) list0[pos] = pack_edge(j, c, L);
-                    atomicAdd(&rc[j], 1);
-                }
-            }
-        }
-    }
+    if (g.chain_child && threadIdx.x == 0) s_count = hdr->extras;
+    __syncthreads();
     deep = block_max(deep, lds);
     const int extras = s_count;
     const long long Etotal = (long long)nob + extras;
@@ -1105,6 +1086,7 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->edge_cap = ecap;
         const int rcap = std::max(p->cap[CAP_ROWA], p->cap[CAP_ROWB]), ccap = std::max(p->cap[CAP_C1], p->cap[CAP_C2]);
         p->rcnt = cv.take<int32_t>(rcap + 8);
+    p->extraRows = cv.take<int32_t>(p->sB == IMUNPACK_BOTH ? (size_t)h + 1 : 0);
         p->ccnt = cv.take<int32_t>(ccap + 8);
         p->ob = cv.take<int32_t>((size_t)3 * p->cap[CAP_OB]);
     }
@@ -1119,14 +1101,32 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
 }
 
 // The OB entries of an UnpackBoth operand, kept for the scatter's fix-up pass: the caller's list need
-// not outlive the call.  Many workgroups, ahead of the (single-workgroup) greedy.
+// not outlive the call.  Many workgroups, ahead of the (single-workgroup) greedy.  For the second
+// operand the same pass finds the edges that the repeated columns add: B_e holds a copy of column k
+// of B in every column slot of A's unpacking that descends from k, so an OB entry (j, k) of B is
+// also an OB entry (j, c) for every such slot c; those go to the head of the greedy's edge list.
 __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict__ ob, int ob_cap,
-                                                      const int32_t *ob_count, int32_t *__restrict__ keep, int keep_cap) {
-    const int n = min(min(*ob_count, ob_cap), keep_cap);
+                                                      const int32_t *ob_count, int32_t *__restrict__ keep, int keep_cap,
+                                                      const int32_t *chain_child, unsigned long long *edges, int ecap,
+                                                      int32_t *extras, int32_t *extra_rows, int sh) {
+    const int n = min(*ob_count, ob_cap);
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < n; t += gridDim.x * blockDim.x) {
-        keep[t] = ob[t];
-        keep[keep_cap + t] = ob[ob_cap + t];
-        keep[2 * (size_t)keep_cap + t] = ob[2 * (size_t)ob_cap + t];
+        const int j = ob[t], k = ob[ob_cap + t], v = ob[2 * (size_t)ob_cap + t];
+        if (t < keep_cap) {
+            keep[t] = j;
+            keep[keep_cap + t] = k;
+            keep[2 * (size_t)keep_cap + t] = v;
+        }
+        if (!chain_child) continue;
+        int c = chain_child[k];
+        if (c < 0) continue;
+        const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
+        const int L = digit_levels((int)av, sh);
+        for (int hop = 0; c >= 0 && hop < 64; c = chain_child[c], ++hop) {
+            const int pos = atomicAdd(extras, 1);
+            if (pos < ecap) edges[pos] = pack_edge(j, c, L);
+            atomicAdd(&extra_rows[j], 1);
+        }
     }
 }
 
@@ -1151,6 +1151,7 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.ecap = std::min(p->cap[first ? CAP_EDGEA : CAP_EDGEB], p->edge_cap);
     g.rcnt = p->rcnt; g.ccnt = p->ccnt;
     g.ob_keep_count = first ? &hdr->nobA : &hdr->nobB;
+    g.extra_rows = first ? nullptr : p->extraRows;
     g.nr_io = first ? &hdr->n_u : &hdr->h_u;
     g.nc_io = first ? &hdr->d1 : &hdr->d_u;
     g.ecount_out = first ? &hdr->edgesA : &hdr->edgesB;
@@ -1167,8 +1168,9 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
         opted_in = 1;
     }
     const int keep_cap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];  // the stride the fix-up pass reads with
-    hipLaunchKernelGGL(ob_copy_kernel, dim3(grid_for(std::min(ob_cap, keep_cap), 256, 128)), dim3(256), 0, st, ob, ob_cap,
-                       ob_count, first ? p->obcopyA : p->obcopyB, keep_cap);
+    hipLaunchKernelGGL(ob_copy_kernel, dim3(grid_for(ob_cap, 256, 128)), dim3(256), 0, st, ob, ob_cap, ob_count,
+                       first ? p->obcopyA : p->obcopyB, keep_cap, (const int32_t *)g.chain_child, g.edges, g.ecap,
+                       &hdr->extras, p->extraRows, p->sh);
     if (lds_bytes <= (size_t)kGreedyLdsMax)
         hipLaunchKernelGGL(greedy_both_kernel<true>, dim3(1), dim3(kPlanThreads), lds_bytes, st, g);
     else
@@ -1187,7 +1189,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     if (idA > p->rowA.cap || idC1 > p->c1.cap || idB > p->rowB.cap) return IMUNPACK_EINVAL;
     hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, 1)), 256, 64)),
                        dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, idB,
-                       &hdr->h_u);
+                       &hdr->h_u, p->extraRows, p->sB == IMUNPACK_BOTH ? h : 0);
     // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
     // this call's own scan produces one.  The two operands are planned one after the other, so one
     // own buffer serves both.
