@@ -178,7 +178,7 @@ extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, i
     const bool vec = sfast == 1 && (nfast % 4) == 0 && (sslow % 4) == 0 && ((uintptr_t)X % 16) == 0;
     const int64_t items = nslow * (vec ? nfast / 4 : nfast);
     int64_t blocks = (items + (int64_t)kSelThreads * kSelItems - 1) / ((int64_t)kSelThreads * kSelItems);
-    if (blocks > 4096) blocks = 4096;
+    if (blocks > 1024) blocks = 1024;  // four per CU: every workgroup merges its histogram with atomics on the same few counters
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(256), 0, st, workspace, k, status_flag);
     const int shifts[3] = {20, 10, 0}, bins[3] = {2048, 1024, 1024};
