@@ -241,7 +241,7 @@ struct GreedyArgs {
     int which_list;
     unsigned long long *edges;     // two lists of ecap packed edges
     int ecap;
-    int32_t *ob_keep_count;
+    int32_t *ob_keep_count;        // header field: the number of OB entries kept for the scatter
     const int32_t *extra_rows;     // second operand: extra edges per row (repeated columns), else null
     int32_t *rcnt, *ccnt;          // live OB count per row / column slot when LDS cannot hold them
     int32_t *nr_io, *nc_io;        // slot counts (header fields)
@@ -275,7 +275,8 @@ __device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int 
 //   - otherwise a batch takes only the slots that share the top count.
 // The starting counts are the operand's scan statistics.  After UnpackA the matrix B_e repeats column
 // k of B once per column slot that descends from k (Alg. 2 line 6 / Alg. 4 line 13): such a slot
-// starts with the count of column k, and every OB entry (j, k) adds one to row j per extra slot.
+// starts with the count of column k, and every OB entry (j, k) adds one to row j per extra slot
+// (ob_copy_kernel finds those extra edges before this kernel starts).
 // A batch is one pass over the live entries: an entry in a split slot keeps digit 0 there and moves
 // floor(v / s) to the new slot (Alg. 4 lines 7-9 / 11-14); if that is In-Bound the entry is finished:
 // it leaves the count of the crossing slot and the list.  The first pass reads the operand's OB list
