@@ -315,10 +315,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     const int jsrc0 = g.layB.tile_src0[tn], nsrcB = g.layB.tile_src0[tn + 1] - jsrc0;
     const bool flatA = g.flatA[tm] != 0, flatB = g.flatB[tn] != 0;
     constexpr int FLD = 260;
-    int32_t *fold = reinterpret_cast<int32_t *>(smem);
+    int32_t *foldbuf = reinterpret_cast<int32_t *>(smem);  // two regions of [64][FLD]
     // behind the staging buffer: per source row of the tile its first physical row (relative to the
     // tile) | levels << 16; the same per source column; the first source row of each chunk
-    int32_t *rowmeta = fold + kChunk * FLD, *colmeta = rowmeta + kTile, *chunk0 = colmeta + kTile;
+    int32_t *rowmeta = foldbuf + 2 * kChunk * FLD, *colmeta = rowmeta + kTile, *chunk0 = colmeta + kTile;
     // scale * 2^final_shift is exact: one multiplication in binary64, one rounding to fp32
     const double scale2 = g.scale * (double)(1ull << g.final_shift);
     const bool vec_ok = flatB && (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (nsrcB % 4) == 0 &&
@@ -379,73 +379,78 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                 }
         }
     };
+    // two chunks per round: every wave parks 64 of its 128 rows (region wm of the staging buffer), then
+    // all threads work the two chunks off
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int half = 0; half < 2; ++half) {
         __syncthreads();
-        if (wm == (c >> 1)) {
 #pragma unroll
-            for (int ii = 0; ii < 2; ++ii)
+        for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
+            for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        fold[(ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD + wn * 128 + jj * 32 + lrow] =
-                            acc[(c & 1) * 2 + ii][jj][r];
-        }
+                for (int r = 0; r < 16; ++r)
+                    foldbuf[(wm * kChunk + ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD + wn * 128 + jj * 32 + lrow] =
+                        acc[half * 2 + ii][jj][r];
         __syncthreads();
-        // source rows of this chunk: cs0 .. cs0 + ns - 1; no source row straddles a chunk
-        const int cs0 = chunk0[c], ns = chunk0[c + 1] - cs0;
-        const int rs0 = cs0 - chunk0[0];  // index of the chunk's first source row in rowmeta
-        if (flatB) {
-            // source columns = physical columns: work items are (source row, four columns)
-            const int col4 = (tid & 63) * 4;
-            if (col4 < nsrcB && flatA) {  // physical order = source order inside the chunk
-                for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
-                    const v4i x = *reinterpret_cast<const v4i *>(fold + r * FLD + col4);
+#pragma unroll 1
+        for (int reg = 0; reg < 2; ++reg) {
+            const int c = 2 * reg + half;  // chunk of the tile: rows [64 c, 64 c + 64)
+            const int32_t *fold = foldbuf + reg * kChunk * FLD;
+            // source rows of this chunk: cs0 .. cs0 + ns - 1; no source row straddles a chunk
+            const int cs0 = chunk0[c], ns = chunk0[c + 1] - cs0;
+            const int rs0 = cs0 - chunk0[0];  // index of the chunk's first source row in rowmeta
+            if (flatB) {
+                // source columns = physical columns: work items are (source row, four columns)
+                const int col4 = (tid & 63) * 4;
+                if (col4 < nsrcB && flatA) {  // physical order = source order inside the chunk
+                    for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                        const v4i x = *reinterpret_cast<const v4i *>(fold + r * FLD + col4);
 #ifdef IMU_GEMM_DIAG
-                    if constexpr ((g_diag & 16) != 0) { if (x[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
+                        if constexpr ((g_diag & 16) != 0) { if (x[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
 #endif
-                    store4_32((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x);
+                        store4_32((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x);
+                    }
+                } else if (col4 < nsrcB) {
+                    for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                        int prel = r, nl = 1;
+                        if (!flatA) {
+                            const int m = rowmeta[rs0 + r];
+                            prel = (m & 0xFFFF) - c * kChunk;
+                            nl = m >> 16;
+                        }
+                        int64_t v[4] = {0, 0, 0, 0};
+                        for (int l = 0; l < nl; ++l) {
+                            const v4i x = *reinterpret_cast<const v4i *>(fold + (prel + l) * FLD + col4);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * l);
+                        }
+#ifdef IMU_GEMM_DIAG
+                        if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
+#endif
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v);
+                    }
                 }
-            } else if (col4 < nsrcB) {
-                for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+            } else {
+                // split source columns: work items are (source row, source column)
+                for (int it = tid; it < ns * nsrcB; it += kGemmThreads) {
+                    const int r = it / nsrcB, jc = it - r * nsrcB;
                     int prel = r, nl = 1;
                     if (!flatA) {
                         const int m = rowmeta[rs0 + r];
                         prel = (m & 0xFFFF) - c * kChunk;
                         nl = m >> 16;
                     }
-                    int64_t v[4] = {0, 0, 0, 0};
-                    for (int l = 0; l < nl; ++l) {
-                        const v4i x = *reinterpret_cast<const v4i *>(fold + (prel + l) * FLD + col4);
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * l);
-                    }
-#ifdef IMU_GEMM_DIAG
-                    if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
-#endif
-                    store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v);
+                    const int cm = colmeta[jc];
+                    const int q0 = cm & 0xFFFF, lj = cm >> 16;
+                    int64_t v = 0;
+                    for (int a = 0; a < nl; ++a)
+                        for (int l = 0; l < lj; ++l)
+                            v += (int64_t)fold[(prel + a) * FLD + q0 + l] << (g.sh * (a + l));
+                    const int64_t o = (int64_t)(cs0 + r) * g.ldc + jsrc0 + jc;
+                    if (g.C_int) g.C_int[o] = v << g.final_shift;
+                    if (g.C_fp) g.C_fp[o] = (float)((double)v * scale2);
                 }
-            }
-        } else {
-            // split source columns: work items are (source row, source column)
-            for (int it = tid; it < ns * nsrcB; it += kGemmThreads) {
-                const int r = it / nsrcB, jc = it - r * nsrcB;
-                int prel = r, nl = 1;
-                if (!flatA) {
-                    const int m = rowmeta[rs0 + r];
-                    prel = (m & 0xFFFF) - c * kChunk;
-                    nl = m >> 16;
-                }
-                const int cm = colmeta[jc];
-                const int q0 = cm & 0xFFFF, lj = cm >> 16;
-                int64_t v = 0;
-                for (int a = 0; a < nl; ++a)
-                    for (int l = 0; l < lj; ++l)
-                        v += (int64_t)fold[(prel + a) * FLD + q0 + l] << (g.sh * (a + l));
-                const int64_t o = (int64_t)(cs0 + r) * g.ldc + jsrc0 + jc;
-                if (g.C_int) g.C_int[o] = v << g.final_shift;
-                if (g.C_fp) g.C_fp[o] = (float)((double)v * scale2);
             }
         }
     }
