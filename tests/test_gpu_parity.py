@@ -384,3 +384,54 @@ def test_percentile_step_feeds_the_quantizer(imu):
         want, st = oracle.rtn_quantize(x.numpy(), step)
         assert st == 0 and int(flag.item()) == 0
         assert np.array_equal(Q.cpu().numpy(), want)
+
+
+def _oracle_matmul(A, B, p, beta_a, beta_b):
+    """A B^T through the oracle: alpha_p, RTN step, RTN, exact int64 GEMM, fp64 dequantisation."""
+    sa = oracle.rtn_step(oracle.percentile_alpha(A, p), beta_a)
+    sb = oracle.rtn_step(oracle.percentile_alpha(B, p), beta_b)
+    Aq, fa = oracle.rtn_quantize(np.ascontiguousarray(A), sa)
+    Bq, fb = oracle.rtn_quantize(np.ascontiguousarray(B), sb)
+    assert fa == 0 and fb == 0
+    return oracle.dequantize(oracle.int_gemm(Aq, Bq), sa, sb)
+
+
+@pytest.mark.parametrize("b,strategies", [(8, (BOTH, BOTH)), (5, (ROW, COL)), (4, (COL, ROW))])
+def test_linear_layer_forward_and_backward(imu, b, strategies):
+    """The three GEMMs of a linear layer (Sec. 3) against the oracle chain on the same operands:
+    Y = X W^T, grad_X = grad_Y W, grad_W = grad_Y^T X, each within 1e-6 relative of the exactly
+    dequantised integer product (the transposed operands go through the strided quantize path)."""
+    from paper_2403_07339_amd import linear
+    g = torch.Generator().manual_seed(100 + b)
+    n, d, h = 200, 320, 136
+    x = torch.randn((n, d), generator=g)
+    x[:, 7] *= 30.0                                     # an outlier channel
+    cfg = linear.QuantConfig(beta_x=31.0, beta_w=31.0, beta_g=255.0, p=95.0, b=b,
+                             strategy_a=strategies[0], strategy_b=strategies[1])
+    layer = linear.IMUnpackLinear(d, h, bias=True, cfg=cfg, device="cuda")
+    with torch.no_grad():
+        w = torch.randn((h, d), generator=g) * 0.05
+        w[torch.rand((h, d), generator=g) < 0.002] *= 25.0
+        layer.weight.copy_(w)
+        layer.bias.copy_(torch.randn(h, generator=g))
+    xg = x.to("cuda").requires_grad_(True)
+    y = layer(xg)
+    gy = torch.randn((n, h), generator=g) * 1e-3
+    gy[torch.rand((n, h), generator=g) < 0.01] *= 40.0   # heavy-tailed gradient
+    y.backward(gy.to("cuda"))
+    xn, wn, gn = x.numpy(), w.numpy(), gy.numpy()
+    bias = layer.bias.detach().cpu().numpy().astype(np.float64)
+    want_c = _oracle_matmul(xn, wn, 95.0, 31.0, 31.0)
+    want_gx = _oracle_matmul(gn, wn.T, 95.0, 255.0, 31.0)
+    want_gw = _oracle_matmul(gn.T, xn.T, 95.0, 255.0, 31.0)
+    # the product is rounded to fp32 once, the bias addition once more: both relative to their own operands
+    got_y = y.detach().cpu().numpy().astype(np.float64)
+    assert (np.abs(got_y - (want_c + bias)) <= 2 * REL_TOL * (np.abs(want_c) + np.abs(bias)[None, :])).all()
+    for got, want in ((xg.grad, want_gx), (layer.weight.grad, want_gw)):
+        got = got.detach().cpu().numpy().astype(np.float64)
+        assert (np.abs(got - want) <= REL_TOL * np.abs(want)).all()
+    assert np.allclose(layer.bias.grad.cpu().numpy(), gn.sum(0), rtol=1e-5, atol=1e-6)
+    # and the quantised layer tracks the fp32 one to within the RTN error of beta = 31 / 255
+    ref = torch.nn.functional.linear(x, w, layer.bias.detach().cpu())
+    rel = (y.detach().cpu() - ref).norm() / ref.norm()
+    assert float(rel) < 0.15
