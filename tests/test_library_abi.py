@@ -52,3 +52,66 @@ def test_binding_matches_header():
     for f in declared_functions():
         assert f in text, f"binding.py does not wrap {f}"
     importlib.import_module("paper_2403_07339_amd.workloads")
+
+
+def test_entry_points_reject_bad_arguments_on_the_host():
+    """Every entry point checks its arguments before the first HIP call, so these return EINVAL (-1)
+    on a machine without a GPU; the pointers passed are never dereferenced."""
+    lib = built_library()
+    EINVAL = -1
+    i64, i32, f32, f64, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_void_p
+    fake = vp(0x1000)   # a non-null address that must not be touched
+    lib.imunpack_quantize.restype = ctypes.c_int
+    lib.imunpack_quantize.argtypes = [vp, i64, i64, i64, i64, f32, i32, vp, i64, vp, vp, vp]
+    assert lib.imunpack_quantize(None, 4, 4, 4, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL      # no input
+    assert lib.imunpack_quantize(fake, 4, 4, 4, 1, 1.0, 9, fake, 4, None, None, None) == EINVAL      # b > 8
+    assert lib.imunpack_quantize(fake, 4, 4, 4, 1, 1.0, 1, fake, 4, None, None, None) == EINVAL      # b < 2
+    assert lib.imunpack_quantize(fake, 4, 4, 4, 1, 0.0, 8, fake, 4, None, None, None) == EINVAL      # step 0
+    assert lib.imunpack_quantize(fake, 4, 4, 4, 1, float("nan"), 8, fake, 4, None, None, None) == EINVAL
+    assert lib.imunpack_quantize(fake, 4, 4, 4, 1, 1.0, 8, fake, 3, None, None, None) == EINVAL      # ldq < cols
+    assert lib.imunpack_quantize(fake, -1, 4, 4, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL
+    lib.imunpack_scan.restype = ctypes.c_int
+    lib.imunpack_scan.argtypes = [vp, i64, i64, i64, i32, vp, vp]
+    assert lib.imunpack_scan(None, 4, 4, 4, 8, None, None) == EINVAL
+    assert lib.imunpack_scan(fake, 4, 4, 3, 8, None, None) == EINVAL
+    lib.imunpack_percentile.restype = ctypes.c_int
+    lib.imunpack_percentile.argtypes = [vp, i64, i64, i64, i64, f64, vp, vp, vp, vp]
+    for p in (0.0, -5.0, 100.0001, float("nan")):
+        assert lib.imunpack_percentile(fake, 4, 4, 4, 1, p, fake, None, fake, None) == EINVAL
+    assert lib.imunpack_percentile(fake, 0, 4, 4, 1, 95.0, fake, None, fake, None) == EINVAL         # empty
+    assert lib.imunpack_percentile(fake, 4, 4, 0, 1, 95.0, fake, None, fake, None) == EINVAL         # stride 0
+    assert lib.imunpack_percentile(fake, 1 << 20, 1 << 20, 1 << 20, 1, 95.0, fake, None, fake, None) == EINVAL  # >= 2^32
+    assert lib.imunpack_percentile(fake, 4, 4, 4, 1, 95.0, fake, None, None, None) == EINVAL         # no workspace
+    lib.imunpack_plan.restype = ctypes.c_int
+    lib.imunpack_plan.argtypes = [vp, i64, i64, i64, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    handle = vp(None)
+    ref = ctypes.byref(handle)
+    assert lib.imunpack_plan(fake, 4, 4, 4, fake, 4, 4, 8, 3, 0, None, None, ref, None) == EINVAL    # unknown strategy
+    assert lib.imunpack_plan(fake, 4, 4, 4, fake, 4, 4, 8, 0, -1, None, None, ref, None) == EINVAL
+    assert lib.imunpack_plan(fake, 4, 4, 3, fake, 4, 4, 8, 0, 0, None, None, ref, None) == EINVAL    # lda < d
+    assert lib.imunpack_plan(fake, 4, 4, 4, fake, 4, 4, 12, 0, 0, None, None, ref, None) == EINVAL   # b
+    assert lib.imunpack_plan(fake, 1 << 25, 4, 4, fake, 4, 4, 8, 0, 0, None, None, ref, None) == EINVAL  # too many rows
+    assert lib.imunpack_plan(fake, 4, 4, 4, fake, 4, 4, 8, 0, 0, None, None, None, None) == EINVAL   # nowhere to put the plan
+    assert handle.value is None
+    for name, nargs in (("imunpack_unpacked_bytes", 4), ("imunpack_unpack", 8), ("imunpack_unpack_canonical", 6),
+                        ("imunpack_gemm", 11), ("imunpack_recombine", 8), ("imunpack_plan_export", 7),
+                        ("imunpack_plan_bounds", 2)):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = None
+        if name == "imunpack_gemm":
+            args = [None, fake, fake, None, fake, fake, i64(4), f32(1.0), f32(1.0), i32(1), None]
+        elif name == "imunpack_recombine":
+            args = [None, fake, f32(1.0), f32(1.0), fake, fake, i64(4), None]
+        else:
+            args = [None] + [fake] * (nargs - 1)
+        assert fn(*args) == EINVAL, name                                                             # no plan
+    lib.imunpack_plan_fusable.restype = ctypes.c_int
+    assert lib.imunpack_plan_fusable(None) == 0
+    lib.imunpack_price.restype = ctypes.c_int
+    lib.imunpack_price.argtypes = [vp, i64, vp, i64, i64, i32, vp, vp, vp, vp, vp]
+    assert lib.imunpack_price(None, 4, None, 4, 4, 8, fake, fake, fake, fake, None) == EINVAL
+    lib.imunpack_diag_mfma_peak.restype = ctypes.c_int
+    lib.imunpack_diag_mfma_peak.argtypes = [i32, i32, vp, vp]
+    assert lib.imunpack_diag_mfma_peak(0, 10, None, None) == EINVAL
+    assert lib.imunpack_diag_mfma_peak(10, 0, None, None) == EINVAL
