@@ -435,3 +435,24 @@ def test_linear_layer_forward_and_backward(imu, b, strategies):
     ref = torch.nn.functional.linear(x, w, layer.bias.detach().cpu())
     rel = (y.detach().cpu() - ref).norm() / ref.norm()
     assert float(rel) < 0.15
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_strategies_and_densities(imu, seed):
+    """Seeded sweep over what the other cases fix: ragged shapes from one row to a few tiles, every
+    bit width, every strategy pair, OB densities from none to most entries, up to five digits, heavy
+    rows / heavy columns / scattered entries mixed."""
+    rng = np.random.default_rng(9000 + seed)
+    b = int(rng.integers(2, 9))
+    s = 1 << (b - 1)
+    n, d, h = (int(rng.integers(1, 520)) for _ in range(3))
+    sa, sb = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+    depth = int(rng.integers(1, 6 if b <= 4 else 4))
+    p_ob = float(rng.choice([0.0, 0.001, 0.02, 0.3, 0.9]))
+    Aq = rand_ints(rng, n, d, s, p_ob, depth)
+    Bq = rand_ints(rng, h, d, s, float(rng.choice([0.0, 0.005, 0.1])), depth)
+    if rng.random() < 0.5 and d > 2:      # heavy columns of A (outlier channels)
+        Aq[:, rng.integers(0, d, 2)] = rng.integers(-(s ** depth), s ** depth + 1, size=(n, 2)).astype(np.int32)
+    if rng.random() < 0.5 and h > 2:      # heavy rows of B
+        Bq[rng.integers(0, h, 2), :] = rng.integers(-(s ** depth), s ** depth + 1, size=(2, d)).astype(np.int32)
+    check_against_oracle(imu, Aq, Bq, b, sa, sb)
