@@ -43,6 +43,7 @@ struct ScatterArgs {
     const int4 *unit_desc;       // in dealing order, the unit's index in z >> 8
     int lev_shift;               // where this operand's level sits in unit_desc.w
     int Mp, Kp, s, sh;
+    int ny;                      // workgroups along y that serve this operand
     int8_t *out;
     unsigned long long *wavesum; // [Mp][waves per row]: every wave of the launch leaves its part of the row norm
 };
@@ -82,8 +83,13 @@ __device__ __forceinline__ int digit0x4(const int (&x)[4], unsigned mask4, unsig
     return (int)r;
 }
 
+// Two operands in one launch when they take the same variant: blockIdx.y below a0.ny serves a0, the
+// rest a1 (an operand's ny is its share of gridDim.y).
 template <bool DENSE>
-__global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a) {
+__global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0, ScatterArgs a1) {
+    const bool second = (int)blockIdx.y >= a0.ny;
+    const ScatterArgs &a = second ? a1 : a0;
+    const int by = second ? (int)blockIdx.y - a0.ny : (int)blockIdx.y;
     const int nunits = a.Kp >> 4, wpr = (nunits + 63) >> 6;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int upos = blockIdx.x * 64 + (int)(threadIdx.x & 63);
@@ -99,7 +105,7 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a)
         const unsigned long long t = sft >= 40u ? (1ull << 44) : (m << sft);
         return t < (1ull << 44) ? t : (1ull << 44);
     };
-    for (int p = blockIdx.y * kScatterWaves + wave; p < a.Mp; p += gridDim.y * kScatterWaves) {
+    for (int p = by * kScatterWaves + wave; p < a.Mp; p += a.ny * kScatterWaves) {
         const int slot = a.prow_slot[p], er = a.prow_exp[p];
         const int si = max(a.prow_src[p], 0);  // asked for together with the other two
         unsigned mag = 0;  // sum of |digit| over the unit
@@ -355,12 +361,14 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     FixupArgs fx[2] = {};
     int fblocks[2] = {0, 0};
     const int wpr = (h.Kp / 16 + 63) / 64;  // waves of the scatter kernel per physical row
+    ScatterArgs sc[2];
+    bool launch[2] = {false, false}, dense[2] = {false, false};
     for (int op = 0; op < 2; ++op) {
         const int rowsP = op ? h.Np : h.Mp;
         if (rowsP <= 0 || h.Kp <= 0) continue;
         const RowLayout &lay = op ? p->layB : p->layA;
         const bool both = (op ? p->sB : p->sA) == IMUNPACK_BOTH;
-        ScatterArgs a;
+        ScatterArgs &a = sc[op];
         a.M = op ? B : A; a.ld = op ? ldb : lda;
         a.prow_slot = lay.prow_slot; a.prow_src = lay.prow_src; a.prow_exp = lay.prow_exp;
         a.col_k = p->cols.colA_k;
@@ -368,11 +376,11 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         a.unit_desc = p->cols.unit_sorted;
         a.lev_shift = op ? 8 : 0;
         a.Mp = rowsP; a.Kp = h.Kp; a.s = p->s; a.sh = p->sh;
+        a.ny = std::min((rowsP + kScatterWaves - 1) / kScatterWaves, 32767);
         a.out = op ? B_eu : A_ue;
         a.wavesum = lay.wavesum;
-        const dim3 grid((unsigned)wpr, (unsigned)std::min((rowsP + kScatterWaves - 1) / kScatterWaves, 65535));
-        if (both) hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, a);
-        else hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, a);
+        launch[op] = true;
+        dense[op] = !both;
         const int nob = op ? h.nobB : h.nobA;
         if (both && nob > 0) {
             FixupArgs &f = fx[op];
@@ -390,6 +398,17 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.wavesum = lay.wavesum; f.wpr = wpr;
             fblocks[op] = (nob + 255) / 256;
         }
+    }
+    auto scatter = [&](const ScatterArgs &x, const ScatterArgs &y, int ny, bool dns) {
+        const dim3 grid((unsigned)wpr, (unsigned)ny);
+        if (dns) hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, x, y);
+        else hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, x, y);
+    };
+    if (launch[0] && launch[1] && dense[0] == dense[1]) {  // one launch: the tail of A overlaps the head of B
+        scatter(sc[0], sc[1], sc[0].ny + sc[1].ny, dense[0]);
+    } else {
+        for (int op = 0; op < 2; ++op)
+            if (launch[op]) scatter(sc[op], sc[op], sc[op].ny, dense[op]);
     }
     if (h.Kp > 0 && h.Mp + h.Np > 0) {
         // after both scatters: the fix-up overwrites zeros they wrote, the scan reads their row norms
