@@ -10,6 +10,7 @@
 // launched on its own and accumulated in int64 (the un-fused path).
 #include "common.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -461,17 +462,18 @@ __global__ __launch_bounds__(256) void recombine_kernel(const int64_t *__restric
                                                         RowLayout layB, int n, int h, int sh,
                                                         int64_t *C_int, float *C_fp, int64_t ldc,
                                                         double scale) {
-    const int i = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n || j >= h) return;
-    const int p0 = layA.src_pstart[i], li = layA.src_nlev[i];
+    if (j >= h) return;
     const int q0 = layB.src_pstart[j], lj = layB.src_nlev[j];
-    int64_t acc = 0;
-    for (int a = 0; a < li; ++a)
-        for (int c = 0; c < lj; ++c) acc += C_u[(int64_t)(p0 + a) * Np + (q0 + c)] << (sh * (a + c));
-    const int64_t o = (int64_t)i * ldc + j;
-    if (C_int) C_int[o] = acc;
-    if (C_fp) C_fp[o] = (float)((double)acc * scale);
+    for (int i = blockIdx.y; i < n; i += gridDim.y) {
+        const int p0 = layA.src_pstart[i], li = layA.src_nlev[i];
+        int64_t acc = 0;
+        for (int a = 0; a < li; ++a)
+            for (int c = 0; c < lj; ++c) acc += C_u[(int64_t)(p0 + a) * Np + (q0 + c)] << (sh * (a + c));
+        const int64_t o = (int64_t)i * ldc + j;
+        if (C_int) C_int[o] = acc;
+        if (C_fp) C_fp[o] = (float)((double)acc * scale);
+    }
 }
 
 // Register-resident back-to-back int8 MFMAs (no memory traffic): what the matrix cores sustain on
@@ -526,8 +528,7 @@ extern "C" int imunpack_recombine(const imunpack_plan_t *p, const void *workspac
     if (!p || !p->valid || !workspace || ldc < p->h) return IMUNPACK_EINVAL;
     if (!C_int && !C_fp) return IMUNPACK_OK;
     IMU_TRY(check_shifts(p));
-    dim3 grid((unsigned)((p->h + 255) / 256), (unsigned)p->n);
-    if (grid.y > 65535u) return IMUNPACK_EINVAL;
+    dim3 grid((unsigned)((p->h + 255) / 256), (unsigned)std::min<int64_t>(p->n, 65535));
     hipLaunchKernelGGL(recombine_kernel, grid, dim3(256), 0, (hipStream_t)stream,
                        (const int64_t *)workspace, p->hdr.Np, p->layA, p->layB, (int)p->n, (int)p->h, p->sh,
                        C_int, C_fp, ldc, (double)scale_A * (double)scale_B);

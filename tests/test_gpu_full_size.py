@@ -109,3 +109,56 @@ def test_percentile_full_size(imu):
         alpha, status = imu.imunpack_percentile(X.to("cuda"), 95.0)
         assert int(status.item()) == 0
         assert alpha.cpu().numpy()[0] == oracle.percentile_alpha(X.numpy(), 95.0)
+
+
+def test_more_rows_than_a_launch_dimension(imu):
+    """70 000 rows: more row blocks than one grid dimension holds in the quantize, scatter and
+    recombine launches.  Quantised integers, plan sizes and both unpacked operands in full; the
+    product at sampled positions and through the column-sum identity."""
+    n, d, h, b = 70001, 256, 384, 8
+    g = torch.Generator().manual_seed(77)
+    A = torch.randn((n, d), generator=g)
+    A[:, 5] *= 60.0
+    A[torch.rand((n, d), generator=g) < 0.0005] *= 300.0
+    B = torch.randn((h, d), generator=g) * 0.02
+    B[torch.rand((h, d), generator=g) < 0.002] *= 40.0
+    sa, sb = float(4 * A.std() / 127), float(4 * B.std() / 127)
+    Aq, fa = oracle.rtn_quantize(A.numpy(), sa)
+    Bq, fb = oracle.rtn_quantize(B.numpy(), sb)
+    assert fa == 0 and fb == 0
+    for strat_a, strat_b in ((imu.BOTH, imu.BOTH), (imu.ROW, imu.COL)):
+        Qa, st_a, f1 = imu.imunpack_quantize(A.to("cuda"), sa, b, want_ob_list=strat_a == imu.BOTH)
+        Qb, st_b, f2 = imu.imunpack_quantize(B.to("cuda"), sb, b, want_ob_list=strat_b == imu.BOTH)
+        assert int(f1.item()) == 0 and int(f2.item()) == 0
+        assert np.array_equal(Qa.cpu().numpy(), Aq) and np.array_equal(Qb.cpu().numpy(), Bq)
+        hnd = oracle.unpack_pair_handle(Aq, Bq, b, strat_a, strat_b)
+        plan = imu.imunpack_plan(Qa, Qb, b, strat_a, strat_b, st_a, st_b)
+        n_u, d_u, h_u, _ = plan.dims()
+        assert (n_u, d_u, h_u) == (hnd.n_u, hnd.d_u, hnd.h_u)
+        A_ue, B_eu = imu.imunpack_unpack(plan, Qa, Qb)
+        Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
+        oa, ob_ = hnd.operands_i8()
+        assert np.array_equal(Ac.cpu().numpy(), oa) and np.array_equal(Bc.cpu().numpy(), ob_)
+        del Ac, Bc, oa, ob_
+        C_int = torch.empty((n, h), dtype=torch.int64, device="cuda")
+        C_fp = torch.empty((n, h), dtype=torch.float32, device="cuda")
+        ws = None if plan.fusable() else torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        imu.imunpack_gemm(plan, A_ue, B_eu, sa, sb, C_int, C_fp, ws, fuse=True)
+        rng = np.random.default_rng(3)
+        rows = np.concatenate([rng.integers(0, n, 2000), [0, n - 1, 65535, 65536]])
+        cols = np.concatenate([rng.integers(0, h, 2000), [0, h - 1, 1, 2]])
+        want = oracle.int_gemm_at(Aq, Bq, rows, cols)
+        ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+        assert np.array_equal(C_int[ri, ci].cpu().numpy(), want)
+        want_fp = oracle.dequantize(want, sa, sb)
+        got_fp = C_fp[ri, ci].cpu().numpy().astype(np.float64)
+        assert (np.abs(got_fp - want_fp) <= REL_TOL * np.abs(want_fp)).all()
+        total = int(C_int.sum().item())
+        assert total == int((Aq.astype(np.int64).sum(0).astype(object) * Bq.astype(np.int64).sum(0).astype(object)).sum())
+        # the un-fused path too (its recombine launch has one block row per source row)
+        ws2 = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        C2 = torch.full((n, h), -1, dtype=torch.int64, device="cuda")
+        imu.imunpack_gemm(plan, A_ue, B_eu, sa, sb, None, None, ws2, fuse=False)
+        imu.imunpack_recombine(plan, ws2, sa, sb, C2, None)
+        assert bool((C2 == C_int).all())
+        hnd.close()
