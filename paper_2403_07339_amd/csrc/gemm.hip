@@ -382,6 +382,32 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     };
     // two chunks per round: every wave parks 64 of its 128 rows (region wm of the staging buffer), then
     // all threads work the two chunks off
+    const bool vec_split = (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (!g.C_fp || ((uintptr_t)g.C_fp % 16) == 0) &&
+                           (!g.C_int || ((uintptr_t)g.C_int % 16) == 0);
+    auto store4_split = [&](int64_t o, int cols_left, const int64_t (&v)[4]) {  // v: before the final shift
+        if (vec_split && cols_left >= 4) {
+            if (g.C_fp) {
+                v4f f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
+                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+            }
+            if (g.C_int) {
+                v2l lo, hi;
+                lo[0] = v[0] << g.final_shift; lo[1] = v[1] << g.final_shift;
+                hi[0] = v[2] << g.final_shift; hi[1] = v[3] << g.final_shift;
+                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
+                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < cols_left) {
+                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
+                    if (g.C_int) g.C_int[o + k] = v[k] << g.final_shift;
+                }
+        }
+    };
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         __syncthreads();
@@ -433,24 +459,97 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                     }
                 }
             } else {
-                // split source columns: work items are (source row, source column)
-                for (int it = tid; it < ns * nsrcB; it += kGemmThreads) {
-                    const int r = it / nsrcB, jc = it - r * nsrcB;
-                    int prel = r, nl = 1;
+                // split source columns: lane l owns source columns 4l .. 4l+3 of the tile (where they sit in
+                // the tile and how many digit levels each has is looked up once per chunk).  Four unsplit
+                // columns side by side are the usual case and go the way of the flat tile (behind a split
+                // column they no longer start at a multiple of four: four words rather than one vector).
+                // A few other quads are then worked off one at a time with the wave's rows spread over its
+                // lanes, so that their level loops run once per wave and quad, not once per row; if most
+                // quads are of that kind, every lane works its own.
+                const int j4 = (tid & 63) * 4;
+                int q0[4], lj[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int cm = j4 + k < nsrcB ? colmeta[j4 + k] : 0;
+                    q0[k] = cm & 0xFFFF;
+                    lj[k] = cm >> 16;  // 0 past the last source column
+                }
+                const bool plain = lj[0] == 1 && lj[1] == 1 && lj[2] == 1 && lj[3] == 1 && q0[1] == q0[0] + 1 &&
+                                   q0[2] == q0[0] + 2 && q0[3] == q0[0] + 3;
+                const unsigned long long others = __ballot(j4 < nsrcB && !plain);
+                auto row_levels = [&](int r, int &prel, int &nl) {
+                    prel = r;
+                    nl = 1;
                     if (!flatA) {
                         const int m = rowmeta[rs0 + r];
                         prel = (m & 0xFFFF) - c * kChunk;
                         nl = m >> 16;
                     }
-                    const int cm = colmeta[jc];
-                    const int q0 = cm & 0xFFFF, lj = cm >> 16;
-                    int64_t v = 0;
-                    for (int a = 0; a < nl; ++a)
-                        for (int l = 0; l < lj; ++l)
-                            v += (int64_t)fold[(prel + a) * FLD + q0 + l] << (g.sh * (a + l));
-                    const int64_t o = (int64_t)(cs0 + r) * g.ldc + jsrc0 + jc;
-                    if (g.C_int) g.C_int[o] = v << g.final_shift;
-                    if (g.C_fp) g.C_fp[o] = (float)((double)v * scale2);
+                };
+                if (plain) {
+                    const bool aligned = (q0[0] & 3) == 0;
+                    for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                        int prel, nl;
+                        row_levels(r, prel, nl);
+                        int64_t v[4] = {0, 0, 0, 0};
+                        for (int a = 0; a < nl; ++a) {
+                            const int32_t *row = fold + (prel + a) * FLD + q0[0];
+                            v4i x;
+                            if (aligned) {
+                                x = *reinterpret_cast<const v4i *>(row);
+                            } else {
+                                x[0] = row[0]; x[1] = row[1]; x[2] = row[2]; x[3] = row[3];
+                            }
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * a);
+                        }
+                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v);
+                    }
+                }
+                const bool many = __popcll(others) > 8;  // mostly split columns: every lane works its own quad
+                if (many && !plain && j4 < nsrcB) {
+                    const int ljmax = max(max(lj[0], lj[1]), max(lj[2], lj[3]));
+                    for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
+                        int prel, nl;
+                        row_levels(r, prel, nl);
+                        int64_t v[4] = {0, 0, 0, 0};
+                        for (int a = 0; a < nl; ++a) {
+                            const int32_t *row = fold + (prel + a) * FLD;
+                            for (int l = 0; l < ljmax; ++l) {
+                                int x[4];
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) x[k] = l < lj[k] ? row[q0[k] + l] : 0;
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * (a + l));
+                            }
+                        }
+                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v);
+                    }
+                }
+                for (unsigned long long m = many ? 0ull : others; m; m &= m - 1) {
+                    const int from = __builtin_ctzll(m);  // the lane that owns this quad
+                    int Q0[4], LJ[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        Q0[k] = __builtin_amdgcn_readlane(q0[k], from);
+                        LJ[k] = __builtin_amdgcn_readlane(lj[k], from);
+                    }
+                    const int ljmax = max(max(LJ[0], LJ[1]), max(LJ[2], LJ[3]));
+                    const int r = (tid >> 6) + (kGemmThreads / 64) * (tid & 63);  // this wave's rows, one per lane
+                    if (r < ns) {
+                        int prel, nl;
+                        row_levels(r, prel, nl);
+                        int64_t v[4] = {0, 0, 0, 0};
+                        for (int a = 0; a < nl; ++a) {
+                            const int32_t *row = fold + (prel + a) * FLD;
+                            for (int l = 0; l < ljmax; ++l) {
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    if (l < LJ[k]) v[k] += (int64_t)row[Q0[k] + l] << (g.sh * (a + l));
+                            }
+                        }
+                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + 4 * from, nsrcB - 4 * from, v);
+                    }
                 }
             }
         }
