@@ -24,6 +24,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef long v2l __attribute__((ext_vector_type(2)));
+typedef float v4f_u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at any float boundary
+typedef long v2l_u __attribute__((ext_vector_type(2), aligned(8)));
 
 constexpr int BM = kTile, BN = kTile, BK = 128;  // bytes (= int8 elements) of K per LDS stage: one full 128-byte line per row
 constexpr int kGemmThreads = 256;                // 4 waves, 2 x 2, each 128 x 128
@@ -322,8 +324,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     int32_t *rowmeta = foldbuf + 2 * kChunk * FLD, *colmeta = rowmeta + kTile, *chunk0 = colmeta + kTile;
     // scale * 2^final_shift is exact: one multiplication in binary64, one rounding to fp32
     const double scale2 = g.scale * (double)(1ull << g.final_shift);
-    const bool vec_ok = flatB && (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (nsrcB % 4) == 0 &&
-                        (!g.C_fp || ((uintptr_t)g.C_fp % 16) == 0) && (!g.C_int || ((uintptr_t)g.C_int % 16) == 0);
     {
         const int isrc0 = g.layA.tile_src0[tm], nsrcA = g.layA.tile_src0[tm + 1] - isrc0;
         if (!flatA && tid < nsrcA)
@@ -332,82 +332,45 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             colmeta[tid] = (g.layB.src_pstart[jsrc0 + tid] - n0) | (g.layB.src_nlev[jsrc0 + tid] << 16);
         if (tid <= kTile / kChunk) chunk0[tid] = g.layA.chunk_src0[tm * (kTile / kChunk) + tid];
     }  // published by the first barrier below
-    auto store4_32 = [&](int64_t o, int cols_left, const v4i &v) {  // a single level: the int32 sums as they are
-        if (vec_ok) {
-            if (g.C_fp) {
-                v4f f;
+    // Four results of one output row leave as 16 bytes of fp32 and / or 32 bytes of int64 (any element
+    // boundary will do: a wave still writes a contiguous kilobyte), fewer than four at the ragged end of
+    // a tile one by one.  v: the integer sums before the final shift.
+    auto store4 = [&](int64_t o, int cols_left, auto v0, auto v1, auto v2, auto v3) {
+        const int64_t w[4] = {(int64_t)v0, (int64_t)v1, (int64_t)v2, (int64_t)v3};
+        float f[4];
+        if (g.C_fp) {
+            if constexpr (sizeof(v0) == 4) {
+                f[0] = (float)((double)v0 * scale2); f[1] = (float)((double)v1 * scale2);
+                f[2] = (float)((double)v2 * scale2); f[3] = (float)((double)v3 * scale2);
+            } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
-                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+                for (int k = 0; k < 4; ++k) f[k] = (float)((double)w[k] * scale2);
             }
-            if (g.C_int) {
-                v2l lo, hi;
-                lo[0] = (int64_t)v[0] << g.final_shift; lo[1] = (int64_t)v[1] << g.final_shift;
-                hi[0] = (int64_t)v[2] << g.final_shift; hi[1] = (int64_t)v[3] << g.final_shift;
-                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
-                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (k < cols_left) {
-                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
-                    if (g.C_int) g.C_int[o + k] = (int64_t)v[k] << g.final_shift;
-                }
         }
-    };
-    auto store4 = [&](int64_t o, int cols_left, const int64_t (&v)[4]) {  // v: before the final shift
-        if (vec_ok) {
+        if (cols_left >= 4) {
             if (g.C_fp) {
-                v4f f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
-                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
+                v4f_u x;
+                x[0] = f[0]; x[1] = f[1]; x[2] = f[2]; x[3] = f[3];
+                __builtin_nontemporal_store(x, reinterpret_cast<v4f_u *>(g.C_fp + o));
             }
             if (g.C_int) {
-                v2l lo, hi;
-                lo[0] = v[0] << g.final_shift; lo[1] = v[1] << g.final_shift;
-                hi[0] = v[2] << g.final_shift; hi[1] = v[3] << g.final_shift;
-                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
-                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
+                v2l_u lo, hi;
+                lo[0] = w[0] << g.final_shift; lo[1] = w[1] << g.final_shift;
+                hi[0] = w[2] << g.final_shift; hi[1] = w[3] << g.final_shift;
+                __builtin_nontemporal_store(lo, reinterpret_cast<v2l_u *>(g.C_int + o));
+                __builtin_nontemporal_store(hi, reinterpret_cast<v2l_u *>(g.C_int + o + 2));
             }
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 if (k < cols_left) {
-                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
-                    if (g.C_int) g.C_int[o + k] = v[k] << g.final_shift;
+                    if (g.C_fp) g.C_fp[o + k] = f[k];
+                    if (g.C_int) g.C_int[o + k] = w[k] << g.final_shift;
                 }
         }
     };
     // two chunks per round: every wave parks 64 of its 128 rows (region wm of the staging buffer), then
     // all threads work the two chunks off
-    const bool vec_split = (g.ldc % 4) == 0 && (jsrc0 % 4) == 0 && (!g.C_fp || ((uintptr_t)g.C_fp % 16) == 0) &&
-                           (!g.C_int || ((uintptr_t)g.C_int % 16) == 0);
-    auto store4_split = [&](int64_t o, int cols_left, const int64_t (&v)[4]) {  // v: before the final shift
-        if (vec_split && cols_left >= 4) {
-            if (g.C_fp) {
-                v4f f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) f[k] = (float)((double)v[k] * scale2);
-                __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(g.C_fp + o));
-            }
-            if (g.C_int) {
-                v2l lo, hi;
-                lo[0] = v[0] << g.final_shift; lo[1] = v[1] << g.final_shift;
-                hi[0] = v[2] << g.final_shift; hi[1] = v[3] << g.final_shift;
-                __builtin_nontemporal_store(lo, reinterpret_cast<v2l *>(g.C_int + o));
-                __builtin_nontemporal_store(hi, reinterpret_cast<v2l *>(g.C_int + o + 2));
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (k < cols_left) {
-                    if (g.C_fp) g.C_fp[o + k] = (float)((double)v[k] * scale2);
-                    if (g.C_int) g.C_int[o + k] = v[k] << g.final_shift;
-                }
-        }
-    };
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         __syncthreads();
@@ -436,7 +399,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #ifdef IMU_GEMM_DIAG
                         if constexpr ((g_diag & 16) != 0) { if (x[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
 #endif
-                        store4_32((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x);
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x[0], x[1], x[2], x[3]);
                     }
                 } else if (col4 < nsrcB) {
                     for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
@@ -455,7 +418,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #ifdef IMU_GEMM_DIAG
                         if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
 #endif
-                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v);
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v[0], v[1], v[2], v[3]);
                     }
                 }
             } else {
@@ -503,7 +466,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #pragma unroll
                             for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * a);
                         }
-                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v);
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v[0], v[1], v[2], v[3]);
                     }
                 }
                 const bool many = __popcll(others) > 8;  // mostly split columns: every lane works its own quad
@@ -523,7 +486,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                                 for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * (a + l));
                             }
                         }
-                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v);
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + j4, nsrcB - j4, v[0], v[1], v[2], v[3]);
                     }
                 }
                 for (unsigned long long m = many ? 0ull : others; m; m &= m - 1) {
@@ -548,7 +511,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                                     if (l < LJ[k]) v[k] += (int64_t)row[Q0[k] + l] << (g.sh * (a + l));
                             }
                         }
-                        store4_split((int64_t)(cs0 + r) * g.ldc + jsrc0 + 4 * from, nsrcB - 4 * from, v);
+                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + 4 * from, nsrcB - 4 * from, v[0], v[1], v[2], v[3]);
                     }
                 }
             }
