@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 # HBM bytes per launch of the GEMM kernel (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this
 # file, each scaled by what the counter reads for a plain copy of known size; the summary of those runs
 # is profiles/bench_workload3_hbm_traffic.md).  Only measured for the default workload.
-GEMM_TRAFFIC_BYTES = {3: 839.0e6}
+GEMM_TRAFFIC_BYTES = {3: 830.0e6}
 
 
 def cpu_baseline(w, budget_rows: int = 4096):
