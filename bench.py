@@ -222,6 +222,19 @@ def main():
     torch.cuda.synchronize()
     ms_step_wq = (time.perf_counter() - t0) * 1e3 / args.steps
     stage_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / args.steps for i in range(5)]
+    # The clock the matrix cores run at inside the step's own GEMM (its first workgroup times its loop
+    # over K with the shader clock and with the constant 100 MHz clock): the power limit holds it below
+    # the 2.4 GHz of the published peak.
+    clock_mhz = None
+    if plan.fusable():
+        ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+        imu.imunpack_diag_clock_probe(ticks)
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        imu.imunpack_diag_clock_probe(None)
+        cyc, wall = ticks.tolist()
+        clock_mhz = 100.0 * cyc / wall if wall > 0 else None
     extra = measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
     n_u, d_u, h_u, ng = plan.dims()
     ba, bb, _ = plan.unpacked_bytes()
@@ -251,6 +264,9 @@ def main():
                      "traffic": GEMM_TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
     }
+    if clock_mhz:
+        out["roofline"]["clock_mhz_in_k_loop"] = clock_mhz
+        out["roofline"]["frac_of_peak_at_that_clock"] = achieved / (INT8_PEAK_TOPS * clock_mhz / 2400.0)
     out["weights_prequantized"] = {"ms_per_step": ms_step_wq, "value": w.ops / (ms_step_wq * 1e-3) / 1e12, "unit": "TOPS",
                                    "note": "same step with the RTN integers and scan statistics of B kept from an "
                                            "earlier step (weights are quantised once); not the headline value"}

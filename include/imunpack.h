@@ -223,6 +223,14 @@ int imunpack_plan_bounds(const imunpack_plan_t *plan, uint64_t *bound);
  * (2 per multiply-add) the launch performs to *ops.  The caller times the stream. */
 int imunpack_diag_mfma_peak(int workgroups, int iters, int64_t *ops, imunpack_stream_t stream);
 
+/* Shader clock under the GEMM's own load (benchmark reporting only).  While `ticks` (device, two
+ * elements, owned by the caller) is set, every fused imunpack_gemm launch of this process has its
+ * first workgroup write ticks[0] = shader clock cycles and ticks[1] = ticks of the constant 100 MHz
+ * clock that its loop over K took; ticks[0] / ticks[1] * 100 is the clock in MHz the matrix cores ran
+ * at, which the power limit holds below the 2400 MHz the published peak assumes.  NULL switches the
+ * probe off (the default).  Not thread safe; set it while no GEMM is in flight. */
+int imunpack_diag_clock_probe(uint64_t *ticks);
+
 #ifdef __cplusplus
 }
 #endif

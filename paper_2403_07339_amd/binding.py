@@ -26,7 +26,7 @@ EXPORTS = [
     "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
-    "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_price",
+    "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_price",
     "imunpack_percentile",
 ]
 
@@ -55,6 +55,7 @@ _lib.imunpack_plan_fusable.argtypes = [_vp]
 _lib.imunpack_percentile.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _vp, _vp, _vp, _vp]
 _lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
+_lib.imunpack_diag_clock_probe.argtypes = [_vp]
 _lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
                                 C.POINTER(C.c_double), C.POINTER(_i32), C.POINTER(_i32), _vp]
 for _name in EXPORTS:
@@ -318,6 +319,14 @@ def imunpack_diag_mfma_peak(workgroups: int, iters: int) -> int:
     ops = _i64(0)
     _check(_lib.imunpack_diag_mfma_peak(int(workgroups), int(iters), C.byref(ops), _stream()), "imunpack_diag_mfma_peak")
     return int(ops.value)
+
+
+def imunpack_diag_clock_probe(ticks: torch.Tensor | None) -> None:
+    """ticks: two int64 on the device that the first workgroup of every later fused GEMM launch fills
+    with {shader clock cycles, 100 MHz ticks} of its loop over K; None switches the probe off."""
+    if ticks is not None:
+        assert ticks.is_cuda and ticks.dtype == torch.int64 and ticks.is_contiguous() and ticks.numel() >= 2
+    _check(_lib.imunpack_diag_clock_probe(_ptr(ticks)), "imunpack_diag_clock_probe")
 
 
 def imunpack_price(stats_a: Stats, n: int, stats_b: Stats, h: int, d: int, b: int):

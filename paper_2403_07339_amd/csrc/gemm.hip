@@ -56,6 +56,8 @@ struct GemmArgs {
     // and writes nothing if the shifted group sum could leave int32
     const unsigned long long *guard;
     int guard_mul;            // s - 1
+    // benchmark reporting: if set, workgroup 0 writes {shader clock ticks, 100 MHz wall ticks} of its K loop
+    unsigned long long *clock_probe;
 };
 
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2,
@@ -193,6 +195,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
         }
     };
 
+    unsigned long long probe_c = 0, probe_w = 0;
+    const bool probing = MODE == 0 && g.clock_probe != nullptr && blockIdx.x == 0;
+    if (probing) {
+        probe_c = __builtin_readcyclecounter();
+        probe_w = wall_clock64();
+    }
     // ---- prologue: k-tile kt0 landed, k-tile kt0+1 in flight, first fragments loaded
     int sa = 0;  // ring slot of A(kt); B(kt) is sa+1, A(kt+1) sa+2, B(kt+1) sa+3, A(kt+2) sa+4, B(kt+2) sa
     half_setup(gA, kt0, 0);
@@ -269,6 +277,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             step(1, stA1, stB1, 0, 0, 8);
             sa = ring(sa, 2);
         }
+    }
+    if (probing && tid == 0) {
+        g.clock_probe[0] = __builtin_readcyclecounter() - probe_c;
+        g.clock_probe[1] = wall_clock64() - probe_w;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before LDS is reused
     __syncthreads();  // all fragment reads done: the buffers may be reused by the epilogue
@@ -568,6 +580,8 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int *sink) {
 
 using namespace imu;
 
+static unsigned long long *g_clock_probe = nullptr;  // device memory of the caller, see imunpack_diag_clock_probe
+
 static int gemm_lds_opt_in() {
     static int done = 0;  // the kernels use 128 KiB of dynamic LDS, above the default limit
     if (!done) {
@@ -643,6 +657,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, cons
         g.final_shift = h.ngroups ? p->sh * h.grp_exp[h.ngroups - 1] : 0;
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
+        g.clock_probe = g_clock_probe;
         hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
         IMU_TRY(launch_status());
         if (!speculate) return IMUNPACK_OK;
@@ -664,6 +679,11 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, cons
     IMU_TRY(launch_status());
     if (fuse != 0)  // the caller asked for final outputs: finish the job here
         return imunpack_recombine(p, workspace, scale_A, scale_B, C_int, C_fp, ldc, stream);
+    return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_diag_clock_probe(uint64_t *ticks) {
+    g_clock_probe = reinterpret_cast<unsigned long long *>(ticks);
     return IMUNPACK_OK;
 }
 

@@ -304,6 +304,36 @@ def test_fused_launch_before_the_bounds_are_known(imu):
     assert np.array_equal(C_int.cpu().numpy(), want)
 
 
+def test_clock_probe_reports_a_plausible_clock_and_leaves_the_result_alone(imu):
+    """While the probe is set a fused GEMM writes {shader cycles, 100 MHz ticks} of its first workgroup's
+    loop over K; the product is the same with and without it, and nothing is written once it is off."""
+    rng = np.random.default_rng(11)
+    Aq = rng.integers(-300, 300, size=(300, 4096)).astype(np.int32)
+    Bq = rng.integers(-300, 300, size=(260, 4096)).astype(np.int32)
+    want = oracle.int_gemm(Aq, Bq)
+    Qa, Qb = torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda()
+    plan = imu.imunpack_plan(Qa, Qb, 8, ROW, COL)
+    A_ue, B_eu = imu.imunpack_unpack(plan, Qa, Qb)
+    assert plan.fusable()
+    C_int = torch.empty(want.shape, dtype=torch.int64, device="cuda")
+    ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    imu.imunpack_diag_clock_probe(ticks)
+    try:
+        imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C_int, None, None, fuse=True)
+        torch.cuda.synchronize()
+    finally:
+        imu.imunpack_diag_clock_probe(None)
+    assert np.array_equal(C_int.cpu().numpy(), want)
+    cyc, wall = ticks.tolist()
+    assert cyc > 0 and wall > 0
+    assert 300.0 < 100.0 * cyc / wall < 3000.0, (cyc, wall)
+    ticks.zero_()
+    imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C_int, None, None, fuse=True)
+    torch.cuda.synchronize()
+    assert ticks.tolist() == [0, 0]
+    assert np.array_equal(C_int.cpu().numpy(), want)
+
+
 @pytest.mark.parametrize("kind,b", [("scattered", 8), ("channels", 8), ("heavy", 4), ("deep", 8), ("clean", 8), ("rows", 3)])
 def test_price_matches_unpacked_sizes(imu, kind, b):
     """Sec. 4.2: the sizes n', d', h' (and so the unpack ratio r) that imunpack_price reads off the scan
