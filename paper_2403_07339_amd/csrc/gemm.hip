@@ -56,6 +56,7 @@ struct GemmArgs {
     // and writes nothing if the shifted group sum could leave int32
     const unsigned long long *guard;
     int guard_mul;            // s - 1
+    int fold_f64;             // no int64 output wanted and every sum over digit levels is exact in binary64
     // benchmark reporting: if set, workgroup 0 writes {shader clock ticks, 100 MHz wall ticks} of its K loop
     unsigned long long *clock_probe;
 };
@@ -348,6 +349,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // boundary will do: a wave still writes a contiguous kilobyte), fewer than four at the ragged end of
     // a tile one by one.  v: the integer sums before the final shift.
     auto store4 = [&](int64_t o, int cols_left, auto v0, auto v1, auto v2, auto v3) {
+        if constexpr (std::is_same<decltype(v0), double>::value) {  // exact integer sums held in binary64; no int64 output
+            const float f[4] = {(float)(v0 * scale2), (float)(v1 * scale2), (float)(v2 * scale2), (float)(v3 * scale2)};
+            if (cols_left >= 4) {
+                v4f_u x;
+                x[0] = f[0]; x[1] = f[1]; x[2] = f[2]; x[3] = f[3];
+                __builtin_nontemporal_store(x, reinterpret_cast<v4f_u *>(g.C_fp + o));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (k < cols_left) g.C_fp[o + k] = f[k];
+            }
+            return;
+        }
         const int64_t w[4] = {(int64_t)v0, (int64_t)v1, (int64_t)v2, (int64_t)v3};
         float f[4];
         if (g.C_fp) {
@@ -414,24 +428,54 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                         store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x[0], x[1], x[2], x[3]);
                     }
                 } else if (col4 < nsrcB) {
-                    for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
-                        int prel = r, nl = 1;
-                        if (!flatA) {
-                            const int m = rowmeta[rs0 + r];
-                            prel = (m & 0xFFFF) - c * kChunk;
-                            nl = m >> 16;
-                        }
-                        int64_t v[4] = {0, 0, 0, 0};
-                        for (int l = 0; l < nl; ++l) {
-                            const v4i x = *reinterpret_cast<const v4i *>(fold + (prel + l) * FLD + col4);
+                    // split rows: the digit levels of a source row are added up, four source rows at a time
+                    // per thread so that their LDS reads are in flight together (a wave works on one row, so
+                    // the level counts are uniform); in binary64 where every sum is exact in it
+                    constexpr int RS = kGemmThreads / 64;
+                    auto fold_rows = [&](auto zero) {
+                        using T = decltype(zero);
+                        for (int r0 = tid >> 6; r0 < ns; r0 += 4 * RS) {
+                            int prel[4], nl[4];
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) v[k] += (int64_t)x[k] << (g.sh * l);
+                            for (int u = 0; u < 4; ++u) {
+                                const int m = r0 + u * RS < ns ? rowmeta[rs0 + r0 + u * RS] : 0;
+                                prel[u] = (m & 0xFFFF) - c * kChunk;
+                                nl[u] = m >> 16;  // 0 past the chunk's last source row
+                            }
+                            const int nlmax = max(max(nl[0], nl[1]), max(nl[2], nl[3]));
+                            T v[4][4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) v[u][k] = zero;
+                            for (int l = 0; l < nlmax; ++l) {
+                                v4i x[4];
+#pragma unroll
+                                for (int u = 0; u < 4; ++u)
+                                    x[u] = l < nl[u] ? *reinterpret_cast<const v4i *>(fold + (prel[u] + l) * FLD + col4)
+                                                     : v4i{0, 0, 0, 0};
+                                if constexpr (std::is_same<T, double>::value) {
+                                    const double wl = (double)(1ull << (g.sh * l));
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                                        for (int k = 0; k < 4; ++k) v[u][k] += (double)x[u][k] * wl;
+                                } else {
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                                        for (int k = 0; k < 4; ++k) v[u][k] += (int64_t)x[u][k] << (g.sh * l);
+                                }
+                            }
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+                                if (r0 + u * RS < ns)
+                                    store4((int64_t)(cs0 + r0 + u * RS) * g.ldc + jsrc0 + col4, nsrcB - col4, v[u][0],
+                                           v[u][1], v[u][2], v[u][3]);
                         }
-#ifdef IMU_GEMM_DIAG
-                        if constexpr ((g_diag & 16) != 0) { if (v[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
-#endif
-                        store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, v[0], v[1], v[2], v[3]);
-                    }
+                    };
+                    if (g.fold_f64) fold_rows(0.0);
+                    else fold_rows((int64_t)0);
                 }
             } else {
                 // split source columns: lane l owns source columns 4l .. 4l+3 of the tile (where they sit in
@@ -658,6 +702,8 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, cons
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
         g.clock_probe = g_clock_probe;
+        // |accumulator| < 2^31, weights up to s^(levels of a row - 1 + levels of a column - 1)
+        g.fold_f64 = !C_int && 31 + p->sh * ((h.lmaxA - 1) + (h.lmaxB - 1)) <= 52;
         hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
         IMU_TRY(launch_status());
         if (!speculate) return IMUNPACK_OK;

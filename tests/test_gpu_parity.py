@@ -133,6 +133,11 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     C_fp2 = torch.full((n, h), -7.0, dtype=torch.float32, device="cuda")
     imu.imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, C_int2, C_fp2, ws, fuse=True)
     results.append(("fused" if plan.fusable() else "fused->fallback", C_int2, C_fp2))
+    # fp32 output alone: the fused epilogue may then add the digit levels up in binary64 instead of
+    # int64, which must not change a single bit of the result
+    C_fp3 = torch.full((n, h), -7.0, dtype=torch.float32, device="cuda")
+    imu.imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, None, C_fp3, ws, fuse=True)
+    assert torch.equal(C_fp3, C_fp2), "fp32-only output differs from the fp32 + int64 call"
     for name, ci, cf in results:
         assert np.array_equal(ci.cpu().numpy(), want), name
         got = cf.cpu().numpy().astype(np.float64)
