@@ -472,6 +472,58 @@ def test_linear_layer_forward_and_backward(imu, b, strategies):
     assert float(rel) < 0.15
 
 
+@pytest.mark.parametrize("b,strategies", [(8, (BOTH, BOTH)), (4, (ROW, COL))])
+def test_attention_gemms_forward_and_backward(imu, b, strategies):
+    """The six GEMMs of self-attention (Sec. 3), two sequences x three heads, each against the oracle
+    chain on the very operands the module fed it (the softmax between them is fp32 arithmetic outside
+    the GEMMs, so the intermediates are taken from the module's trace):
+    P = Q K^T, O = M V, grad_M = grad_O V^T, grad_V = M^T grad_O, grad_Q = grad_P K, grad_K = grad_P^T Q."""
+    from paper_2403_07339_amd import attention, linear
+    g = torch.Generator().manual_seed(300 + b)
+    lead, T, dh = (2, 3), 72, 40
+    q = torch.randn((*lead, T, dh), generator=g)
+    k = torch.randn((*lead, T, dh), generator=g)
+    v = torch.randn((*lead, T, dh), generator=g)
+    k[..., 5] *= 12.0                                     # an outlier channel in the keys
+    cfg = linear.QuantConfig(beta_x=31.0, beta_w=31.0, beta_g=255.0, p=95.0, b=b,
+                             strategy_a=strategies[0], strategy_b=strategies[1])
+    trace = {}
+    attn = attention.IMUnpackAttention(cfg, trace)
+    qd, kd, vd = (t.to("cuda").requires_grad_(True) for t in (q, k, v))
+    out = attn(qd, kd, vd)
+    go = torch.randn((*lead, T, dh), generator=g) * 1e-2
+    go[torch.rand(go.shape, generator=g) < 0.01] *= 30.0
+    out.backward(go.to("cuda"))
+    assert out.shape == (*lead, T, dh) and set(trace) == {"P", "M", "O", "grad_M", "grad_P"}
+    t = {name: val.detach().cpu().numpy() for name, val in trace.items()}
+    gq, gk, gv = (x.grad.detach().cpu().numpy() for x in (qd, kd, vd))
+    qn, kn, vn, gon = q.numpy(), k.numpy(), v.numpy(), go.numpy()
+    bx, bg = 31.0, 255.0
+
+    def close(got, want):
+        return (np.abs(got.astype(np.float64) - want) <= REL_TOL * np.abs(want)).all()
+
+    assert np.array_equal(t["O"], out.detach().cpu().numpy())
+    for i in range(lead[0]):
+        for j in range(lead[1]):
+            M, gP = t["M"][i, j], t["grad_P"][i, j]
+            assert close(t["P"][i, j], _oracle_matmul(qn[i, j], kn[i, j], 95.0, bx, bx))
+            assert close(t["O"][i, j], _oracle_matmul(M, vn[i, j].T, 95.0, bx, bx))
+            assert close(t["grad_M"][i, j], _oracle_matmul(gon[i, j], vn[i, j], 95.0, bg, bx))
+            assert close(gv[i, j], _oracle_matmul(M.T, gon[i, j].T, 95.0, bx, bg))
+            assert close(gq[i, j], _oracle_matmul(gP, kn[i, j].T, 95.0, bg, bx))
+            assert close(gk[i, j], _oracle_matmul(gP.T, qn[i, j].T, 95.0, bg, bx))
+    # the fp32 steps between the GEMMs, and the whole against fp32 attention
+    scale = 1.0 / np.sqrt(dh)
+    Mref = torch.softmax(trace["P"].cpu() * scale, -1).numpy()
+    assert np.allclose(t["M"], Mref, rtol=1e-5, atol=1e-7)
+    gPref = (t["grad_M"] - (t["grad_M"] * t["M"]).sum(-1, keepdims=True)) * t["M"] * scale
+    assert np.allclose(t["grad_P"], gPref, rtol=1e-4, atol=1e-8)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v)
+    rel = (out.detach().cpu() - ref).norm() / ref.norm()
+    assert float(rel) < 0.2
+
+
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_random_shapes_strategies_and_densities(imu, seed):
     """Seeded sweep over what the other cases fix: ragged shapes from one row to a few tiles, every
