@@ -254,14 +254,14 @@ struct GreedyArgs {
 // An edge of the greedy: an OB entry's current row slot, column slot and the number of base-s digits
 // it still has there (>= 2 while it is OB).  Only that number matters: a split moves floor(v / s) on.
 constexpr int kEdgeSlotBits = 29;
+constexpr unsigned kEdgeSlotMask = (1u << kEdgeSlotBits) - 1u;
+// A packed edge is two 32-bit words, so that a pass never needs 64-bit arithmetic: the low word holds
+// the row slot, the high word the column slot, and the three bits above each slot number hold the low
+// and the high half of the number of digits left (2 .. 63, so a packed edge is never 0).
 __device__ __forceinline__ unsigned long long pack_edge(int row, int col, int levels) {
-    return (unsigned long long)(unsigned)row | ((unsigned long long)(unsigned)col << kEdgeSlotBits) |
-           ((unsigned long long)(unsigned)levels << (2 * kEdgeSlotBits));
-}
-__device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int &col, int &levels) {
-    row = (int)(e & ((1u << kEdgeSlotBits) - 1));
-    col = (int)((e >> kEdgeSlotBits) & ((1u << kEdgeSlotBits) - 1));
-    levels = (int)(e >> (2 * kEdgeSlotBits));
+    const unsigned lo = (unsigned)row | (((unsigned)levels & 7u) << kEdgeSlotBits);
+    const unsigned hi = (unsigned)col | (((unsigned)levels >> 3) << kEdgeSlotBits);
+    return (unsigned long long)lo | ((unsigned long long)hi << 32);
 }
 
 // The sequential algorithm splits, at every step, the row or column with the top OB count (rows win
@@ -279,9 +279,9 @@ __device__ __forceinline__ void unpack_edge(unsigned long long e, int &row, int 
 // (ob_copy_kernel finds those extra edges before this kernel starts).
 // A batch is one pass over the live entries: an entry in a split slot keeps digit 0 there and moves
 // floor(v / s) to the new slot (Alg. 4 lines 7-9 / 11-14); if that is In-Bound the entry is finished:
-// it leaves the count of the crossing slot and the list.  The first pass reads the operand's OB list
-// itself; its survivors and those of every later pass are written, compacted, to a list of packed
-// edges.  The order inside a batch only decides the numbers of the appended slots; it is recorded as
+// it leaves the count of the crossing slot and the list.  The entries are packed edges (row slot,
+// column slot, digits left); the first list comes from ob_copy_kernel, the survivors of every pass are
+// written, compacted, to the other of two lists.  The order inside a batch only decides the numbers of the appended slots; it is recorded as
 // a sort key (batch, count descending, split slot) and the appended slots are renumbered on the host
 // when the plan is exported.
 template <bool LDS>
@@ -296,7 +296,6 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     if (hdr->overflow) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned long long below = (1ull << lane) - 1ull;
-    const int32_t *__restrict__ ob = g.ob;
     int nr = *g.nr_io, nc;
     if (g.cols_init) {
         nc = *g.cols_init;
@@ -316,14 +315,6 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     const int rpad = (g.rows.cap + 7) & ~3, cpad = (g.cols.cap + 7) & ~3;  // int4 reads may run past the last slot
     int32_t *rc = LDS ? lds_counts : g.rcnt;
     int32_t *cc = LDS ? lds_counts + rpad : g.ccnt;
-    // number of base-s digits of a magnitude: ceil(bits / sh), the division as a multiplication
-    const unsigned inv_sh = (65536u + (unsigned)g.sh - 1u) / (unsigned)g.sh;
-    auto levels_of = [&](int v) -> int {
-        if (v == 0) return 0;
-        const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
-        const unsigned bits = 32u - (unsigned)__clz(av);
-        return (int)(((bits + (unsigned)g.sh - 1u) * inv_sh) >> 16);
-    };
     // ---- starting counts
     int deep = 0;
     const int s2 = g.s * g.s;
@@ -338,10 +329,10 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         s_top[0] = s_top[1] = 0;
     }
     __syncthreads();
-    // ---- the extra edges of repeated columns (second operand only) were found by ob_copy_kernel: they
-    // head the first edge list, and the rows they touch start with that many more OB entries
+    // ---- the first edge list was written by ob_copy_kernel: one packed edge per OB entry, then the extra
+    // edges of repeated columns (second operand only; the rows they touch start with that many more OB
+    // entries)
     unsigned long long *list0 = g.edges, *list1 = g.edges + ((g.ecap + 1) & ~1);  // both 16-byte aligned
-    constexpr int U = 4;
     if (g.chain_child && threadIdx.x == 0) s_count = hdr->extras;
     __syncthreads();
     deep = block_max(deep, lds);
@@ -355,7 +346,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         if (threadIdx.x == 0) flag_overflow(hdr, g.whichE, (int)min(Etotal, 1ll << 30));
         return;
     }
-    int E = extras, cur = 0;
+    int E = (int)Etotal, cur = 0;  // live edges; they are in list `cur`
     const long long max_batches = 32ll * Etotal + 64;  // every batch retires >= one digit of one entry
     for (long long bid = 0;; ++bid) {
         if (bid > max_batches || bid >= 65535) {
@@ -494,73 +485,50 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             break;
         }
         // (4) the pass.  The survivors of U entries per lane are appended with one counter update per wave.
-        unsigned long long *dst = bid == 0 ? list1 : (cur ? list0 : list1);
-        constexpr unsigned long long kSlotMask = (1ull << kEdgeSlotBits) - 1ull;
-        const int xshift = isrow ? 0 : kEdgeSlotBits, oshift = isrow ? kEdgeSlotBits : 0;
+        unsigned long long *dst = cur ? list0 : list1;
         auto process = [&](auto &e) {  // e[u]: packed edge, 0 if absent
             constexpr int U = sizeof(e) / sizeof(unsigned long long);
+            unsigned xw[U], ow[U];  // the word that names the slot on the batch's side, and the other one
             int c[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)  // marks do not change during a pass; slot 0's count is harmless for absent edges
-                c[u] = cnt[(int)((e[u] >> xshift) & kSlotMask)];
-            int before = 0, all = 0;
+            for (int u = 0; u < U; ++u) {  // marks do not change during a pass; slot 0's count is harmless for absent edges
+                const unsigned lo = (unsigned)e[u], hi = (unsigned)(e[u] >> 32);
+                xw[u] = isrow ? lo : hi;
+                ow[u] = isrow ? hi : lo;
+                c[u] = cnt[xw[u] & kEdgeSlotMask];
+            }
+            int off[U], all = 0;  // survivors are packed edge by edge: the lanes of a store write side by side
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (e[u] != 0ull && c[u] < 0 && -c[u] - 1 < nb) {
-                    if ((e[u] >> (2 * kEdgeSlotBits)) > 2ull) {  // still OB in the new slot: move on
-                        const unsigned long long newX = (unsigned long long)(N + (-c[u] - 1));
-                        atomicAdd(&cnt[(int)newX], 1);
-                        e[u] = ((e[u] & ~(kSlotMask << xshift)) | (newX << xshift)) - (1ull << (2 * kEdgeSlotBits));
+                bool live = (xw[u] | ow[u]) != 0u;
+                if (live && c[u] < 0 && -c[u] - 1 < nb) {
+                    const unsigned lo = isrow ? xw[u] : ow[u], hi = isrow ? ow[u] : xw[u];
+                    const unsigned levels = (lo >> kEdgeSlotBits) | ((hi >> kEdgeSlotBits) << 3);
+                    if (levels > 2u) {  // still OB in the new slot: move on, one digit fewer
+                        const unsigned newX = (unsigned)(N + (-c[u] - 1)), lev = levels - 1u;
+                        atomicAdd(&cnt[newX], 1);
+                        const unsigned r = isrow ? newX : (lo & kEdgeSlotMask), q = isrow ? (hi & kEdgeSlotMask) : newX;
+                        e[u] = pack_edge((int)r, (int)q, (int)lev);
                     } else {
-                        atomicSub(&other[(int)((e[u] >> oshift) & kSlotMask)], 1);
-                        e[u] = 0ull;
+                        atomicSub(&other[ow[u] & kEdgeSlotMask], 1);
+                        live = false;
                     }
                 }
-                const unsigned long long m = __ballot(e[u] != 0ull);
-                before += __popcll(m & below);
+                const unsigned long long m = __ballot(live);
+                off[u] = live ? all + __popcll(m & below) : -1;
                 all += __popcll(m);
             }
             if (!all) return;
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_count, all);
-            base = __shfl(base, 0, 64) + before;
+            base = __shfl(base, 0, 64);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (e[u] != 0ull) dst[base++] = e[u];
+                if (off[u] >= 0) dst[base + off[u]] = e[u];
         };
-        if (bid == 0) {  // the operand's OB list itself
-            int j[U], k[U], v[U];
-            auto fetch = [&](int t0, int (&fj)[U], int (&fk)[U], int (&fv)[U]) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int t = t0 + u * kPlanThreads + (int)threadIdx.x;
-                    fj[u] = fk[u] = fv[u] = 0;
-                    if (t < nob) {
-                        fj[u] = ob[t];
-                        fk[u] = ob[g.ob_cap + t];
-                        fv[u] = ob[2 * (size_t)g.ob_cap + t];
-                    }
-                }
-            };
-            fetch(0, j, k, v);
-            for (int t0 = 0; t0 < nob; t0 += kPlanThreads * U) {
-                int j2[U], k2[U], v2[U];
-                fetch(t0 + kPlanThreads * U, j2, k2, v2);  // past the end: all absent
-                unsigned long long e[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int lev = levels_of(v[u]);
-                    e[u] = lev >= 2 ? pack_edge(j[u], k[u], lev) : 0ull;
-                }
-                process(e);
-#pragma unroll
-                for (int u = 0; u < U; ++u) { j[u] = j2[u]; k[u] = k2[u]; v[u] = v2[u]; }
-            }
-        }
         {  // the list of packed edges, two per load
             constexpr int U2 = 8;
-            const unsigned long long *__restrict__ src = (bid == 0 || cur == 0) ? list0 : list1;
-            unsigned long long ed[U2];
+            const unsigned long long *__restrict__ src = cur ? list1 : list0;
             auto fetch = [&](int e0, unsigned long long (&fe)[U2]) {
 #pragma unroll
                 for (int u = 0; u < U2; u += 2) {
@@ -575,6 +543,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                     }
                 }
             };
+            unsigned long long ed[U2];
             fetch(0, ed);
             for (int e0 = 0; e0 < E; e0 += kPlanThreads * U2) {
                 unsigned long long ed2[U2];
@@ -586,7 +555,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         }
         __syncthreads();
         E = s_count;
-        cur = bid == 0 ? 1 : (cur ^ 1);
+        cur ^= 1;
         if (isrow) nr += nb; else nc += nb;
     }
     if (threadIdx.x == 0) {
@@ -1105,7 +1074,8 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
 // not outlive the call.  Many workgroups, ahead of the (single-workgroup) greedy.  For the second
 // operand the same pass finds the edges that the repeated columns add: B_e holds a copy of column k
 // of B in every column slot of A's unpacking that descends from k, so an OB entry (j, k) of B is
-// also an OB entry (j, c) for every such slot c; those go to the head of the greedy's edge list.
+// also an OB entry (j, c) for every such slot c.  The pass also writes the greedy's first edge list:
+// entry t of the OB list packed at position t, the edges of repeated columns behind the last entry.
 __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict__ ob, int ob_cap,
                                                       const int32_t *ob_count, int32_t *__restrict__ keep, int keep_cap,
                                                       const int32_t *chain_child, unsigned long long *edges, int ecap,
@@ -1118,13 +1088,13 @@ __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict_
             keep[keep_cap + t] = k;
             keep[2 * (size_t)keep_cap + t] = v;
         }
-        if (!chain_child) continue;
-        int c = chain_child[k];
-        if (c < 0) continue;
         const unsigned av = v < 0 ? 0u - (unsigned)v : (unsigned)v;
         const int L = digit_levels((int)av, sh);
+        if (t < ecap) edges[t] = L >= 2 ? pack_edge(j, k, L) : 0ull;  // 0: no edge
+        if (!chain_child) continue;
+        int c = chain_child[k];
         for (int hop = 0; c >= 0 && hop < 64; c = chain_child[c], ++hop) {
-            const int pos = atomicAdd(extras, 1);
+            const int pos = n + atomicAdd(extras, 1);
             if (pos < ecap) edges[pos] = pack_edge(j, c, L);
             atomicAdd(&extra_rows[j], 1);
         }
