@@ -249,9 +249,11 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
 // (512 bytes per column and instruction), quantised, staged in LDS column-major, and then written
 // and scanned row by row exactly as on the fast path (512 bytes of Q per row).
 constexpr int kTrTile = 128, kTrPitch = kTrTile + 1;
+constexpr int kTrThreads = 1024, kTrWaves = kTrThreads / 64;  // LDS admits two workgroups per CU: 32 waves keep the loads coming
+constexpr int kTrPerWave = kTrTile / kTrWaves;               // columns (then rows) of the tile per wave, two per instruction
 
 template <bool FROM_FLOAT>
-__global__ __launch_bounds__(256) void qscan_tr_kernel(const void *__restrict__ Xv, int64_t rows, int64_t cols,
+__global__ __launch_bounds__(kTrThreads) void qscan_tr_kernel(const void *__restrict__ Xv, int64_t rows, int64_t cols,
                                                        int64_t sx_c, float scale, int s,
                                                        int32_t *__restrict__ Q, int64_t ldq, int32_t *rowcnt,
                                                        int32_t *colcnt, int32_t *rowmax, int32_t *colmax,
@@ -264,11 +266,11 @@ __global__ __launch_bounds__(256) void qscan_tr_kernel(const void *__restrict__ 
     const int half = lane >> 5, l32 = lane & 31;
     const int64_t r0 = (int64_t)blockIdx.x * kTrTile, c0 = (int64_t)blockIdx.y * kTrTile;
     int bad = 0;
-    // ---- read: wave w takes columns [32w, 32w+32), two per instruction, four rows per lane
+    // ---- read: wave w takes kTrPerWave columns, two per instruction, four rows per lane
     const int64_t rl = r0 + 4 * l32;  // rows % 4 == 0 on this path
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-        const int cc = 32 * wave + 2 * it + half;
+#pragma unroll
+    for (int it = 0; it < kTrPerWave / 2; ++it) {
+        const int cc = kTrPerWave * wave + 2 * it + half;
         const int64_t c = c0 + cc;
         int4 raw = make_int4(0, 0, 0, 0);
         const bool ok = c < cols && rl < rows;
@@ -282,12 +284,12 @@ __global__ __launch_bounds__(256) void qscan_tr_kernel(const void *__restrict__ 
         for (int i = 0; i < 4; ++i) tile[cc * kTrPitch + 4 * l32 + i] = q[i];
     }
     __syncthreads();
-    // ---- write and scan: wave w takes rows [32w, 32w+32), two per instruction, four columns per lane
+    // ---- write and scan: wave w takes kTrPerWave rows, two per instruction, four columns per lane
     int ccnt[4] = {0, 0, 0, 0}, cmax[4] = {0, 0, 0, 0};
     const int64_t cl = c0 + 4 * l32;  // cols % 4 == 0 on this path
     const unsigned long long mine = half ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull;
-    for (int it = 0; it < 16; ++it) {
-        const int rr = 32 * wave + 2 * it + half;
+    for (int it = 0; it < kTrPerWave / 2; ++it) {
+        const int rr = kTrPerWave * wave + 2 * it + half;
         const int64_t r = r0 + rr;
         const bool ok = r < rows && cl < cols;
         int q[4];
@@ -327,20 +329,22 @@ __global__ __launch_bounds__(256) void qscan_tr_kernel(const void *__restrict__ 
     if (ob) ob_flush(&stage, ob, ob_cap, ob_count);
     if (colcnt || colmax) {
         __syncthreads();  // the tile has been consumed: its memory takes the column partials
-        int32_t *part = tile;  // [2][8 half-waves][128 columns]
+        constexpr int HW = 2 * kTrWaves;
+        int32_t *part = tile;  // [2][HW half-waves][128 columns]
+        static_assert(2 * HW * kTrTile <= kTrTile * kTrPitch, "the partials must fit the tile");
         const int hw = 2 * wave + half;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            part[(0 * 8 + hw) * kTrTile + 4 * l32 + i] = ccnt[i];
-            part[(1 * 8 + hw) * kTrTile + 4 * l32 + i] = cmax[i];
+            part[(0 * HW + hw) * kTrTile + 4 * l32 + i] = ccnt[i];
+            part[(1 * HW + hw) * kTrTile + 4 * l32 + i] = cmax[i];
         }
         __syncthreads();
         if (threadIdx.x < kTrTile) {
             int cnt = 0, mx = 0;
 #pragma unroll
-            for (int w8 = 0; w8 < 8; ++w8) {
-                cnt += part[(0 * 8 + w8) * kTrTile + threadIdx.x];
-                mx = max(mx, part[(1 * 8 + w8) * kTrTile + threadIdx.x]);
+            for (int w8 = 0; w8 < HW; ++w8) {
+                cnt += part[(0 * HW + w8) * kTrTile + threadIdx.x];
+                mx = max(mx, part[(1 * HW + w8) * kTrTile + threadIdx.x]);
             }
             const int64_t col = c0 + threadIdx.x;
             if (col < cols) {
@@ -417,7 +421,7 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
     } else if (sx_r == 1 && (rows % 4) == 0 && (cols % 4) == 0 && (sx_c % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
                (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0)) && (cols + kTrTile - 1) / kTrTile <= 65535) {
         dim3 grid((unsigned)((rows + kTrTile - 1) / kTrTile), (unsigned)((cols + kTrTile - 1) / kTrTile));
-        hipLaunchKernelGGL(qscan_tr_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_c, scale, s, Q,
+        hipLaunchKernelGGL(qscan_tr_kernel<FROM_FLOAT>, grid, dim3(kTrThreads), 0, stream, X, rows, cols, sx_c, scale, s, Q,
                            ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     } else {
         dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
