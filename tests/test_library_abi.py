@@ -115,3 +115,16 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     lib.imunpack_diag_mfma_peak.argtypes = [i32, i32, vp, vp]
     assert lib.imunpack_diag_mfma_peak(0, 10, None, None) == EINVAL
     assert lib.imunpack_diag_mfma_peak(10, 0, None, None) == EINVAL
+
+
+def test_layers_reject_operands_that_do_not_form_a_product():
+    """The batched A B^T of the attention layer checks its shapes before anything reaches the library
+    (runs without a GPU: the check comes first)."""
+    import pytest
+    import torch
+    from paper_2403_07339_amd import attention, linear
+    cfg = linear.QuantConfig()
+    for a, b in (((2, 3, 8, 5), (2, 3, 7, 4)), ((2, 3, 8, 5), (3, 2, 7, 5)), ((8, 5), (1, 7, 5))):
+        with pytest.raises(ValueError):
+            attention.quantized_bmm(torch.zeros(a), torch.zeros(b), 31.0, 31.0, cfg)
+    assert cfg.b == 8 and cfg.p == 95.0
