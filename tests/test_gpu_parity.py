@@ -74,6 +74,32 @@ def test_quantize_and_scan(imu, shape, b):
     assert np.array_equal(sts.colcnt.cpu().numpy(), cc) and np.array_equal(sts.rowmax.cpu().numpy(), rm)
 
 
+@pytest.mark.parametrize("shape,b,frac", [((300, 520), 8, 0.01), ((132, 260), 4, 0.2), ((1024, 384), 8, 0.0005),
+                                          ((256, 256), 2, 0.9)])
+def test_ob_entry_list_for_every_input_layout(imu, shape, b, frac):
+    """The OB entry list (row, column, value of every entry with |q| >= s, in any order) that UnpackBoth
+    plans from, for a row-major operand, a transposed view (the tiled transposing kernel) and a view with
+    neither stride 1: the same set as the definition gives, each entry once."""
+    g = torch.Generator().manual_seed(shape[0] + 7 * shape[1] + b)
+    x = torch.randn(shape, generator=g)
+    x[torch.rand(shape, generator=g) < frac] *= 300.0
+    scale = float(np.float32(0.021))
+    s = 1 << (b - 1)
+    want = oracle_quant(x, scale)
+    ii, jj = np.nonzero(np.abs(want.astype(np.int64)) >= s)
+    want_set = sorted(zip(ii.tolist(), jj.tolist(), want[ii, jj].tolist()))
+    wide = dev(torch.zeros(shape[0], 3 * shape[1]))
+    wide[:, 1::3] = dev(x)
+    for view in (dev(x), dev(x.t().contiguous()).t(), wide[:, 1::3]):
+        st = imu.Stats.empty(shape[0], shape[1], view.device, ob_cap=shape[0] * shape[1])  # room for every entry
+        Q, st, status = imu.imunpack_quantize(view, scale, b, stats=st)
+        assert int(status.item()) == 0 and np.array_equal(Q.cpu().numpy(), want)
+        n_ob = int(st.ob_count.item())
+        assert n_ob == len(want_set) <= st.ob.shape[1]
+        ob = st.ob[:, :n_ob].cpu().numpy()
+        assert sorted(zip(ob[0].tolist(), ob[1].tolist(), ob[2].tolist())) == want_set
+
+
 def test_quantize_flags_bad_input(imu):
     x = torch.ones(8, 8)
     x[3, 4] = float("nan")
