@@ -223,6 +223,11 @@ int imunpack_plan_bounds(const imunpack_plan_t *plan, uint64_t *bound);
  * (2 per multiply-add) the launch performs to *ops.  The caller times the stream. */
 int imunpack_diag_mfma_peak(int workgroups, int iters, int64_t *ops, imunpack_stream_t stream);
 
+/* Measured HBM rate (benchmark reporting only): copies `bytes` (a multiple of 1 MiB, at most 65535 MiB)
+ * from src to dst (device, 16-byte aligned, not overlapping) in the access pattern of the quantize pass,
+ * with non-temporal loads and stores.  The caller times the stream; the traffic is 2 * bytes. */
+int imunpack_diag_copy(const void *src, void *dst, int64_t bytes, imunpack_stream_t stream);
+
 /* Shader clock under the GEMM's own load (benchmark reporting only).  While `ticks` (device, two
  * elements, owned by the caller) is set, every fused imunpack_gemm launch of this process has its
  * first workgroup write ticks[0] = shader clock cycles and ticks[1] = ticks of the constant 100 MHz

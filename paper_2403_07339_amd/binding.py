@@ -26,7 +26,7 @@ EXPORTS = [
     "imunpack_quantize", "imunpack_scan", "imunpack_plan", "imunpack_plan_dims", "imunpack_plan_export",
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
-    "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_price",
+    "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
     "imunpack_percentile",
 ]
 
@@ -56,6 +56,7 @@ _lib.imunpack_percentile.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _v
 _lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 _lib.imunpack_diag_clock_probe.argtypes = [_vp]
+_lib.imunpack_diag_copy.argtypes = [_vp, _vp, _i64, _vp]
 _lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
                                 C.POINTER(C.c_double), C.POINTER(_i32), C.POINTER(_i32), _vp]
 for _name in EXPORTS:
@@ -319,6 +320,16 @@ def imunpack_diag_mfma_peak(workgroups: int, iters: int) -> int:
     ops = _i64(0)
     _check(_lib.imunpack_diag_mfma_peak(int(workgroups), int(iters), C.byref(ops), _stream()), "imunpack_diag_mfma_peak")
     return int(ops.value)
+
+
+def imunpack_diag_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Streams src to dst (contiguous device tensors of equal byte size, a multiple of 1 MiB) with the
+    library's copy kernel on the current stream; returns the bytes moved (read + written)."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(_lib.imunpack_diag_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()), "imunpack_diag_copy")
+    return 2 * nbytes
 
 
 def imunpack_diag_clock_probe(ticks: torch.Tensor | None) -> None:

@@ -356,6 +356,26 @@ __global__ __launch_bounds__(kTrThreads) void qscan_tr_kernel(const void *__rest
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
 }
 
+// Device-to-device copy in the access pattern of the fast quantize path (a workgroup moves 64 rows x
+// 1 KiB of a matrix with 16 KiB rows, non-temporal loads and stores): the rate the memory system gives
+// a kernel that does nothing else, for the measured-peak line of the benchmark.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    constexpr size_t kPitch = 1024;  // float4 per row
+    const size_t cb = (blockIdx.x + blockIdx.y) % gridDim.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t base = (size_t)blockIdx.y * 64 * kPitch + cb * 64 + lane;
+    const v4f *s = reinterpret_cast<const v4f *>(src);
+    v4f *d = reinterpret_cast<v4f *>(dst);
+    for (int r0 = wave; r0 < 64; r0 += 16) {
+        v4f v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(s + base + (size_t)(r0 + 4 * u) * kPitch);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(v[u], d + base + (size_t)(r0 + 4 * u) * kPitch);
+    }
+}
+
 // Clears up to six int32 arrays in one launch.
 struct ZeroList {
     int32_t *p[6];
@@ -450,4 +470,13 @@ extern "C" int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64
                              const imunpack_stats_t *stats, imunpack_stream_t stream) {
     if (!Q || ldq < cols) return IMUNPACK_EINVAL;
     return imu::scan_i32(Q, rows, cols, ldq, b, stats, (hipStream_t)stream);
+}
+
+extern "C" int imunpack_diag_copy(const void *src, void *dst, int64_t bytes, imunpack_stream_t stream) {
+    constexpr int64_t kBlock = 64 * 16384;  // one band of 64 rows of 16 KiB
+    if (!src || !dst || bytes <= 0 || bytes % kBlock || bytes / kBlock > 65535 || (uintptr_t)src % 16 || (uintptr_t)dst % 16)
+        return IMUNPACK_EINVAL;
+    hipLaunchKernelGGL(imu::stream_copy_kernel, dim3(16, (unsigned)(bytes / kBlock)), dim3(256), 0, (hipStream_t)stream,
+                       (const float4 *)src, (float4 *)dst);
+    return imu::launch_status();
 }

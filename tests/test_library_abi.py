@@ -115,6 +115,11 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     lib.imunpack_diag_mfma_peak.argtypes = [i32, i32, vp, vp]
     assert lib.imunpack_diag_mfma_peak(0, 10, None, None) == EINVAL
     assert lib.imunpack_diag_mfma_peak(10, 0, None, None) == EINVAL
+    lib.imunpack_diag_copy.restype = ctypes.c_int
+    lib.imunpack_diag_copy.argtypes = [vp, vp, ctypes.c_int64, vp]
+    assert lib.imunpack_diag_copy(None, fake, 1 << 20, None) == EINVAL
+    assert lib.imunpack_diag_copy(fake, fake, (1 << 20) + 16, None) == EINVAL    # not whole bands of 64 rows
+    assert lib.imunpack_diag_copy(fake, fake, 0, None) == EINVAL
 
 
 def test_layers_reject_operands_that_do_not_form_a_product():
