@@ -203,9 +203,7 @@ struct FixupArgs {
     const int32_t *row_phys, *col_phys, *col_sexp;
     int Kp, s, sh;
     int8_t *out;
-    unsigned long long *rowsum, *bound;
-    const unsigned long long *wavesum;  // what the scatter kernel left per row and wave
-    int wpr;
+    unsigned long long *rowsum; // per physical row: what the digits placed here add to the row norm
 };
 
 // The whole norm of physical row p as far as it is known: the scatter kernel's parts plus `placed`.
@@ -219,10 +217,8 @@ __device__ __forceinline__ unsigned long long row_norm(const unsigned long long 
 // rowsum[p] += term for every lane that gets here together.  Atomics on one address are served one
 // after the other, and the OB entries of a heavy row sit side by side in the list: in two rounds, the
 // lanes that name the same row as the first lane still waiting are added up and share one atomic; the
-// lanes left after that issue their own.  Returns the row's sum after the addition in the lanes that
-// issued an atomic (`led`).
-__device__ __forceinline__ unsigned long long add_to_row(unsigned long long *rowsum, int p, unsigned long long term,
-                                                         bool &led) {
+// lanes left after that issue their own.
+__device__ __forceinline__ void add_to_row(unsigned long long *rowsum, int p, unsigned long long term) {
     const int lane = threadIdx.x & 63;
     const int lo = (int)(unsigned)term, hi = (int)(unsigned)(term >> 32);
     unsigned long long pending = __ballot(1), sum = term;
@@ -243,37 +239,14 @@ __device__ __forceinline__ unsigned long long add_to_row(unsigned long long *row
         }
         pending &= ~same;
     }
-    led = mine;
-    return mine ? atomicAdd(&rowsum[p], sum) + sum : 0ull;
+    if (mine) atomicAdd(&rowsum[p], sum);
 }
 
-// Both operands in one launch: blocks [0, blocks_a) serve fa, the next blocks_b serve fb; the blocks
-// behind them raise the two bounds to the largest row norm.  A row norm that this launch still adds
-// to is covered twice, by whichever partial value the scan reads and by the value that the last
-// addition returns.
-__global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int blocks_b,
-                             const unsigned long long *rowsum_a, const unsigned long long *wavesum_a, int rows_a,
-                             unsigned long long *bound_a, const unsigned long long *rowsum_b,
-                             const unsigned long long *wavesum_b, int rows_b, unsigned long long *bound_b, int wpr) {
-    if ((int)blockIdx.x >= blocks_a + blocks_b) {
-        const int nscan = gridDim.x - blocks_a - blocks_b;
-        unsigned long long ma = 0, mb = 0;
-        for (int t = ((int)blockIdx.x - blocks_a - blocks_b) * blockDim.x + threadIdx.x; t < rows_a + rows_b;
-             t += nscan * blockDim.x) {
-            if (t < rows_a) ma = max(ma, row_norm(wavesum_a, wpr, t, rowsum_a[t]));
-            else mb = max(mb, row_norm(wavesum_b, wpr, t - rows_a, rowsum_b[t - rows_a]));
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            ma = max(ma, (unsigned long long)__shfl_xor((long long)ma, off, 64));
-            mb = max(mb, (unsigned long long)__shfl_xor((long long)mb, off, 64));
-        }
-        if ((threadIdx.x & 63) == 0) {
-            if (ma > __hip_atomic_load(bound_a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_a, ma);
-            if (mb > __hip_atomic_load(bound_b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_b, mb);
-        }
-        return;
-    }
+// Both operands in one launch: blocks [0, blocks_a) serve fa, the next blocks_b serve fb.  What a digit
+// placed here adds to its row's norm goes to rowsum; bound_kernel, launched behind this one, takes the
+// largest norm (a wait for the sum inside this kernel, to keep the bound current entry by entry, was
+// half its run time).
+__global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int blocks_b) {
     const bool first = (int)blockIdx.x < blocks_a;
     const FixupArgs &f = first ? fa : fb;
     const int block = first ? blockIdx.x : blockIdx.x - blocks_a;
@@ -303,17 +276,31 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
                     f.out[(int64_t)p * f.Kp + q] = dg;
                     const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
                     const unsigned long long term = nsft >= 40u ? (1ull << 44) : ((unsigned long long)m << nsft);
-                    bool led;
-                    const unsigned long long placed = add_to_row(f.rowsum, p, term, led);
-                    if (led) {
-                        const unsigned long long now = row_norm(f.wavesum, f.wpr, p, placed);
-                        // the bound only grows: a plain (possibly stale) read filters most of the updates
-                        if (now > __hip_atomic_load(f.bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                            atomicMax(f.bound, now);
-                    }
+                    add_to_row(f.rowsum, p, term);
                 }
             }
         }
+    }
+}
+
+// The accumulator bounds: the largest row norm of either operand (the scatter kernel's parts per wave
+// plus what the fix-up pass placed).
+__global__ void bound_kernel(const unsigned long long *rowsum_a, const unsigned long long *wavesum_a, int rows_a,
+                             unsigned long long *bound_a, const unsigned long long *rowsum_b,
+                             const unsigned long long *wavesum_b, int rows_b, unsigned long long *bound_b, int wpr) {
+    unsigned long long ma = 0, mb = 0;
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < rows_a + rows_b; t += gridDim.x * blockDim.x) {
+        if (t < rows_a) ma = max(ma, row_norm(wavesum_a, wpr, t, rowsum_a[t]));
+        else mb = max(mb, row_norm(wavesum_b, wpr, t - rows_a, rowsum_b[t - rows_a]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        ma = max(ma, (unsigned long long)__shfl_xor((long long)ma, off, 64));
+        mb = max(mb, (unsigned long long)__shfl_xor((long long)mb, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {  // the bound only grows: a plain (possibly stale) read filters most of the updates
+        if (ma > __hip_atomic_load(bound_a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_a, ma);
+        if (mb > __hip_atomic_load(bound_b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(bound_b, mb);
     }
 }
 
@@ -394,8 +381,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.c2_child = p->c2.child;
             f.row_phys = lay.row_phys; f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
             f.Kp = h.Kp; f.s = p->s; f.sh = p->sh;
-            f.out = a.out; f.rowsum = lay.rowsum; f.bound = &p->d_hdr->bound[op];
-            f.wavesum = lay.wavesum; f.wpr = wpr;
+            f.out = a.out; f.rowsum = lay.rowsum;
             fblocks[op] = (nob + 255) / 256;
         }
     }
@@ -411,13 +397,16 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             if (launch[op]) scatter(sc[op], sc[op], sc[op].ny, dense[op]);
     }
     if (h.Kp > 0 && h.Mp + h.Np > 0) {
-        // after both scatters: the fix-up overwrites zeros they wrote, the scan reads their row norms
-        if (!fblocks[0]) fx[0] = fx[1];  // never dereferenced, but keep the argument well-formed
-        if (!fblocks[1]) fx[1] = fx[0];
-        const int nscan = std::min(64, (h.Mp + h.Np + 255) / 256);
-        hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1] + nscan), dim3(256), 0, st, fx[0], fx[1],
-                           fblocks[0], fblocks[1], p->layA.rowsum, p->layA.wavesum, h.Mp, &p->d_hdr->bound[0],
-                           p->layB.rowsum, p->layB.wavesum, h.Np, &p->d_hdr->bound[1], wpr);
+        // after both scatters: the fix-up overwrites zeros they wrote; then the bounds from the row norms
+        if (fblocks[0] + fblocks[1] > 0) {
+            if (!fblocks[0]) fx[0] = fx[1];  // never dereferenced, but keep the argument well-formed
+            if (!fblocks[1]) fx[1] = fx[0];
+            hipLaunchKernelGGL(fixup_kernel, dim3(fblocks[0] + fblocks[1]), dim3(256), 0, st, fx[0], fx[1], fblocks[0],
+                               fblocks[1]);
+        }
+        const int nscan = std::min(256, (h.Mp + h.Np + 255) / 256);
+        hipLaunchKernelGGL(bound_kernel, dim3(nscan), dim3(256), 0, st, p->layA.rowsum, p->layA.wavesum, h.Mp,
+                           &p->d_hdr->bound[0], p->layB.rowsum, p->layB.wavesum, h.Np, &p->d_hdr->bound[1], wpr);
     }
     IMU_TRY(launch_status());
     // The bounds travel to the host on the plan's side stream, behind the scatter: the caller's stream is
