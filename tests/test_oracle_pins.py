@@ -443,6 +443,51 @@ def test_pair_col_col_structure():
     assert u.B.tolist() == [[2, 3, 2, 0, 0, 0, 0], [64, 5, 64, 56, 56, 2, 2]]
 
 
+def test_copy_out_accessors_match_the_pinned_dense_copy():
+    """The two copy-outs the GPU parity tests read the oracle through (int8 operands, Pi / S without
+    the operands) against hand-worked values and against dense(), which the identities above pin: on
+    non-square shapes (a row-stride or cast slip would show), every strategy pair, and a matrix whose
+    storage has grown past its first capacity (row stride != column count inside the oracle)."""
+    b, s = 8, 128
+    A = np.array([[300, 1]], dtype=np.int32)
+    B = np.array([[2, 3], [40000, 5]], dtype=np.int32)
+    h = oracle.unpack_pair_handle(A, B, b, COL, COL)     # the hand-worked case of test_pair_col_col_structure
+    a8, b8 = h.operands_i8()
+    assert a8.dtype == np.int8 and b8.dtype == np.int8
+    assert a8.tolist() == [[44, 1, 2, 44, 2, 44, 2]]
+    assert b8.tolist() == [[2, 3, 2, 0, 0, 0, 0], [64, 5, 64, 56, 56, 2, 2]]
+    S, pas, paw, pbs, pbw = h.meta()
+    assert S.tolist() == [1, 1, 128, 128, 128 * 128, 128 ** 2, 128 ** 3]
+    assert pas.tolist() == [0] and paw.tolist() == [1] and pbs.tolist() == [0, 1] and pbw.tolist() == [1, 1]
+    h.close()
+    # negative digits survive the cast; Pi of a row split (hand-worked: -300 = -(2*128 + 44))
+    h = oracle.unpack_pair_handle(np.array([[-300, 7], [5, -6]], dtype=np.int32),
+                                  np.array([[1, 2], [3, 4], [-129, 0]], dtype=np.int32), b, ROW, ROW)
+    a8, b8 = h.operands_i8()
+    assert a8.tolist() == [[-44, 7], [5, -6], [-2, 0]]
+    assert b8.tolist() == [[1, 2], [3, 4], [-1, 0], [-1, 0]]
+    S, pas, paw, pbs, pbw = h.meta()
+    assert S.tolist() == [1, 1]
+    assert pas.tolist() == [0, 1, 0] and paw.tolist() == [1, 1, 128]
+    assert pbs.tolist() == [0, 1, 2, 2] and pbw.tolist() == [1, 1, 1, 128]
+    h.close()
+    rng = np.random.default_rng(2024)
+    for bb in (2, 4, 8):
+        ss = 1 << (bb - 1)
+        for sa, sb in itertools.product(STRATS, STRATS):
+            Am = rand_int_matrix(rng, 9, 13, ss, p_ob=0.3, depth=4)     # grows well past the first capacity
+            Bm = rand_int_matrix(rng, 5, 13, ss, p_ob=0.3, depth=4)
+            h = oracle.unpack_pair_handle(Am, Bm, bb, sa, sb)
+            u = h.dense()
+            a8, b8 = h.operands_i8()
+            assert a8.shape == u.A.shape and b8.shape == u.B.shape
+            assert np.array_equal(a8.astype(np.int32), u.A) and np.array_equal(b8.astype(np.int32), u.B)
+            for got, want in zip(h.meta(), (u.S, u.piA_src, u.piA_w, u.piB_src, u.piB_w)):
+                assert got.dtype == np.int64 and np.array_equal(got, want)
+            assert (h.n_u, h.d_u, h.h_u) == (u.A.shape[0], u.A.shape[1], u.B.shape[0])
+            h.close()
+
+
 def test_brute_force_tiny_matrices():
     """All 2x2 A over a value set that straddles every digit boundary, a few partners,
     all nine strategy pairs, b in {2,3,4}: exact product, In-Bound digits, termination."""
