@@ -67,6 +67,10 @@ def lib():
         L.orc_result_copy_i8.restype = None
         L.orc_result_copy_meta.argtypes = [C.c_void_p, i64p, i64p, i64p, i64p, i64p]
         L.orc_result_copy_meta.restype = None
+        L.orc_result_num_ops.argtypes = [C.c_void_p]
+        L.orc_result_num_ops.restype = C.c_int64
+        L.orc_result_copy_trace.argtypes = [C.c_void_p, i64p, i64p]
+        L.orc_result_copy_trace.restype = None
         L.orc_result_max_abs.argtypes = [C.c_void_p]
         L.orc_result_max_abs.restype = C.c_int32
         L.orc_result_free.argtypes = [C.c_void_p]
@@ -185,6 +189,26 @@ class UnpackHandle:
         lib().orc_result_copy_meta(self._ptr, _p(S, C.c_int64), _p(pas, C.c_int64),
                                    _p(paw, C.c_int64), _p(pbs, C.c_int64), _p(pbw, C.c_int64))
         return S, pas, paw, pbs, pbw
+
+    def trace(self):
+        """(col_parent, ops): col_parent[c] = the column that column c was appended for (-1 for the d
+        columns the first Unpack call started from); ops = one row (call, kind, index) per split in the
+        order they were made: call 0 / 1 = the first / second Unpack of Sec. 4 'Combining everything',
+        kind 0 = a row split (Alg. 1 l.4-6, Alg. 4 l.7-9), 1 = a column split (Alg. 2 l.4-7, Alg. 4
+        l.11-14), index = the split row / column at that moment."""
+        col_parent = np.empty(self.d_u, dtype=np.int64)
+        ops = np.empty((int(lib().orc_result_num_ops(self._ptr)), 3), dtype=np.int64)
+        lib().orc_result_copy_trace(self._ptr, _p(col_parent, C.c_int64), _p(ops, C.c_int64))
+        return col_parent, ops
+
+    def col_src(self):
+        """The original column each unpacked column descends from (col_parent followed to its root)."""
+        parent, _ = self.trace()
+        src = np.arange(self.d_u, dtype=np.int64)
+        for c in range(self.d_u):          # a parent always has a smaller index
+            if parent[c] >= 0:
+                src[c] = src[parent[c]]
+        return src
 
     def operands_i8(self):
         """A_ue, B_eu as int8 (check max_abs() <= 127 first)."""

@@ -205,6 +205,18 @@ static void vec_push(vec_t *x, int64_t val)
     x->v[x->len++] = val;
 }
 
+/* A record of what the algorithms did, kept beside their outputs (bookkeeping, no arithmetic):
+ * col_parent[c] = the column that column c was appended for (Alg. 2 line 4 / Alg. 4 line 11:
+ * the column it took floor(. / s) of, and whose copy the partner received), -1 for the columns
+ * the first Unpack call started from; ops = one triple per split, in the order the splits were
+ * made: (which Unpack call of Sec. 4 "Combining everything": 0 or 1, 0 = row split / 1 = column
+ * split, index of the split row or column at that moment). */
+typedef struct {
+    vec_t col_parent;
+    vec_t ops;
+    int call;
+} trace_t;
+
 /* ------------------------------------------------------------------ */
 /* the single split steps the three algorithms share by definition     */
 /* ------------------------------------------------------------------ */
@@ -224,8 +236,9 @@ static int col_has_ob(mat_t *A, int64_t j, int32_t s)
 }
 
 /* Alg. 1 lines 4-6 (= Alg. 4 lines 7-9): split row i of A, extend Pi. */
-static void split_row(mat_t *A, int64_t i, int32_t s, vec_t *pi_src, vec_t *pi_w)
+static void split_row(mat_t *A, int64_t i, int32_t s, vec_t *pi_src, vec_t *pi_w, trace_t *tr)
 {
+    vec_push(&tr->ops, tr->call); vec_push(&tr->ops, 0); vec_push(&tr->ops, i);
     int64_t nr = mat_append_row(A);
     for (int64_t c = 0; c < A->cols; ++c) {
         int32_t v = *mat_at(A, i, c);
@@ -237,8 +250,10 @@ static void split_row(mat_t *A, int64_t i, int32_t s, vec_t *pi_src, vec_t *pi_w
 }
 
 /* Alg. 2 lines 4-7 (= Alg. 4 lines 11-14): split column j of A, duplicate column j of B, extend S. */
-static void split_col(mat_t *A, mat_t *B, int64_t j, int32_t s, vec_t *S)
+static void split_col(mat_t *A, mat_t *B, int64_t j, int32_t s, vec_t *S, trace_t *tr)
 {
+    vec_push(&tr->ops, tr->call); vec_push(&tr->ops, 1); vec_push(&tr->ops, j);
+    vec_push(&tr->col_parent, j);
     int64_t nc = mat_append_col(A);
     for (int64_t r = 0; r < A->rows; ++r) {
         int32_t v = *mat_at(A, r, j);
@@ -252,25 +267,25 @@ static void split_col(mat_t *A, mat_t *B, int64_t j, int32_t s, vec_t *S)
 }
 
 /* Alg. 1 */
-static void unpack_row(mat_t *A, int b, vec_t *pi_src, vec_t *pi_w)
+static void unpack_row(mat_t *A, int b, vec_t *pi_src, vec_t *pi_w, trace_t *tr)
 {
     int32_t s = (int32_t)1 << (b - 1);
     int64_t i = 0;
     while (i < A->rows) {
         if (row_has_ob(A, i, s))
-            split_row(A, i, s, pi_src, pi_w);
+            split_row(A, i, s, pi_src, pi_w, tr);
         ++i;
     }
 }
 
 /* Alg. 2 */
-static void unpack_column(mat_t *A, mat_t *B, vec_t *S, int b)
+static void unpack_column(mat_t *A, mat_t *B, vec_t *S, int b, trace_t *tr)
 {
     int32_t s = (int32_t)1 << (b - 1);
     int64_t i = 0;
     while (i < A->cols) {
         if (col_has_ob(A, i, s))
-            split_col(A, B, i, s, S);
+            split_col(A, B, i, s, S, tr);
         ++i;
     }
 }
@@ -278,7 +293,8 @@ static void unpack_column(mat_t *A, mat_t *B, vec_t *S, int b)
 /* Alg. 4.  recount != 0 recomputes every OB count from the matrix at every
  * step instead of updating the counts after each split (bookkeeping only:
  * tests check that both give the same result). */
-static void unpack_both(mat_t *A, mat_t *B, vec_t *S, int b, vec_t *pi_src, vec_t *pi_w, int recount)
+static void unpack_both(mat_t *A, mat_t *B, vec_t *S, int b, vec_t *pi_src, vec_t *pi_w, int recount,
+                        trace_t *tr)
 {
     int32_t s = (int32_t)1 << (b - 1);
     vec_t rc = vec_new(0), cc = vec_new(0);
@@ -314,7 +330,7 @@ static void unpack_both(mat_t *A, mat_t *B, vec_t *S, int b, vec_t *pi_src, vec_
                     else cc.v[c]--;
                 }
             }
-            split_row(A, i, s, pi_src, pi_w);
+            split_row(A, i, s, pi_src, pi_w, tr);
             rc.v[i] = 0;
             vec_push(&rc, newcount);
         } else {
@@ -326,7 +342,7 @@ static void unpack_both(mat_t *A, mat_t *B, vec_t *S, int b, vec_t *pi_src, vec_
                     else rc.v[r]--;
                 }
             }
-            split_col(A, B, j, s, S);
+            split_col(A, B, j, s, S, tr);
             cc.v[j] = 0;
             vec_push(&cc, newcount);
         }
@@ -337,14 +353,14 @@ static void unpack_both(mat_t *A, mat_t *B, vec_t *S, int b, vec_t *pi_src, vec_
 
 /* Alg. 5: Pi starts as I for every strategy; S and B pass through for UnpackRow. */
 static void unpack_dispatch(mat_t *A, mat_t *B, vec_t *S, int b, int strategy,
-                            vec_t *pi_src, vec_t *pi_w, int recount)
+                            vec_t *pi_src, vec_t *pi_w, int recount, trace_t *tr)
 {
     if (strategy == ORC_ROW)
-        unpack_row(A, b, pi_src, pi_w);
+        unpack_row(A, b, pi_src, pi_w, tr);
     else if (strategy == ORC_COL)
-        unpack_column(A, B, S, b);
+        unpack_column(A, B, S, b, tr);
     else
-        unpack_both(A, B, S, b, pi_src, pi_w, recount);
+        unpack_both(A, B, S, b, pi_src, pi_w, recount, tr);
 }
 
 /* ------------------------------------------------------------------ */
@@ -356,6 +372,7 @@ typedef struct {
     vec_t S;                  /* diagonal of S_uu, length d'    */
     vec_t piA_src, piA_w;     /* Pi_A: column t has weight piA_w[t] at row piA_src[t] */
     vec_t piB_src, piB_w;     /* Pi_B likewise                  */
+    trace_t tr;               /* column parents and the sequence of splits */
 } orc_result_t;
 
 static vec_t identity_src(int64_t n)
@@ -386,7 +403,11 @@ orc_result_t *orc_unpack(const int32_t *A, int64_t n, int64_t d, const int32_t *
     R->piA_w = ones(n);
     R->piB_src = identity_src(h);
     R->piB_w = ones(h);
-    unpack_dispatch(&R->A, &R->B, &R->S, b, strategy, &R->piA_src, &R->piA_w, recount);
+    R->tr.col_parent = vec_new(0);
+    for (int64_t c = 0; c < d; ++c) vec_push(&R->tr.col_parent, -1);
+    R->tr.ops = vec_new(0);
+    R->tr.call = 0;
+    unpack_dispatch(&R->A, &R->B, &R->S, b, strategy, &R->piA_src, &R->piA_w, recount, &R->tr);
     return R;
 }
 
@@ -397,7 +418,8 @@ orc_result_t *orc_unpack_pair(const int32_t *A, int64_t n, int64_t d, const int3
                               int b, int strategy_a, int strategy_b, int recount)
 {
     orc_result_t *R = orc_unpack(A, n, d, B, h, NULL, b, strategy_a, recount);
-    unpack_dispatch(&R->B, &R->A, &R->S, b, strategy_b, &R->piB_src, &R->piB_w, recount);
+    R->tr.call = 1;
+    unpack_dispatch(&R->B, &R->A, &R->S, b, strategy_b, &R->piB_src, &R->piB_w, recount, &R->tr);
     return R;
 }
 
@@ -428,6 +450,7 @@ void orc_result_free(orc_result_t *R)
     if (!R) return;
     free(R->A.v); free(R->B.v); free(R->S.v);
     free(R->piA_src.v); free(R->piA_w.v); free(R->piB_src.v); free(R->piB_w.v);
+    free(R->tr.col_parent.v); free(R->tr.ops.v);
     free(R);
 }
 
@@ -531,4 +554,14 @@ void orc_result_copy_meta(orc_result_t *R, int64_t *S,
     memcpy(piA_w, R->piA_w.v, (size_t)R->piA_w.len * sizeof(int64_t));
     memcpy(piB_src, R->piB_src.v, (size_t)R->piB_src.len * sizeof(int64_t));
     memcpy(piB_w, R->piB_w.v, (size_t)R->piB_w.len * sizeof(int64_t));
+}
+
+/* the record of the splits: number of splits, then (into caller buffers) col_parent (d') and the
+ * triples (3 per split) */
+int64_t orc_result_num_ops(const orc_result_t *R) { return R->tr.ops.len / 3; }
+
+void orc_result_copy_trace(const orc_result_t *R, int64_t *col_parent, int64_t *ops)
+{
+    memcpy(col_parent, R->tr.col_parent.v, (size_t)R->tr.col_parent.len * sizeof(int64_t));
+    memcpy(ops, R->tr.ops.v, (size_t)R->tr.ops.len * sizeof(int64_t));
 }

@@ -488,6 +488,101 @@ def test_copy_out_accessors_match_the_pinned_dense_copy():
             h.close()
 
 
+def _replay_split_trace(A, B, b, sa, sb, ops):
+    """Applies the recorded splits one by one with numpy on Python integers, checking at every step that
+    the split is the one the algorithm in charge must make at that moment.  Returns the final
+    (first operand, second operand, diag S, column parents)."""
+    s = 1 << (b - 1)
+    M = [obj(A), obj(B)]                     # M[0]: the operand of the first Unpack call, M[1]: of the second
+    S = [1] * A.shape[1]
+    parent = [-1] * A.shape[1]
+    last_fifo = {0: -1, 1: -1}
+    trunc_div = np.vectorize(lambda v: int(abs(v) // s) * (1 if v >= 0 else -1), otypes=[object])
+    for call, kind, idx in ops.tolist():
+        X, P = M[call], M[1 - call]          # the matrix being unpacked and its partner
+        strat = sa if call == 0 else sb
+        ob = np.abs(X) >= s
+        rc, cc = ob.sum(1), ob.sum(0)
+        if strat == BOTH:                    # Alg. 4: top count, rows on c0 >= c1, lowest index among equals
+            c0, c1 = rc.max(), cc.max()
+            assert max(c0, c1) > 0
+            if c0 >= c1:
+                assert kind == 0 and idx == int(np.argmax(rc))
+            else:
+                assert kind == 1 and idx == int(np.argmax(cc))
+        else:                                # Alg. 1 / 2: one visit per row / column in index order, split iff OB
+            assert kind == (0 if strat == ROW else 1)
+            assert idx > last_fifo[call]
+            skipped = range(last_fifo[call] + 1, idx)
+            assert not any((rc if kind == 0 else cc)[t] for t in skipped)
+            assert (rc if kind == 0 else cc)[idx] > 0
+            last_fifo[call] = idx
+        if kind == 0:
+            row = X[idx].copy()
+            q = trunc_div(row)
+            X[idx] = row - s * q
+            M[call] = np.vstack([X, q[None, :]])
+        else:
+            col = X[:, idx].copy()
+            q = trunc_div(col)
+            X[:, idx] = col - s * q
+            M[call] = np.hstack([X, q[:, None]])
+            M[1 - call] = np.hstack([P, P[:, idx:idx + 1]])
+            S.append(s * S[idx])
+            parent.append(idx)
+    return M[0], M[1], S, parent
+
+
+@pytest.mark.parametrize("b", [2, 4, 8])
+def test_split_trace_replays_to_the_same_result(b):
+    """The recorded sequence of splits and the column parents: replayed step by step they give the
+    oracle's own unpacked operands and S, each step is the one its algorithm prescribes on the
+    replayed state, and nothing Out-of-Bound is left at the end (so the sequence is complete)."""
+    rng = np.random.default_rng(900 + b)
+    s = 1 << (b - 1)
+    for sa, sb in itertools.product(STRATS, STRATS):
+        A = rand_int_matrix(rng, 6, 8, s, p_ob=0.2, depth=3)
+        B = rand_int_matrix(rng, 7, 8, s, p_ob=0.2, depth=3)
+        h = oracle.unpack_pair_handle(A, B, b, sa, sb)
+        u = h.dense()
+        parent, ops = h.trace()
+        assert all(c0 <= c1 for c0, c1 in zip(ops[:-1, 0], ops[1:, 0]))     # the first call's splits come first
+        Au, Bu, S, par = _replay_split_trace(A, B, b, sa, sb, ops)
+        assert np.array_equal(Au, obj(u.A)) and np.array_equal(Bu, obj(u.B))
+        assert S == [int(x) for x in u.S] and par == parent.tolist()
+        assert np.abs(u.A).max() < s and np.abs(u.B).max() < s
+        # a column's parent holds the digit below it: S[c] = s * S[parent], and col_src follows the chain
+        src = h.col_src()
+        for c in range(len(par)):
+            assert src[c] == (c if par[c] < 0 else src[par[c]])
+        h.close()
+
+
+def test_column_parents_name_the_duplicated_partner_column():
+    """Alg. 2 line 6 / Alg. 4 line 13: the partner receives a copy of the split column, so after one
+    Unpack call column c of B_e equals column col_src[c] of B, whatever the strategy."""
+    rng = np.random.default_rng(31)
+    for b, strat in itertools.product((3, 8), (COL, BOTH)):
+        s = 1 << (b - 1)
+        A = rand_int_matrix(rng, 12, 9, s, p_ob=0.25, depth=4)
+        A[:, 2] = s * s + 1                 # a column with more OB entries than any row: UnpackBoth splits it
+        B = rng.integers(-1000, 1000, size=(4, 9)).astype(np.int32)
+        h = oracle.unpack_handle(A, B, b, strat)
+        u = h.dense()
+        src = h.col_src()
+        assert u.B.shape[1] == u.A.shape[1] > 9
+        assert np.array_equal(u.B, B[:, src])
+        assert set(src[:9].tolist()) == set(range(9)) and src[:9].tolist() == list(range(9))
+        h.close()
+    # hand-worked: the COL/COL example above
+    h = oracle.unpack_pair_handle(np.array([[300, 1]], dtype=np.int32), np.array([[2, 3], [40000, 5]], dtype=np.int32),
+                                  8, COL, COL)
+    parent, ops = h.trace()
+    assert parent.tolist() == [-1, -1, 0, 0, 2, 3, 4] and h.col_src().tolist() == [0, 1, 0, 0, 0, 0, 0]
+    assert ops.tolist() == [[0, 1, 0], [1, 1, 0], [1, 1, 2], [1, 1, 3], [1, 1, 4]]
+    h.close()
+
+
 def test_brute_force_tiny_matrices():
     """All 2x2 A over a value set that straddles every digit boundary, a few partners,
     all nine strategy pairs, b in {2,3,4}: exact product, In-Bound digits, termination."""
