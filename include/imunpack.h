@@ -27,6 +27,10 @@
  * Conventions
  *   - Every pointer named "device" is GPU memory owned by the caller (hipMalloc / a PyTorch
  *     tensor); "host" pointers are ordinary host memory.  The library owns only plan objects.
+ *   - A plan object belongs to one thread at a time.  Calls that take a const plan only read it;
+ *     the others (re-planning, unpack, GEMM, the bound queries and the exports) update state kept in
+ *     it (host mirrors of device results, lazily built tables) and must not run concurrently on the
+ *     same plan.  Different plans are independent.
  *   - Every function returns IMUNPACK_OK (0) or a negative error code; nothing throws or aborts.
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on it unless stated otherwise.
@@ -92,13 +96,17 @@ int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r
 /* ---- (1)+(2) RTN quantisation fused with the heavy-hitter scan --------------------------------
  * Sec. 2, Eq. (quantized_A) with the step supplied by the caller:
  *     Q[r*ldq + c] = rint(X[r*sx_r + c*sx_c] / scale)      (int32, no clipping)
+ * The paper prints the scaling as a multiplication by 0.5 beta / alpha_p; the reading taken here is a
+ * binary32 division by the step scale = alpha_p / (0.5 beta) (the two can differ in the last bit of
+ * the quotient, and so at rounding ties; the oracle the library is checked against divides too).
  * and, in the same pass, the statistics of Q for bit width b (any of the four stats pointers, or
  * stats itself, may be NULL to skip it).  X, Q, stats, status: device.  X may be any strided view
- * (sx_c == 1 and sx_r == 1 have fast paths); Q is written row-major.
+ * with sx_r, sx_c >= 1 (sx_c == 1 and sx_r == 1 have fast paths); Q is written row-major.
  * status (device int32, may be NULL) is set to 0, then to 1 if any input is NaN/Inf or any
  * quotient has magnitude >= 2^31 (such outputs are written as 0); the call itself still returns
  * IMUNPACK_OK -- read status when convenient.
- * Errors: EINVAL (null X/Q, rows/cols < 0, ldq < cols, scale not finite or <= 0, b outside [2,8]). */
+ * Errors: EINVAL (null X/Q, rows/cols < 0, a stride < 1, ldq < cols, scale not finite or <= 0,
+ * b outside [2,8]). */
 int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
                       float scale, int b, int32_t *Q, int64_t ldq,
                       const imunpack_stats_t *stats, int32_t *status, imunpack_stream_t stream);
@@ -112,14 +120,16 @@ int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int
  * unpacking: UnpackRow / UnpackColumn append one slot per further digit of the largest magnitude of
  * a row / column, so n', d', h' follow from rowmax / colmax (for UnpackColumn on both operands a
  * column k of A with LA digits meets LB digits of column k of B: LA * LB columns).
- * stats_A, stats_B: device, rowmax and colmax required.  dims_out (host, may be NULL):
- * [pair][3] = n', d', h' for the pairs (strategy_A, strategy_B) = (ROW,ROW), (ROW,COL), (COL,ROW),
- * (COL,COL); ratio_out (host, may be NULL): their r.  best_A / best_B (host, may be NULL): the
- * pair with the smallest r (first in that order on ties).  UnpackBoth is priced by planning with
- * it (imunpack_plan + imunpack_plan_dims).  Synchronises the stream.
+ * stats_A, stats_B: device, rowmax and colmax required.  workspace: device, 8-byte aligned,
+ * IMUNPACK_PRICE_WORKSPACE_BYTES, contents irrelevant before and after (the call allocates nothing).
+ * dims_out (host, may be NULL): [pair][3] = n', d', h' for the pairs (strategy_A, strategy_B) =
+ * (ROW,ROW), (ROW,COL), (COL,ROW), (COL,COL); ratio_out (host, may be NULL): their r.  best_A / best_B
+ * (host, may be NULL): the pair with the smallest r (first in that order on ties).  UnpackBoth is
+ * priced by planning with it (imunpack_plan + imunpack_plan_dims).  Synchronises the stream.
  * Errors: EINVAL, ERANGE (a size does not fit int64), EHIP. */
+#define IMUNPACK_PRICE_WORKSPACE_BYTES 64
 int imunpack_price(const imunpack_stats_t *stats_A, int64_t n, const imunpack_stats_t *stats_B,
-                   int64_t h, int64_t d, int b, int64_t *dims_out, double *ratio_out,
+                   int64_t h, int64_t d, int b, void *workspace, int64_t *dims_out, double *ratio_out,
                    int *best_A, int *best_B, imunpack_stream_t stream);
 
 /* ---- (3) unpack plan (Alg. 1, 2, 4, 5 and the two-operand composition of Sec. 4) -------------
@@ -148,11 +158,18 @@ int imunpack_plan_dims(const imunpack_plan_t *plan, int64_t *n_u, int64_t *d_u, 
 /* The plan in the order the paper's algorithms produce it (host buffers sized from
  * imunpack_plan_dims; any may be NULL).  Pi_A column R is s^rowA_exp[R] at row rowA_src[R]; Pi_B
  * likewise; S_uu[c,c] = s^col_exp[c]; col_src[c] is the original column that unpacked column c
- * descends from.  Synchronises the stream used by imunpack_plan. */
-int imunpack_plan_export(const imunpack_plan_t *plan,
-                         int32_t *rowA_src, int32_t *rowA_exp,  /* n' */
-                         int32_t *rowB_src, int32_t *rowB_exp,  /* h' */
-                         int32_t *col_src, int32_t *col_exp);   /* d' */
+ * descends from; col_parent[c] is the column that column c was appended for (the one whose
+ * floor(. / s) it took and whose copy the partner received: Alg. 2 lines 4-7, Alg. 4 lines 11-14),
+ * -1 for the d original columns.  ops (3 * (n' - n + h' - h + d' - d) int32, that count also written
+ * to *n_ops) lists every split in the order the paper's algorithms make them, as triples
+ * (0 = first / 1 = second Unpack call of Sec. 4 "Combining everything", 0 = row split / 1 = column
+ * split, index of the split row or column at that moment).
+ * Synchronises the stream used by imunpack_plan. */
+int imunpack_plan_export(imunpack_plan_t *plan,
+                         int32_t *rowA_src, int32_t *rowA_exp,                   /* n' */
+                         int32_t *rowB_src, int32_t *rowB_exp,                   /* h' */
+                         int32_t *col_src, int32_t *col_exp, int32_t *col_parent, /* d' */
+                         int32_t *ops, int64_t *n_ops);
 
 int imunpack_plan_destroy(imunpack_plan_t *plan);
 
@@ -172,7 +189,7 @@ int imunpack_unpack(imunpack_plan_t *plan, const int32_t *A, int64_t lda,
                     imunpack_stream_t stream);
 
 /* Test aid: re-orders the physical operands into the paper's order, dense n' x d' and h' x d'. */
-int imunpack_unpack_canonical(const imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
+int imunpack_unpack_canonical(imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
                               int8_t *A_canon, int8_t *B_canon, imunpack_stream_t stream);
 
 /* ---- (5) int8 MFMA GEMM (Alg. 3) ---------------------------------------------------------------
@@ -186,7 +203,7 @@ int imunpack_unpack_canonical(const imunpack_plan_t *plan, const int8_t *A_ue, c
  * fuse == 0: writes the unpacked product C_u = A_ue S_uu B_eu^T as int64 into workspace
  *   (imunpack_unpacked_bytes) for imunpack_recombine; C_int / C_fp are ignored.
  * ldc: row stride of C_int and C_fp in elements (>= h).  scale_A, scale_B: the RTN steps. */
-int imunpack_gemm(const imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
+int imunpack_gemm(imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
                   void *workspace, int64_t *C_int, float *C_fp, int64_t ldc,
                   float scale_A, float scale_B, int fuse, imunpack_stream_t stream);
 
@@ -207,7 +224,7 @@ int imunpack_last_hip_error(void);
 /* Which GEMM path the plan's last imunpack_unpack selected: 1 = single fused launch is exact,
  * 0 = the shifted group sum may exceed int32 and the un-fused path is required.  Waits for that
  * unpack to finish on the device. */
-int imunpack_plan_fusable(const imunpack_plan_t *plan);
+int imunpack_plan_fusable(imunpack_plan_t *plan);
 
 /* The two numbers that decision rests on, as the plan's last imunpack_unpack measured them:
  * bound[0] = max over the rows R of A_ue of sum_c s^e(c) |A_ue[R, c]|, bound[1] the same for B_eu,
@@ -215,7 +232,7 @@ int imunpack_plan_fusable(const imunpack_plan_t *plan);
  * is at most s - 1 in magnitude, so |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound[0], bound[1]), and
  * the fused launch is exact when that stays below 2^31.  Values of 2^44 and more are reported
  * saturated (at least 2^44).  bound: host, two elements.  Waits like imunpack_plan_fusable. */
-int imunpack_plan_bounds(const imunpack_plan_t *plan, uint64_t *bound);
+int imunpack_plan_bounds(imunpack_plan_t *plan, uint64_t *bound);
 
 /* Measured matrix-core peak (benchmark reporting only, not part of the method): launches
  * `workgroups` workgroups of 4 waves that each issue 8 * iters register-resident

@@ -1,6 +1,6 @@
 """Self-attention whose six GEMMs run on the exact low-bit integer path.
 
-Sec. 3 of arXiv 2403.07339 lists, beside the GEMMs of the linear layer, those of self-attention,
+Sec. 1 ("Notations") of arXiv 2403.07339 lists, beside the GEMMs of the linear layer, those of self-attention,
 
     P = Q K^T            O = M V                 (forward;  M = softmax(P), scaling factors omitted there)
     grad_Q = grad_P K    grad_K = grad_P^T Q     grad_M = grad_O V^T    grad_V = M^T grad_O   (backward)

@@ -42,7 +42,7 @@ _lib.imunpack_scan.argtypes = [_vp, _i64, _i64, _i64, _i32, C.POINTER(_Stats), _
 _lib.imunpack_plan.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32,
                                C.POINTER(_Stats), C.POINTER(_Stats), C.POINTER(_vp), _vp]
 _lib.imunpack_plan_dims.argtypes = [_vp, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), C.POINTER(C.c_int32)]
-_lib.imunpack_plan_export.argtypes = [_vp] + [_vp] * 6
+_lib.imunpack_plan_export.argtypes = [_vp] + [_vp] * 8 + [C.POINTER(_i64)]
 _lib.imunpack_plan_destroy.argtypes = [_vp]
 _lib.imunpack_unpacked_bytes.argtypes = [_vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
 _lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
@@ -57,7 +57,7 @@ _lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 _lib.imunpack_diag_clock_probe.argtypes = [_vp]
 _lib.imunpack_diag_copy.argtypes = [_vp, _vp, _i64, _vp]
-_lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, C.POINTER(_i64),
+_lib.imunpack_price.argtypes = [C.POINTER(_Stats), _i64, C.POINTER(_Stats), _i64, _i64, _i32, _vp, C.POINTER(_i64),
                                 C.POINTER(C.c_double), C.POINTER(_i32), C.POINTER(_i32), _vp]
 for _name in EXPORTS:
     if _name != "imunpack_strerror":
@@ -202,10 +202,19 @@ class Plan:
 
     def export(self):
         """Canonical plan as host int32 tensors: rowA_src, rowA_exp, rowB_src, rowB_exp, col_src, col_exp."""
+        return self.export_all()[:6]
+
+    def export_all(self):
+        """export() plus col_parent (d') and the sequence of splits, one row (call, kind, index) each."""
         n_u, d_u, h_u, _ = self.dims()
-        outs = [torch.empty(k, dtype=torch.int32) for k in (n_u, n_u, h_u, h_u, d_u, d_u)]
-        _check(_lib.imunpack_plan_export(self._h, *[o.data_ptr() for o in outs]), "imunpack_plan_export")
-        return outs
+        n_ops = (n_u - self.n) + (h_u - self.h) + (d_u - self.d)
+        outs = [torch.empty(k, dtype=torch.int32) for k in (n_u, n_u, h_u, h_u, d_u, d_u, d_u)]
+        ops = torch.empty((n_ops, 3), dtype=torch.int32)
+        got = _i64(-1)
+        _check(_lib.imunpack_plan_export(self._h, *[o.data_ptr() for o in outs], ops.data_ptr(), C.byref(got)),
+               "imunpack_plan_export")
+        assert got.value == n_ops
+        return outs + [ops]
 
     def unpacked_bytes(self):
         a, b_, w = C.c_size_t(), C.c_size_t(), C.c_size_t()
@@ -340,7 +349,11 @@ def imunpack_diag_clock_probe(ticks: torch.Tensor | None) -> None:
     _check(_lib.imunpack_diag_clock_probe(_ptr(ticks)), "imunpack_diag_clock_probe")
 
 
-def imunpack_price(stats_a: Stats, n: int, stats_b: Stats, h: int, d: int, b: int):
+PRICE_WORKSPACE_BYTES = 64
+
+
+def imunpack_price(stats_a: Stats, n: int, stats_b: Stats, h: int, d: int, b: int,
+                   workspace: torch.Tensor | None = None):
     """Prices the four pairs of one-axis strategies from the scan statistics (no unpacking).  Returns
     (dims, ratios, best): dims[(sA, sB)] = (n', d', h'), ratios[(sA, sB)] = r, best = the pair with
     the smallest r."""
@@ -348,7 +361,9 @@ def imunpack_price(stats_a: Stats, n: int, stats_b: Stats, h: int, d: int, b: in
     ratios = (C.c_double * 4)()
     ba, bb = _i32(0), _i32(0)
     ca, cb = stats_a._c(), stats_b._c()
-    _check(_lib.imunpack_price(C.byref(ca), n, C.byref(cb), h, d, b, dims, ratios, C.byref(ba), C.byref(bb),
+    if workspace is None:
+        workspace = torch.empty(PRICE_WORKSPACE_BYTES // 8, dtype=torch.int64, device=stats_a.rowmax.device)
+    _check(_lib.imunpack_price(C.byref(ca), n, C.byref(cb), h, d, b, workspace.data_ptr(), dims, ratios, C.byref(ba), C.byref(bb),
                                _stream()), "imunpack_price")
     pairs = [(ROW, ROW), (ROW, COL), (COL, ROW), (COL, COL)]
     return ({p: tuple(int(dims[3 * q + c]) for c in range(3)) for q, p in enumerate(pairs)},

@@ -11,6 +11,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -95,15 +96,12 @@ __device__ __forceinline__ const int8_t *uniform_ptr(const int8_t *p) {
     return (const int8_t *)(((uint64_t)hi << 32) | lo);
 }
 
-// LDS tile: [256 rows][64 B]; the four 16-byte chunks of a row are XOR-swizzled with bits 2..3 of
-// the row, which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks)
-// conflict-free.  Chunk kc of row r lives at r*64 + ((kc ^ ((r >> 2) & 3)) << 4).
+// LDS half-stage: [256 rows][128 B] of one operand; the eight 16-byte chunks of a row are XOR-swizzled
+// with bits 1..3 of the row (chunk kc of row r lives at r*128 + ((kc ^ ((r >> 1) & 7)) << 4)), which
+// makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks) conflict-free.
 template <int MODE>  // 0: fused epilogue, 1: int64 segment into C_u
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-#ifdef IMU_GEMM_DIAG
-    constexpr int g_diag = IMU_GEMM_DIAG;  // diagnostics build only (wrong results by design)
-#endif
     if (MODE == 0 && g.guard) {
         const unsigned long long b0 = g.guard[0], b1 = g.guard[1];
         const unsigned long long m = b0 < b1 ? b0 : b1;
@@ -136,18 +134,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     const int8_t *pg = nullptr;
     unsigned dl = 0;
     auto half_setup = [&](const int8_t *gbase, int kt, int slot) {
-#ifdef IMU_GEMM_DIAG
-        const int ktc = (g_diag & 1) ? (kt & 1) : min(kt, kt1 - 1);
-#else
         const int ktc = min(kt, kt1 - 1);
-#endif
         pg = uniform_ptr(gbase + (int64_t)ktc * BK);
         dl = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(slot * kHalfBytes) + (unsigned)(wave * 8192));
     };
     auto dma_one = [&](int u) {  // u = 0..7: rows [64 wave + 8u, +8) of the half-stage set up last
-#ifdef IMU_GEMM_DIAG
-        if constexpr ((g_diag & 2) != 0) return;
-#endif
         dma16(dl + u * 1024, voff[u], pg);
     };
 
@@ -268,9 +259,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             step(1, stA, stB, 2, 3, 3);
             step(0, stA, stB, 3, 6, 2);
             asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
-#ifdef IMU_GEMM_DIAG
-            if constexpr ((g_diag & 4) == 0)
-#endif
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             half_setup(gB, kt + 2, sa);
@@ -325,9 +313,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // row-contiguous and the digit levels of a source row (which the planner keeps inside one chunk)
     // and of a source column (inside one tile) can be added up:
     // C_int[i,j] = sum_{levels a of i, c of j} s^(a+c) * acc[row(i,a)][col(j,c)].
-#ifdef IMU_GEMM_DIAG
-    if constexpr ((g_diag & 32) != 0) { if (acc[0][0][0] == 0x12345) g.C_fp[0] = 1.0f; return; }
-#endif
     const int jsrc0 = g.layB.tile_src0[tn], nsrcB = g.layB.tile_src0[tn + 1] - jsrc0;
     const bool flatA = g.flatA[tm] != 0, flatB = g.flatB[tn] != 0;
     constexpr int FLD = 260;
@@ -422,9 +407,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
                 if (col4 < nsrcB && flatA) {  // physical order = source order inside the chunk
                     for (int r = tid >> 6; r < ns; r += kGemmThreads / 64) {
                         const v4i x = *reinterpret_cast<const v4i *>(fold + r * FLD + col4);
-#ifdef IMU_GEMM_DIAG
-                        if constexpr ((g_diag & 16) != 0) { if (x[0] == 0x12345) g.C_fp[0] = 1.0f; continue; }
-#endif
                         store4((int64_t)(cs0 + r) * g.ldc + jsrc0 + col4, nsrcB - col4, x[0], x[1], x[2], x[3]);
                     }
                 } else if (col4 < nsrcB) {
@@ -624,14 +606,17 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int *sink) {
 
 using namespace imu;
 
-static unsigned long long *g_clock_probe = nullptr;  // device memory of the caller, see imunpack_diag_clock_probe
+// device memory of the caller, see imunpack_diag_clock_probe
+static std::atomic<unsigned long long *> g_clock_probe{nullptr};
 
 static int gemm_lds_opt_in() {
-    static int done = 0;  // the kernels use 128 KiB of dynamic LDS, above the default limit
-    if (!done) {
+    // the kernels use all 160 KiB of a CU's LDS as dynamic shared memory, above the default limit; the
+    // attribute is idempotent, so two threads racing through here both set the same value
+    static std::atomic<int> done{0};
+    if (!done.load(std::memory_order_acquire)) {
         IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
         IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
-        done = 1;
+        done.store(1, std::memory_order_release);
     }
     return IMUNPACK_OK;
 }
@@ -655,11 +640,10 @@ extern "C" int imunpack_recombine(const imunpack_plan_t *p, const void *workspac
     return launch_status();
 }
 
-extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, const int8_t *B_eu,
+extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
                              void *workspace, int64_t *C_int, float *C_fp, int64_t ldc, float scale_A,
                              float scale_B, int fuse, imunpack_stream_t stream) {
-    if (!cp || !cp->valid || !cp->unpacked || !A_ue || !B_eu) return IMUNPACK_EINVAL;
-    Plan *p = const_cast<Plan *>(cp);
+    if (!p || !p->valid || !p->unpacked || !A_ue || !B_eu) return IMUNPACK_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (h.mtiles <= 0 || h.ntiles <= 0) return IMUNPACK_OK;
@@ -701,7 +685,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, cons
         g.final_shift = h.ngroups ? p->sh * h.grp_exp[h.ngroups - 1] : 0;
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
-        g.clock_probe = g_clock_probe;
+        g.clock_probe = g_clock_probe.load(std::memory_order_relaxed);
         // |accumulator| < 2^31, weights up to s^(levels of a row - 1 + levels of a column - 1)
         g.fold_f64 = !C_int && 31 + p->sh * ((h.lmaxA - 1) + (h.lmaxB - 1)) <= 52;
         hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
@@ -729,7 +713,7 @@ extern "C" int imunpack_gemm(const imunpack_plan_t *cp, const int8_t *A_ue, cons
 }
 
 extern "C" int imunpack_diag_clock_probe(uint64_t *ticks) {
-    g_clock_probe = reinterpret_cast<unsigned long long *>(ticks);
+    g_clock_probe.store(reinterpret_cast<unsigned long long *>(ticks), std::memory_order_relaxed);
     return IMUNPACK_OK;
 }
 

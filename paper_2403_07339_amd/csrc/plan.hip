@@ -17,6 +17,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -960,6 +961,10 @@ __global__ __launch_bounds__(256) void price_kernel(const int32_t *rowmaxA, int6
     }
 }
 
+__global__ void clear_sums_kernel(unsigned long long *p, int count) {
+    if ((int)threadIdx.x < count) p[threadIdx.x] = 0;
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -1132,11 +1137,11 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.whichE = first ? CAP_EDGEA : CAP_EDGEB;
     g.s = p->s; g.sh = p->sh;
     const size_t lds_bytes = ((size_t)((rows.cap + 7) & ~3) + (size_t)((cols.cap + 7) & ~3)) * sizeof(int32_t);
-    static int opted_in = 0;
-    if (!opted_in) {
+    static std::atomic<int> opted_in{0};  // the attribute is idempotent: a race sets the same value twice
+    if (!opted_in.load(std::memory_order_acquire)) {
         IMU_HIP(hipFuncSetAttribute((const void *)greedy_both_kernel<true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kGreedyLdsMax));
-        opted_in = 1;
+        opted_in.store(1, std::memory_order_release);
     }
     const int keep_cap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];  // the stride the fix-up pass reads with
     hipLaunchKernelGGL(ob_copy_kernel, dim3(grid_for(ob_cap, 256, 128)), dim3(256), 0, st, ob, ob_cap, ob_count,
@@ -1364,12 +1369,13 @@ namespace imu {
 // order is (count at the split descending, index of the split slot ascending), the index being the
 // canonical one.  key = run << 48 | (0xFFFFFF - count) << 24 | split slot (internal numbering).
 static int canonical_order(const SlotSet &set, int nbase, int count, const std::vector<int> *base_canon,
-                           hipStream_t st, std::vector<int> &canon_of) {
+                           hipStream_t st, std::vector<int> &canon_of, std::vector<unsigned long long> &key) {
     canon_of.assign((size_t)count, 0);
+    key.clear();
     for (int x = 0; x < nbase && x < count; ++x) canon_of[x] = base_canon ? (*base_canon)[x] : x;
     const int extra = count - nbase;
     if (extra <= 0) return IMUNPACK_OK;
-    std::vector<unsigned long long> key((size_t)extra);
+    key.resize((size_t)extra);
     IMU_HIP(hipMemcpyAsync(key.data(), set.key + nbase, (size_t)extra * sizeof(unsigned long long),
                            hipMemcpyDeviceToHost, st));
     IMU_HIP(hipStreamSynchronize(st));
@@ -1404,6 +1410,7 @@ static int canonical_order(const SlotSet &set, int nbase, int count, const std::
 
 struct CanonHost {
     std::vector<int> rowA, rowB, c1, c2;  // internal slot -> canonical slot
+    std::vector<unsigned long long> keyA, keyB, key1, key2;  // sort keys of the appended slots of each set
 };
 
 static int fetch_i32(std::vector<int32_t> &dst, const int32_t *src, size_t count, hipStream_t st) {
@@ -1415,10 +1422,10 @@ static int fetch_i32(std::vector<int32_t> &dst, const int32_t *src, size_t count
 static int build_canonical(Plan *p, CanonHost &c) {
     hipStream_t st = p->stream;
     const PlanHeader &h = p->hdr;
-    IMU_TRY(canonical_order(p->rowA, (int)p->n, h.n_u, nullptr, st, c.rowA));
-    IMU_TRY(canonical_order(p->rowB, (int)p->h, h.h_u, nullptr, st, c.rowB));
-    IMU_TRY(canonical_order(p->c1, (int)p->d, h.d1, nullptr, st, c.c1));
-    IMU_TRY(canonical_order(p->c2, h.d1, h.d_u, &c.c1, st, c.c2));
+    IMU_TRY(canonical_order(p->rowA, (int)p->n, h.n_u, nullptr, st, c.rowA, c.keyA));
+    IMU_TRY(canonical_order(p->rowB, (int)p->h, h.h_u, nullptr, st, c.rowB, c.keyB));
+    IMU_TRY(canonical_order(p->c1, (int)p->d, h.d1, nullptr, st, c.c1, c.key1));
+    IMU_TRY(canonical_order(p->c2, h.d1, h.d_u, &c.c1, st, c.c2, c.key2));
     if (!p->canon_valid) {
         // physical row / column of every canonical slot, for imunpack_unpack_canonical
         std::vector<int32_t> phys, out;
@@ -1446,11 +1453,10 @@ int ensure_canonical(Plan *p) {
 
 }  // namespace imu
 
-extern "C" int imunpack_plan_export(const imunpack_plan_t *cp, int32_t *rowA_src, int32_t *rowA_exp,
+extern "C" int imunpack_plan_export(imunpack_plan_t *p, int32_t *rowA_src, int32_t *rowA_exp,
                                     int32_t *rowB_src, int32_t *rowB_exp, int32_t *col_src,
-                                    int32_t *col_exp) {
-    if (!cp || !cp->valid) return IMUNPACK_EINVAL;
-    Plan *p = const_cast<Plan *>(cp);
+                                    int32_t *col_exp, int32_t *col_parent, int32_t *ops, int64_t *n_ops) {
+    if (!p || !p->valid) return IMUNPACK_EINVAL;
     hipStream_t st = p->stream;
     const PlanHeader &h = p->hdr;
     CanonHost c;
@@ -1481,6 +1487,46 @@ extern "C" int imunpack_plan_export(const imunpack_plan_t *cp, int32_t *rowA_src
             if (col_exp) col_exp[c.c2[x]] = ex1[r1] + ex[x];
         }
     }
+    // The appended slots in the paper's numbering are numbered in the order their splits were made, and
+    // the sort key of an appended slot names the slot that was split for it (low 24 bits, internal
+    // numbering) and the run it was made in (level of the closed-form UnpackRow / UnpackColumn, batch of
+    // UnpackBoth; a batch holds splits of one kind only).
+    const int d = (int)p->d, nA = (int)p->n, nB = (int)p->h;
+    auto parent_of = [](const std::vector<unsigned long long> &key, int t) { return (int)(key[(size_t)t] & 0xFFFFFF); };
+    if (col_parent) {
+        for (int x = 0; x < h.d1; ++x)  // the columns the second call started from: originals and A's appended ones
+            col_parent[c.c2[x]] = x < d ? -1 : c.c2[(size_t)parent_of(c.key1, x - d)];
+        for (int x = h.d1; x < h.d_u; ++x) col_parent[c.c2[x]] = c.c2[(size_t)parent_of(c.key2, x - h.d1)];
+    }
+    const int64_t total_ops = (int64_t)(h.n_u - nA) + (h.d1 - d) + (h.h_u - nB) + (h.d_u - h.d1);
+    if (n_ops) *n_ops = total_ops;
+    if (ops) {
+        struct Op { unsigned long long run; int kind, canon, parent; };
+        int64_t at = 0;
+        for (int call = 0; call < 2; ++call) {
+            const std::vector<int> &rc = call ? c.rowB : c.rowA, &cc = call ? c.c2 : c.c1;
+            const std::vector<unsigned long long> &rk = call ? c.keyB : c.keyA, &ck = call ? c.key2 : c.key1;
+            const int rbase = call ? nB : nA, cbase = call ? h.d1 : d;
+            std::vector<Op> seq;
+            seq.reserve(rk.size() + ck.size());
+            for (size_t t = 0; t < rk.size(); ++t)
+                seq.push_back({rk[t] >> 48, 0, rc[(size_t)rbase + t], rc[(size_t)parent_of(rk, (int)t)]});
+            for (size_t t = 0; t < ck.size(); ++t)
+                seq.push_back({ck[t] >> 48, 1, cc[(size_t)cbase + t], cc[(size_t)parent_of(ck, (int)t)]});
+            // one-axis strategies append along one axis only: creation order is the numbering; UnpackBoth
+            // interleaves the axes batch by batch
+            std::sort(seq.begin(), seq.end(), [](const Op &a, const Op &b) {
+                if (a.run != b.run) return a.run < b.run;
+                return a.canon < b.canon;
+            });
+            for (const Op &o : seq) {
+                ops[3 * at] = call;
+                ops[3 * at + 1] = o.kind;
+                ops[3 * at + 2] = o.parent;
+                ++at;
+            }
+        }
+    }
     return IMUNPACK_OK;
 }
 
@@ -1501,27 +1547,21 @@ extern "C" int imunpack_plan_destroy(imunpack_plan_t *p) {
 }
 
 extern "C" int imunpack_price(const imunpack_stats_t *stA, int64_t n, const imunpack_stats_t *stB, int64_t h,
-                              int64_t d, int b, int64_t *dims_out, double *ratio_out, int *best_A, int *best_B,
-                              imunpack_stream_t stream) {
-    if (!stA || !stB || !stA->rowmax || !stA->colmax || !stB->rowmax || !stB->colmax || n <= 0 || h <= 0 ||
-        d <= 0 || b < 2 || b > 8)
+                              int64_t d, int b, void *workspace, int64_t *dims_out, double *ratio_out, int *best_A,
+                              int *best_B, imunpack_stream_t stream) {
+    if (!stA || !stB || !stA->rowmax || !stA->colmax || !stB->rowmax || !stB->colmax || !workspace || n <= 0 ||
+        h <= 0 || d <= 0 || b < 2 || b > 8 || (uintptr_t)workspace % 8)
         return IMUNPACK_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    unsigned long long *sums = nullptr, host[5];
-    IMU_HIP(hipMalloc((void **)&sums, sizeof(host)));
-    int rc = IMUNPACK_OK;
-    hipError_t e = hipMemsetAsync(sums, 0, sizeof(host), st);
-    if (e == hipSuccess) {
-        const int64_t longest = std::max(std::max(n, h), d);
-        hipLaunchKernelGGL(price_kernel, dim3(grid_for(longest, 256, 1024)), dim3(256), 0, st, stA->rowmax, n,
-                           stB->rowmax, h, stA->colmax, stB->colmax, d, b - 1, sums);
-        e = hipGetLastError();
-    }
-    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) { g_last_hip_error = (int)e; rc = IMUNPACK_EHIP; }
-    (void)hipFree(sums);
-    if (rc != IMUNPACK_OK) return rc;
+    unsigned long long *sums = static_cast<unsigned long long *>(workspace), host[5];
+    static_assert(IMUNPACK_PRICE_WORKSPACE_BYTES >= sizeof(host), "workspace");
+    hipLaunchKernelGGL(clear_sums_kernel, dim3(1), dim3(64), 0, st, sums, 5);
+    const int64_t longest = std::max(std::max(n, h), d);
+    hipLaunchKernelGGL(price_kernel, dim3(grid_for(longest, 256, 1024)), dim3(256), 0, st, stA->rowmax, n,
+                       stB->rowmax, h, stA->colmax, stB->colmax, d, b - 1, sums);
+    IMU_TRY(launch_status());
+    IMU_HIP(hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st));
+    IMU_HIP(hipStreamSynchronize(st));
     // (strategy_A, strategy_B): (ROW,ROW), (ROW,COL), (COL,ROW), (COL,COL)
     const unsigned long long dims[4][3] = {{host[0], (unsigned long long)d, host[1]},
                                             {host[0], host[3], (unsigned long long)h},

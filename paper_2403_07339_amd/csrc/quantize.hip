@@ -418,6 +418,7 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
                      hipStream_t stream) {
     if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
     if (FROM_FLOAT && (!Q || ldq < cols || !(scale > 0.0f) || !(scale < 3.0e38f))) return IMUNPACK_EINVAL;
+    if (sx_r < 1 || sx_c < 1) return IMUNPACK_EINVAL;
     IMU_TRY(zero_stats(st, rows, cols, FROM_FLOAT ? status : nullptr, stream));
     if (rows == 0 || cols == 0) return IMUNPACK_OK;
     const int s = 1 << (b - 1);

@@ -437,16 +437,14 @@ int resolve_bound(Plan *p) {
 }
 }  // namespace imu
 
-extern "C" int imunpack_plan_fusable(const imunpack_plan_t *cp) {
-    if (!cp || !cp->valid || !cp->unpacked) return 0;
-    Plan *p = const_cast<Plan *>(cp);
+extern "C" int imunpack_plan_fusable(imunpack_plan_t *p) {
+    if (!p || !p->valid || !p->unpacked) return 0;
     if (resolve_bound(p) != IMUNPACK_OK) return 0;
     return p->fusable;
 }
 
-extern "C" int imunpack_plan_bounds(const imunpack_plan_t *cp, uint64_t *bound) {
-    if (!cp || !cp->valid || !cp->unpacked || !bound) return IMUNPACK_EINVAL;
-    Plan *p = const_cast<Plan *>(cp);
+extern "C" int imunpack_plan_bounds(imunpack_plan_t *p, uint64_t *bound) {
+    if (!p || !p->valid || !p->unpacked || !bound) return IMUNPACK_EINVAL;
     IMU_TRY(resolve_bound(p));
     bound[0] = p->hdr.bound[0];
     bound[1] = p->hdr.bound[1];
@@ -455,10 +453,9 @@ extern "C" int imunpack_plan_bounds(const imunpack_plan_t *cp, uint64_t *bound) 
 
 namespace imu { int ensure_canonical(Plan *p); }
 
-extern "C" int imunpack_unpack_canonical(const imunpack_plan_t *cp, const int8_t *A_ue, const int8_t *B_eu,
+extern "C" int imunpack_unpack_canonical(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
                                          int8_t *A_canon, int8_t *B_canon, imunpack_stream_t stream) {
-    if (!cp || !cp->valid) return IMUNPACK_EINVAL;
-    Plan *p = const_cast<Plan *>(cp);
+    if (!p || !p->valid) return IMUNPACK_EINVAL;
     IMU_TRY(ensure_canonical(p));  // host-side renumbering into the paper's order (synchronises)
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;

@@ -1,6 +1,6 @@
 """A linear layer whose three GEMMs run on the exact low-bit integer path.
 
-Sec. 3 of arXiv 2403.07339 lists the GEMMs of a Transformer; for a linear layer they are
+Sec. 1 ("Notations") of arXiv 2403.07339 lists the GEMMs of a Transformer; for a linear layer they are
 
     Y      = X  W^T          (forward)
     grad_X = grad_Y  W       (backward, input)

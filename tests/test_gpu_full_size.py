@@ -3,9 +3,9 @@ test_gpu_parity.py), in the launch configuration bench.py times: caller-provided
 lists from the fused quantize pass, fused GEMM epilogue.
 
 Compared in full: the quantized integers, the unpack plan and both unpacked int8 operands in the
-paper's order (the CPU oracle unpacks the full operands in seconds).  The int64 product is compared
-at sampled positions the oracle computes one by one, and in full through an identity that holds at
-any size: sum_ij C[i,j] = sum_k (sum_i A[i,k]) (sum_j B[j,k])."""
+paper's order (the CPU oracle unpacks the full operands in seconds), the int64 product and the fp32
+output, from the fused launch and from the un-fused path (the oracle's triple loop takes a few seconds
+per workload on the host cores)."""
 import numpy as np
 import pytest
 import torch
@@ -57,7 +57,10 @@ def test_workload_full_size(imu, index):
     n_u, d_u, h_u, ng = plan.dims()
     assert (n_u, d_u, h_u) == (hnd.n_u, hnd.d_u, hnd.h_u)
     S, pas, paw, pbs, pbw = hnd.meta()
-    ra_s, ra_e, rb_s, rb_e, c_s, c_e = [t.numpy().astype(np.int64) for t in plan.export()]
+    ra_s, ra_e, rb_s, rb_e, c_s, c_e, c_par, ops = [t.numpy().astype(np.int64) for t in plan.export_all()]
+    want_parent, want_ops = hnd.trace()
+    assert np.array_equal(c_s, hnd.col_src()) and np.array_equal(c_par, want_parent)
+    assert np.array_equal(ops, want_ops)          # every split, in the order Alg. 1 / 2 / 4 make them
     assert np.array_equal(ra_s, pas) and np.array_equal(s ** ra_e.astype(object), paw.astype(object))
     assert np.array_equal(rb_s, pbs) and np.array_equal(s ** rb_e.astype(object), pbw.astype(object))
     assert np.array_equal(s ** c_e.astype(object), S.astype(object))
@@ -80,21 +83,31 @@ def test_workload_full_size(imu, index):
     C_int = torch.empty((w.n, w.h), dtype=torch.int64, device="cuda")
     C_fp = torch.empty((w.n, w.h), dtype=torch.float32, device="cuda")
     imu.imunpack_gemm(plan, A_ue, B_eu, w.scale_a, w.scale_b, C_int, C_fp, None, fuse=True)
-    rng = np.random.default_rng(index)
-    rows, cols = rng.integers(0, w.n, 4096), rng.integers(0, w.h, 4096)
-    want = oracle.int_gemm_at(Aq, Bq, rows, cols)
-    ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
-    assert np.array_equal(C_int[ri, ci].cpu().numpy(), want)
-    want_fp = oracle.dequantize(want, w.scale_a, w.scale_b)
-    got_fp = C_fp[ri, ci].cpu().numpy().astype(np.float64)
-    assert (np.abs(got_fp - want_fp) <= REL_TOL * np.abs(want_fp)).all()
+    # the whole int64 product, element by element, against the oracle's triple loop
+    want = oracle.int_gemm(Aq, Bq)
+    got = C_int.cpu().numpy()
+    assert got.shape == want.shape and np.array_equal(got, want)
+    del got
+    # the fp32 output against the oracle's fp64 dequantisation, in full (row bands keep the host copies small)
+    C_fp_h = C_fp.cpu().numpy()
+    for r0 in range(0, w.n, 2048):
+        ref64 = oracle.dequantize(want[r0:r0 + 2048], w.scale_a, w.scale_b)
+        assert (np.abs(C_fp_h[r0:r0 + 2048].astype(np.float64) - ref64) <= REL_TOL * np.abs(ref64)).all()
+    del C_fp_h
     # the product identity through the oracle's own unpacked operands, at a few positions
-    assert np.array_equal(hnd.product_at(rows[:64], cols[:64]), want[:64])
-    # whole-output identity
-    total = int(C_int.sum().item())
-    col_a = Aq.astype(np.int64).sum(0)
-    col_b = Bq.astype(np.int64).sum(0)
-    assert total == int((col_a.astype(object) * col_b.astype(object)).sum())
+    rng = np.random.default_rng(index)
+    rows, cols = rng.integers(0, w.n, 64), rng.integers(0, w.h, 64)
+    assert np.array_equal(hnd.product_at(rows, cols), want[rows, cols])
+    # the un-fused path (one launch per diagonal entry of S into the int64 unpacked product, then the
+    # recombination kernel) against the oracle as well
+    ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+    C2 = torch.full((w.n, w.h), -1, dtype=torch.int64, device="cuda")
+    C2_fp = torch.full((w.n, w.h), float("nan"), dtype=torch.float32, device="cuda")
+    imu.imunpack_gemm(plan, A_ue, B_eu, w.scale_a, w.scale_b, None, None, ws, fuse=False)
+    imu.imunpack_recombine(plan, ws, w.scale_a, w.scale_b, C2, C2_fp)
+    assert np.array_equal(C2.cpu().numpy(), want)
+    assert torch.equal(C2_fp, C_fp)          # the same single rounding of the same integers
+    del ws, C2, C2_fp, want
     # every fp32 output is the rounded dequantisation of its own int64 (checked on the device in fp64)
     ref = C_int.to(torch.float64) * (float(np.float32(w.scale_a)) * float(np.float32(w.scale_b)))
     err = (C_fp.to(torch.float64) - ref).abs()

@@ -100,6 +100,30 @@ def test_ob_entry_list_for_every_input_layout(imu, shape, b, frac):
         assert sorted(zip(ob[0].tolist(), ob[1].tolist(), ob[2].tolist())) == want_set
 
 
+@pytest.mark.parametrize("scale,lo_exp,negate", [(1.0, 21, False), (0.75, 21, True), (0.0371, -3, False)])
+def test_quantize_every_float_of_two_binades(imu, scale, lo_exp, negate):
+    """Every binary32 value of two adjacent binades (2 x 2^23 bit patterns) through the quantizer: the
+    division must be the correctly rounded one and the rounding half-to-even for each of them.  With
+    step 1 the binades [2^21, 2^23) hold every tie k + 0.5 up to 2^22; steps 0.75 and 0.0371 make
+    nearly every quotient inexact, so a reciprocal-multiply or a fused form would show."""
+    scale = float(np.float32(scale))
+    lo = np.float32(2.0 ** lo_exp).view(np.uint32)
+    bits = np.arange(int(lo), int(lo) + (1 << 24), dtype=np.uint32)
+    if negate:
+        bits = bits | np.uint32(0x80000000)
+    x = bits.view(np.float32).reshape(4096, 4096)
+    assert np.isfinite(x).all() and np.abs(x).min() == np.float32(2.0 ** lo_exp)
+    want, st = oracle.rtn_quantize(x, scale)
+    assert st == 0
+    Q, _, status = imu.imunpack_quantize(dev(torch.from_numpy(x)), scale, 8, want_stats=False)
+    assert int(status.item()) == 0
+    assert np.array_equal(Q.cpu().numpy(), want)
+    # the transposing path runs the same arithmetic on the same values
+    Qt, _, status = imu.imunpack_quantize(dev(torch.from_numpy(x)).t(), scale, 8, want_stats=False)
+    assert int(status.item()) == 0
+    assert np.array_equal(Qt.cpu().numpy(), want.T)
+
+
 def test_quantize_flags_bad_input(imu):
     x = torch.ones(8, 8)
     x[3, 4] = float("nan")
@@ -130,7 +154,10 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     plan = imu.imunpack_plan(A_d, B_d, b, sa, sb)
     n_u, d_u, h_u, ng = plan.dims()
     assert (n_u, d_u, h_u) == (hnd.n_u, hnd.d_u, hnd.h_u)
-    ra_s, ra_e, rb_s, rb_e, c_s, c_e = [t.numpy().astype(np.int64) for t in plan.export()]
+    ra_s, ra_e, rb_s, rb_e, c_s, c_e, c_par, ops = [t.numpy().astype(np.int64) for t in plan.export_all()]
+    want_parent, want_ops = hnd.trace()
+    assert np.array_equal(c_s, hnd.col_src()) and np.array_equal(c_par, want_parent)
+    assert np.array_equal(ops, want_ops)          # every split, in the order Alg. 1 / 2 / 4 make them
     assert np.array_equal(ra_s, pas) and np.array_equal(s ** ra_e.astype(object), paw.astype(object))
     assert np.array_equal(rb_s, pbs) and np.array_equal(s ** rb_e.astype(object), pbw.astype(object))
     assert np.array_equal(s ** c_e.astype(object), S.astype(object))

@@ -70,6 +70,8 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert lib.imunpack_quantize(fake, 4, 4, 4, 1, float("nan"), 8, fake, 4, None, None, None) == EINVAL
     assert lib.imunpack_quantize(fake, 4, 4, 4, 1, 1.0, 8, fake, 3, None, None, None) == EINVAL      # ldq < cols
     assert lib.imunpack_quantize(fake, -1, 4, 4, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL
+    assert lib.imunpack_quantize(fake, 4, 4, 0, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL      # stride 0
+    assert lib.imunpack_quantize(fake, 4, 4, 4, -1, 1.0, 8, fake, 4, None, None, None) == EINVAL     # negative stride
     lib.imunpack_scan.restype = ctypes.c_int
     lib.imunpack_scan.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     assert lib.imunpack_scan(None, 4, 4, 4, 8, None, None) == EINVAL
@@ -94,7 +96,7 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert lib.imunpack_plan(fake, 4, 4, 4, fake, 4, 4, 8, 0, 0, None, None, None, None) == EINVAL   # nowhere to put the plan
     assert handle.value is None
     for name, nargs in (("imunpack_unpacked_bytes", 4), ("imunpack_unpack", 8), ("imunpack_unpack_canonical", 6),
-                        ("imunpack_gemm", 11), ("imunpack_recombine", 8), ("imunpack_plan_export", 7),
+                        ("imunpack_gemm", 11), ("imunpack_recombine", 8), ("imunpack_plan_export", 10),
                         ("imunpack_plan_bounds", 2)):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
@@ -109,8 +111,8 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     lib.imunpack_plan_fusable.restype = ctypes.c_int
     assert lib.imunpack_plan_fusable(None) == 0
     lib.imunpack_price.restype = ctypes.c_int
-    lib.imunpack_price.argtypes = [vp, i64, vp, i64, i64, i32, vp, vp, vp, vp, vp]
-    assert lib.imunpack_price(None, 4, None, 4, 4, 8, fake, fake, fake, fake, None) == EINVAL
+    lib.imunpack_price.argtypes = [vp, i64, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
+    assert lib.imunpack_price(None, 4, None, 4, 4, 8, fake, fake, fake, fake, fake, None) == EINVAL
     lib.imunpack_diag_mfma_peak.restype = ctypes.c_int
     lib.imunpack_diag_mfma_peak.argtypes = [i32, i32, vp, vp]
     assert lib.imunpack_diag_mfma_peak(0, 10, None, None) == EINVAL
