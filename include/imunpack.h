@@ -93,6 +93,19 @@ int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r
                         double p, float *alpha, int32_t *status_flag, void *workspace,
                         imunpack_stream_t stream);
 
+/* The same range estimate for callers that cannot allocate device memory or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the counters and the
+ * selection state live in a fixed array of IMUNPACK_PERCENTILE_WORKSPACE_BYTES of device memory that the
+ * library's code object carries, one copy per GPU, held until the process ends.  The call itself
+ * allocates and frees nothing.  Arguments, result and errors as imunpack_percentile without the
+ * workspace, except that more than IMUNPACK_PERCENTILE_STATIC_MAX_ENTRIES entries (what the array's
+ * 32-bit counters can count) return ERANGE.  The array is cleared at the start of every call; all calls
+ * on one GPU share it, so two calls that overlap on one GPU (different streams or threads) race: issue
+ * them on one stream, or order them with events. */
+#define IMUNPACK_PERCENTILE_STATIC_MAX_ENTRIES 4294967295ll
+int imunpack_percentile_static(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                               double p, float *alpha, int32_t *status_flag, imunpack_stream_t stream);
+
 /* ---- (1)+(2) RTN quantisation fused with the heavy-hitter scan --------------------------------
  * Sec. 2, Eq. (quantized_A) with the step supplied by the caller:
  *     Q[r*ldq + c] = rint(X[r*sx_r + c*sx_c] / scale)      (int32, no clipping)

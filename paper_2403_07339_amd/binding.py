@@ -27,7 +27,7 @@ EXPORTS = [
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
-    "imunpack_percentile",
+    "imunpack_percentile", "imunpack_percentile_static",
 ]
 
 
@@ -53,6 +53,7 @@ _lib.imunpack_strerror.argtypes = [_i32]
 _lib.imunpack_strerror.restype = C.c_char_p
 _lib.imunpack_plan_fusable.argtypes = [_vp]
 _lib.imunpack_percentile.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _vp, _vp, _vp, _vp]
+_lib.imunpack_percentile_static.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _vp, _vp, _vp]
 _lib.imunpack_plan_bounds.argtypes = [_vp, C.POINTER(C.c_uint64)]
 _lib.imunpack_diag_mfma_peak.argtypes = [_i32, _i32, C.POINTER(_i64), _vp]
 _lib.imunpack_diag_clock_probe.argtypes = [_vp]
@@ -135,6 +136,17 @@ def imunpack_percentile(X: torch.Tensor, p: float, alpha: torch.Tensor | None = 
     _check(_lib.imunpack_percentile(X.data_ptr(), X.shape[0], X.shape[1], X.stride(0), X.stride(1), float(p),
                                     alpha.data_ptr(), status.data_ptr(), workspace.data_ptr(), _stream()),
            "imunpack_percentile")
+    return alpha, status
+
+
+def imunpack_percentile_static(X: torch.Tensor, p: float, alpha: torch.Tensor, status: torch.Tensor | None = None):
+    """imunpack_percentile on the library's own fixed scratch array: the call allocates nothing, so the
+    caller passes the one-element outputs.  Returns (alpha, status)."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+    assert alpha.is_cuda and alpha.dtype == torch.float32 and alpha.numel() >= 1
+    _check(_lib.imunpack_percentile_static(X.data_ptr(), X.shape[0], X.shape[1], X.stride(0), X.stride(1), float(p),
+                                           alpha.data_ptr(), _ptr(status), _stream()),
+           "imunpack_percentile_static")
     return alpha, status
 
 

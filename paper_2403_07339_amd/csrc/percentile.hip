@@ -13,6 +13,7 @@
 #include "common.h"
 
 #include <cmath>
+#include <mutex>
 
 namespace imu {
 
@@ -159,14 +160,9 @@ __global__ __launch_bounds__(1024) void select_pick_kernel(void *ws, int shift, 
 
 using namespace imu;
 
-extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
-                                   double p, float *alpha, int32_t *status_flag, void *workspace,
-                                   imunpack_stream_t stream) {
-    if (!X || !alpha || !workspace || rows <= 0 || cols <= 0 || sx_r < 1 || sx_c < 1 || !(p > 0.0) || !(p <= 100.0))
-        return IMUNPACK_EINVAL;
-    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols >= (int64_t)1 << 32) return IMUNPACK_EINVAL;
+static int run_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, double p,
+                          float *alpha, int32_t *status_flag, void *workspace, hipStream_t st) {
     static_assert(IMUNPACK_PERCENTILE_WORKSPACE_BYTES >= kSelBins * sizeof(unsigned) + sizeof(SelState), "workspace");
-    hipStream_t st = (hipStream_t)stream;
     const int64_t N = rows * cols;
     double kd = std::ceil(p * (double)N / 100.0);
     if (kd < 1.0) kd = 1.0;
@@ -180,6 +176,7 @@ extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, i
     int64_t blocks = (items + (int64_t)kSelThreads * kSelItems - 1) / ((int64_t)kSelThreads * kSelItems);
     if (blocks > 1024) blocks = 1024;  // four per CU: every workgroup merges its histogram with atomics on the same few counters
     if (blocks < 1) blocks = 1;
+    // the init kernel clears the counters and the state: whatever an earlier call left in the workspace is gone
     hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(256), 0, st, workspace, k, status_flag);
     const int shifts[3] = {20, 10, 0}, bins[3] = {2048, 1024, 1024};
     for (int pass = 0; pass < 3; ++pass) {
@@ -192,4 +189,47 @@ extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, i
         hipLaunchKernelGGL(select_pick_kernel, dim3(1), dim3(1024), 0, st, workspace, shifts[pass], bins[pass], alpha);
     }
     return launch_status();
+}
+
+extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                                   double p, float *alpha, int32_t *status_flag, void *workspace,
+                                   imunpack_stream_t stream) {
+    if (!X || !alpha || !workspace || rows <= 0 || cols <= 0 || sx_r < 1 || sx_c < 1 || !(p > 0.0) || !(p <= 100.0))
+        return IMUNPACK_EINVAL;
+    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols >= (int64_t)1 << 32) return IMUNPACK_EINVAL;
+    return run_percentile(X, rows, cols, sx_r, sx_c, p, alpha, status_flag, workspace, (hipStream_t)stream);
+}
+
+// ---- the same selection for callers that cannot allocate ------------------------------------------
+// The counters and the selection state live in a file-scope device array instead of a caller
+// workspace.  Every GPU holds its own copy of the array at its own address, which the host learns
+// once per device; host code only ever uses that address, never the array's name.
+static __device__ __align__(256) unsigned char scratch[IMUNPACK_PERCENTILE_WORKSPACE_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void *g_scratch_ptr[kMaxDevices];  // per device, nullptr until that device's first call
+
+extern "C" int imunpack_percentile_static(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
+                                          double p, float *alpha, int32_t *status_flag,
+                                          imunpack_stream_t stream) {
+    if (!X || !alpha || rows <= 0 || cols <= 0 || sx_r < 1 || sx_c < 1 || !(p > 0.0) || !(p <= 100.0))
+        return IMUNPACK_EINVAL;
+    // the scratch array's counters are 32 bits wide: more entries than they can count are refused
+    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols > IMUNPACK_PERCENTILE_STATIC_MAX_ENTRIES)
+        return IMUNPACK_ERANGE;
+    int dev = -1;
+    IMU_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return IMUNPACK_EINVAL;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        if (!g_scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            IMU_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));  // the current device's copy
+            if (!ptr) return IMUNPACK_EHIP;
+            g_scratch_ptr[dev] = ptr;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    return run_percentile(X, rows, cols, sx_r, sx_c, p, alpha, status_flag, ws, (hipStream_t)stream);
 }
