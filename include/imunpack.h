@@ -187,16 +187,22 @@ int imunpack_plan_export(imunpack_plan_t *plan,
 int imunpack_plan_destroy(imunpack_plan_t *plan);
 
 /* ---- (4) digit scatter (Eq. (mod); Alg. 1 l.4-5, Alg. 2 l.4-6, Alg. 4 l.7-8, 11-13) -----------
- * Writes A_ue and B_eu as int8 in the plan's *physical* layout: rows grouped by source row (all
+ * Writes the unpacked operands as int8 in the plan's *physical* layout: rows grouped by source row (all
  * digit levels of a row of A inside one 64-row chunk of a GEMM tile, of a row of B inside one tile),
- * columns grouped by diagonal entry of S_uu and ordered by source column inside a group, both
- * zero-padded to tile multiples.  The partner's columns are duplicated where a column was split.
+ * both padded to tile multiples.  B_eu is stored in full, its columns grouped by diagonal entry of S_uu
+ * in whole k-tiles of 128.  Of A_ue only the columns of A_u are stored, each once ("A store"): where
+ * column unpacking of the partner repeats a column (Alg. 2 line 6 / Alg. 4 line 13) the GEMM reads the
+ * stored one again, so the copies cost neither memory nor traffic.
  * imunpack_unpacked_bytes gives the buffer sizes and the workspace an un-fused GEMM needs.
  * A, B: the int32 operands the plan was made from.  A_ue, B_eu: device, caller-allocated.
  * imunpack_unpack does not wait for the device: the accumulator bounds that select the GEMM path
  * reach the host later, and imunpack_gemm / imunpack_plan_fusable wait for them. */
 int imunpack_unpacked_bytes(const imunpack_plan_t *plan, size_t *bytes_A, size_t *bytes_B,
                             size_t *bytes_workspace);
+/* The shape of the two buffers (host output, six values): physical rows, stored columns and bytes from
+ * one row to the next, of the A store and then of B_eu.  bytes_A = rows * pitch.  The bytes of a row
+ * behind its stored columns are neither written nor read. */
+int imunpack_plan_layout(const imunpack_plan_t *plan, int64_t *shape);
 int imunpack_unpack(imunpack_plan_t *plan, const int32_t *A, int64_t lda,
                     const int32_t *B, int64_t ldb, int8_t *A_ue, int8_t *B_eu,
                     imunpack_stream_t stream);

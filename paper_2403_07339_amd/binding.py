@@ -27,7 +27,7 @@ EXPORTS = [
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
-    "imunpack_percentile", "imunpack_percentile_static",
+    "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout",
 ]
 
 
@@ -45,6 +45,7 @@ _lib.imunpack_plan_dims.argtypes = [_vp, C.POINTER(_i64), C.POINTER(_i64), C.POI
 _lib.imunpack_plan_export.argtypes = [_vp] + [_vp] * 8 + [C.POINTER(_i64)]
 _lib.imunpack_plan_destroy.argtypes = [_vp]
 _lib.imunpack_unpacked_bytes.argtypes = [_vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+_lib.imunpack_plan_layout.argtypes = [_vp, C.POINTER(_i64)]
 _lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
 _lib.imunpack_unpack_canonical.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.imunpack_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _i32, _vp]
@@ -232,6 +233,12 @@ class Plan:
         a, b_, w = C.c_size_t(), C.c_size_t(), C.c_size_t()
         _check(_lib.imunpack_unpacked_bytes(self._h, C.byref(a), C.byref(b_), C.byref(w)), "imunpack_unpacked_bytes")
         return a.value, b_.value, w.value
+
+    def layout(self):
+        """((rows, stored columns, row pitch in bytes) of the A store, the same of B_eu)."""
+        v = (_i64 * 6)()
+        _check(_lib.imunpack_plan_layout(self._h, v), "imunpack_plan_layout")
+        return (int(v[0]), int(v[1]), int(v[2])), (int(v[3]), int(v[4]), int(v[5]))
 
     def fusable(self) -> bool:
         return bool(_lib.imunpack_plan_fusable(self._h))

@@ -40,6 +40,7 @@ constexpr int kTile = 256;       // GEMM output tile edge in unpacked rows (both
 constexpr int kChunk = 64;       // physical rows the GEMM epilogue holds at a time; no source row straddles a chunk
 constexpr int kKPad = 128;       // every exponent group is padded to a multiple of this many columns
 constexpr int kMaxGroups = 64;   // distinct diagonal entries of S the planner supports
+constexpr int kMaxRuns = 128;    // stretches of consecutive k-tiles that read consecutive blocks of the A store
 constexpr uint32_t kNever = 0xFFFFFFFFu;  // split time of a row/column that is never split
 
 // One set of growing row (or column) slots: what Pi (or S) needs per slot, plus the split
@@ -57,12 +58,20 @@ struct SlotSet {
 struct PlanHeader {
     int32_t n_u, h_u, d1, d_u;       // n', h', columns after unpacking A, d'
     int32_t Mp, Np, Kp;              // physical (padded) sizes
+    int32_t KA;                      // stored columns of A (a multiple of 128)
+    int32_t ldA, ldB;                // bytes from one physical row to the next in the A store / in B_eu: the width
+                                     // rounded up to an odd multiple of 256, so that the rows of a tile that are
+                                     // read together spread over the memory channels
     int32_t mtiles, ntiles;
     int32_t lmaxA, lmaxB;            // largest number of digit levels of a row of A / B
     int32_t ngroups;
     int32_t grp_exp[kMaxGroups];     // exponent of s per group, descending
     int32_t grp_k0[kMaxGroups];      // first physical column
-    int32_t grp_len[kMaxGroups];     // real columns (without padding)
+    int32_t grp_len[kMaxGroups];     // columns of the group (whole k-tiles)
+    int32_t nruns;                   // k-tiles [run_kt0[i], run_kt0[i+1]) read blocks run_blk0[i], run_blk0[i]+1, ... of the A store
+    int32_t run_kt0[kMaxRuns];
+    int32_t run_blk0[kMaxRuns];
+    int32_t run_grp[kMaxRuns];       // the group the run belongs to
     int32_t edgesA, edgesB, obcount; // OB entry lists built for UnpackBoth
     int32_t nobA, nobB;              // OB entries of A / B kept for the scatter (UnpackBoth operands)
     int32_t overflow;                // bit set: which capacity was too small
@@ -70,7 +79,7 @@ struct PlanHeader {
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
     uint32_t cols_done;              // column-layout workgroups that have finished (the last one orders the units)
     int32_t extras;                  // edges that the repeated columns of B_e add to B's OB entries (UnpackBoth on B)
-    int32_t pad_;
+    int32_t pad_[3];
     unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
 };
 
@@ -91,22 +100,34 @@ struct RowLayout {
     // weighted L1 norm  sum_c s^e(c) |digit|  per physical row, in pieces: what the fix-up pass placed
     // (cleared by the planner) and one partial sum per wave of the scatter kernel
     unsigned long long *rowsum;   // [Mp]
-    unsigned long long *wavesum;  // [Mp][waves per row]
+    unsigned long long *wavesum;  // [Mp][windows per row]
 };
 
+// Columns.  B_eu is stored in full: Kp physical columns, one GEMM k-tile per 128 of them, grouped by
+// the exponent of the diagonal entry of S.  A_ue repeats column r of A_u in every column slot of the
+// second unpacking that descends from r (Alg. 2 line 6 / Alg. 4 line 13); those copies are not
+// stored.  The A store holds every column of A_u once, level by level (level 0 = the d original
+// columns in order, level a = the columns appended by a-fold splits, ordered by original column), each
+// level padded to whole blocks of 128, plus a few blocks of gathered copies for exponent groups that
+// use only a small part of a level; the GEMM reads A's k-tile t from block ktile_ablk[t] of the store.
 struct ColLayout {
-    int32_t *pcol_slot;   // [Kp] canonical column slot, -1 = padding
-    int32_t *col_phys;    // [d'] physical column of canonical slot
-    int32_t *colA_k;      // [Kp] original column k (-1 = padding)
-    int32_t *colA_c1;     // [Kp] column slot after unpacking A that this column copies
-    int32_t *colA_e;      // [Kp] its digit level along the columns of A
+    int32_t *pcol_slot;   // [Kp] column slot of the second unpacking in this column of B_eu, -1 = zero column
+    int32_t *col_phys;    // [d'] column of B_eu of every column slot of the second unpacking
+    int32_t *colB_k;      // [Kp] original column (-1 = zero column)
     int32_t *colB_e;      // [Kp] digit level along the columns of B_e
     int32_t *col_sexp;    // [Kp] exponent of the diagonal entry of S
-    int4 *unit_desc;      // [Kp/16] per 16-column unit: lowest and highest source column (-1: all padding),
-                          // bit 0 of z: 16 consecutive source columns, bit 1: one digit level pair for all
-                          // its columns; w: level along A | along B << 8 | exponent of S << 16
-    int4 *unit_sorted;    // [Kp/16] the same descriptors with the unit's index in z >> 8, the units with both
-                          // bits set first: the order in which the scatter kernel deals them to its lanes
+    int4 *unitB;          // [Kp/16] per 16-column unit: x, y = lowest and highest original column (-1: nothing to
+                          // read), z bit 0: 16 consecutive original columns, bit 1: one digit level for all of
+                          // them, bit 2: one weight for all of them; w = that level | exponent of S << 16
+    int32_t *acol_phys;   // [d'] stored column of A that every column slot of the second unpacking reads
+    int32_t *apos;        // [columns of A_u] stored column of every column slot of A's unpacking
+    int32_t *colA_k;      // [KA] original column (-1 = padding)
+    int32_t *colA_e;      // [KA] digit level along the columns of A
+    unsigned long long *colA_w;   // [KA] sum of s^e over the column slots that read this stored column (what an
+                                  // entry of it weighs in the row norm behind the accumulator bound)
+    int4 *unitA;          // [KA/16] as unitB (w = level only)
+    unsigned long long *unitA_w;  // [KA/16] the weight of the unit's columns if they share one
+    int32_t *ktile_ablk;  // [Kp/128] block of the A store that GEMM k-tile t reads
 };
 
 }  // namespace imu
@@ -149,7 +170,8 @@ struct imunpack_plan {
     int bothA, bothB;                 // slot numbering of the set needs the export-time sort
     // canonical (paper-order) numbering, built lazily by the export / test paths
     int canon_valid;
-    int32_t *canon_rowphysA, *canon_rowphysB, *canon_colphys;   // device, indexed by canonical slot
+    int32_t *canon_rowphysA, *canon_rowphysB, *canon_colphys, *canon_acolphys;   // device, indexed by canonical slot
+    int32_t *tmpApos;
     int fusable;      // set by imunpack_unpack
     int unpacked;
     int valid;

@@ -35,12 +35,15 @@ constexpr int kRing = 5;                         // LDS ring of half-stages: A(k
 constexpr int kGemmLds = kRing * kHalfBytes;     // all 160 KiB of the CU's LDS
 
 struct GemmArgs {
-    const int8_t *A, *B;      // [Mp][Kp], [Np][Kp]
-    int Kp, mtiles, ntiles;
+    const int8_t *A, *B;      // the A store [Mp][ldA] and B_eu [Np][ldB] (row pitches in bytes)
+    int ldA, ldB, Kp, mtiles, ntiles;
     int kt0, kt1;             // k-tile range of this launch
-    int nbound;               // Horner boundaries inside the range
-    int bound_kt[kMaxGroups]; // shift the accumulators after this k-tile ...
-    int bound_sh[kMaxGroups]; // ... by this many bits
+    // The range is cut into segments at the k-tiles where the exponent group changes (Horner step) or
+    // where the walk through the A store jumps: k-tile kt of segment i reads block kt + seg_delta[i].
+    int nbound;               // boundaries inside the range
+    int bound_kt[kMaxGroups]; // segment i ends with this k-tile ...
+    int bound_sh[kMaxGroups]; // ... after which the accumulators are shifted by this many bits (0: same group)
+    int seg_delta[kMaxGroups + 1];
     // fused epilogue
     RowLayout layA, layB;
     const int32_t *flatA, *flatB;   // per tile: 1 if every source row of the tile has a single level
@@ -119,27 +122,42 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // (1 KiB) per load; lane l writes slot l&7 of row l>>3, so it fetches the 16-byte chunk that
     // belongs there under the swizzle: chunk kc of row r lives at r*128 + ((kc ^ ((r >> 1) & 7)) << 4),
     // which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks) conflict-free.
-    unsigned voff[8];
+    unsigned voffA[8], voffB[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const int row = 64 * wave + 8 * u + (lane >> 3);
         const int kc = (lane & 7) ^ ((row >> 1) & 7);
-        voff[u] = (unsigned)row * (unsigned)g.Kp + (unsigned)(kc * 16);
+        voffA[u] = (unsigned)row * (unsigned)g.ldA + (unsigned)(kc * 16);
+        voffB[u] = (unsigned)row * (unsigned)g.ldB + (unsigned)(kc * 16);
     }
-    const int8_t *gA = g.A + (int64_t)m0 * g.Kp, *gB = g.B + (int64_t)n0 * g.Kp;
+    const int8_t *gA = g.A + (int64_t)m0 * g.ldA, *gB = g.B + (int64_t)n0 * g.ldB;
     // Loads past the end of the range are clamped to the last k-tile: they land in a free slot and
     // are never read, which keeps the count of outstanding loads the same in every iteration.
     const int kt0 = g.kt0, kt1 = g.kt1;
+    // The loads run two k-tiles ahead of the arithmetic and so cross into the next segment earlier: they
+    // keep a segment pointer of their own.  Lane i holds the end and the block offset of segment i, so
+    // that moving on to the next segment is two lane reads and no memory access inside the loop.
+    const int v_end = lane < g.nbound ? g.bound_kt[lane] + 1 : kt1;
+    const int v_delta = g.seg_delta[min(lane, g.nbound)];
+    int la_seg = 0, la_end = __builtin_amdgcn_readlane(v_end, 0), la_delta = __builtin_amdgcn_readlane(v_delta, 0);
     auto ring = [](int slot, int k) { slot += k; return slot >= kRing ? slot - kRing : slot; };
     const int8_t *pg = nullptr;
     unsigned dl = 0;
-    auto half_setup = [&](const int8_t *gbase, int kt, int slot) {
+    auto half_setup = [&](bool isA, int kt, int slot) {
         const int ktc = min(kt, kt1 - 1);
-        pg = uniform_ptr(gbase + (int64_t)ktc * BK);
+        int blk = ktc;
+        if (isA) {
+            // k-tiles are asked for in ascending order, one further per call: at most one segment ends
+            la_seg += ktc >= la_end ? 1 : 0;
+            la_end = __builtin_amdgcn_readlane(v_end, la_seg);
+            la_delta = __builtin_amdgcn_readlane(v_delta, la_seg);
+            blk = ktc + la_delta;
+        }
+        pg = uniform_ptr((isA ? gA : gB) + (int64_t)blk * BK);
         dl = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(slot * kHalfBytes) + (unsigned)(wave * 8192));
     };
-    auto dma_one = [&](int u) {  // u = 0..7: rows [64 wave + 8u, +8) of the half-stage set up last
-        dma16(dl + u * 1024, voff[u], pg);
+    auto dma_one = [&](bool isA, int u) {  // u = 0..7: rows [64 wave + 8u, +8) of the half-stage set up last
+        dma16(dl + u * 1024, isA ? voffA[u] : voffB[u], pg);
     };
 
     // ---- LDS -> registers: operand fragments of v_mfma_i32_32x32x32_i8 (lane: row lane%32, 16 K-bytes
@@ -174,13 +192,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // One step = 16 MFMAs on the fragments in buffer `cur`, interleaved with the 8 fragment loads of
     // the next k-step into the other buffer and with `ndma` direct-to-LDS loads (starting at block
     // `dma0`) of the half-stage set up last.
-    auto step = [&](int cur, const int8_t *sta, const int8_t *stb, int next_ks, int dma0, int ndma) {
+    auto step = [&](int cur, const int8_t *sta, const int8_t *stb, int next_ks, bool isA, int dma0, int ndma) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             load_frag(sta, stb, next_ks, cur ^ 1, q);
             acc[mi[2 * q]][mj[2 * q]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                 fa[cur][mi[2 * q]], fb[cur][mj[2 * q]], acc[mi[2 * q]][mj[2 * q]], 0, 0, 0);
-            if (q < ndma) dma_one(dma0 + q);
+            if (q < ndma) dma_one(isA, dma0 + q);
             acc[mi[2 * q + 1]][mj[2 * q + 1]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                 fa[cur][mi[2 * q + 1]], fb[cur][mj[2 * q + 1]], acc[mi[2 * q + 1]][mj[2 * q + 1]], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -195,18 +213,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     }
     // ---- prologue: k-tile kt0 landed, k-tile kt0+1 in flight, first fragments loaded
     int sa = 0;  // ring slot of A(kt); B(kt) is sa+1, A(kt+1) sa+2, B(kt+1) sa+3, A(kt+2) sa+4, B(kt+2) sa
-    half_setup(gA, kt0, 0);
+    half_setup(true, kt0, 0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(u);
-    half_setup(gB, kt0, 1);
+    for (int u = 0; u < 8; ++u) dma_one(true, u);
+    half_setup(false, kt0, 1);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(u);
-    half_setup(gA, kt0 + 1, 2);
+    for (int u = 0; u < 8; ++u) dma_one(false, u);
+    half_setup(true, kt0 + 1, 2);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(u);
-    half_setup(gB, kt0 + 1, 3);
+    for (int u = 0; u < 8; ++u) dma_one(true, u);
+    half_setup(false, kt0 + 1, 3);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(u);
+    for (int u = 0; u < 8; ++u) dma_one(false, u);
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -220,7 +238,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // kt+1 and stream B(kt+2) into the slot of A(kt).
     int kt = kt0;
     for (int seg = 0; seg <= g.nbound; ++seg) {
-        if (seg > 0) {  // start of the next exponent group: Horner step
+        if (seg > 0 && g.bound_sh[seg - 1] != 0) {  // start of the next exponent group: Horner step
             // The accumulators fill the whole accumulation register file (a0..a255), so shifting every
             // one of those registers shifts every accumulator, whichever block sits where.  Written
             // out by hand: left to the compiler, this step spills three blocks to scratch memory.
@@ -253,17 +271,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
         for (; kt < kend; ++kt) {
             const int8_t *stA = smem + sa * kHalfBytes, *stB = smem + ring(sa, 1) * kHalfBytes;
             const int8_t *stA1 = smem + ring(sa, 2) * kHalfBytes, *stB1 = smem + ring(sa, 3) * kHalfBytes;
-            half_setup(gA, kt + 2, ring(sa, 4));
+            half_setup(true, kt + 2, ring(sa, 4));
             __builtin_amdgcn_sched_barrier(0);
-            step(0, stA, stB, 1, 0, 3);
-            step(1, stA, stB, 2, 3, 3);
-            step(0, stA, stB, 3, 6, 2);
+            step(0, stA, stB, 1, true, 0, 3);
+            step(1, stA, stB, 2, true, 3, 3);
+            step(0, stA, stB, 3, true, 6, 2);
             asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            half_setup(gB, kt + 2, sa);
+            half_setup(false, kt + 2, sa);
             __builtin_amdgcn_sched_barrier(0);
-            step(1, stA1, stB1, 0, 0, 8);
+            step(1, stA1, stB1, 0, false, 0, 8);
             sa = ring(sa, 2);
         }
     }
@@ -652,17 +670,22 @@ extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = A_ue; g.B = B_eu;
-    g.Kp = h.Kp; g.mtiles = h.mtiles; g.ntiles = h.ntiles;
+    g.ldA = h.ldA; g.ldB = h.ldB; g.Kp = h.Kp; g.mtiles = h.mtiles; g.ntiles = h.ntiles;
     g.layA = p->layA; g.layB = p->layB;
     g.flatA = p->layA.tile_flat; g.flatB = p->layB.tile_flat;
     g.sh = p->sh;
     g.Np = h.Np;
     const int grid = h.mtiles * h.ntiles;
     bool fused = fuse != 0;
+    const bool too_many_runs = h.nruns > 63;  // more segments than the lanes of a wave can hold the tables of
     // The bounds of the last imunpack_unpack may still be on their way to the host.  If the fused
     // launch was exact for this plan object the last time, it goes out now with a guard (the kernel
     // checks the bounds on the device and writes nothing if they are too large), and only then does
     // the host wait: the GPU does not idle while the answer travels.
+    if (fused && too_many_runs) {
+        if (!workspace) return IMUNPACK_ERANGE;
+        fused = false;
+    }
     const bool speculate = fused && p->bound_pending && p->guess_fusable;
     if (!speculate) {
         IMU_TRY(resolve_bound(p));
@@ -677,10 +700,13 @@ extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_
         g.guard_mul = p->s - 1;
         g.kt0 = 0; g.kt1 = h.Kp / BK;
         g.nbound = 0;
-        for (int q = 0; q + 1 < h.ngroups; ++q) {
-            g.bound_kt[g.nbound] = h.grp_k0[q + 1] / BK - 1;
-            g.bound_sh[g.nbound] = p->sh * (h.grp_exp[q] - h.grp_exp[q + 1]);
-            ++g.nbound;
+        for (int r = 0; r < h.nruns; ++r) {
+            g.seg_delta[r] = h.run_blk0[r] - h.run_kt0[r];
+            if (r + 1 < h.nruns) {
+                g.bound_kt[g.nbound] = h.run_kt0[r + 1] - 1;
+                g.bound_sh[g.nbound] = p->sh * (h.grp_exp[h.run_grp[r]] - h.grp_exp[h.run_grp[r + 1]]);
+                ++g.nbound;
+            }
         }
         g.final_shift = h.ngroups ? p->sh * h.grp_exp[h.ngroups - 1] : 0;
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
@@ -698,12 +724,13 @@ extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_
     }
     if (!workspace) return IMUNPACK_EINVAL;
     g.C_u = (int64_t *)workspace;
-    for (int q = 0; q < h.ngroups; ++q) {
-        g.kt0 = h.grp_k0[q] / BK;
-        g.kt1 = g.kt0 + (h.grp_len[q] + BK - 1) / BK;
+    for (int r = 0; r < h.nruns; ++r) {  // one launch per stretch of consecutive blocks of the A store
+        g.kt0 = h.run_kt0[r];
+        g.kt1 = r + 1 < h.nruns ? h.run_kt0[r + 1] : h.Kp / BK;
         g.nbound = 0;
-        g.seg_shift = p->sh * h.grp_exp[q];
-        g.seg_first = q == 0;
+        g.seg_delta[0] = h.run_blk0[r] - h.run_kt0[r];
+        g.seg_shift = p->sh * h.grp_exp[h.run_grp[r]];
+        g.seg_first = r == 0;
         hipLaunchKernelGGL(gemm_i8_kernel<1>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
     }
     IMU_TRY(launch_status());

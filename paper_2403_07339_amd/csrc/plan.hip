@@ -150,7 +150,8 @@ __device__ __forceinline__ void identity_slot(const SlotSet &set, int x) {
 // Clears the header and makes the first na / nb / nc slots of three sets unsplit originals (a count
 // of 0 skips a set).  The counts are known to the host, which has sized the sets for them.
 __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_a, SlotSet b, int nb,
-                             int32_t *count_b, SlotSet c, int nc, int32_t *count_c, int32_t *zeroed, int nzeroed) {
+                             int32_t *count_b, SlotSet c, int nc, int32_t *count_c, int32_t *zeroed, int nzeroed,
+                             int32_t *zeroed2, int nzeroed2) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         static_assert(sizeof(PlanHeader) % sizeof(int32_t) == 0, "header is cleared word by word");
         for (size_t i = 0; i < sizeof(PlanHeader) / sizeof(int32_t); ++i) reinterpret_cast<int32_t *>(hdr)[i] = 0;
@@ -163,6 +164,7 @@ __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nb; x += stride) identity_slot(b, x);
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nc; x += stride) identity_slot(c, x);
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nzeroed; x += stride) zeroed[x] = 0;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < nzeroed2; x += stride) zeroed2[x] = 0;
 }
 
 // slots 0..N-1 become unsplit originals, N read from the device
@@ -692,30 +694,83 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
     }
 }
 
-// Columns: grouped by the exponent of the diagonal entry of S (Alg. 3 runs one GEMM per distinct
-// entry), highest exponent first, each group zero-padded to a multiple of kKPad.  Inside a group the
-// columns are ordered by the original column k they copy (ties: by the digit level along A's
-// unpacking), so that a run of physical columns reads a run of source columns.  A column slot c of
-// the second unpacking descends from slot r = c2.root[c] of the first, which descends from original
-// column k = c1.root[r]; its exponent is c1.exp[r] + c2.exp[c].
-// Also written: a descriptor per 16-column unit, which lets the scatter kernel pick its path without
-// the per-column arrays.
-constexpr int kColBlocks = 8;  // workgroups that share the column layout, one exponent group at a time each
+// Columns.  B_eu is laid out group by group (Alg. 3 runs one GEMM per distinct diagonal entry of S),
+// highest exponent first, in whole k-tiles of kKPad columns.  A column slot c of the second unpacking
+// descends from slot r = c2.root[c] of the first, which descends from original column k = c1.root[r];
+// it holds digit level eB = c2.exp[c] of column r of B_e, its exponent is e = eA + eB with
+// eA = c1.exp[r], and the column of A_ue beside it is a copy of column r of A_u.
+// The A store holds A_u once: level a (the slots with eA = a) in ascending original column, padded to
+// whole k-tiles; level 0 is the d original columns in place.  Inside group e the slots with eA = a
+// form a subset of level a.  If that subset is (nearly) all of the level, the group walks the level's
+// stored k-tiles as they are and B_eu gets a zero column where the level has a column the group has
+// not ("shared": nothing of A is copied); otherwise the subset's columns are gathered, ordered by
+// (original column, eA), into k-tiles of their own at the end of the group, and the columns of A they
+// need are stored once more in extra blocks behind the levels ("gathered").
+constexpr int kColBlocks = 8;    // workgroups that share the column layout, one exponent group at a time each
+constexpr int kMaxLevelsA = 16;  // digit levels along the columns of A that the layout supports
+
+__device__ __forceinline__ unsigned long long weight_of(int e, int sh) {  // s^e, saturating at 2^44
+    const int bits = e * sh;
+    return bits >= 44 ? (1ull << 44) : (1ull << bits);
+}
 
 __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayout &cols, int d, int cap_phys,
                             int s, int sh, int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOffAll,
                             PlanHeader *hdr, int *lds, int part) {
-    __shared__ int hist[kMaxGroups];
-    __shared__ int s_gexp[kMaxGroups], s_gk0[kMaxGroups];
-    __shared__ int s_ng, s_kp, s_bad;
-    const int D = hdr->d_u;
+    __shared__ int hist2[kMaxGroups * kMaxLevelsA];          // column slots per (exponent e, level a of A)
+    __shared__ int cntA[kMaxLevelsA], lvlbase[kMaxLevelsA + 1];  // columns per level of A; first stored column
+    __shared__ int kbase[kMaxGroups * kMaxLevelsA];          // first column of B_eu of a shared (e, a), -1: gathered
+    __shared__ int s_gk0[kMaxGroups], s_gext[kMaxGroups], s_cbase[kMaxGroups], s_xbase[kMaxGroups], s_ccount[kMaxGroups];
+    __shared__ int s_kp, s_ka, s_ka_levels, s_bad, s_la;
+    const int D = hdr->d_u, D1 = hdr->d1;
     int32_t *tmpOff = tmpOffAll + (size_t)part * (d + 1);
-    for (int e = threadIdx.x; e < kMaxGroups; e += kPlanThreads) hist[e] = 0;
+    for (int t = threadIdx.x; t < kMaxGroups * kMaxLevelsA; t += kPlanThreads) hist2[t] = 0;
+    if (threadIdx.x < kMaxLevelsA) cntA[threadIdx.x] = 0;
     if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
-    // every part computes the same per-slot values and the same group table (the stores of the
-    // parts coincide); a part then lays out the groups part, part + kColBlocks, ...
-    constexpr int V = 8;  // column slots per thread and step, loaded side by side
+    // every part computes the same per-slot values and the same tables (the stores of the parts
+    // coincide); a part then lays out the groups part, part + kColBlocks, ...
+    constexpr int V = 8;  // slots per thread and step, loaded side by side
+    // ---- levels of A
+    for (int r0 = threadIdx.x; r0 < D1; r0 += kPlanThreads * V) {
+        int a[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) a[u] = r0 + u * kPlanThreads < D1 ? c1.exp[r0 + u * kPlanThreads] : -1;
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            if (a[u] < 0) continue;
+            if (a[u] < kMaxLevelsA) atomicAdd(&cntA[a[u]], 1);
+            else s_bad = 1;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0, la = 1;
+        for (int a = 0; a < kMaxLevelsA; ++a) {
+            lvlbase[a] = run;
+            run += (cntA[a] + kKPad - 1) / kKPad * kKPad;
+            if (cntA[a]) la = a + 1;
+        }
+        lvlbase[kMaxLevelsA] = run;
+        s_ka_levels = run;
+        s_la = la;
+    }
+    __syncthreads();
+    const int la = s_la;
+    // ---- stored column of every column slot of A's unpacking: level 0 in place, level a >= 1 by rank
+    // among the original columns whose chain reaches that level
+    for (int k = threadIdx.x; k < d; k += kPlanThreads) cols.apos[k] = k;
+    for (int a = 1; a < la; ++a) {
+        auto slot_at = [&](int k) {
+            int r = k;
+            for (int i = 0; i < a && r >= 0; ++i) r = c1.child[r];
+            return r;
+        };
+        ordered_select(
+            d, lvlbase[a], [&](int k) { return slot_at(k) >= 0; },
+            [&](int k, int pos) { cols.apos[slot_at(k)] = pos; }, lds);
+    }
+    // ---- per column slot of the second unpacking: exponent, levels, original column
     for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
         int r[V], eb[V], ea[V], k[V];
 #pragma unroll
@@ -737,8 +792,8 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             tmpE[c] = e | (ea[u] << 8) | (eb[u] << 16);
             tmpK[c] = k[u];
             tmpR[c] = r[u];
-            if (e < kMaxGroups && ea[u] < 256 && eb[u] < 256) {
-                atomicAdd(&hist[e], 1);
+            if (e < kMaxGroups && ea[u] < kMaxLevelsA && eb[u] < 256) {
+                atomicAdd(&hist2[e * kMaxLevelsA + ea[u]], 1);
             } else {
                 atomicMin(&hdr->err, IMUNPACK_ERANGE);
                 s_bad = 1;
@@ -746,62 +801,132 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int ng = 0, k0 = 0;
-        const long long lim = 2147483647ll / ((long long)(s - 1) * (s - 1));
-        for (int e = kMaxGroups - 1; e >= 0; --e) {
-            if (!hist[e]) continue;
-            if (e * sh > 62 || hist[e] > lim) atomicMin(&hdr->err, IMUNPACK_ERANGE);
-            s_gexp[ng] = e;
-            s_gk0[ng] = k0;
-            if (part == 0) {
-                hdr->grp_exp[ng] = e;
-                hdr->grp_k0[ng] = k0;
-                hdr->grp_len[ng] = hist[e];
-            }
-            k0 += (hist[e] + kKPad - 1) / kKPad * kKPad;
-            ++ng;
+    // ---- the k-tiles of every group: lane e of the first wave takes exponent e
+    if (threadIdx.x < 64) {
+        const int e = threadIdx.x;
+        int tiles_sh = 0, ccount = 0, members = 0;
+        for (int a = 0; a < kMaxLevelsA; ++a) {
+            const int m = hist2[e * kMaxLevelsA + a];
+            members += m;
+            const bool shared = m > 0 && (long long)m * 8 >= (long long)cntA[a] * 7;
+            kbase[e * kMaxLevelsA + a] = shared ? tiles_sh * kKPad : -1;  // relative to the group's start for now
+            if (shared) tiles_sh += (cntA[a] + kKPad - 1) / kKPad;
+            else ccount += m;
         }
+        const int tiles_c = (ccount + kKPad - 1) / kKPad;
+        const int tiles = tiles_sh + tiles_c;
+        int nrun = tiles_c > 0 ? 1 : 0;  // stretches of k-tiles that walk consecutive blocks of the A store
+        for (int a = 0; a < kMaxLevelsA; ++a)
+            if (kbase[e * kMaxLevelsA + a] >= 0) ++nrun;
+        // groups come highest exponent first: sums over the lanes above this one
+        int above = tiles, above_c = tiles_c, above_n = members > 0 ? 1 : 0, above_r = nrun;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t0 = __shfl_down(above, off, 64), t1 = __shfl_down(above_c, off, 64), t2 = __shfl_down(above_n, off, 64),
+                      t3 = __shfl_down(above_r, off, 64);
+            if (e + off < 64) { above += t0; above_c += t1; above_n += t2; above_r += t3; }
+        }
+        const int k0 = (above - tiles) * kKPad, xb = above_c - tiles_c, g = above_n - (members > 0 ? 1 : 0);
         if (part == 0) {
-            hdr->ngroups = ng;
-            hdr->Kp = k0;
-            if (k0 > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
+            int ri = above_r - nrun;
+            for (int a = 0; a < kMaxLevelsA; ++a) {
+                const int kb = kbase[e * kMaxLevelsA + a];
+                if (kb < 0) continue;
+                if (ri < kMaxRuns) {
+                    hdr->run_kt0[ri] = (k0 + kb) / kKPad;
+                    hdr->run_blk0[ri] = lvlbase[a] / kKPad;
+                    hdr->run_grp[ri] = g;
+                }
+                ++ri;
+            }
+            if (tiles_c > 0 && ri < kMaxRuns) {
+                hdr->run_kt0[ri] = k0 / kKPad + tiles_sh;
+                hdr->run_blk0[ri] = s_ka_levels / kKPad + xb;
+                hdr->run_grp[ri] = g;
+            }
+            const int total_r = __shfl(above_r, 0, 64);
+            if (e == 0) {
+                hdr->nruns = total_r;
+                if (total_r > kMaxRuns) atomicMin(&hdr->err, IMUNPACK_ERANGE);
+            }
         }
-        s_ng = ng;
-        s_kp = k0;
+        for (int a = 0; a < kMaxLevelsA; ++a)
+            if (kbase[e * kMaxLevelsA + a] >= 0) kbase[e * kMaxLevelsA + a] += k0;
+        s_cbase[e] = k0 + tiles_sh * kKPad;
+        s_xbase[e] = xb;
+        s_ccount[e] = ccount;
+        s_gk0[e] = k0;
+        s_gext[e] = tiles * kKPad;
+        const int total_tiles = __shfl(above, 0, 64), total_c = __shfl(above_c, 0, 64), ngroups = __shfl(above_n, 0, 64);
+        if (e == 0) {
+            s_kp = total_tiles * kKPad;
+            s_ka = s_ka_levels + total_c * kKPad;
+        }
+        if (members > 0) {
+            const long long lim = 2147483647ll / ((long long)(s - 1) * (s - 1));
+            if (e * sh > 62 || tiles * kKPad > lim) atomicMin(&hdr->err, IMUNPACK_ERANGE);
+            if (part == 0) {
+                hdr->grp_exp[g] = e;
+                hdr->grp_k0[g] = k0;
+                hdr->grp_len[g] = tiles * kKPad;
+            }
+        }
+        if (part == 0 && e == 0) {
+            hdr->ngroups = ngroups;
+            hdr->Kp = total_tiles * kKPad;
+            hdr->KA = s_ka_levels + total_c * kKPad;
+            hdr->ldA = (((s_ka_levels + total_c * kKPad + 255) / 256) | 1) * 256;
+            hdr->ldB = (((total_tiles * kKPad + 255) / 256) | 1) * 256;
+            if (total_tiles * kKPad > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
+        }
     }
     __syncthreads();
-    const int ng = s_ng, Kp = s_kp;
+    const int Kp = s_kp, KA = s_ka, ka_levels = s_ka_levels;
     if (Kp > cap_phys || s_bad) return;
-    for (int g = part; g < ng; g += kColBlocks) {
-        const int ge = s_gexp[g], q0 = s_gk0[g], q1 = g + 1 < ng ? s_gk0[g + 1] : Kp;
+    // ---- the stored levels of A (first part)
+    if (part == 0) {
+        for (int q = threadIdx.x; q < ka_levels; q += kPlanThreads) {
+            cols.colA_k[q] = -1;
+            cols.colA_e[q] = 0;
+        }
+        __syncthreads();
+        for (int r = threadIdx.x; r < D1; r += kPlanThreads) {
+            const int q = cols.apos[r];
+            cols.colA_k[q] = c1.root[r];
+            cols.colA_e[q] = c1.exp[r];
+        }
+    }
+    for (int e = kMaxGroups - 1 - part; e >= 0; e -= kColBlocks) {  // any fixed assignment of groups to parts will do
+        const int q0 = s_gk0[e], q1 = q0 + s_gext[e];
+        if (q1 == q0) continue;  // uniform
         for (int q = q0 + threadIdx.x; q < q1; q += kPlanThreads) {
             cols.pcol_slot[q] = -1;
-            cols.colA_k[q] = -1;
-            cols.colA_c1[q] = 0;
-            cols.colA_e[q] = 0;
+            cols.colB_k[q] = -1;
             cols.colB_e[q] = 0;
-            cols.col_sexp[q] = 0;
+            cols.col_sexp[q] = e;
         }
-        for (int k = threadIdx.x; k < d; k += kPlanThreads) tmpOff[k] = 0;
-        __syncthreads();
-        for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
-            int pe[V], k[V];
-#pragma unroll
-            for (int u = 0; u < V; ++u) {
-                const int c = c0 + u * kPlanThreads;
-                pe[u] = c < D ? tmpE[c] : -1;
-                k[u] = c < D ? tmpK[c] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < V; ++u)
-                if (pe[u] >= 0 && (pe[u] & 0xFF) == ge) atomicAdd(&tmpOff[k[u]], 1);
+        // k-tile table: shared levels walk their stored blocks, gathered k-tiles get blocks of their own
+        for (int a = 0; a < kMaxLevelsA; ++a) {
+            const int kb = kbase[e * kMaxLevelsA + a];
+            if (kb < 0) continue;
+            const int nt = (cntA[a] + kKPad - 1) / kKPad;
+            for (int j = threadIdx.x; j < nt; j += kPlanThreads) cols.ktile_ablk[kb / kKPad + j] = lvlbase[a] / kKPad + j;
         }
+        const int cbase = s_cbase[e], ccount = s_ccount[e], xcol0 = ka_levels + s_xbase[e] * kKPad;
+        const int ctiles = (ccount + kKPad - 1) / kKPad;
+        for (int j = threadIdx.x; j < ctiles; j += kPlanThreads) cols.ktile_ablk[cbase / kKPad + j] = xcol0 / kKPad + j;
+        for (int q = threadIdx.x; q < ctiles * kKPad; q += kPlanThreads) {
+            cols.colA_k[xcol0 + q] = -1;
+            cols.colA_e[xcol0 + q] = 0;
+            cols.colA_w[xcol0 + q] = 0;
+        }
+        if (ccount > 0)
+            for (int k = threadIdx.x; k < d; k += kPlanThreads) tmpOff[k] = 0;
         __syncthreads();
-        ordered_scan(
-            d, q0, [&](int k) { return tmpOff[k]; }, [&](int k, int pre) { tmpOff[k] = pre; }, lds);
+        const unsigned long long w = weight_of(e, sh);
+        // shared members go where their column of A is stored; gathered ones are counted per original column
         for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
-            int pe[V], k[V], rr[V], q[V];
+            int pe[V], k[V], rr[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 const int c = c0 + u * kPlanThreads;
@@ -811,72 +936,102 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             }
 #pragma unroll
             for (int u = 0; u < V; ++u) {
-                if (pe[u] < 0 || (pe[u] & 0xFF) != ge) pe[u] = -1;
-                q[u] = pe[u] >= 0 ? atomicAdd(&tmpOff[k[u]], 1) : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < V; ++u) {
-                if (pe[u] < 0) continue;
-                cols.pcol_slot[q[u]] = c0 + u * kPlanThreads;
-                cols.colA_k[q[u]] = k[u];
-                cols.colA_c1[q[u]] = rr[u];
-                cols.colA_e[q[u]] = (pe[u] >> 8) & 0xFF;
-                cols.colB_e[q[u]] = (pe[u] >> 16) & 0xFF;
-                cols.col_sexp[q[u]] = ge;
-            }
-        }
-        __syncthreads();
-        // columns of one group that copy the same source column: order them by their level along A
-        for (int k = threadIdx.x; k < d; k += kPlanThreads) {
-            const int end = tmpOff[k], beg = k ? tmpOff[k - 1] : q0;
-            for (int i = beg + 1; i < end; ++i) {
-                const int slot = cols.pcol_slot[i], c1s = cols.colA_c1[i], ea = cols.colA_e[i], eb = cols.colB_e[i];
-                int j = i - 1;
-                while (j >= beg && cols.colA_e[j] > ea) {
-                    cols.pcol_slot[j + 1] = cols.pcol_slot[j];
-                    cols.colA_c1[j + 1] = cols.colA_c1[j];
-                    cols.colA_e[j + 1] = cols.colA_e[j];
-                    cols.colB_e[j + 1] = cols.colB_e[j];
-                    --j;
+                if (pe[u] < 0 || (pe[u] & 0xFF) != e) continue;
+                const int a = (pe[u] >> 8) & 0xFF, kb = kbase[e * kMaxLevelsA + a];
+                if (kb < 0) {
+                    atomicAdd(&tmpOff[k[u]], 1);
+                    continue;
                 }
-                cols.pcol_slot[j + 1] = slot;
-                cols.colA_c1[j + 1] = c1s;
-                cols.colA_e[j + 1] = ea;
-                cols.colB_e[j + 1] = eb;
+                const int c = c0 + u * kPlanThreads, qa = cols.apos[rr[u]], q = kb + (qa - lvlbase[a]);
+                cols.pcol_slot[q] = c;
+                cols.colB_k[q] = k[u];
+                cols.colB_e[q] = (pe[u] >> 16) & 0xFF;
+                cols.col_phys[c] = q;
+                cols.acol_phys[c] = qa;
+                atomicAdd(&cols.colA_w[qa], w);
+            }
+        }
+        if (ccount > 0) {  // uniform
+            __syncthreads();
+            ordered_scan(
+                d, cbase, [&](int k) { return tmpOff[k]; }, [&](int k, int pre) { tmpOff[k] = pre; }, lds);
+            for (int c0 = threadIdx.x; c0 < D; c0 += kPlanThreads * V) {
+                int pe[V], k[V], q[V];
+#pragma unroll
+                for (int u = 0; u < V; ++u) {
+                    const int c = c0 + u * kPlanThreads;
+                    pe[u] = c < D ? tmpE[c] : -1;
+                    k[u] = c < D ? tmpK[c] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < V; ++u) {
+                    if (pe[u] < 0 || (pe[u] & 0xFF) != e || kbase[e * kMaxLevelsA + ((pe[u] >> 8) & 0xFF)] >= 0) pe[u] = -1;
+                    q[u] = pe[u] >= 0 ? atomicAdd(&tmpOff[k[u]], 1) : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < V; ++u) {
+                    if (pe[u] < 0) continue;
+                    cols.pcol_slot[q[u]] = c0 + u * kPlanThreads;
+                    cols.colB_k[q[u]] = k[u];
+                    cols.colB_e[q[u]] = (pe[u] >> 16) & 0xFF;
+                    cols.colA_e[xcol0 + (q[u] - cbase)] = (pe[u] >> 8) & 0xFF;
+                }
+            }
+            __syncthreads();
+            // gathered columns of one group that copy the same original column: order them by their level along A
+            for (int k = threadIdx.x; k < d; k += kPlanThreads) {
+                const int end = tmpOff[k], beg = k ? tmpOff[k - 1] : cbase;
+                for (int i = beg + 1; i < end; ++i) {
+                    const int slot = cols.pcol_slot[i], ea = cols.colA_e[xcol0 + (i - cbase)], eb = cols.colB_e[i];
+                    int j = i - 1;
+                    while (j >= beg && cols.colA_e[xcol0 + (j - cbase)] > ea) {
+                        cols.pcol_slot[j + 1] = cols.pcol_slot[j];
+                        cols.colA_e[xcol0 + (j + 1 - cbase)] = cols.colA_e[xcol0 + (j - cbase)];
+                        cols.colB_e[j + 1] = cols.colB_e[j];
+                        --j;
+                    }
+                    cols.pcol_slot[j + 1] = slot;
+                    cols.colA_e[xcol0 + (j + 1 - cbase)] = ea;
+                    cols.colB_e[j + 1] = eb;
+                }
+            }
+            __syncthreads();
+            for (int q = cbase + threadIdx.x; q < cbase + ccount; q += kPlanThreads) {
+                const int c = cols.pcol_slot[q], qa = xcol0 + (q - cbase);
+                cols.col_phys[c] = q;
+                cols.acol_phys[c] = qa;
+                cols.colA_k[qa] = cols.colB_k[q];
+                cols.colA_w[qa] = w;
             }
         }
         __syncthreads();
-        for (int q = q0 + threadIdx.x; q < q1; q += kPlanThreads) {
-            const int c = cols.pcol_slot[q];
-            if (c >= 0) cols.col_phys[c] = q;
-        }
-        // per 16-column unit: what the scatter kernel needs to pick its path without the per-column arrays
+        // per 16-column unit of B_eu: what the scatter kernel needs to pick its path without the per-column arrays
         for (int u = q0 / 16 + threadIdx.x; u < q1 / 16; u += kPlanThreads) {
             const int qq = 16 * u;
-            const int k0 = cols.colA_k[qq], ea0 = cols.colA_e[qq], eb0 = cols.colB_e[qq];
-            int kmin = 0x7fffffff, kmax = -1;
+            const int k0 = cols.colB_k[qq];
+            int kmin = 0x7fffffff, kmax = -1, efirst = -1;
             bool run = k0 >= 0, uniform = true;
             for (int j = 0; j < 16; ++j) {
-                const int k = cols.colA_k[qq + j];
+                const int k = cols.colB_k[qq + j];
                 run = run && k == k0 + j;
-                if (k >= 0) {
-                    kmin = min(kmin, k);
-                    kmax = max(kmax, k);
-                    uniform = uniform && cols.colA_e[qq + j] == ea0 && cols.colB_e[qq + j] == eb0;
-                }
+                if (k < 0) continue;
+                kmin = min(kmin, k);
+                kmax = max(kmax, k);
+                const int eb = cols.colB_e[qq + j];
+                if (efirst < 0) efirst = eb;
+                else uniform = uniform && eb == efirst;  // one level for all real columns
             }
             int4 ud;
             ud.x = kmax < 0 ? -1 : kmin;
             ud.y = kmax;
-            ud.z = (run ? 1 : 0) | (uniform ? 2 : 0);
-            ud.w = (ea0 & 0xFF) | ((eb0 & 0xFF) << 8) | ((ge & 0xFF) << 16);
-            cols.unit_desc[u] = ud;
+            ud.z = (run ? 1 : 0) | (uniform ? 2 : 0) | 4;
+            ud.w = (max(efirst, 0) & 0xFF) | ((e & 0xFF) << 16);
+            cols.unitB[u] = ud;
         }
         __syncthreads();
     }
-    // The workgroup that finishes last deals the units out: those that copy 16 consecutive source
-    // columns at one digit level first (in order), the others behind them, so that the lanes of a
-    // wave of the scatter kernel nearly always take the same path.
+    // The workgroup that finishes last describes the units of the A store: every part has added its
+    // weights by then.
     __shared__ int s_last;
     __threadfence();
     __syncthreads();
@@ -884,37 +1039,33 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
     __syncthreads();
     if (!s_last) return;
     __threadfence();  // what the other workgroups wrote before their increment is visible past this fence
-    // every wave owns a contiguous segment of the units: count its fast ones, then place all of them
-    const int nunits = Kp / 16;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int useg = ((nunits + kPlanWaves - 1) / kPlanWaves + 63) & ~63;
-    const int ulo = wave * useg, uhi = min(nunits, ulo + useg);
-    int cnt = 0;
-    for (int u0 = ulo; u0 < uhi; u0 += 64) {
-        const int u = u0 + lane;
-        cnt += __popcll(__ballot(u < uhi && (cols.unit_desc[u].z & 3) == 3));
-    }
-    if (lane == 0) lds[wave] = cnt;
-    __syncthreads();
-    int before = 0, nfast = 0;
-#pragma unroll
-    for (int w = 0; w < kPlanWaves; ++w) {
-        const int c = lds[w];
-        if (w < wave) before += c;
-        nfast += c;
-    }
-    const unsigned long long below = (1ull << lane) - 1ull;
-    for (int u0 = ulo; u0 < uhi; u0 += 64) {
-        const int u = u0 + lane;
-        int4 ud = u < uhi ? cols.unit_desc[u] : make_int4(0, 0, 0, 0);
-        const bool f = u < uhi && (ud.z & 3) == 3;
-        const unsigned long long m = __ballot(f);
-        const int fast_before = before + __popcll(m & below);  // fast units in front of u
-        if (u < uhi) {
-            ud.z = (ud.z & 3) | (u << 8);
-            cols.unit_sorted[f ? fast_before : nfast + (u - fast_before)] = ud;
+    for (int u = threadIdx.x; u < KA / 16; u += kPlanThreads) {
+        const int qq = 16 * u;
+        int kmin = 0x7fffffff, kmax = -1, efirst = -1, kfirst = -1, jfirst = 0;
+        unsigned long long wfirst = 0;
+        bool run = true, uniform = true, onew = true;
+        for (int j = 0; j < 16; ++j) {
+            const int k = __hip_atomic_load(&cols.colA_k[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (k < 0) {
+                run = false;
+                continue;
+            }
+            const int ea = __hip_atomic_load(&cols.colA_e[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long w = __hip_atomic_load(&cols.colA_w[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (efirst < 0) { efirst = ea; kfirst = k; jfirst = j; wfirst = w; }
+            run = run && k == kfirst + (j - jfirst) && jfirst == 0;
+            uniform = uniform && ea == efirst;
+            onew = onew && w == wfirst;
+            kmin = min(kmin, k);
+            kmax = max(kmax, k);
         }
-        before += __popcll(m);
+        int4 ud;
+        ud.x = kmax < 0 ? -1 : kmin;
+        ud.y = kmax;
+        ud.z = (run && kmax >= 0 ? 1 : 0) | (uniform ? 2 : 0) | (onew ? 4 : 0);
+        ud.w = max(efirst, 0) & 0xFF;
+        cols.unitA[u] = ud;
+        cols.unitA_w[u] = wfirst < (1ull << 44) ? wfirst : (1ull << 44);
     }
 }
 
@@ -1018,19 +1169,24 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         l.chunk_src0 = cv.take<int32_t>(pc / kChunk + 8);
         l.tile_flat = cv.take<int32_t>(pc / kTile + 2);
         l.rowsum = cv.take<unsigned long long>(pc);
-        l.wavesum = cv.take<unsigned long long>((size_t)pc * ((phys_cap_cols(p->cap[CAP_C2]) / 16 + 63) / 64));
+        l.wavesum = cv.take<unsigned long long>((size_t)pc * ((phys_cap_cols(p->cap[CAP_C2]) + 1023) / 1024));
     }
     {
         const int kc = phys_cap_cols(p->cap[CAP_C2]);
         p->cols.pcol_slot = cv.take<int32_t>(kc);
         p->cols.col_phys = cv.take<int32_t>(p->cap[CAP_C2]);
-        p->cols.colA_k = cv.take<int32_t>(kc);
-        p->cols.colA_c1 = cv.take<int32_t>(kc);
-        p->cols.colA_e = cv.take<int32_t>(kc);
+        p->cols.colB_k = cv.take<int32_t>(kc);
         p->cols.colB_e = cv.take<int32_t>(kc);
         p->cols.col_sexp = cv.take<int32_t>(kc);
-        p->cols.unit_desc = cv.take<int4>(kc / 16 + 1);
-        p->cols.unit_sorted = cv.take<int4>(kc / 16 + 1);
+        p->cols.unitB = cv.take<int4>(kc / 16 + 1);
+        p->cols.acol_phys = cv.take<int32_t>(p->cap[CAP_C2]);
+        p->cols.apos = cv.take<int32_t>(p->cap[CAP_C1]);
+        p->cols.colA_k = cv.take<int32_t>(kc);
+        p->cols.colA_e = cv.take<int32_t>(kc);
+        p->cols.colA_w = cv.take<unsigned long long>(kc);
+        p->cols.unitA = cv.take<int4>(kc / 16 + 1);
+        p->cols.unitA_w = cv.take<unsigned long long>(kc / 16 + 1);
+        p->cols.ktile_ablk = cv.take<int32_t>(kc / kKPad + 1);
         p->tmpE = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpK = cv.take<int32_t>(p->cap[CAP_C2]);
         p->tmpR = cv.take<int32_t>(p->cap[CAP_C2]);
@@ -1039,6 +1195,7 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
     p->canon_rowphysA = cv.take<int32_t>(p->cap[CAP_ROWA]);
     p->canon_rowphysB = cv.take<int32_t>(p->cap[CAP_ROWB]);
     p->canon_colphys = cv.take<int32_t>(p->cap[CAP_C2]);
+    p->canon_acolphys = cv.take<int32_t>(p->cap[CAP_C2]);
     if (own_statsA) {
         p->statsA[0] = cv.take<int32_t>(n); p->statsA[1] = cv.take<int32_t>(d);
         p->statsA[2] = cv.take<int32_t>(n); p->statsA[3] = cv.take<int32_t>(d);
@@ -1163,9 +1320,12 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     const int idA = p->sA != IMUNPACK_ROW ? n : 0, idC1 = p->sA != IMUNPACK_COL ? d : 0,
               idB = p->sB != IMUNPACK_ROW ? h : 0;
     if (idA > p->rowA.cap || idC1 > p->c1.cap || idB > p->rowB.cap) return IMUNPACK_EINVAL;
-    hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, 1)), 256, 64)),
+    // also cleared: the weights of the stored columns of A (the column layout adds to them)
+    const int kcA = phys_cap_cols(p->cap[CAP_C2]);
+    hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, kcA)), 256, 64)),
                        dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, idB,
-                       &hdr->h_u, p->extraRows, p->sB == IMUNPACK_BOTH ? h : 0);
+                       &hdr->h_u, p->extraRows, p->sB == IMUNPACK_BOTH ? h : 0,
+                       reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA);
     // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
     // this call's own scan produces one.  The two operands are planned one after the other, so one
     // own buffer serves both.
@@ -1440,6 +1600,7 @@ static int build_canonical(Plan *p, CanonHost &c) {
         IMU_TRY(upload(p->layA.row_phys, c.rowA, p->canon_rowphysA));
         IMU_TRY(upload(p->layB.row_phys, c.rowB, p->canon_rowphysB));
         IMU_TRY(upload(p->cols.col_phys, c.c2, p->canon_colphys));
+        IMU_TRY(upload(p->cols.acol_phys, c.c2, p->canon_acolphys));
         p->canon_valid = 1;
     }
     return IMUNPACK_OK;

@@ -1,6 +1,8 @@
 // Digit scatter (Sec. 4, Eq. (mod); Alg. 1 l.4-5, Alg. 2 l.4-6, Alg. 4 l.7-8 and 11-13): writes the
-// unpacked int8 operands A_ue and B_eu in the plan's physical layout, gathering from the int32
-// operands.  HBM-bound: 4 B read per source element, 1 B written per unpacked element.
+// unpacked int8 operands in the plan's physical layout, gathering from the int32 operands: B_eu in
+// full, and of A_ue every column of A_u once (the copies that column unpacking of the partner asks
+// for, Alg. 2 line 6 / Alg. 4 line 13, are not stored: the GEMM reads a stored column wherever a copy
+// of it stands).  HBM-bound: 4 B read per source element, 1 B written per stored element.
 //
 // Where an entry's digits go.  A split of a row (column) keeps digit 0 of every entry of that row
 // (column) in place and moves floor(v / s) to the appended row (column); a row or column is split
@@ -23,29 +25,33 @@ namespace imu { int poll_ready(Plan *p); }
 
 namespace imu {
 
-// One thread per (physical row, 16-column output unit), independent of every other thread: it reads
-// the 16 source values of its unit and writes the unit's 16 bytes.  A wave is 64 units of one row (its
-// row data travel in scalar registers) and also leaves  sum_c s^e(c) |digit|  of what it wrote, its
-// part of the row's weighted L1 norm.  The columns of a group are ordered by source column, so nearly
-// every unit copies 16 consecutive source columns (64 contiguous bytes); the planner deals those units
-// out first, the others (which gather through the column table) behind them, so the lanes of a wave
-// nearly always take the same path.  No staging and no barriers: the launch is a stream of short
-// waves, eight to a SIMD, which is what keeps enough loads in flight.
+// A wave writes a band of kBandRows physical rows of one window of 64 output units (1024 stored
+// columns): lane l owns unit l of the window for every row of the band, so what describes the unit
+// (where its 16 source values sit, their digit level, their weight in the row norm) is decoded once
+// per wave and not once per row.  Per row a lane reads the 16 source values of its unit (64
+// contiguous bytes when the unit copies 16 consecutive source columns, which the column layout makes
+// the rule) and writes the unit's 16 bytes; the wave also leaves  sum_c w(c) |digit|  of what it
+// wrote, its part of the row's weighted L1 norm.  Rows are taken two at a time so that eight 16-byte
+// loads per lane are in flight; the launch has exactly one wave per (band, window) of either operand,
+// no empty workgroups, no staging and no barriers.
 constexpr int kScatterThreads = 256;
-constexpr int kScatterWaves = kScatterThreads / 64;  // = physical rows per workgroup
+constexpr int kScatterWaves = kScatterThreads / 64;
+constexpr int kBandRows = 16;  // divides kTile: the padded row counts are multiples of it
 
 struct ScatterArgs {
     const int32_t *M;            // the int32 operand, row-major
-    int64_t ld;
+    int64_t ldm;
     const int32_t *prow_slot, *prow_src, *prow_exp;  // per physical row
-    const int32_t *col_k;        // per physical column: source column, -1 = padding
-    const int32_t *col_e;        // per physical column: digit level along this operand's column axis
-    const int4 *unit_desc;       // in dealing order, the unit's index in z >> 8
-    int lev_shift;               // where this operand's level sits in unit_desc.w
-    int Mp, Kp, s, sh;
-    int ny;                      // workgroups along y that serve this operand
+    const int32_t *col_k;        // per stored column: source column, -1 = none
+    const int32_t *col_e;        // per stored column: digit level along this operand's column axis
+    const unsigned long long *col_w;   // per stored column: weight in the row norm (nullptr: s^exponent of the unit)
+    const int4 *unit;            // per 16 stored columns, see ColLayout
+    const unsigned long long *unit_w;  // per unit: the weight its columns share (nullptr: s^exponent of the unit)
+    int rows, W, ld, s, sh;      // physical rows, stored columns, bytes from one row of `out` to the next
+    int nwin;                    // windows of 1024 stored columns
+    int items;                   // waves that serve this operand: (rows / kBandRows) * nwin
     int8_t *out;
-    unsigned long long *wavesum; // [Mp][waves per row]: every wave of the launch leaves its part of the row norm
+    unsigned long long *wavesum; // [rows][nwin]: every wave leaves its part of the row norm
 };
 
 typedef int v4i_u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at any int boundary
@@ -83,104 +89,139 @@ __device__ __forceinline__ int digit0x4(const int (&x)[4], unsigned mask4, unsig
     return (int)r;
 }
 
-// Two operands in one launch when they take the same variant: blockIdx.y below a0.ny serves a0, the
-// rest a1 (an operand's ny is its share of gridDim.y).
+__device__ __forceinline__ unsigned long long sat44(unsigned long long m, unsigned long long w) {
+    if (m == 0) return 0;
+    if (w >= (1ull << 44) || m >= (1ull << 20)) return 1ull << 44;
+    const unsigned long long t = m * w;
+    return t < (1ull << 44) ? t : (1ull << 44);
+}
+
+// Two operands in one launch when they take the same variant: waves below a0.items serve a0, the rest a1.
 template <bool DENSE>
 __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0, ScatterArgs a1) {
-    const bool second = (int)blockIdx.y >= a0.ny;
-    const ScatterArgs &a = second ? a1 : a0;
-    const int by = second ? (int)blockIdx.y - a0.ny : (int)blockIdx.y;
-    const int nunits = a.Kp >> 4, wpr = (nunits + 63) >> 6;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int upos = blockIdx.x * 64 + (int)(threadIdx.x & 63);
+    const int lane = (int)(threadIdx.x & 63);
+    int item = (int)blockIdx.x * kScatterWaves + wave;
+    const bool second = item >= a0.items;
+    const ScatterArgs &a = second ? a1 : a0;
+    if (second) item -= a0.items;
+    if (item >= a.items) return;  // uniform per wave; no barriers anywhere
+    const int band = item / a.nwin, win = item - band * a.nwin;
+    const int nunits = a.W >> 4;
+    const int upos = win * 64 + lane;
     const bool inside = upos < nunits;
-    const int4 ud = inside ? a.unit_desc[upos] : make_int4(-1, -1, 3, 0);
-    const int q0 = (ud.z >> 8) * 16;
+    const int4 ud = inside ? a.unit[upos] : make_int4(-1, -1, 7, 0);
+    const int q0 = upos * 16;
     const int kmin = ud.x, kmax = ud.y;
-    const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0;
-    const int ecu = (ud.w >> a.lev_shift) & 0xFF;
-    const unsigned nsft = (unsigned)(a.sh * ((ud.w >> 16) & 0xFF));  // weight of the unit's columns in the row norm
+    const bool run = (ud.z & 1) != 0, uniform = (ud.z & 2) != 0, onew = (ud.z & 4) != 0;
+    const int ecu = ud.w & 0xFF;
+    // what an entry of this unit weighs in the row norm: s^(exponent of S) for B_eu, the sum of those
+    // over the column slots that read the stored column for A
+    unsigned long long wgt = 0;
+    if (inside && kmax >= 0)
+        wgt = a.unit_w ? a.unit_w[upos] : ((ud.w >> 16) * a.sh >= 44 ? (1ull << 44) : (1ull << ((ud.w >> 16) * a.sh)));
     const unsigned mask4 = (unsigned)(a.s - 1) * 0x01010101u;
-    auto weighted = [](unsigned long long m, unsigned sft) {  // saturating, far above what a fused GEMM tolerates
-        const unsigned long long t = sft >= 40u ? (1ull << 44) : (m << sft);
-        return t < (1ull << 44) ? t : (1ull << 44);
-    };
-    for (int p = by * kScatterWaves + wave; p < a.Mp; p += a.ny * kScatterWaves) {
-        const int slot = a.prow_slot[p], er = a.prow_exp[p];
-        const int si = max(a.prow_src[p], 0);  // asked for together with the other two
-        unsigned mag = 0;  // sum of |digit| over the unit
-        // padding row, padding columns, or (UnpackBoth operands hold digit 0 at level (0, 0) only; every
-        // operand: no digit that high) a unit that holds nothing
-        const unsigned usft = (unsigned)(a.sh * (er + ecu));
-        const bool empty = !inside || slot < 0 || kmax < 0 || (uniform && (DENSE ? usft >= 32u : er + ecu != 0));
-        int4 o = make_int4(0, 0, 0, 0);
-        if (!empty) {
-            const int32_t *src = a.M + (int64_t)si * a.ld;
-            int v[4][4];
-            if (run) {
+    const int p_first = band * kBandRows;
+    for (int r0 = 0; r0 < kBandRows; r0 += 2) {
+        int si[2], er[2];
+        bool live[2];
+        int v[2][4][4];
+        // ---- both rows' loads first
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const v4i_u x = *reinterpret_cast<const v4i_u *>(src + kmin + 4 * j);
-                    v[j][0] = x.x; v[j][1] = x.y; v[j][2] = x.z; v[j][3] = x.w;
-                }
-            } else {  // gather through the column table
+        for (int h = 0; h < 2; ++h) {
+            const int p = __builtin_amdgcn_readfirstlane(p_first + r0 + h);
+            const int slot = a.prow_slot[p];
+            er[h] = a.prow_exp[p];
+            si[h] = max(a.prow_src[p], 0);
+            // padding row, padding unit, or (UnpackBoth operands hold digit 0 at level (0, 0) only; every
+            // operand: no digit that high) a unit that holds nothing in this row
+            const unsigned usft = (unsigned)(a.sh * (er[h] + ecu));
+            live[h] = inside && slot >= 0 && kmax >= 0 && !(uniform && (DENSE ? usft >= 32u : er[h] + ecu != 0));
+            if (live[h]) {
+                const int32_t *src = a.M + (int64_t)si[h] * a.ldm;
+                if (run) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int4 kk = *reinterpret_cast<const int4 *>(a.col_k + q0 + 4 * j);
-                    v[j][0] = kk.x >= 0 ? src[kk.x] : 0;
-                    v[j][1] = kk.y >= 0 ? src[kk.y] : 0;
-                    v[j][2] = kk.z >= 0 ? src[kk.z] : 0;
-                    v[j][3] = kk.w >= 0 ? src[kk.w] : 0;
-                }
-            }
-            int pk[4];
-            if (uniform) {
-                if (!DENSE || usft == 0u) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) pk[j] = digit0x4(v[j], mask4, mag);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) pk[j] = digits4(v[j], usft, a.sh, mag);
-                }
-            } else {  // a digit level per column
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int4 ee = *reinterpret_cast<const int4 *>(a.col_e + q0 + 4 * j);
-                    const int ec[4] = {ee.x, ee.y, ee.z, ee.w};
-                    int dg[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int t = er + ec[i];
-                        const unsigned sft = (unsigned)(a.sh * t);
-                        const int one[4] = {v[j][i], 0, 0, 0};
-                        unsigned m1 = 0;
-                        const bool holds = DENSE ? sft < 32u : t == 0;
-                        dg[i] = holds ? (digits4(one, sft, a.sh, m1) & 0xFF) : 0;
-                        mag += holds ? m1 : 0u;
+                    for (int j = 0; j < 4; ++j) {
+                        const v4i_u x = *reinterpret_cast<const v4i_u *>(src + kmin + 4 * j);
+                        v[h][j][0] = x.x; v[h][j][1] = x.y; v[h][j][2] = x.z; v[h][j][3] = x.w;
                     }
-                    pk[j] = dg[0] | (dg[1] << 8) | (dg[2] << 16) | (dg[3] << 24);
+                } else {  // gather through the column table
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int4 kk = *reinterpret_cast<const int4 *>(a.col_k + q0 + 4 * j);
+                        v[h][j][0] = kk.x >= 0 ? src[kk.x] : 0;
+                        v[h][j][1] = kk.y >= 0 ? src[kk.y] : 0;
+                        v[h][j][2] = kk.z >= 0 ? src[kk.z] : 0;
+                        v[h][j][3] = kk.w >= 0 ? src[kk.w] : 0;
+                    }
                 }
             }
-            o = make_int4(pk[0], pk[1], pk[2], pk[3]);
         }
-        if (inside) *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.Kp + q0) = o;
-        // ---- the wave's part of the row norm
-        const unsigned long long nz = __ballot(mag != 0);
-        unsigned long long total = 0;
-        if (nz != 0) {
-            const unsigned n1 = (unsigned)__builtin_amdgcn_readlane((int)nsft, __builtin_ctzll(nz));
-            if (__all(mag == 0 || nsft == n1)) {  // one exponent of S: add the magnitudes, weigh once
-                unsigned t = mag;
+        // ---- digits, store, norm
 #pragma unroll
-                for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
-                total = weighted(t, n1);
-            } else {
-                total = weighted(mag, nsft);
+        for (int h = 0; h < 2; ++h) {
+            const int p = p_first + r0 + h;
+            unsigned mag = 0;               // sum of |digit| over the unit (columns that share the weight wgt)
+            unsigned long long wsum = 0;    // weighted sum, for units whose columns weigh differently
+            int4 o = make_int4(0, 0, 0, 0);
+            if (live[h]) {
+                int pk[4];
+                const unsigned usft = (unsigned)(a.sh * (er[h] + ecu));
+                if (uniform && onew) {
+                    if (!DENSE || usft == 0u) {
 #pragma unroll
-                for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
+                        for (int j = 0; j < 4; ++j) pk[j] = digit0x4(v[h][j], mask4, mag);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) pk[j] = digits4(v[h][j], usft, a.sh, mag);
+                    }
+                } else {  // a digit level and / or a weight per column
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int4 ee = *reinterpret_cast<const int4 *>(a.col_e + q0 + 4 * j);
+                        const int ec[4] = {ee.x, ee.y, ee.z, ee.w};
+                        int dg[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int t = er[h] + ec[i];
+                            const unsigned sft = (unsigned)(a.sh * t);
+                            const int one[4] = {v[h][j][i], 0, 0, 0};
+                            unsigned m1 = 0;
+                            const bool holds = DENSE ? sft < 32u : t == 0;
+                            dg[i] = holds ? (digits4(one, sft, a.sh, m1) & 0xFF) : 0;
+                            if (holds && m1) {
+                                if (onew) mag += m1;
+                                else wsum += sat44(m1, a.col_w[q0 + 4 * j + i]);
+                            }
+                        }
+                        pk[j] = dg[0] | (dg[1] << 8) | (dg[2] << 16) | (dg[3] << 24);
+                    }
+                }
+                o = make_int4(pk[0], pk[1], pk[2], pk[3]);
             }
+            if (inside) *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.ld + q0) = o;
+            // ---- the wave's part of the row norm
+            const unsigned long long nz = __ballot(mag != 0 || wsum != 0);
+            unsigned long long total = 0;
+            if (nz != 0) {
+                const int first = __builtin_ctzll(nz);
+                const unsigned wlo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)wgt, first);
+                const unsigned whi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wgt >> 32), first);
+                const unsigned long long w1 = ((unsigned long long)whi << 32) | wlo;
+                if (__all(wsum == 0 && (mag == 0 || wgt == w1))) {  // one weight: add the magnitudes, weigh once
+                    unsigned t = mag;
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
+                    total = sat44(t, w1);
+                } else {
+                    total = wsum + sat44(mag, wgt);
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
+                    if (total > (1ull << 44)) total = 1ull << 44;
+                }
+            }
+            if (lane == 0) a.wavesum[(int64_t)p * a.nwin + win] = total;
         }
-        if ((threadIdx.x & 63) == 0) a.wavesum[(int64_t)p * wpr + blockIdx.x] = total;
     }
 }
 
@@ -189,7 +230,8 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0
 // split first (Alg. 4 lines 7-9 / 11-14) and leaves its own digit 0 there.
 //   second == 0 (A): the entry's column chain lives in the column slots of A's unpacking; A_ue then
 //     repeats column r of A_u in every column slot of the second unpacking that descends from r
-//     (Alg. 2 line 6 / Alg. 4 line 13), so every digit is written once per such slot.
+//     (Alg. 2 line 6 / Alg. 4 line 13): the digit is stored wherever such a slot reads its column of A
+//     (mostly one and the same stored column), and counts in the row norm once per such slot.
 //   second == 1 (B): B_e holds a copy of column k of B in every column slot r of A's unpacking that
 //     descends from k, and each copy is unpacked on its own.
 struct FixupArgs {
@@ -200,8 +242,10 @@ struct FixupArgs {
     SlotSet rows, cset;         // the operand's row slots and the column slots of its own unpacking
     const int32_t *c1_child;    // second == 1: child links among the column slots of A's unpacking
     const int32_t *c2_child;    // second == 0: child links among the column slots of the second unpacking
-    const int32_t *row_phys, *col_phys, *col_sexp;
-    int Kp, s, sh;
+    const int32_t *row_phys;
+    const int32_t *out_col;     // per column slot of the second unpacking: the stored column that holds it
+    const int32_t *col_phys, *col_sexp;  // its column of B_eu, and per such column the exponent of S
+    int W, s, sh;               // bytes from one row of `out` to the next
     int8_t *out;
     unsigned long long *rowsum; // per physical row: what the digits placed here add to the row norm
 };
@@ -272,9 +316,8 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
                 const int p = f.row_phys[R];
                 const int8_t dg = (int8_t)(v < 0 ? -m : m);
                 for (int c = C, hops = 0; c >= 0 && hops < 4096; c = f.second ? -1 : f.c2_child[c], ++hops) {
-                    const int q = f.col_phys[c];
-                    f.out[(int64_t)p * f.Kp + q] = dg;
-                    const unsigned nsft = (unsigned)(f.sh * f.col_sexp[q]);
+                    f.out[(int64_t)p * f.W + f.out_col[c]] = dg;
+                    const unsigned nsft = (unsigned)(f.sh * f.col_sexp[f.col_phys[c]]);
                     const unsigned long long term = nsft >= 40u ? (1ull << 44) : ((unsigned long long)m << nsft);
                     add_to_row(f.rowsum, p, term);
                 }
@@ -287,11 +330,12 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
 // plus what the fix-up pass placed).
 __global__ void bound_kernel(const unsigned long long *rowsum_a, const unsigned long long *wavesum_a, int rows_a,
                              unsigned long long *bound_a, const unsigned long long *rowsum_b,
-                             const unsigned long long *wavesum_b, int rows_b, unsigned long long *bound_b, int wpr) {
+                             const unsigned long long *wavesum_b, int rows_b, unsigned long long *bound_b, int wpr_a,
+                             int wpr_b) {
     unsigned long long ma = 0, mb = 0;
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < rows_a + rows_b; t += gridDim.x * blockDim.x) {
-        if (t < rows_a) ma = max(ma, row_norm(wavesum_a, wpr, t, rowsum_a[t]));
-        else mb = max(mb, row_norm(wavesum_b, wpr, t - rows_a, rowsum_b[t - rows_a]));
+        if (t < rows_a) ma = max(ma, row_norm(wavesum_a, wpr_a, t, rowsum_a[t]));
+        else mb = max(mb, row_norm(wavesum_b, wpr_b, t - rows_a, rowsum_b[t - rows_a]));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -313,7 +357,7 @@ __global__ void reset_bound_kernel(PlanHeader *hdr, unsigned long long *rowsum_a
     for (int t = t0; t < rows_b; t += stride) rowsum_b[t] = 0;
 }
 
-// canon[R][c] = phys[row_phys[R]][col_phys[c]]
+// canon[R][c] = phys[row_phys[R]][col_phys[c]]; Kp: stored columns per physical row
 __global__ void canonical_kernel(const int8_t *__restrict__ phys, int Kp, const int32_t *row_phys,
                                  const int32_t *col_phys, int nrows, int ncols, int8_t *__restrict__ canon) {
     const int R = blockIdx.x;
@@ -329,9 +373,16 @@ using namespace imu;
 extern "C" int imunpack_unpacked_bytes(const imunpack_plan_t *p, size_t *bytes_A, size_t *bytes_B,
                                        size_t *bytes_workspace) {
     if (!p || !p->valid) return IMUNPACK_EINVAL;
-    if (bytes_A) *bytes_A = (size_t)p->hdr.Mp * p->hdr.Kp;
-    if (bytes_B) *bytes_B = (size_t)p->hdr.Np * p->hdr.Kp;
+    if (bytes_A) *bytes_A = (size_t)p->hdr.Mp * p->hdr.ldA;
+    if (bytes_B) *bytes_B = (size_t)p->hdr.Np * p->hdr.ldB;
     if (bytes_workspace) *bytes_workspace = (size_t)p->hdr.Mp * p->hdr.Np * sizeof(int64_t);
+    return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_plan_layout(const imunpack_plan_t *p, int64_t *shape) {
+    if (!p || !p->valid || !shape) return IMUNPACK_EINVAL;
+    const int64_t v[6] = {p->hdr.Mp, p->hdr.KA, p->hdr.ldA, p->hdr.Np, p->hdr.Kp, p->hdr.ldB};
+    memcpy(shape, v, sizeof(v));
     return IMUNPACK_OK;
 }
 
@@ -347,23 +398,26 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
                            p->layB.rowsum, h.Np);
     FixupArgs fx[2] = {};
     int fblocks[2] = {0, 0};
-    const int wpr = (h.Kp / 16 + 63) / 64;  // waves of the scatter kernel per physical row
     ScatterArgs sc[2];
+    memset(sc, 0, sizeof(sc));
     bool launch[2] = {false, false}, dense[2] = {false, false};
     for (int op = 0; op < 2; ++op) {
         const int rowsP = op ? h.Np : h.Mp;
-        if (rowsP <= 0 || h.Kp <= 0) continue;
+        const int W = op ? h.Kp : h.KA;
+        if (rowsP <= 0 || W <= 0) continue;
         const RowLayout &lay = op ? p->layB : p->layA;
         const bool both = (op ? p->sB : p->sA) == IMUNPACK_BOTH;
         ScatterArgs &a = sc[op];
-        a.M = op ? B : A; a.ld = op ? ldb : lda;
+        a.M = op ? B : A; a.ldm = op ? ldb : lda;
         a.prow_slot = lay.prow_slot; a.prow_src = lay.prow_src; a.prow_exp = lay.prow_exp;
-        a.col_k = p->cols.colA_k;
+        a.col_k = op ? p->cols.colB_k : p->cols.colA_k;
         a.col_e = op ? p->cols.colB_e : p->cols.colA_e;
-        a.unit_desc = p->cols.unit_sorted;
-        a.lev_shift = op ? 8 : 0;
-        a.Mp = rowsP; a.Kp = h.Kp; a.s = p->s; a.sh = p->sh;
-        a.ny = std::min((rowsP + kScatterWaves - 1) / kScatterWaves, 32767);
+        a.col_w = op ? nullptr : p->cols.colA_w;
+        a.unit = op ? p->cols.unitB : p->cols.unitA;
+        a.unit_w = op ? nullptr : p->cols.unitA_w;
+        a.rows = rowsP; a.W = W; a.ld = op ? h.ldB : h.ldA; a.s = p->s; a.sh = p->sh;
+        a.nwin = (W + 1023) / 1024;
+        a.items = (rowsP / kBandRows) * a.nwin;
         a.out = op ? B_eu : A_ue;
         a.wavesum = lay.wavesum;
         launch[op] = true;
@@ -379,22 +433,26 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.cset = op ? p->c2 : p->c1;
             f.c1_child = p->c1.child;
             f.c2_child = p->c2.child;
-            f.row_phys = lay.row_phys; f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
-            f.Kp = h.Kp; f.s = p->s; f.sh = p->sh;
+            f.row_phys = lay.row_phys;
+            f.out_col = op ? p->cols.col_phys : p->cols.acol_phys;
+            f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
+            f.W = op ? h.ldB : h.ldA; f.s = p->s; f.sh = p->sh;
             f.out = a.out; f.rowsum = lay.rowsum;
             fblocks[op] = (nob + 255) / 256;
         }
     }
-    auto scatter = [&](const ScatterArgs &x, const ScatterArgs &y, int ny, bool dns) {
-        const dim3 grid((unsigned)wpr, (unsigned)ny);
+    auto scatter = [&](const ScatterArgs &x, const ScatterArgs &y, int items, bool dns) {
+        const dim3 grid((unsigned)((items + kScatterWaves - 1) / kScatterWaves));
         if (dns) hipLaunchKernelGGL(scatter_kernel<true>, grid, dim3(kScatterThreads), 0, st, x, y);
         else hipLaunchKernelGGL(scatter_kernel<false>, grid, dim3(kScatterThreads), 0, st, x, y);
     };
+    ScatterArgs none;
+    memset(&none, 0, sizeof(none));
     if (launch[0] && launch[1] && dense[0] == dense[1]) {  // one launch: the tail of A overlaps the head of B
-        scatter(sc[0], sc[1], sc[0].ny + sc[1].ny, dense[0]);
+        scatter(sc[0], sc[1], sc[0].items + sc[1].items, dense[0]);
     } else {
         for (int op = 0; op < 2; ++op)
-            if (launch[op]) scatter(sc[op], sc[op], sc[op].ny, dense[op]);
+            if (launch[op]) scatter(sc[op], none, sc[op].items, dense[op]);
     }
     if (h.Kp > 0 && h.Mp + h.Np > 0) {
         // after both scatters: the fix-up overwrites zeros they wrote; then the bounds from the row norms
@@ -406,7 +464,8 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         }
         const int nscan = std::min(256, (h.Mp + h.Np + 255) / 256);
         hipLaunchKernelGGL(bound_kernel, dim3(nscan), dim3(256), 0, st, p->layA.rowsum, p->layA.wavesum, h.Mp,
-                           &p->d_hdr->bound[0], p->layB.rowsum, p->layB.wavesum, h.Np, &p->d_hdr->bound[1], wpr);
+                           &p->d_hdr->bound[0], p->layB.rowsum, p->layB.wavesum, h.Np, &p->d_hdr->bound[1],
+                           sc[0].nwin, sc[1].nwin);
     }
     IMU_TRY(launch_status());
     // The bounds travel to the host on the plan's side stream, behind the scatter: the caller's stream is
@@ -460,10 +519,10 @@ extern "C" int imunpack_unpack_canonical(imunpack_plan_t *p, const int8_t *A_ue,
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (A_ue && A_canon && h.n_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, h.Kp, p->canon_rowphysA,
-                           p->canon_colphys, h.n_u, h.d_u, A_canon);
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, h.ldA, p->canon_rowphysA,
+                           p->canon_acolphys, h.n_u, h.d_u, A_canon);
     if (B_eu && B_canon && h.h_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, h.Kp, p->canon_rowphysB,
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, h.ldB, p->canon_rowphysB,
                            p->canon_colphys, h.h_u, h.d_u, B_canon);
     return launch_status();
 }

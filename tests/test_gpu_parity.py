@@ -167,9 +167,16 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     oa, ob = hnd.operands_i8()
     assert np.array_equal(Ac.cpu().numpy(), oa)
     assert np.array_equal(Bc.cpu().numpy(), ob)
-    # padding of the physical layout must be zero: total magnitude is preserved
-    assert int(A_ue.to(torch.int64).abs().sum().item()) == int(np.abs(oa.astype(np.int64)).sum())
-    assert int(B_eu.to(torch.int64).abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
+    # B_eu is stored in full and its padding (and the zero columns beside columns of A it has no copy
+    # for) must be zero: total magnitude is preserved.  Of A_ue every column of A_u is stored once (the
+    # repeated columns are read from there), plus a few gathered copies: never more than A_ue holds.
+    (ra, wa, pa), (rb, wb, pb) = plan.layout()
+    assert A_ue.numel() == ra * pa == plan.unpacked_bytes()[0] and B_eu.numel() == rb * pb == plan.unpacked_bytes()[1]
+    stored_b = B_eu.view(rb, pb)[:, :wb].to(torch.int64)
+    assert int(stored_b.abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
+    stored_a = A_ue.view(ra, pa)[:, :wa].to(torch.int64)
+    assert int(stored_a.abs().sum().item()) <= int(np.abs(oa.astype(np.int64)).sum())
+    assert wa <= wb and wa % 128 == 0 and wb % 128 == 0
     check_bounds(plan, oa, ob, S, s)
     want = oracle.int_gemm(Aq, Bq)
     want_fp = oracle.dequantize(want, scale_a, scale_b)
