@@ -875,8 +875,11 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
             hdr->ngroups = ngroups;
             hdr->Kp = total_tiles * kKPad;
             hdr->KA = s_ka_levels + total_c * kKPad;
-            hdr->ldA = (((s_ka_levels + total_c * kKPad + 255) / 256) | 1) * 256;
-            hdr->ldB = (((total_tiles * kKPad + 255) / 256) | 1) * 256;
+            // row pitches: wide rows get an odd multiple of 256 bytes (power-of-two strides put the rows
+            // of a tile, which are read together, on the same few memory channels)
+            const int wa = s_ka_levels + total_c * kKPad, wb = total_tiles * kKPad;
+            hdr->ldA = wa >= 2048 ? (((wa + 255) / 256) | 1) * 256 : wa;
+            hdr->ldB = wb >= 2048 ? (((wb + 255) / 256) | 1) * 256 : wb;
             if (total_tiles * kKPad > cap_phys) flag_overflow(hdr, CAP_C2, 2 * D);
         }
     }
