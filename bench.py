@@ -106,17 +106,17 @@ def measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C
     names = workloads.STRATEGY_NAMES
     _, ratios, _ = imu.imunpack_price(st_a, w.n, st_b, w.h, w.d, w.b)
     mix_plan = imu.Plan()
-    # the OB entry lists that UnpackBoth plans from, whatever the configured strategies are
-    mst_a = st_a if st_a.ob is not None else imu.Stats.empty(w.n, w.d, A.device, imu.Stats.default_ob_cap(w.n, w.d))
-    mst_b = st_b if st_b.ob is not None else imu.Stats.empty(w.h, w.d, A.device, imu.Stats.default_ob_cap(w.h, w.d))
-    imu.imunpack_quantize(A, w.scale_a, w.b, Qa, mst_a, status[0:1])
-    imu.imunpack_quantize(B, w.scale_b, w.b, Qb, mst_b, status[1:2])
     # UnpackBoth is a sequential greedy (Alg. 4; the paper itself uses it for weights at load time only):
     # on an operand where more than 1 % of the entries are out of bound its planner alone takes far
     # longer than the whole step of any other pair, so such pairs are neither planned nor timed here.
     s_ob = 1 << (w.b - 1)
     dense_ob = {0: float((Qa.abs() >= s_ob).float().mean().item()) > 0.01,
                 1: float((Qb.abs() >= s_ob).float().mean().item()) > 0.01}
+    # the OB entry lists that UnpackBoth plans from, for the operands it is tried on
+    mst_a = st_a if (st_a.ob is not None or dense_ob[0]) else imu.Stats.empty(w.n, w.d, A.device, imu.Stats.default_ob_cap(w.n, w.d))
+    mst_b = st_b if (st_b.ob is not None or dense_ob[1]) else imu.Stats.empty(w.h, w.d, A.device, imu.Stats.default_ob_cap(w.h, w.d))
+    imu.imunpack_quantize(A, w.scale_a, w.b, Qa, mst_a, status[0:1])
+    imu.imunpack_quantize(B, w.scale_b, w.b, Qb, mst_b, status[1:2])
     configured = (w.strategy_a, w.strategy_b)
     all_r = {}
     for sa in (imu.ROW, imu.COL, imu.BOTH):
