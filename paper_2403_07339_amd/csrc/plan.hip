@@ -577,9 +577,11 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
 // goes to chunk floor(P_i / (kChunk - (Lmax-1))): a closed form, and the rows of a chunk never exceed
 // kChunk.
 __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count_dev, const RowLayout &lay,
-                            int cap_phys, int cap_tiles, int32_t *tmpP, PlanHeader *hdr, int operand, int chunk,
-                            int *lds) {
-    int32_t *nlev = lay.src_nlev;
+                            int cap_phys, int cap_tiles, int32_t *tmpP_global, PlanHeader *hdr, int operand, int chunk,
+                            int *lds, int32_t *fast /* 2 * nbase ints of LDS, or nullptr */) {
+    // the level counts and their running sums are scanned and searched over and over: in LDS when they fit
+    int32_t *nlev = fast ? fast : lay.src_nlev;
+    int32_t *tmpP = fast ? fast + nbase : tmpP_global;
     int lm = 1;
     constexpr int V = 4;  // source rows per thread and step: their chains are walked side by side
     for (int i0 = threadIdx.x; i0 < nbase; i0 += kPlanThreads * V) {
@@ -607,6 +609,7 @@ __device__ void rows_layout(const SlotSet &rows, int nbase, const int32_t *count
             const int i = i0 + u * kPlanThreads;
             if (i < nbase) {
                 nlev[i] = L[u];
+                if (fast) lay.src_nlev[i] = L[u];  // the GEMM epilogue reads it from memory
                 lm = max(lm, L[u]);
             }
         }
@@ -1076,12 +1079,15 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
 __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     SlotSet rowA, int n, RowLayout layA, int cap_physA, int32_t *tmpPA, SlotSet rowB, int h, RowLayout layB,
     int cap_physB, int32_t *tmpPB, SlotSet c1, SlotSet c2, ColLayout cols, int d, int cap_physC, int s, int sh,
-    int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr) {
+    int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr, int fast_lds) {
     __shared__ int lds[40];
+    extern __shared__ __attribute__((aligned(16))) int32_t fast_rows[];  // 2 * max(n, h) ints, if the launch gave them
     if (hdr->overflow) return;
     // rows of A: the GEMM epilogue folds them chunk by chunk; rows of B (columns of C): tile by tile
-    if (blockIdx.x == 0) rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, kChunk, lds);
-    else if (blockIdx.x == 1) rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, kTile, lds);
+    if (blockIdx.x == 0)
+        rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, kChunk, lds, fast_lds ? fast_rows : nullptr);
+    else if (blockIdx.x == 1)
+        rows_layout(rowB, h, &hdr->h_u, layB, cap_physB, cap_physB / kTile + 2, tmpPB, hdr, 1, kTile, lds, fast_lds ? fast_rows : nullptr);
     else {
         cols_layout(c1, c2, cols, d, cap_physC, s, sh, tmpE, tmpK, tmpR, tmpOff, hdr, lds, (int)blockIdx.x - 2);
         if (blockIdx.x == 2 && threadIdx.x == 0) hdr->bound[0] = hdr->bound[1] = 0;
@@ -1267,6 +1273,7 @@ __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict_
 }
 
 static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
+static constexpr int kLayoutLdsMax = 128 * 1024;  // dynamic LDS the layouts kernel may use (its static tables take about 12 KiB)
 
 // ob: the operand's OB entry list ([3][ob_cap], count on the device)
 static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const int32_t *ob_count,
@@ -1374,10 +1381,18 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
         else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
     // ---- physical layouts
-    hipLaunchKernelGGL(layouts_kernel, dim3(2 + kColBlocks), dim3(kPlanThreads), 0, st, p->rowA, n, p->layA,
+    // the row layouts keep two ints per source row in LDS when that fits beside the column layout's tables
+    const size_t fast_bytes = (size_t)2 * std::max(n, h) * sizeof(int32_t);
+    const int fast_lds = fast_bytes <= (size_t)kLayoutLdsMax ? 1 : 0;
+    static std::atomic<int> layouts_opted_in{0};  // the attribute is idempotent: a race sets the same value twice
+    if (!layouts_opted_in.load(std::memory_order_acquire)) {
+        IMU_HIP(hipFuncSetAttribute((const void *)layouts_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLayoutLdsMax));
+        layouts_opted_in.store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(layouts_kernel, dim3(2 + kColBlocks), dim3(kPlanThreads), fast_lds ? fast_bytes : 0, st, p->rowA, n, p->layA,
                        phys_cap_rows(p->cap[CAP_ROWA]), p->tmpPA, p->rowB, h, p->layB,
                        phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
-                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr);
+                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr, fast_lds);
     return launch_status();
 }
 
