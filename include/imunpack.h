@@ -49,6 +49,7 @@ extern "C" {
 
 typedef void *imunpack_stream_t;
 typedef struct imunpack_plan imunpack_plan_t;
+typedef struct imunpack_batch imunpack_batch_t;
 
 enum { IMUNPACK_ROW = 0, IMUNPACK_COL = 1, IMUNPACK_BOTH = 2 };
 
@@ -92,6 +93,16 @@ typedef struct {
 int imunpack_percentile(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c,
                         double p, float *alpha, int32_t *status_flag, void *workspace,
                         imunpack_stream_t stream);
+
+/* The RTN step of Eq. (quantized_A) itself, formed on the device: beta integers are to cover
+ * [-alpha_p, alpha_p], so one step is alpha_p / (0.5 beta) (one binary32 division; Sec. 2, the sentence
+ * after Eq. (quantized_A) defines alpha_p).  A matrix whose p-th percentile is 0 (mostly zeros) falls back
+ * to its largest magnitude, an all-zero one to the step 1.  Arguments as imunpack_percentile; step:
+ * device, one float, written when the stream gets there (imunpack_gemm_batched hands such steps from
+ * kernel to kernel without the host reading them).  Errors: EINVAL (also beta not a positive finite number). */
+int imunpack_rtn_step(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, double p,
+                      float beta, float *step, int32_t *status_flag, void *workspace,
+                      imunpack_stream_t stream);
 
 /* The same range estimate for callers that cannot allocate device memory or bring a workspace (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the counters and the
@@ -225,6 +236,26 @@ int imunpack_unpack_canonical(imunpack_plan_t *plan, const int8_t *A_ue, const i
 int imunpack_gemm(imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
                   void *workspace, int64_t *C_int, float *C_fp, int64_t ldc,
                   float scale_A, float scale_B, int fuse, imunpack_stream_t stream);
+
+/* ---- the whole path over a strided batch of products (Sec. 1 "Notations": the GEMMs of a Transformer) -
+ * C_i = step_A,i * step_B,i * (RTN(A_i / step_A,i) RTN(B_i / step_B,i)^T), i = 0 .. batch-1, the integer
+ * product evaluated exactly with b-bit digits (Sec. 4), as fp32.  Every item is a GEMM of its own: its own
+ * percentile steps alpha_p / (0.5 beta) (Eq. (quantized_A)), its own unpack plan.  A_i: n x d at
+ * A + i * sa_b, element (r, c) at offset r * sa_r + c * sa_c (so transposed operands are views, nothing is
+ * copied); B_i: h x d likewise; C_i: n x h row-major at C + i * sc_b with row stride ldc.  All device, fp32.
+ * *ctx == NULL creates a context; passing it again reuses its buffers (Q_A, Q_B, statistics, the unpacked
+ * operands, a plan: they only grow), so steady-state calls allocate nothing.  The library owns the context;
+ * release it with imunpack_batch_destroy.  The steps never leave the device; per item the host waits once,
+ * inside the plan call, for the sizes of the unpacked problem.  Synchronises the stream before returning.
+ * Errors: EINVAL; ERANGE if any operand held a NaN or Inf or a quotient beyond 32 bits (the outputs of
+ * that item are then undefined); ENOMEM; EHIP. */
+int imunpack_gemm_batched(const float *A, int64_t sa_b, int64_t sa_r, int64_t sa_c,
+                          const float *B, int64_t sb_b, int64_t sb_r, int64_t sb_c,
+                          int64_t batch, int64_t n, int64_t d, int64_t h,
+                          double p, float beta_A, float beta_B, int b, int strategy_A, int strategy_B,
+                          float *C, int64_t sc_b, int64_t ldc, imunpack_batch_t **ctx,
+                          imunpack_stream_t stream);
+int imunpack_batch_destroy(imunpack_batch_t *ctx);
 
 /* ---- (6) recombination and dequantisation (Sec. 4 "Reconstructing A"; Eq. (quantized_gemm)) ---
  * C_int = Pi_A C_u Pi_B^T by shift-and-add in int64 from the workspace of an un-fused

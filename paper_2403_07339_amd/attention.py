@@ -5,12 +5,12 @@ Sec. 1 ("Notations") of arXiv 2403.07339 lists, beside the GEMMs of the linear l
     P = Q K^T            O = M V                 (forward;  M = softmax(P), scaling factors omitted there)
     grad_Q = grad_P K    grad_K = grad_P^T Q     grad_M = grad_O V^T    grad_V = M^T grad_O   (backward)
 
-one set per sequence and head.  Each is computed as in Sec. 2 and Sec. 4 by ``linear.quantized_matmul``:
+one set per sequence and head.  Each is computed as in Sec. 2 and Sec. 4 by ``imunpack_gemm_batched``:
 both operands RTN-quantised with their own step alpha_p / (0.5 beta), the integer GEMM evaluated exactly
 with b-bit digits, the result scaled back.  Every matrix of every sequence and head is an operand of its
 own (its own percentile, its own plan); the operands are strided views, nothing is copied or transposed
 on the way in.  The softmax and its derivative are not GEMMs and stay in fp32 torch arithmetic.
-Integration on top of the C ABI binding: a loop over sequences and heads, one pipeline call per GEMM.
+Integration on top of the C ABI binding: one strided-batched call per GEMM of the layer.
 """
 from __future__ import annotations
 
@@ -18,20 +18,17 @@ import math
 
 import torch
 
-from .linear import QuantConfig, quantized_matmul
+from . import binding as imu
+from .linear import QuantConfig
 
 
 def quantized_bmm(A: torch.Tensor, B: torch.Tensor, beta_a: float, beta_b: float, cfg: QuantConfig) -> torch.Tensor:
     """A B^T over the leading dimensions: A [..., n, d], B [..., h, d] (fp32 device tensors, any strides,
-    equal leading shapes) -> [..., n, h]; every matrix pair is one exact integer GEMM."""
+    equal leading shapes) -> [..., n, h]; every matrix pair is one exact integer GEMM.  One call of the
+    library's strided-batched entry point for all sequences and heads."""
     if A.shape[:-2] != B.shape[:-2] or A.shape[-1] != B.shape[-1]:
         raise ValueError(f"shapes {tuple(A.shape)} and {tuple(B.shape)} do not form a batched A B^T")
-    lead = A.shape[:-2]
-    out = torch.empty(*lead, A.shape[-2], B.shape[-2], dtype=torch.float32, device=A.device)
-    A3, B3, O3 = A.reshape(-1, *A.shape[-2:]), B.reshape(-1, *B.shape[-2:]), out.view(-1, *out.shape[-2:])
-    for i in range(A3.shape[0]):
-        O3[i].copy_(quantized_matmul(A3[i], B3[i], beta_a, beta_b, cfg))
-    return out
+    return imu.imunpack_gemm_batched(A, B, cfg.p, beta_a, beta_b, cfg.b, cfg.strategy_a, cfg.strategy_b)
 
 
 class _AttentionFunction(torch.autograd.Function):

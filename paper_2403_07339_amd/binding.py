@@ -27,7 +27,8 @@ EXPORTS = [
     "imunpack_plan_destroy", "imunpack_unpacked_bytes", "imunpack_unpack", "imunpack_unpack_canonical",
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
-    "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout",
+    "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout", "imunpack_rtn_step",
+    "imunpack_gemm_batched", "imunpack_batch_destroy",
 ]
 
 
@@ -45,6 +46,10 @@ _lib.imunpack_plan_dims.argtypes = [_vp, C.POINTER(_i64), C.POINTER(_i64), C.POI
 _lib.imunpack_plan_export.argtypes = [_vp] + [_vp] * 8 + [C.POINTER(_i64)]
 _lib.imunpack_plan_destroy.argtypes = [_vp]
 _lib.imunpack_unpacked_bytes.argtypes = [_vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+_lib.imunpack_rtn_step.argtypes = [_vp, _i64, _i64, _i64, _i64, C.c_double, _f32, _vp, _vp, _vp, _vp]
+_lib.imunpack_gemm_batched.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _i64, _i64, _i64, _i64, _i64, C.c_double,
+                                       _f32, _f32, _i32, _i32, _i32, _vp, _i64, _i64, C.POINTER(_vp), _vp]
+_lib.imunpack_batch_destroy.argtypes = [_vp]
 _lib.imunpack_plan_layout.argtypes = [_vp, C.POINTER(_i64)]
 _lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
 _lib.imunpack_unpack_canonical.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
@@ -340,6 +345,99 @@ def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale
     if int(st_a.item()) or int(st_b.item()):
         raise ImunpackError(ERANGE, "imunpack_quantize status")
     return C_int, C_fp, plan
+
+
+def imunpack_rtn_step(X: torch.Tensor, p: float, beta: float, step: torch.Tensor | None = None,
+                      status: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """The RTN step alpha_p(X) / (0.5 beta) of Eq. (quantized_A), formed on the device.  Returns (step, status),
+    one-element device tensors; nothing is read back."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+    if step is None:
+        step = torch.empty(1, dtype=torch.float32, device=X.device)
+    if status is None:
+        status = torch.empty(1, dtype=torch.int32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(PERCENTILE_WORKSPACE_BYTES, dtype=torch.uint8, device=X.device)
+    _check(_lib.imunpack_rtn_step(X.data_ptr(), X.shape[0], X.shape[1], X.stride(0), X.stride(1), float(p), float(beta),
+                                  step.data_ptr(), status.data_ptr(), workspace.data_ptr(), _stream()), "imunpack_rtn_step")
+    return step, status
+
+
+class BatchContext:
+    """Owns an imunpack_batch_t: the buffers that imunpack_gemm_batched reuses from call to call."""
+
+    def __init__(self):
+        self._h = _vp(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def destroy(self):
+        if self._h and self._h.value:
+            _lib.imunpack_batch_destroy(self._h)
+            self._h = _vp(None)
+
+
+def _as_batch(t: torch.Tensor):
+    """[..., rows, cols] as (base tensor, batch count, batch stride) when the leading dimensions collapse
+    into one stride (they do for contiguous tensors and their transposes), else None."""
+    lead = t.shape[:-2]
+    count = 1
+    for s_ in lead:
+        count *= s_
+    if count <= 1:
+        return count, 0
+    stride = None
+    expect = None
+    for size, st in zip(reversed(lead), reversed(t.stride()[:-2])):
+        if size == 1:
+            continue
+        if stride is None:
+            stride, expect = st, st * size
+        elif st != expect:
+            return None
+        else:
+            expect = st * size
+    return count, stride
+
+
+def imunpack_gemm_batched(A: torch.Tensor, B: torch.Tensor, p: float, beta_a: float, beta_b: float, b: int,
+                          strategy_a: int, strategy_b: int, out: torch.Tensor | None = None,
+                          ctx: BatchContext | None = None) -> torch.Tensor:
+    """A B^T over the leading dimensions on the exact integer path: A [..., n, d], B [..., h, d] fp32 device
+    tensors with equal leading shapes and any strides (transposed views are passed as they are); every
+    matrix pair is quantised with its own percentile steps.  Returns [..., n, h] fp32."""
+    assert A.is_cuda and B.is_cuda and A.dtype == torch.float32 and B.dtype == torch.float32
+    assert A.dim() >= 2 and A.shape[:-2] == B.shape[:-2] and A.shape[-1] == B.shape[-1]
+    n, d, h = A.shape[-2], A.shape[-1], B.shape[-2]
+    if out is None:
+        out = torch.empty(*A.shape[:-2], n, h, dtype=torch.float32, device=A.device)
+    assert out.is_contiguous() and out.shape == (*A.shape[:-2], n, h)
+    ba, bb = _as_batch(A), _as_batch(B)
+    if ba is None or bb is None:   # leading dimensions that do not collapse: one call per leading index
+        for i in range(A.shape[0]):
+            imunpack_gemm_batched(A[i], B[i], p, beta_a, beta_b, b, strategy_a, strategy_b, out[i], ctx)
+        return out
+    if ctx is None:
+        ctx = _default_batch_context()
+    _check(_lib.imunpack_gemm_batched(A.data_ptr(), ba[1], A.stride(-2), A.stride(-1), B.data_ptr(), bb[1], B.stride(-2),
+                                      B.stride(-1), ba[0], n, d, h, float(p), float(beta_a), float(beta_b), b, strategy_a,
+                                      strategy_b, out.data_ptr(), n * h, h, C.byref(ctx._h), _stream()),
+           "imunpack_gemm_batched")
+    return out
+
+
+_BATCH_CTX = None
+
+
+def _default_batch_context() -> BatchContext:
+    global _BATCH_CTX
+    if _BATCH_CTX is None:
+        _BATCH_CTX = BatchContext()
+    return _BATCH_CTX
 
 
 def imunpack_diag_mfma_peak(workgroups: int, iters: int) -> int:

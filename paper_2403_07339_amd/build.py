@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libimunpack.so")
-SOURCES = ["api.hip", "percentile.hip", "quantize.hip", "plan.hip", "unpack.hip", "gemm.hip"]
+SOURCES = ["api.hip", "percentile.hip", "quantize.hip", "plan.hip", "unpack.hip", "gemm.hip", "batched.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

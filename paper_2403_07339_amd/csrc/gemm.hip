@@ -52,6 +52,7 @@ struct GemmArgs {
     float *C_fp;
     int64_t ldc;
     double scale;             // scale_A * scale_B
+    const float *scale_a_dev, *scale_b_dev;  // if set: the two RTN steps are read from device memory instead
     // un-fused: C_u[p][q] (+)= acc << seg_shift
     int64_t *C_u;
     int Np;
@@ -339,7 +340,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // tile) | levels << 16; the same per source column; the first source row of each chunk
     int32_t *rowmeta = foldbuf + 2 * kChunk * FLD, *colmeta = rowmeta + kTile, *chunk0 = colmeta + kTile;
     // scale * 2^final_shift is exact: one multiplication in binary64, one rounding to fp32
-    const double scale2 = g.scale * (double)(1ull << g.final_shift);
+    const double scale2 = (g.scale_a_dev ? (double)*g.scale_a_dev * (double)*g.scale_b_dev : g.scale) *
+                          (double)(1ull << g.final_shift);
     {
         const int isrc0 = g.layA.tile_src0[tm], nsrcA = g.layA.tile_src0[tm + 1] - isrc0;
         if (!flatA && tid < nsrcA)
@@ -579,9 +581,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 __global__ __launch_bounds__(256) void recombine_kernel(const int64_t *__restrict__ C_u, int Np, RowLayout layA,
                                                         RowLayout layB, int n, int h, int sh,
                                                         int64_t *C_int, float *C_fp, int64_t ldc,
-                                                        double scale) {
+                                                        double scale_val, const float *scale_a_dev,
+                                                        const float *scale_b_dev) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= h) return;
+    const double scale = scale_a_dev ? (double)*scale_a_dev * (double)*scale_b_dev : scale_val;
     const int q0 = layB.src_pstart[j], lj = layB.src_nlev[j];
     for (int i = blockIdx.y; i < n; i += gridDim.y) {
         const int p0 = layA.src_pstart[i], li = layA.src_nlev[i];
@@ -645,23 +649,33 @@ static int check_shifts(const Plan *p) {
     return maxexp * p->sh <= 62 ? IMUNPACK_OK : IMUNPACK_ERANGE;
 }
 
-extern "C" int imunpack_recombine(const imunpack_plan_t *p, const void *workspace, float scale_A,
-                                  float scale_B, int64_t *C_int, float *C_fp, int64_t ldc,
-                                  imunpack_stream_t stream) {
+namespace imu {
+int recombine_impl(const imunpack_plan_t *p, const void *workspace, float scale_A, float scale_B,
+                   const float *scale_a_dev, const float *scale_b_dev, int64_t *C_int, float *C_fp, int64_t ldc,
+                   hipStream_t stream) {
     if (!p || !p->valid || !workspace || ldc < p->h) return IMUNPACK_EINVAL;
     if (!C_int && !C_fp) return IMUNPACK_OK;
     IMU_TRY(check_shifts(p));
     dim3 grid((unsigned)((p->h + 255) / 256), (unsigned)std::min<int64_t>(p->n, 65535));
-    hipLaunchKernelGGL(recombine_kernel, grid, dim3(256), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(recombine_kernel, grid, dim3(256), 0, stream,
                        (const int64_t *)workspace, p->hdr.Np, p->layA, p->layB, (int)p->n, (int)p->h, p->sh,
-                       C_int, C_fp, ldc, (double)scale_A * (double)scale_B);
+                       C_int, C_fp, ldc, (double)scale_A * (double)scale_B, scale_a_dev, scale_b_dev);
     return launch_status();
 }
+}  // namespace imu
 
-extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
-                             void *workspace, int64_t *C_int, float *C_fp, int64_t ldc, float scale_A,
-                             float scale_B, int fuse, imunpack_stream_t stream) {
-    if (!p || !p->valid || !p->unpacked || !A_ue || !B_eu) return IMUNPACK_EINVAL;
+extern "C" int imunpack_recombine(const imunpack_plan_t *p, const void *workspace, float scale_A,
+                                  float scale_B, int64_t *C_int, float *C_fp, int64_t ldc,
+                                  imunpack_stream_t stream) {
+    return recombine_impl(p, workspace, scale_A, scale_B, nullptr, nullptr, C_int, C_fp, ldc, (hipStream_t)stream);
+}
+
+namespace imu {
+int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *workspace, int64_t *C_int,
+              float *C_fp, int64_t ldc, float scale_A, float scale_B, const float *scale_a_dev,
+              const float *scale_b_dev, int fuse, imunpack_stream_t stream) {
+    if (!p || !p->valid || !p->unpacked || !A_ue || !B_eu || (scale_a_dev == nullptr) != (scale_b_dev == nullptr))
+        return IMUNPACK_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (h.mtiles <= 0 || h.ntiles <= 0) return IMUNPACK_OK;
@@ -711,6 +725,7 @@ extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_
         g.final_shift = h.ngroups ? p->sh * h.grp_exp[h.ngroups - 1] : 0;
         g.C_int = C_int; g.C_fp = C_fp; g.ldc = ldc;
         g.scale = (double)scale_A * (double)scale_B;
+        g.scale_a_dev = scale_a_dev; g.scale_b_dev = scale_b_dev;
         g.clock_probe = g_clock_probe.load(std::memory_order_relaxed);
         // |accumulator| < 2^31, weights up to s^(levels of a row - 1 + levels of a column - 1)
         g.fold_f64 = !C_int && 31 + p->sh * ((h.lmaxA - 1) + (h.lmaxB - 1)) <= 52;
@@ -735,8 +750,15 @@ extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_
     }
     IMU_TRY(launch_status());
     if (fuse != 0)  // the caller asked for final outputs: finish the job here
-        return imunpack_recombine(p, workspace, scale_A, scale_B, C_int, C_fp, ldc, stream);
+        return recombine_impl(p, workspace, scale_A, scale_B, scale_a_dev, scale_b_dev, C_int, C_fp, ldc, st);
     return IMUNPACK_OK;
+}
+}  // namespace imu
+
+extern "C" int imunpack_gemm(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu,
+                             void *workspace, int64_t *C_int, float *C_fp, int64_t ldc, float scale_A,
+                             float scale_B, int fuse, imunpack_stream_t stream) {
+    return gemm_impl(p, A_ue, B_eu, workspace, C_int, C_fp, ldc, scale_A, scale_B, nullptr, nullptr, fuse, stream);
 }
 
 extern "C" int imunpack_diag_clock_probe(uint64_t *ticks) {

@@ -25,6 +25,8 @@ struct SelState {
     unsigned prefix;           // digits fixed so far (in place)
     unsigned prefix_mask;      // which bits those are
     unsigned long long k;      // rank wanted among the entries that agree with the prefix (1-based)
+    unsigned maxbits;          // largest magnitude seen (as its bit pattern), gathered by the first pass
+    unsigned pad_;
 };
 
 // Workspace layout: kSelBins counters, then the state.
@@ -41,6 +43,7 @@ __global__ void select_init_kernel(void *ws, unsigned long long k, int32_t *stat
         st->prefix = 0;
         st->prefix_mask = 0;
         st->k = k;
+        st->maxbits = 0;
         if (status) *status = 0;
     }
 }
@@ -58,9 +61,11 @@ __global__ __launch_bounds__(kSelThreads) void select_count_kernel(const float *
     const SelState st = *sel_state(ws);
     const unsigned bmask = (unsigned)nbins - 1u;
     bool nan = false;
+    unsigned umax = 0;
     auto take = [&](float x) {
         const unsigned u = __float_as_uint(x) & 0x7fffffffu;
         nan = nan || u > 0x7f800000u;
+        umax = max(umax, u);
         if ((u & st.prefix_mask) == st.prefix) atomicAdd(&lh[(u >> shift) & bmask], 1u);
     };
     const int64_t per_line = VEC ? nfast / 4 : nfast;
@@ -105,6 +110,21 @@ __global__ __launch_bounds__(kSelThreads) void select_count_kernel(const float *
     for (int i = threadIdx.x; i < nbins; i += kSelThreads)
         if (lh[i]) atomicAdd(&hist[i], lh[i]);
     if (status && __ballot(nan) && (threadIdx.x & 63) == 0) atomicOr(status, 1);
+    if (shift == 20) {  // first pass: the largest magnitude, for the step's fall-back
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) umax = max(umax, (unsigned)__shfl_xor((int)umax, off, 64));
+        if ((threadIdx.x & 63) == 0 && umax) atomicMax(&sel_state(ws)->maxbits, umax);
+    }
+}
+
+// The RTN step of Eq. (quantized_A): beta integers cover [-alpha_p, alpha_p], so one step is
+// alpha_p / (0.5 beta), formed once in binary32.  A matrix whose p-th percentile is 0 (mostly zeros)
+// falls back to its largest magnitude, an all-zero (or non-finite) one to 1.  *step holds alpha_p on
+// entry (the selection's last pass wrote it there) and the step on exit.
+__global__ void rtn_step_kernel(void *ws, float half_beta, float *step) {
+    float a = *step;
+    if (!(a > 0.0f)) a = __uint_as_float(sel_state(ws)->maxbits);
+    *step = (a > 0.0f && a < __uint_as_float(0x7f800000u)) ? __fdiv_rn(a, half_beta) : 1.0f;
 }
 
 // One workgroup: the bin whose cumulative count reaches k becomes the next digit.
@@ -198,6 +218,18 @@ extern "C" int imunpack_percentile(const float *X, int64_t rows, int64_t cols, i
         return IMUNPACK_EINVAL;
     if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols >= (int64_t)1 << 32) return IMUNPACK_EINVAL;
     return run_percentile(X, rows, cols, sx_r, sx_c, p, alpha, status_flag, workspace, (hipStream_t)stream);
+}
+
+extern "C" int imunpack_rtn_step(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, double p,
+                                 float beta, float *step, int32_t *status_flag, void *workspace,
+                                 imunpack_stream_t stream) {
+    if (!X || !step || !workspace || rows <= 0 || cols <= 0 || sx_r < 1 || sx_c < 1 || !(p > 0.0) || !(p <= 100.0) ||
+        !(beta > 0.0f) || !(beta < 3.0e38f))
+        return IMUNPACK_EINVAL;
+    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols >= (int64_t)1 << 32) return IMUNPACK_EINVAL;
+    IMU_TRY(run_percentile(X, rows, cols, sx_r, sx_c, p, step, status_flag, workspace, (hipStream_t)stream));
+    hipLaunchKernelGGL(rtn_step_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, workspace, (float)(0.5 * (double)beta), step);
+    return launch_status();
 }
 
 // ---- the same selection for callers that cannot allocate ------------------------------------------

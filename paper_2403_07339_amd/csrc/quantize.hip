@@ -15,6 +15,13 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
+// The RTN step: a value of the call, or (callers that keep it on the device) read from memory.  A step
+// that is not a positive finite number turns every quotient into a flagged 0.
+__device__ __forceinline__ float step_of(float value, const float *ptr) {
+    const float s = ptr ? *ptr : value;
+    return (s > 0.0f && s < 3.0e38f) ? s : __uint_as_float(0x7fc00000u);
+}
+
 // q = rint(x / scale): correctly rounded binary32 division, then round half to even.
 __device__ __forceinline__ int32_t rtn_one(float x, float scale, int &bad) {
     float r = rintf(__fdiv_rn(x, scale));
@@ -110,7 +117,8 @@ __device__ __forceinline__ void ob_flush(ObStage *sg, int32_t *ob, int ob_cap, i
 // a wave reads one 1 KiB row segment per instruction (float4 per lane).
 template <bool FROM_FLOAT>
 __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__ Xv, int64_t rows,
-                                                        int64_t cols, int64_t ldx, float scale, int s,
+                                                        int64_t cols, int64_t ldx, float scale_val,
+                                                        const float *scale_ptr, int s,
                                                         int32_t *__restrict__ Q, int64_t ldq,
                                                         int32_t *rowcnt, int32_t *colcnt,
                                                         int32_t *rowmax, int32_t *colmax,
@@ -122,6 +130,7 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
         if (threadIdx.x == 0) stage.count = 0;
         __syncthreads();
     }
+    const float scale = step_of(scale_val, scale_ptr);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // Workgroup ids are dealt round-robin to the 8 XCDs; rotating the column block with the row block
     // lets every XCD touch every column block (and so every memory channel) while the workgroups that
@@ -192,7 +201,8 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
 template <bool FROM_FLOAT>
 __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict__ Xv, int64_t rows,
                                                          int64_t cols, int64_t sx_r, int64_t sx_c,
-                                                         float scale, int s, int32_t *__restrict__ Q,
+                                                         float scale_val, const float *scale_ptr, int s,
+                                                         int32_t *__restrict__ Q,
                                                          int64_t ldq, int32_t *rowcnt, int32_t *colcnt,
                                                          int32_t *rowmax, int32_t *colmax,
                                                          int32_t *status, int32_t *ob, int ob_cap,
@@ -200,6 +210,7 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
     __shared__ int32_t tile[64][65];
     __shared__ int lds[2 * 4 * 64];
     __shared__ ObStage stage;
+    const float scale = step_of(scale_val, scale_ptr);
     if (ob && threadIdx.x == 0) stage.count = 0;  // published by the barrier after the tile is filled
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -261,13 +272,14 @@ constexpr int kTrPerWave = kTrTile / kTrWaves;               // columns (then ro
 
 template <bool FROM_FLOAT>
 __global__ __launch_bounds__(kTrThreads) void qscan_tr_kernel(const void *__restrict__ Xv, int64_t rows, int64_t cols,
-                                                       int64_t sx_c, float scale, int s,
-                                                       int32_t *__restrict__ Q, int64_t ldq, int32_t *rowcnt,
+                                                       int64_t sx_c, float scale_val, const float *scale_ptr,
+                                                       int s, int32_t *__restrict__ Q, int64_t ldq, int32_t *rowcnt,
                                                        int32_t *colcnt, int32_t *rowmax, int32_t *colmax,
                                                        int32_t *status, int32_t *ob, int ob_cap,
                                                        int32_t *ob_count) {
     __shared__ int32_t tile[kTrTile * kTrPitch];  // [column][row]
     __shared__ ObStage stage;
+    const float scale = step_of(scale_val, scale_ptr);
     if (ob && threadIdx.x == 0) stage.count = 0;  // published by the barrier after the tile is filled
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int half = lane >> 5, l32 = lane & 31;
@@ -420,11 +432,11 @@ static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, in
 }
 
 template <bool FROM_FLOAT>
-static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
-                     int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status,
-                     hipStream_t stream) {
+int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
+              const float *scale_dev, int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status,
+              hipStream_t stream) {
     if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
-    if (FROM_FLOAT && (!Q || ldq < cols || !(scale > 0.0f) || !(scale < 3.0e38f))) return IMUNPACK_EINVAL;
+    if (FROM_FLOAT && (!Q || ldq < cols || (!scale_dev && (!(scale > 0.0f) || !(scale < 3.0e38f))))) return IMUNPACK_EINVAL;
     if (sx_r < 1 || sx_c < 1) return IMUNPACK_EINVAL;
     IMU_TRY(zero_stats(st, rows, cols, FROM_FLOAT ? status : nullptr, stream));
     if (rows == 0 || cols == 0) return IMUNPACK_OK;
@@ -444,24 +456,31 @@ static int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, in
         if ((rows + rpw - 1) / rpw > 65535) rpw = ((rows + 65534) / 65535 + 3) / 4 * 4;
         dim3 grid((unsigned)cblocks, (unsigned)((rows + rpw - 1) / rpw));
         hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count,
+                           scale, scale_dev, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count,
                            (int)rpw);
     } else if (sx_r == 1 && (rows % 4) == 0 && (cols % 4) == 0 && (sx_c % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
                (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0)) && (cols + kTrTile - 1) / kTrTile <= 65535) {
         dim3 grid((unsigned)((rows + kTrTile - 1) / kTrTile), (unsigned)((cols + kTrTile - 1) / kTrTile));
-        hipLaunchKernelGGL(qscan_tr_kernel<FROM_FLOAT>, grid, dim3(kTrThreads), 0, stream, X, rows, cols, sx_c, scale, s, Q,
+        hipLaunchKernelGGL(qscan_tr_kernel<FROM_FLOAT>, grid, dim3(kTrThreads), 0, stream, X, rows, cols, sx_c, scale, scale_dev, s, Q,
                            ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     } else {
         dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
         hipLaunchKernelGGL(qscan_tile_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           sx_c, scale, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
+                           sx_c, scale, scale_dev, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count);
     }
     return launch_status();
 }
 
+// quantize with the step kept on the device (the batched call)
+int quantize_dev_step(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, const float *step_dev,
+                      int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status, hipStream_t stream) {
+    if (!step_dev) return IMUNPACK_EINVAL;
+    return run_qscan<true>(X, rows, cols, sx_r, sx_c, 1.0f, step_dev, b, Q, ldq, st, status, stream);
+}
+
 int scan_i32(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
              const imunpack_stats_t *st, hipStream_t stream) {
-    return run_qscan<false>(Q, rows, cols, ldq, 1, 1.0f, b, nullptr, 0, st, nullptr, stream);
+    return run_qscan<false>(Q, rows, cols, ldq, 1, 1.0f, nullptr, b, nullptr, 0, st, nullptr, stream);
 }
 
 }  // namespace imu
@@ -470,7 +489,7 @@ extern "C" int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int
                                  float scale, int b, int32_t *Q, int64_t ldq,
                                  const imunpack_stats_t *stats, int32_t *status,
                                  imunpack_stream_t stream) {
-    return imu::run_qscan<true>(X, rows, cols, sx_r, sx_c, scale, b, Q, ldq, stats, status,
+    return imu::run_qscan<true>(X, rows, cols, sx_r, sx_c, scale, nullptr, b, Q, ldq, stats, status,
                                 (hipStream_t)stream);
 }
 

@@ -7,11 +7,10 @@ Sec. 1 ("Notations") of arXiv 2403.07339 lists the GEMMs of a Transformer; for a
     grad_W = grad_Y^T  X     (backward, weight)
 
 Each is computed as in Sec. 2: both operands are RTN-quantised with the step alpha_p / (0.5 beta)
-(Eq. (quantized_A); alpha_p from ``imunpack_percentile``), the integer GEMM is evaluated exactly with
-b-bit digits (Sec. 4: plan, unpack, int8 MFMA GEMM, recombination) and the result is scaled back
-(Eq. (quantized_gemm)).  The weights stay in fp32 (master copy); nothing here allocates through
-anything but torch.  Integration on top of the C ABI binding: every arithmetic step runs in the HIP
-library.
+(Eq. (quantized_A)), the integer GEMM is evaluated exactly with b-bit digits (Sec. 4: plan, unpack,
+int8 MFMA GEMM, recombination) and the result is scaled back (Eq. (quantized_gemm)) -- all inside
+``imunpack_gemm_batched`` of the C ABI, which keeps the steps on the device.  The weights stay in fp32
+(master copy).  Integration only: every arithmetic step of the method runs in the HIP library.
 """
 from __future__ import annotations
 
@@ -36,25 +35,11 @@ class QuantConfig:
     strategy_b: int = imu.BOTH
 
 
-def rtn_step(t: torch.Tensor, p: float, beta: float) -> float:
-    """alpha_p(t) / (0.5 beta) in binary32; a matrix whose p-th percentile is 0 (mostly zeros) falls
-    back to its largest magnitude, an all-zero matrix to 1."""
-    alpha, status = imu.imunpack_percentile(t, p)
-    if int(status.item()) != 0:
-        raise ValueError("NaN in a GEMM operand")
-    a = alpha.item()
-    if not a > 0.0:
-        a = float(t.abs().max().item())
-    if not a > 0.0 or a == float("inf"):
-        return 1.0
-    return float(torch.tensor(a, dtype=torch.float32) / torch.tensor(0.5 * beta, dtype=torch.float32))
-
-
 def quantized_matmul(A: torch.Tensor, B: torch.Tensor, beta_a: float, beta_b: float, cfg: QuantConfig) -> torch.Tensor:
-    """A B^T for A: n x d, B: h x d (fp32 device tensors, any strides), on the exact integer path."""
-    sa, sb = rtn_step(A, cfg.p, beta_a), rtn_step(B, cfg.p, beta_b)
-    _, C_fp, _ = imu.exact_int_gemm(A, B, sa, sb, cfg.b, cfg.strategy_a, cfg.strategy_b, want_int=False, want_fp=True)
-    return C_fp
+    """A B^T for A: n x d, B: h x d (fp32 device tensors, any strides), on the exact integer path: one
+    call of the library's batched entry point with a batch of one.  The RTN steps alpha_p / (0.5 beta) are
+    formed and used on the device; nothing of the method is computed here."""
+    return imu.imunpack_gemm_batched(A, B, cfg.p, beta_a, beta_b, cfg.b, cfg.strategy_a, cfg.strategy_b)
 
 
 class _LinearFunction(torch.autograd.Function):

@@ -614,3 +614,49 @@ def test_random_shapes_strategies_and_densities(imu, seed):
     if rng.random() < 0.5 and h > 2:      # heavy rows of B
         Bq[rng.integers(0, h, 2), :] = rng.integers(-(s ** depth), s ** depth + 1, size=(2, d)).astype(np.int32)
     check_against_oracle(imu, Aq, Bq, b, sa, sb)
+
+
+def test_rtn_step_on_the_device(imu):
+    """alpha_p / (0.5 beta) formed on the device against the oracle's order statistic and binary32 division;
+    the fall-backs for a mostly-zero and an all-zero matrix (largest magnitude, then 1)."""
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn((300, 260), generator=g) * 0.7
+    x[torch.rand(x.shape, generator=g) < 0.01] *= 90.0
+    xd = dev(x)
+    for p, beta, view, view_d in ((95.0, 31.0, x, xd), (99.0, 255.0, x.t(), xd.t()), (50.0, 15.0, x[:, ::2], xd[:, ::2])):
+        step, status = imu.imunpack_rtn_step(view_d, p, beta)
+        want = oracle.rtn_step(oracle.percentile_alpha(view.contiguous().numpy(), p), beta)
+        assert int(status.item()) == 0
+        assert step.cpu().numpy().view(np.uint32)[0] == np.float32(want).view(np.uint32)
+    sparse = torch.zeros((64, 64))
+    sparse[3, 5] = -7.5                                    # the 95th percentile of the magnitudes is 0
+    step, _ = imu.imunpack_rtn_step(dev(sparse), 95.0, 31.0)
+    assert step.item() == float(np.float32(7.5) / np.float32(15.5))
+    step, _ = imu.imunpack_rtn_step(dev(torch.zeros((64, 64))), 95.0, 31.0)
+    assert step.item() == 1.0
+
+
+@pytest.mark.parametrize("b,strategies", [(8, (BOTH, BOTH)), (4, (ROW, COL)), (6, (COL, BOTH))])
+def test_gemm_batched_matches_the_oracle_chain_per_item(imu, b, strategies):
+    """imunpack_gemm_batched: five products of one shape in one call, operands passed as strided views (one
+    of them transposed), each against the oracle chain percentile -> step -> RTN -> exact int64 GEMM -> fp64
+    dequantisation on that item's own operands; a second call on the same context with a smaller shape."""
+    g = torch.Generator().manual_seed(500 + b)
+    ctx = imu.BatchContext()
+    for batch, n, d, h in ((5, 48, 72, 56), (2, 17, 40, 9)):
+        a = torch.randn((batch, n, d), generator=g)
+        a[:, :, 3] *= 25.0
+        bt = torch.randn((batch, d, h), generator=g) * 0.03          # stored d x h: B_i is its transpose
+        bt[torch.rand(bt.shape, generator=g) < 0.004] *= 30.0
+        A_d, B_d = dev(a), dev(bt).transpose(-1, -2)
+        out = imu.imunpack_gemm_batched(A_d, B_d, 95.0, 31.0, 63.0, b, strategies[0], strategies[1], ctx=ctx)
+        assert out.shape == (batch, n, h)
+        got = out.cpu().numpy().astype(np.float64)
+        for i in range(batch):
+            want = _oracle_matmul(a[i].numpy(), bt[i].t().contiguous().numpy(), 95.0, 31.0, 63.0)
+            assert (np.abs(got[i] - want) <= REL_TOL * np.abs(want)).all(), i
+    with pytest.raises(imu.ImunpackError):                           # a NaN in one item is reported
+        bad = a.clone()
+        bad[1, 2, 3] = float("nan")
+        imu.imunpack_gemm_batched(dev(bad), B_d, 95.0, 31.0, 63.0, b, strategies[0], strategies[1], ctx=ctx)
+    ctx.destroy()

@@ -113,6 +113,23 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     lib.imunpack_price.restype = ctypes.c_int
     lib.imunpack_price.argtypes = [vp, i64, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
     assert lib.imunpack_price(None, 4, None, 4, 4, 8, fake, fake, fake, fake, fake, None) == EINVAL
+    lib.imunpack_rtn_step.restype = ctypes.c_int
+    lib.imunpack_rtn_step.argtypes = [vp, i64, i64, i64, i64, f64, f32, vp, vp, vp, vp]
+    assert lib.imunpack_rtn_step(fake, 4, 4, 4, 1, 95.0, 0.0, fake, None, fake, None) == EINVAL      # beta 0
+    assert lib.imunpack_rtn_step(fake, 4, 4, 4, 1, 95.0, 31.0, None, None, fake, None) == EINVAL     # nowhere to put the step
+    lib.imunpack_gemm_batched.restype = ctypes.c_int
+    lib.imunpack_gemm_batched.argtypes = [vp, i64, i64, i64, vp, i64, i64, i64, i64, i64, i64, i64, f64, f32, f32, i32, i32,
+                                          i32, vp, i64, i64, vp, vp]
+    bctx = vp(None)
+    bref = ctypes.byref(bctx)
+    assert lib.imunpack_gemm_batched(fake, 16, 4, 1, fake, 16, 4, 1, 2, 4, 4, 4, 95.0, 31.0, 31.0, 8, 0, 0, fake, 16, 3, bref, None) == EINVAL   # ldc < h
+    assert lib.imunpack_gemm_batched(fake, 16, 4, 0, fake, 16, 4, 1, 2, 4, 4, 4, 95.0, 31.0, 31.0, 8, 0, 0, fake, 16, 4, bref, None) == EINVAL   # stride 0
+    assert lib.imunpack_gemm_batched(fake, 16, 4, 1, fake, 16, 4, 1, 2, 4, 4, 4, 95.0, 31.0, 31.0, 8, 0, 5, fake, 16, 4, bref, None) == EINVAL   # strategy
+    assert lib.imunpack_gemm_batched(fake, 16, 4, 1, fake, 16, 4, 1, 2, 4, 4, 4, 0.0, 31.0, 31.0, 8, 0, 0, fake, 16, 4, bref, None) == EINVAL    # p
+    assert lib.imunpack_gemm_batched(fake, 16, 4, 1, fake, 16, 4, 1, 2, 4, 4, 4, 95.0, 31.0, 31.0, 8, 0, 0, fake, 16, 4, None, None) == EINVAL   # no context slot
+    assert bctx.value is None
+    lib.imunpack_batch_destroy.restype = ctypes.c_int
+    assert lib.imunpack_batch_destroy(None) == 0
     lib.imunpack_diag_mfma_peak.restype = ctypes.c_int
     lib.imunpack_diag_mfma_peak.argtypes = [i32, i32, vp, vp]
     assert lib.imunpack_diag_mfma_peak(0, 10, None, None) == EINVAL
