@@ -231,9 +231,10 @@ def main():
             if marks is not None:
                 marks[i].record()
         mark(0)
-        imu.imunpack_quantize(A, w.scale_a, w.b, Qa, st_a, status[0:1])
         if quantize_b:
-            imu.imunpack_quantize(B, w.scale_b, w.b, Qb, st_b, status[1:2])
+            imu.imunpack_quantize_pair(A, B, w.scale_a, w.scale_b, w.b, Qa, Qb, st_a, st_b, status)
+        else:
+            imu.imunpack_quantize(A, w.scale_a, w.b, Qa, st_a, status[0:1])
         mark(1)
         imu.imunpack_plan(Qa, Qb, w.b, w.strategy_a, w.strategy_b, st_a, st_b, plan)
         mark(2)
@@ -309,7 +310,7 @@ def main():
                      "traffic": traffic.get("gemm_i8_kernel"), "ms": gemm_ms, "ops": gemm_ops,
                      "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
         "roofline_passes": {
-            "quantize+scan": hbm_entry(["qscan_vec_kernel", "qscan_tr_kernel", "qscan_tile_kernel", "zero_lists_kernel"],
+            "quantize+scan": hbm_entry(["qscan_vec_pair_kernel", "qscan_vec_kernel", "qscan_tr_kernel", "qscan_tile_kernel", "zero_lists_kernel"],
                                        q_bytes, stage_ms[0]),
             "scatter": hbm_entry(["scatter_kernel", "fixup_kernel", "bound_kernel"], u_bytes, stage_ms[2],
                                  {"stored_and_read_bytes": 4.0 * (n * d + h * d) + ba + bb}),

@@ -135,6 +135,17 @@ int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int64_t sx_r, 
                       float scale, int b, int32_t *Q, int64_t ldq,
                       const imunpack_stats_t *stats, int32_t *status, imunpack_stream_t stream);
 
+/* The same for both operands of one product A B^T (A: n x d, B: h x d, Sec. 2 Eq. (quantized_A) applied to
+ * each with its own step): results as two imunpack_quantize calls, issued as one clearing launch and,
+ * when both operands take the unit-column-stride fast path, one launch over the rows of both (fewer
+ * launches, and the shorter operand fills the tail of the longer one).  status (device, may be NULL):
+ * two int32, status[0] for A and status[1] for B.  Errors: as imunpack_quantize. */
+int imunpack_quantize_pair(const float *A, int64_t n, int64_t sa_r, int64_t sa_c, float scale_A, int32_t *QA,
+                           int64_t ldqa, const imunpack_stats_t *stats_A, const float *B, int64_t h,
+                           int64_t sb_r, int64_t sb_c, float scale_B, int32_t *QB, int64_t ldqb,
+                           const imunpack_stats_t *stats_B, int64_t d, int b, int32_t *status,
+                           imunpack_stream_t stream);
+
 /* ---- (2) stand-alone scan of an integer operand (Sec. 4, IB/OB definition) -------------------- */
 int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
                   const imunpack_stats_t *stats, imunpack_stream_t stream);

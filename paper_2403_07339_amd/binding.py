@@ -28,7 +28,7 @@ EXPORTS = [
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
     "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout", "imunpack_rtn_step",
-    "imunpack_gemm_batched", "imunpack_batch_destroy",
+    "imunpack_gemm_batched", "imunpack_batch_destroy", "imunpack_quantize_pair",
 ]
 
 
@@ -39,6 +39,8 @@ class _Stats(C.Structure):
 
 _vp, _i64, _i32, _f32 = C.c_void_p, C.c_int64, C.c_int, C.c_float
 _lib.imunpack_quantize.argtypes = [_vp, _i64, _i64, _i64, _i64, _f32, _i32, _vp, _i64, C.POINTER(_Stats), _vp, _vp]
+_lib.imunpack_quantize_pair.argtypes = [_vp, _i64, _i64, _i64, _f32, _vp, _i64, C.POINTER(_Stats),
+                                        _vp, _i64, _i64, _i64, _f32, _vp, _i64, C.POINTER(_Stats), _i64, _i32, _vp, _vp]
 _lib.imunpack_scan.argtypes = [_vp, _i64, _i64, _i64, _i32, C.POINTER(_Stats), _vp]
 _lib.imunpack_plan.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32,
                                C.POINTER(_Stats), C.POINTER(_Stats), C.POINTER(_vp), _vp]
@@ -174,6 +176,33 @@ def imunpack_quantize(X: torch.Tensor, scale: float, b: int, Q: torch.Tensor | N
                                   Q.data_ptr(), Q.stride(0), C.byref(cs) if cs else None,
                                   status.data_ptr(), _stream()), "imunpack_quantize")
     return Q, stats, status
+
+
+def imunpack_quantize_pair(A: torch.Tensor, B: torch.Tensor, scale_a: float, scale_b: float, b: int,
+                           Qa: torch.Tensor | None = None, Qb: torch.Tensor | None = None,
+                           stats_a: Stats | None = None, stats_b: Stats | None = None,
+                           status: torch.Tensor | None = None, want_ob_list=(False, False)):
+    """imunpack_quantize for both operands of A B^T (A: n x d, B: h x d) with fewer launches.
+    Returns (Qa, Qb, stats_a, stats_b, status) with status[0] for A and status[1] for B."""
+    assert A.is_cuda and B.is_cuda and A.dtype == torch.float32 and B.dtype == torch.float32
+    assert A.dim() == 2 and B.dim() == 2 and A.shape[1] == B.shape[1]
+    (n, d), h = A.shape, B.shape[0]
+    if Qa is None:
+        Qa = torch.empty((n, d), dtype=torch.int32, device=A.device)
+    if Qb is None:
+        Qb = torch.empty((h, d), dtype=torch.int32, device=A.device)
+    if stats_a is None:
+        stats_a = Stats.empty(n, d, A.device, Stats.default_ob_cap(n, d) if want_ob_list[0] else 0)
+    if stats_b is None:
+        stats_b = Stats.empty(h, d, A.device, Stats.default_ob_cap(h, d) if want_ob_list[1] else 0)
+    if status is None:
+        status = torch.empty(2, dtype=torch.int32, device=A.device)
+    ca, cb = stats_a._c(), stats_b._c()
+    _check(_lib.imunpack_quantize_pair(A.data_ptr(), n, A.stride(0), A.stride(1), float(scale_a), Qa.data_ptr(), Qa.stride(0),
+                                       C.byref(ca), B.data_ptr(), h, B.stride(0), B.stride(1), float(scale_b), Qb.data_ptr(),
+                                       Qb.stride(0), C.byref(cb), d, b, status.data_ptr(), _stream()),
+           "imunpack_quantize_pair")
+    return Qa, Qb, stats_a, stats_b, status
 
 
 def imunpack_scan(Q: torch.Tensor, b: int, stats: Stats | None = None) -> Stats:
@@ -327,8 +356,8 @@ def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale
     """The whole hot path: quantize -> plan -> unpack -> GEMM (+ recombine, dequantise).
     Returns (C_int or None, C_fp or None, plan)."""
     dev = A_fp.device
-    Aq, sa, st_a = imunpack_quantize(A_fp, scale_a, b, want_ob_list=strategy_a == BOTH)
-    Bq, sb, st_b = imunpack_quantize(B_fp, scale_b, b, want_ob_list=strategy_b == BOTH)
+    Aq, Bq, sa, sb, st = imunpack_quantize_pair(A_fp, B_fp, scale_a, scale_b, b,
+                                                want_ob_list=(strategy_a == BOTH, strategy_b == BOTH))
     plan = imunpack_plan(Aq, Bq, b, strategy_a, strategy_b, sa, sb, plan)
     A_ue, B_eu = imunpack_unpack(plan, Aq, Bq)
     n, h = A_fp.shape[0], B_fp.shape[0]
@@ -342,7 +371,7 @@ def exact_int_gemm(A_fp: torch.Tensor, B_fp: torch.Tensor, scale_a: float, scale
     else:
         imunpack_gemm(plan, A_ue, B_eu, scale_a, scale_b, None, None, ws, fuse=False)
         imunpack_recombine(plan, ws, scale_a, scale_b, C_int, C_fp)
-    if int(st_a.item()) or int(st_b.item()):
+    if int(st.amax().item()):
         raise ImunpackError(ERANGE, "imunpack_quantize status")
     return C_int, C_fp, plan
 

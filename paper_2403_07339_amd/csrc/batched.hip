@@ -14,8 +14,10 @@
 #include <new>
 
 namespace imu {
-int quantize_dev_step(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, const float *step_dev,
-                      int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status, hipStream_t stream);
+int quantize_pair(const float *A, int64_t n, int64_t sa_r, int64_t sa_c, float scale_A, const float *scale_A_dev,
+                  int32_t *QA, int64_t ldqa, const imunpack_stats_t *stA, const float *B, int64_t h, int64_t sb_r,
+                  int64_t sb_c, float scale_B, const float *scale_B_dev, int32_t *QB, int64_t ldqb,
+                  const imunpack_stats_t *stB, int64_t d, int b, int32_t *status, hipStream_t stream);
 int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *workspace, int64_t *C_int,
               float *C_fp, int64_t ldc, float scale_A, float scale_B, const float *scale_a_dev,
               const float *scale_b_dev, int fuse, imunpack_stream_t stream);
@@ -123,8 +125,8 @@ extern "C" int imunpack_gemm_batched(const float *A, int64_t sa_b, int64_t sa_r,
         // the steps stay on the device: percentile -> step -> division in the quantizer -> product in the epilogue
         IMU_TRY(imunpack_rtn_step(Ai, n, d, sa_r, sa_c, p, beta_A, steps, flags, pws, st));
         IMU_TRY(imunpack_rtn_step(Bi, h, d, sb_r, sb_c, p, beta_B, steps + 1, flags + 1, pws, st));
-        IMU_TRY(quantize_dev_step(Ai, n, d, sa_r, sa_c, steps, b, Qa, d, &stA, flags + 2, st));
-        IMU_TRY(quantize_dev_step(Bi, h, d, sb_r, sb_c, steps + 1, b, Qb, d, &stB, flags + 3, st));
+        IMU_TRY(quantize_pair(Ai, n, sa_r, sa_c, 1.0f, steps, Qa, d, &stA, Bi, h, sb_r, sb_c, 1.0f, steps + 1, Qb, d, &stB, d,
+                              b, flags + 2, st));
         hipLaunchKernelGGL(gather_status_kernel, dim3(1), dim3(64), 0, st, flags, 4, any);
         IMU_TRY(imunpack_plan(Qa, n, d, d, Qb, h, d, b, strategy_A, strategy_B, &stA, &stB, &c->plan, st));
         size_t ba = 0, bb = 0, bw = 0;

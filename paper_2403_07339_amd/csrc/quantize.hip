@@ -9,9 +9,26 @@
 
 namespace imu {
 
-__device__ __forceinline__ int wave_max_i32(int v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, 64));
+// Largest of a non-negative value over the wave, valid in lane 63 only.  Data-parallel-primitive moves
+// inside the vector ALU (shifts within a row of 16 lanes, then the last lane of a row broadcast to the
+// next rows); lanes without a source read 0, the neutral element here.
+__device__ __forceinline__ int wave_max_nonneg_lane63(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true));  // row_shr:1
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true));  // row_shr:2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));  // row_shr:4
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true));  // row_shr:8
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1 and 3
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// The same over each half of the wave, valid in lanes 31 and 63.
+__device__ __forceinline__ int half_wave_max_nonneg_last(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));
     return v;
 }
 
@@ -115,41 +132,53 @@ __device__ __forceinline__ void ob_flush(ObStage *sg, int32_t *ob, int ob_cap, i
 
 // Fast path: unit column stride, 16-byte aligned rows.  Workgroup = rows_per_wg rows x 256 columns;
 // a wave reads one 1 KiB row segment per instruction (float4 per lane).
+struct VecOperand {
+    const void *X;
+    int64_t rows, ldx;
+    float scale_val;
+    const float *scale_ptr;
+    int32_t *Q;
+    int64_t ldq;
+    int32_t *rowcnt, *colcnt, *rowmax, *colmax, *status, *ob;
+    int ob_cap;
+    int32_t *ob_count;
+    int rows_per_wg;
+    int row_blocks;  // workgroups along the rows
+};
+
 template <bool FROM_FLOAT>
-__global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__ Xv, int64_t rows,
-                                                        int64_t cols, int64_t ldx, float scale_val,
-                                                        const float *scale_ptr, int s,
-                                                        int32_t *__restrict__ Q, int64_t ldq,
-                                                        int32_t *rowcnt, int32_t *colcnt,
-                                                        int32_t *rowmax, int32_t *colmax,
-                                                        int32_t *status, int32_t *ob, int ob_cap,
-                                                        int32_t *ob_count, int rows_per_wg) {
-    __shared__ int lds[2 * 4 * 256];
-    __shared__ ObStage stage;
+__device__ __forceinline__ void qscan_vec_body(const VecOperand &a, int64_t cols, int s, int by, int *lds, ObStage &stage) {
+    const void *__restrict__ Xv = a.X;
+    int32_t *__restrict__ Q = a.Q;
+    const int64_t rows = a.rows, ldx = a.ldx, ldq = a.ldq;
+    int32_t *rowcnt = a.rowcnt, *colcnt = a.colcnt, *rowmax = a.rowmax, *colmax = a.colmax, *status = a.status;
+    int32_t *ob = a.ob, *ob_count = a.ob_count;
+    const int ob_cap = a.ob_cap, rows_per_wg = a.rows_per_wg;
     if (ob) {
         if (threadIdx.x == 0) stage.count = 0;
         __syncthreads();
     }
-    const float scale = step_of(scale_val, scale_ptr);
+    const float scale = step_of(a.scale_val, a.scale_ptr);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // Workgroup ids are dealt round-robin to the 8 XCDs; rotating the column block with the row block
     // lets every XCD touch every column block (and so every memory channel) while the workgroups that
     // run together still cover whole rows.
-    const int cbx = (blockIdx.x + blockIdx.y) % gridDim.x;
+    const int cbx = (blockIdx.x + by) % gridDim.x;
     const int64_t c0 = (int64_t)cbx * 256 + lane * 4;
-    const int64_t r_base = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t r_base = (int64_t)by * rows_per_wg;
     const int64_t r_end = min(rows, r_base + rows_per_wg);
     int ccnt[4] = {0, 0, 0, 0}, cmax[4] = {0, 0, 0, 0};
     int bad = 0;
     const bool in_cols = c0 < cols;  // cols % 4 == 0 on this path
-    // four rows per step: their loads are issued together, before any of them is used
+    // four rows per step: their loads are issued together, before any of them is used (keeping the next
+    // step's loads in flight as well was slower: 0.113 against 0.105 ms for both operands of the benchmark)
     for (int64_t rb = r_base + wave; rb < r_end; rb += 16) {  // uniform per wave
         int4 raw[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int64_t r = rb + 4 * v;
             raw[v] = make_int4(0, 0, 0, 0);
-            if (in_cols && r < r_end)  // read once: non-temporal (0.125 -> 0.109 ms for both operands of the benchmark workload)
+            if (in_cols && r < r_end)  // read once: non-temporal (0.125 -> 0.109 ms)
                 raw[v] = load_nt16(reinterpret_cast<const int32_t *>(Xv) + r * ldx + c0);
         }
 #pragma unroll
@@ -170,23 +199,27 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
             cmax[0] = max(cmax[0], a0); cmax[1] = max(cmax[1], a1);
             cmax[2] = max(cmax[2], a2); cmax[3] = max(cmax[3], a3);
             // row statistics: popcount of the wave's ballots, wave-wide max
+            const unsigned long long b0 = __ballot(o0), b1 = __ballot(o1), b2 = __ballot(o2), b3 = __ballot(o3);
+            const int n0 = __popcll(b0), n1 = __popcll(b1), n2 = __popcll(b2), n3 = __popcll(b3);
+            const int rc = n0 + n1 + n2 + n3;
             if (rowcnt || rowmax) {
-                const int rc = __popcll(__ballot(o0)) + __popcll(__ballot(o1)) + __popcll(__ballot(o2)) +
-                               __popcll(__ballot(o3));
-                const int rm = wave_max_i32(max(max(a0, a1), max(a2, a3)));
-                if (lane == 0) {
+                const int rm = wave_max_nonneg_lane63(max(max(a0, a1), max(a2, a3)));
+                if (lane == 63) {
                     if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
                     if (rowmax && rm) atomicMax(&rowmax[r], rm);
                 }
             }
-            if (ob) {  // rare, lane by lane: append the OB entries (row, column, value) to the staged list
-                const int qv[4] = {q.x, q.y, q.z, q.w};
-                const int ov[4] = {o0, o1, o2, o3};
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (ov[u])
-                        ob_push(&stage, atomicAdd(&stage.count, 1), (int32_t)r, (int32_t)(c0 + u), qv[u], ob,
-                                ob_cap, ob_count);
+            if (ob && rc) {  // uniform per wave, rare: append the OB entries (row, column, value) to the staged list
+                int base = 0;
+                if (lane == 0) base = atomicAdd(&stage.count, rc);
+                base = __shfl(base, 0, 64);
+                const unsigned long long below = (1ull << lane) - 1ull;
+                const int p0 = base + __popcll(b0 & below), p1 = base + n0 + __popcll(b1 & below),
+                          p2 = base + n0 + n1 + __popcll(b2 & below), p3 = base + n0 + n1 + n2 + __popcll(b3 & below);
+                if (o0) ob_push(&stage, p0, (int32_t)r, (int32_t)c0, q.x, ob, ob_cap, ob_count);
+                if (o1) ob_push(&stage, p1, (int32_t)r, (int32_t)(c0 + 1), q.y, ob, ob_cap, ob_count);
+                if (o2) ob_push(&stage, p2, (int32_t)r, (int32_t)(c0 + 2), q.z, ob, ob_cap, ob_count);
+                if (o3) ob_push(&stage, p3, (int32_t)r, (int32_t)(c0 + 3), q.w, ob, ob_cap, ob_count);
             }
         }
     }
@@ -194,6 +227,23 @@ __global__ __launch_bounds__(256) void qscan_vec_kernel(const void *__restrict__
     if (colcnt || colmax)
         flush_columns<4>(ccnt, cmax, (int64_t)cbx * 256, cols, colcnt, colmax, lds);
     if (FROM_FLOAT && status && __ballot(bad) && lane == 0) atomicOr(status, 1);
+}
+
+template <bool FROM_FLOAT>
+__global__ __launch_bounds__(256) void qscan_vec_kernel(VecOperand a, int64_t cols, int s) {
+    __shared__ int lds[2 * 4 * 256];
+    __shared__ ObStage stage;
+    qscan_vec_body<FROM_FLOAT>(a, cols, s, blockIdx.y, lds, stage);
+}
+
+// Both operands of a product (same inner dimension) in one launch: the row blocks of the second follow
+// those of the first, so that the end of the one overlaps the start of the other.
+__global__ __launch_bounds__(256) void qscan_vec_pair_kernel(VecOperand a, VecOperand b, int64_t cols, int s) {
+    __shared__ int lds[2 * 4 * 256];
+    __shared__ ObStage stage;
+    const int by = blockIdx.y;
+    if (by < a.row_blocks) qscan_vec_body<true>(a, cols, s, by, lds, stage);
+    else qscan_vec_body<true>(b, cols, s, by - a.row_blocks, lds, stage);
 }
 
 // General path: any strides.  Workgroup = 64 x 64 tile staged through LDS so that reads follow the
@@ -244,8 +294,8 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
         cmax[0] = max(cmax[0], a);
         const unsigned long long bo = __ballot(o);
         const int rc = __popcll(bo);
-        const int rm = wave_max_i32(a);
-        if (lane == 0 && r < rows) {
+        const int rm = wave_max_nonneg_lane63(a);
+        if (lane == 63 && r < rows) {
             if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
             if (rowmax && rm) atomicMax(&rowmax[r], rm);
         }
@@ -330,9 +380,8 @@ __global__ __launch_bounds__(kTrThreads) void qscan_tr_kernel(const void *__rest
             int rc = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) rc += __popcll(__ballot(o[i]) & mine);
-#pragma unroll
-            for (int off = 16; off > 0; off >>= 1) rm = max(rm, __shfl_xor(rm, off, 64));  // inside the half-wave
-            if (l32 == 0 && r < rows) {
+            rm = half_wave_max_nonneg_last(rm);
+            if (l32 == 31 && r < rows) {
                 if (rowcnt && rc) atomicAdd(&rowcnt[r], rc);
                 if (rowmax && rm) atomicMax(&rowmax[r], rm);
             }
@@ -395,14 +444,15 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const float4 *__restri
     }
 }
 
-// Clears up to six int32 arrays in one launch.
+// Clears up to twelve int32 arrays (the statistics of two operands) in one launch.
+constexpr int kZeroArrays = 12;
 struct ZeroList {
-    int32_t *p[6];
-    int64_t len[6];
+    int32_t *p[kZeroArrays];
+    int64_t len[kZeroArrays];
 };
 __global__ void zero_lists_kernel(ZeroList z) {
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < kZeroArrays; ++i) {
         int32_t *p = z.p[i];
         const int64_t len = z.len[i];
         if (!p) continue;
@@ -411,19 +461,22 @@ __global__ void zero_lists_kernel(ZeroList z) {
     }
 }
 
-static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, int32_t *status,
-                      hipStream_t stream) {
-    ZeroList z;
+// adds the arrays of one operand's statistics to the list, from entry `at` on; returns the longest of them
+static int64_t list_stats(ZeroList &z, int at, const imunpack_stats_t *st, int64_t rows, int64_t cols, int32_t *status) {
     int64_t longest = 0;
-    for (int i = 0; i < 6; ++i) { z.p[i] = nullptr; z.len[i] = 0; }
+    for (int i = 0; i < 6; ++i) { z.p[at + i] = nullptr; z.len[at + i] = 0; }
     if (st) {
         int32_t *p[4] = {st->rowcnt, st->colcnt, st->rowmax, st->colmax};
         const int64_t len[4] = {rows, cols, rows, cols};
         for (int i = 0; i < 4; ++i)
-            if (p[i] && len[i] > 0) { z.p[i] = p[i]; z.len[i] = len[i]; longest = len[i] > longest ? len[i] : longest; }
-        if (st->ob && st->ob_count) { z.p[4] = st->ob_count; z.len[4] = 1; longest = longest > 1 ? longest : 1; }
+            if (p[i] && len[i] > 0) { z.p[at + i] = p[i]; z.len[at + i] = len[i]; longest = len[i] > longest ? len[i] : longest; }
+        if (st->ob && st->ob_count) { z.p[at + 4] = st->ob_count; z.len[at + 4] = 1; longest = longest > 1 ? longest : 1; }
     }
-    if (status) { z.p[5] = status; z.len[5] = 1; longest = longest > 1 ? longest : 1; }
+    if (status) { z.p[at + 5] = status; z.len[at + 5] = 1; longest = longest > 1 ? longest : 1; }
+    return longest;
+}
+
+static int zero_listed(const ZeroList &z, int64_t longest, hipStream_t stream) {
     if (longest == 0) return IMUNPACK_OK;
     int blocks = (int)((longest + 255) / 256);
     if (blocks > 256) blocks = 256;
@@ -431,13 +484,45 @@ static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, in
     return launch_status();
 }
 
+static int zero_stats(const imunpack_stats_t *st, int64_t rows, int64_t cols, int32_t *status,
+                      hipStream_t stream) {
+    ZeroList z;
+    for (int i = 0; i < kZeroArrays; ++i) { z.p[i] = nullptr; z.len[i] = 0; }
+    return zero_listed(z, list_stats(z, 0, st, rows, cols, status), stream);
+}
+
+// The operand's description for the fast path, if it qualifies (unit column stride, rows and pointers
+// aligned to 16 bytes).
+template <bool FROM_FLOAT>
+static bool vec_operand(VecOperand &o, const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
+                        const float *scale_dev, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status) {
+    const bool vec = sx_c == 1 && (cols % 4) == 0 && (sx_r % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
+                     (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0));
+    if (!vec) return false;
+    int64_t rpw = 64;  // 16, 32 and 128 rows per workgroup were all slower
+    if ((rows + rpw - 1) / rpw > 32767) rpw = ((rows + 32766) / 32767 + 3) / 4 * 4;
+    int32_t *ob = (st && st->ob && st->ob_count && st->ob_cap > 0) ? st->ob : nullptr;
+    o = VecOperand{X, rows, sx_r, scale, scale_dev, Q, ldq,
+                   st ? st->rowcnt : nullptr, st ? st->colcnt : nullptr, st ? st->rowmax : nullptr, st ? st->colmax : nullptr,
+                   status, ob, ob ? (int)st->ob_cap : 0, ob ? st->ob_count : nullptr, (int)rpw, (int)((rows + rpw - 1) / rpw)};
+    return true;
+}
+
+template <bool FROM_FLOAT>
+static int check_qscan_args(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
+                            const float *scale_dev, int b, const int32_t *Q, int64_t ldq, const imunpack_stats_t *st) {
+    if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
+    if (FROM_FLOAT && (!Q || ldq < cols || (!scale_dev && (!(scale > 0.0f) || !(scale < 3.0e38f))))) return IMUNPACK_EINVAL;
+    if (sx_r < 1 || sx_c < 1) return IMUNPACK_EINVAL;
+    if (st && st->ob_cap > 0x7fffffff / 3) return IMUNPACK_EINVAL;
+    return IMUNPACK_OK;
+}
+
 template <bool FROM_FLOAT>
 int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, float scale,
               const float *scale_dev, int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status,
               hipStream_t stream) {
-    if (!X || rows < 0 || cols < 0 || b < 2 || b > 8) return IMUNPACK_EINVAL;
-    if (FROM_FLOAT && (!Q || ldq < cols || (!scale_dev && (!(scale > 0.0f) || !(scale < 3.0e38f))))) return IMUNPACK_EINVAL;
-    if (sx_r < 1 || sx_c < 1) return IMUNPACK_EINVAL;
+    IMU_TRY(check_qscan_args<FROM_FLOAT>(X, rows, cols, sx_r, sx_c, scale, scale_dev, b, Q, ldq, st));
     IMU_TRY(zero_stats(st, rows, cols, FROM_FLOAT ? status : nullptr, stream));
     if (rows == 0 || cols == 0) return IMUNPACK_OK;
     const int s = 1 << (b - 1);
@@ -445,19 +530,12 @@ int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t s
     int32_t *rowmax = st ? st->rowmax : nullptr, *colmax = st ? st->colmax : nullptr;
     int32_t *ob = (st && st->ob && st->ob_count && st->ob_cap > 0) ? st->ob : nullptr;
     int32_t *ob_count = ob ? st->ob_count : nullptr;
-    if (st && st->ob_cap > 0x7fffffff / 3) return IMUNPACK_EINVAL;
     const int ob_cap = ob ? (int)st->ob_cap : 0;
     if (!FROM_FLOAT && !rowcnt && !colcnt && !rowmax && !colmax && !ob) return IMUNPACK_OK;
-    const bool vec = sx_c == 1 && (cols % 4) == 0 && (sx_r % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
-                     (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0));
-    if (vec) {
-        const int64_t cblocks = (cols + 255) / 256;
-        int64_t rpw = 64;  // 16, 32 and 128 rows per workgroup were all slower
-        if ((rows + rpw - 1) / rpw > 65535) rpw = ((rows + 65534) / 65535 + 3) / 4 * 4;
-        dim3 grid((unsigned)cblocks, (unsigned)((rows + rpw - 1) / rpw));
-        hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, X, rows, cols, sx_r,
-                           scale, scale_dev, s, Q, ldq, rowcnt, colcnt, rowmax, colmax, status, ob, ob_cap, ob_count,
-                           (int)rpw);
+    VecOperand vo;
+    if (vec_operand<FROM_FLOAT>(vo, X, rows, cols, sx_r, sx_c, scale, scale_dev, Q, ldq, st, status)) {
+        dim3 grid((unsigned)((cols + 255) / 256), (unsigned)vo.row_blocks);
+        hipLaunchKernelGGL(qscan_vec_kernel<FROM_FLOAT>, grid, dim3(256), 0, stream, vo, cols, s);
     } else if (sx_r == 1 && (rows % 4) == 0 && (cols % 4) == 0 && (sx_c % 4) == 0 && ((uintptr_t)X % 16) == 0 &&
                (!FROM_FLOAT || ((ldq % 4) == 0 && ((uintptr_t)Q % 16) == 0)) && (cols + kTrTile - 1) / kTrTile <= 65535) {
         dim3 grid((unsigned)((rows + kTrTile - 1) / kTrTile), (unsigned)((cols + kTrTile - 1) / kTrTile));
@@ -471,11 +549,32 @@ int run_qscan(const void *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t s
     return launch_status();
 }
 
-// quantize with the step kept on the device (the batched call)
-int quantize_dev_step(const float *X, int64_t rows, int64_t cols, int64_t sx_r, int64_t sx_c, const float *step_dev,
-                      int b, int32_t *Q, int64_t ldq, const imunpack_stats_t *st, int32_t *status, hipStream_t stream) {
-    if (!step_dev) return IMUNPACK_EINVAL;
-    return run_qscan<true>(X, rows, cols, sx_r, sx_c, 1.0f, step_dev, b, Q, ldq, st, status, stream);
+// Both operands of one product: a single clearing launch and, when both take the fast path, a single
+// quantise-and-scan launch; otherwise one call after the other.  A step is a value of the call or, when
+// its device pointer is given (the batched call keeps the steps on the device), read from there.
+int quantize_pair(const float *A, int64_t n, int64_t sa_r, int64_t sa_c, float scale_A, const float *scale_A_dev,
+                  int32_t *QA, int64_t ldqa, const imunpack_stats_t *stA, const float *B, int64_t h, int64_t sb_r,
+                  int64_t sb_c, float scale_B, const float *scale_B_dev, int32_t *QB, int64_t ldqb,
+                  const imunpack_stats_t *stB, int64_t d, int b, int32_t *status, hipStream_t stream) {
+    int32_t *stat_a = status, *stat_b = status ? status + 1 : nullptr;
+    IMU_TRY(check_qscan_args<true>(A, n, d, sa_r, sa_c, scale_A, scale_A_dev, b, QA, ldqa, stA));
+    IMU_TRY(check_qscan_args<true>(B, h, d, sb_r, sb_c, scale_B, scale_B_dev, b, QB, ldqb, stB));
+    VecOperand va, vb;
+    const bool paired = n > 0 && h > 0 && d > 0 &&
+                        vec_operand<true>(va, A, n, d, sa_r, sa_c, scale_A, scale_A_dev, QA, ldqa, stA, stat_a) &&
+                        vec_operand<true>(vb, B, h, d, sb_r, sb_c, scale_B, scale_B_dev, QB, ldqb, stB, stat_b);
+    if (!paired) {
+        IMU_TRY(run_qscan<true>(A, n, d, sa_r, sa_c, scale_A, scale_A_dev, b, QA, ldqa, stA, stat_a, stream));
+        return run_qscan<true>(B, h, d, sb_r, sb_c, scale_B, scale_B_dev, b, QB, ldqb, stB, stat_b, stream);
+    }
+    ZeroList z;
+    const int64_t la = list_stats(z, 0, stA, n, d, stat_a), lb = list_stats(z, 6, stB, h, d, stat_b);
+    IMU_TRY(zero_listed(z, std::max(la, lb), stream));
+    const bool b_first = vb.row_blocks > va.row_blocks;  // the longer operand first: the shorter one fills its tail
+    const VecOperand &first = b_first ? vb : va, &second = b_first ? va : vb;
+    dim3 grid((unsigned)((d + 255) / 256), (unsigned)(first.row_blocks + second.row_blocks));
+    hipLaunchKernelGGL(qscan_vec_pair_kernel, grid, dim3(256), 0, stream, first, second, d, 1 << (b - 1));
+    return launch_status();
 }
 
 int scan_i32(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,
@@ -491,6 +590,15 @@ extern "C" int imunpack_quantize(const float *X, int64_t rows, int64_t cols, int
                                  imunpack_stream_t stream) {
     return imu::run_qscan<true>(X, rows, cols, sx_r, sx_c, scale, nullptr, b, Q, ldq, stats, status,
                                 (hipStream_t)stream);
+}
+
+extern "C" int imunpack_quantize_pair(const float *A, int64_t n, int64_t sa_r, int64_t sa_c, float scale_A, int32_t *QA,
+                                      int64_t ldqa, const imunpack_stats_t *stats_A, const float *B, int64_t h,
+                                      int64_t sb_r, int64_t sb_c, float scale_B, int32_t *QB, int64_t ldqb,
+                                      const imunpack_stats_t *stats_B, int64_t d, int b, int32_t *status,
+                                      imunpack_stream_t stream) {
+    return imu::quantize_pair(A, n, sa_r, sa_c, scale_A, nullptr, QA, ldqa, stats_A, B, h, sb_r, sb_c, scale_B, nullptr, QB,
+                              ldqb, stats_B, d, b, status, (hipStream_t)stream);
 }
 
 extern "C" int imunpack_scan(const int32_t *Q, int64_t rows, int64_t cols, int64_t ldq, int b,

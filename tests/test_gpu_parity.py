@@ -74,6 +74,41 @@ def test_quantize_and_scan(imu, shape, b):
     assert np.array_equal(sts.colcnt.cpu().numpy(), cc) and np.array_equal(sts.rowmax.cpu().numpy(), rm)
 
 
+@pytest.mark.parametrize("n,h,d,b", [(200, 333, 520, 8), (70, 64, 256, 4), (1, 129, 4, 8), (130, 131, 130, 8), (64, 1, 256, 8)])
+def test_quantize_pair_matches_the_oracle_for_both_operands(imu, n, h, d, b):
+    """Both operands of a product in one call (one clearing launch, one launch over the rows of both when
+    both take the fast path; d = 130 takes the general path): integers, all four statistics, the OB lists
+    and the two status flags against the oracle's RTN (Sec. 2, Eq. quantized_A) and the IB/OB definition
+    (Sec. 4); a NaN in B raises only B's flag."""
+    g = torch.Generator().manual_seed(n + 31 * h + d + b)
+    xa, xb = torch.randn((n, d), generator=g) * 2, torch.randn((h, d), generator=g)
+    xa[torch.rand((n, d), generator=g) < 0.02] *= 150.0
+    xb[torch.rand((h, d), generator=g) < 0.01] *= 90.0
+    sa, sb = float(np.float32(0.0371)), float(np.float32(0.0113))
+    s = 1 << (b - 1)
+    sta = imu.Stats.empty(n, d, "cuda", ob_cap=max(1, n * d))
+    stb = imu.Stats.empty(h, d, "cuda", ob_cap=max(1, h * d))
+    Qa, Qb, sta, stb, status = imu.imunpack_quantize_pair(dev(xa), dev(xb), sa, sb, b, stats_a=sta, stats_b=stb)
+    assert status.cpu().tolist() == [0, 0]
+    for x, scale, Q, st in ((xa, sa, Qa, sta), (xb, sb, Qb, stb)):
+        if x.shape[0] == 0:
+            continue
+        want = oracle_quant(x, scale)
+        assert np.array_equal(Q.cpu().numpy(), want)
+        rc, cc, rm, cm = np_stats(want, s)
+        assert np.array_equal(st.rowcnt.cpu().numpy(), rc) and np.array_equal(st.colcnt.cpu().numpy(), cc)
+        assert np.array_equal(st.rowmax.cpu().numpy(), rm) and np.array_equal(st.colmax.cpu().numpy(), cm)
+        ii, jj = np.nonzero(np.abs(want.astype(np.int64)) >= s)
+        n_ob = int(st.ob_count.item())
+        assert n_ob == len(ii)
+        ob = st.ob[:, :n_ob].cpu().numpy()
+        assert sorted(zip(ob[0].tolist(), ob[1].tolist(), ob[2].tolist())) == sorted(zip(ii.tolist(), jj.tolist(), want[ii, jj].tolist()))
+    if h > 0:
+        xb[h // 2, d // 3] = float("nan")
+        *_, status = imu.imunpack_quantize_pair(dev(xa), dev(xb), sa, sb, b)
+        assert status.cpu().tolist() == [0, 1]
+
+
 @pytest.mark.parametrize("shape,b,frac", [((300, 520), 8, 0.01), ((132, 260), 4, 0.2), ((1024, 384), 8, 0.0005),
                                           ((256, 256), 2, 0.9)])
 def test_ob_entry_list_for_every_input_layout(imu, shape, b, frac):

@@ -72,6 +72,12 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert lib.imunpack_quantize(fake, -1, 4, 4, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL
     assert lib.imunpack_quantize(fake, 4, 4, 0, 1, 1.0, 8, fake, 4, None, None, None) == EINVAL      # stride 0
     assert lib.imunpack_quantize(fake, 4, 4, 4, -1, 1.0, 8, fake, 4, None, None, None) == EINVAL     # negative stride
+    lib.imunpack_quantize_pair.restype = ctypes.c_int
+    lib.imunpack_quantize_pair.argtypes = [vp, i64, i64, i64, f32, vp, i64, vp, vp, i64, i64, i64, f32, vp, i64, vp, i64, i32, vp, vp]
+    pair = lambda A=fake, n=4, sa_c=1, sc_a=1.0, QB=fake, ldqb=4, b=8: lib.imunpack_quantize_pair(
+        A, n, 4, sa_c, sc_a, fake, 4, None, fake, 4, 4, 1, 1.0, QB, ldqb, None, 4, b, None, None)
+    assert pair(A=None) == EINVAL and pair(QB=None) == EINVAL and pair(b=9) == EINVAL and pair(sc_a=0.0) == EINVAL
+    assert pair(ldqb=3) == EINVAL and pair(n=-1) == EINVAL and pair(sa_c=0) == EINVAL
     lib.imunpack_scan.restype = ctypes.c_int
     lib.imunpack_scan.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     assert lib.imunpack_scan(None, 4, 4, 4, 8, None, None) == EINVAL
