@@ -130,6 +130,46 @@ struct ColLayout {
     int32_t *ktile_ablk;  // [Kp/128] block of the A store that GEMM k-tile t reads
 };
 
+// ---- wave-wide reductions and scans on the vector ALU's data-parallel-primitive moves (shifts within a
+// row of 16 lanes, then the last lane of a row broadcast to the following rows) instead of permutes
+// through LDS.  Lanes without a source read 0, so these serve sums and maxima of non-negative values.
+#if defined(__HIPCC__)
+#define IMU_DPP(v, ctrl, rows, zero_fill) __builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), (rows), 0xf, (zero_fill))
+// Inclusive prefix sum over the 64 lanes (lane 63 holds the wave's total).
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+    v += IMU_DPP(v, 0x111, 0xf, true);   // row_shr:1
+    v += IMU_DPP(v, 0x112, 0xf, true);   // row_shr:2
+    v += IMU_DPP(v, 0x114, 0xf, true);   // row_shr:4
+    v += IMU_DPP(v, 0x118, 0xf, true);   // row_shr:8
+    v += IMU_DPP(v, 0x142, 0xa, false);  // row_bcast:15 into rows 1 and 3
+    v += IMU_DPP(v, 0x143, 0xc, false);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+// Sum over the wave, valid in lane 63 only.
+__device__ __forceinline__ unsigned wave_sum_lane63(unsigned v) { return (unsigned)wave_inclusive_sum((int)v); }
+// Largest of a non-negative value over the wave, valid in lane 63 only.
+__device__ __forceinline__ int wave_max_nonneg_lane63(int v) {
+    v = max(v, IMU_DPP(v, 0x111, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x112, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x114, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x118, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x142, 0xa, false));
+    v = max(v, IMU_DPP(v, 0x143, 0xc, false));
+    return v;
+}
+// The same over each half of the wave, valid in lanes 31 and 63.
+__device__ __forceinline__ int half_wave_max_nonneg_last(int v) {
+    v = max(v, IMU_DPP(v, 0x111, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x112, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x114, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x118, 0xf, true));
+    v = max(v, IMU_DPP(v, 0x142, 0xa, false));
+    return v;
+}
+// Lane 63's value in every lane (a scalar register).
+__device__ __forceinline__ int from_lane63(int v) { return __builtin_amdgcn_readlane(v, 63); }
+#endif
+
 }  // namespace imu
 
 // Opaque plan object.

@@ -30,11 +30,10 @@ constexpr int kPlanWaves = kPlanThreads / 64;
 // ---------------------------------------------------------------------------------------------
 // workgroup-wide helpers (kPlanThreads threads)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int block_max(int v, int *lds /* >= 40 ints */) {
+__device__ __forceinline__ int block_max(int v /* >= 0 */, int *lds /* >= 40 ints */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, 64));
-    if (lane == 0) lds[wave] = v;
+    v = wave_max_nonneg_lane63(v);
+    if (lane == 63) lds[wave] = v;
     __syncthreads();
     int r = lds[0];
 #pragma unroll
@@ -110,9 +109,8 @@ __device__ __forceinline__ int ordered_scan(int N, int base, V value, E emit, in
         const int x = x0 + lane;
         if (x < hi) sum += value(x);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    if (lane == 0) lds[wave] = sum;
+    sum = wave_inclusive_sum(sum);
+    if (lane == 63) lds[wave] = sum;
     __syncthreads();
     int run = base, total = 0;
 #pragma unroll
@@ -124,14 +122,9 @@ __device__ __forceinline__ int ordered_scan(int N, int base, V value, E emit, in
     for (int x0 = lo; x0 < hi; x0 += 64) {
         const int x = x0 + lane;
         const int v = x < hi ? value(x) : 0;
-        int incl = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
-        }
+        const int incl = wave_inclusive_sum(v);
         if (x < hi) emit(x, run + incl - v);
-        run += __shfl(incl, 63, 64);
+        run += from_lane63(incl);
     }
     __syncthreads();
     return total;
@@ -382,12 +375,9 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             }
             m1 = max(max(m1, max(c.x, c.y)), max(c.z, c.w));
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            m0 = max(m0, __shfl_xor(m0, off, 64));
-            m1 = max(m1, __shfl_xor(m1, off, 64));
-        }
-        if (lane == 0) {
+        m0 = wave_max_nonneg_lane63(m0);
+        m1 = wave_max_nonneg_lane63(m1);
+        if (lane == 63) {
             atomicMax(&s_top[0], m0);
             atomicMax(&s_top[1], m1);
         }

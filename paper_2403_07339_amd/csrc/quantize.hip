@@ -9,29 +9,6 @@
 
 namespace imu {
 
-// Largest of a non-negative value over the wave, valid in lane 63 only.  Data-parallel-primitive moves
-// inside the vector ALU (shifts within a row of 16 lanes, then the last lane of a row broadcast to the
-// next rows); lanes without a source read 0, the neutral element here.
-__device__ __forceinline__ int wave_max_nonneg_lane63(int v) {
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true));  // row_shr:1
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true));  // row_shr:2
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));  // row_shr:4
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true));  // row_shr:8
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1 and 3
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2 and 3
-    return v;
-}
-
-// The same over each half of the wave, valid in lanes 31 and 63.
-__device__ __forceinline__ int half_wave_max_nonneg_last(int v) {
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true));
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true));
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true));
-    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));
-    return v;
-}
-
 // The RTN step: a value of the call, or (callers that keep it on the device) read from memory.  A step
 // that is not a positive finite number turns every quotient into a flagged 0.
 __device__ __forceinline__ float step_of(float value, const float *ptr) {

@@ -211,18 +211,15 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0
                 const unsigned whi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wgt >> 32), first);
                 const unsigned long long w1 = ((unsigned long long)whi << 32) | wlo;
                 if (__all(wsum == 0 && (mag == 0 || wgt == w1))) {  // one weight: add the magnitudes, weigh once
-                    unsigned t = mag;
-#pragma unroll
-                    for (int off = 32; off > 0; off >>= 1) t += (unsigned)__shfl_xor((int)t, off, 64);
-                    total = sat44(t, w1);
+                    total = sat44(wave_sum_lane63(mag), w1);  // lane 63 holds the sum
                 } else {
                     total = wsum + sat44(mag, wgt);
 #pragma unroll
                     for (int off = 32; off > 0; off >>= 1) total += (unsigned long long)__shfl_xor((long long)total, off, 64);
-                    if (total > (1ull << 44)) total = 1ull << 44;
+                    if (total > (1ull << 44)) total = 1ull << 44;  // every lane holds the sum
                 }
             }
-            if (lane == 0) a.wavesum[(int64_t)p * a.nwin + win] = total;
+            if (lane == 63) a.wavesum[(int64_t)p * a.nwin + win] = total;
         }
     }
 }
