@@ -514,7 +514,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             if (!all) return;
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_count, all);
-            base = __shfl(base, 0, 64);
+            base = __builtin_amdgcn_readfirstlane(base);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (off[u] >= 0) dst[base + off[u]] = e[u];

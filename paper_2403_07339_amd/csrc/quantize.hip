@@ -189,7 +189,7 @@ __device__ __forceinline__ void qscan_vec_body(const VecOperand &a, int64_t cols
             if (ob && rc) {  // uniform per wave, rare: append the OB entries (row, column, value) to the staged list
                 int base = 0;
                 if (lane == 0) base = atomicAdd(&stage.count, rc);
-                base = __shfl(base, 0, 64);
+                base = __builtin_amdgcn_readfirstlane(base);
                 const unsigned long long below = (1ull << lane) - 1ull;
                 const int p0 = base + __popcll(b0 & below), p1 = base + n0 + __popcll(b1 & below),
                           p2 = base + n0 + n1 + __popcll(b2 & below), p3 = base + n0 + n1 + n2 + __popcll(b3 & below);
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void qscan_tile_kernel(const void *__restrict_
         if (ob && rc) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&stage.count, rc);
-            base = __shfl(base, 0, 64);
+            base = __builtin_amdgcn_readfirstlane(base);
             const int pos = base + __popcll(bo & ((1ull << lane) - 1ull));
             if (o) ob_push(&stage, pos, (int32_t)r, (int32_t)c, q, ob, ob_cap, ob_count);
         }
