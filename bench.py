@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, 5.0 POP/s
+FP6_PEAK_TOPS = 10100.0   # dense fp6 / fp4 MFMA peak, 10.1 PFLOP/s
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
 
@@ -185,6 +186,8 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-int64", action="store_true", help="also write the int64 product (parity output)")
+    ap.add_argument("--digits", choices=["int8", "fp6"], default="int8",
+                    help="storage of the digits: fp6 (e2m3 codes on the f8f6f4 matrix instruction) needs b <= 4")
     ap.add_argument("--steps-only", action="store_true",
                     help="only the warm-up and the timed steps, no side measurements: the command the profiles are taken with")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -226,6 +229,10 @@ def main():
     bufs = {"A": None, "B": None, "ws": None}
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
 
+    fp6 = args.digits == "fp6"
+    assert not fp6 or w.b <= 4, "--digits fp6 needs a workload with b <= 4"
+    mfma_peak = FP6_PEAK_TOPS if fp6 else INT8_PEAK_TOPS
+
     def step(marks=None, quantize_b=True, c_int=C_int):
         def mark(i):
             if marks is not None:
@@ -237,6 +244,8 @@ def main():
             imu.imunpack_quantize(A, w.scale_a, w.b, Qa, st_a, status[0:1])
         mark(1)
         imu.imunpack_plan(Qa, Qb, w.b, w.strategy_a, w.strategy_b, st_a, st_b, plan)
+        if fp6 and plan.digits() != imu.DIGITS_FP6:
+            plan.set_digits(imu.DIGITS_FP6)   # stays with the plan object from here on
         mark(2)
         ba, bb, bw = plan.unpacked_bytes()
         if bufs["A"] is None or bufs["A"].numel() < ba:
@@ -297,7 +306,7 @@ def main():
         "dtype": "int8 digits, int32 accumulate, int64 recombine", "data": "synthetic",
         "config": {"workload": w.name, "n": n, "d": d, "h": h, "b": w.b,
                    "strategy": f"{workloads.STRATEGY_NAMES[w.strategy_a]}/{workloads.STRATEGY_NAMES[w.strategy_b]}",
-                   "outputs": "fp32" + ("+int64" if args.with_int64 else "")},
+                   "outputs": "fp32" + ("+int64" if args.with_int64 else ""), "digits": args.digits},
         "frac_of_int8_peak": value / INT8_PEAK_TOPS,
         "unpack": {"n_u": n_u, "d_u": d_u, "h_u": h_u, "groups": ng,
                    "ratio_r": (n_u * d_u * h_u) / (n * d * h), "fused_epilogue": bool(plan.fusable()),
@@ -305,9 +314,9 @@ def main():
                    "stored_columns": {"A_store": wa, "B_eu": wb}},
         "stage_ms": {"quantize+scan": stage_ms[0], "plan": stage_ms[1], "scatter": stage_ms[2],
                      "gemm+recombine+dequant": gemm_ms, "host_gap": ms_step - sum(stage_ms)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel<0>", "achieved": achieved, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
-                     "traffic": traffic.get("gemm_i8_kernel"), "ms": gemm_ms, "ops": gemm_ops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_f6_kernel<0>" if fp6 else "gemm_i8_kernel<0>", "achieved": achieved,
+                     "peak": mfma_peak, "unit": "TOP/s", "frac": achieved / mfma_peak,
+                     "traffic": traffic.get("gemm_f6_kernel" if fp6 else "gemm_i8_kernel"), "ms": gemm_ms, "ops": gemm_ops,
                      "algorithmic_bytes": float(ba + bb + 4 * n * h + (8 * n * h if args.with_int64 else 0))},
         "roofline_passes": {
             "quantize+scan": hbm_entry(["qscan_vec_pair_kernel", "qscan_vec_kernel", "qscan_tr_kernel", "qscan_tile_kernel", "zero_lists_kernel"],
@@ -359,7 +368,7 @@ def main():
     extra = measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
     if clock_mhz:
         out["roofline"]["clock_mhz_in_k_loop"] = clock_mhz
-        out["roofline"]["frac_of_peak_at_that_clock"] = achieved / (INT8_PEAK_TOPS * clock_mhz / 2400.0)
+        out["roofline"]["frac_of_peak_at_that_clock"] = achieved / (mfma_peak * clock_mhz / 2400.0)
     out["weights_prequantized"] = {"ms_per_step": ms_step_wq, "value": w.ops / (ms_step_wq * 1e-3) / 1e12, "unit": "TOPS",
                                    "note": "same step with the RTN integers and scan statistics of B kept from an "
                                            "earlier step (weights are quantised once); not the headline value"}

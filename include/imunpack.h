@@ -208,6 +208,23 @@ int imunpack_plan_export(imunpack_plan_t *plan,
 
 int imunpack_plan_destroy(imunpack_plan_t *plan);
 
+/* ---- digit storage format of the unpacked operands ---------------------------------------------
+ * Sec. 4.2 ("arbitrarily low" bit widths): for b <= 4 every digit lies in [-7, 7] and is exactly
+ * representable in the 6-bit floating-point format e2m3 (1 sign, 2 exponent, 3 mantissa bits), which the
+ * matrix cores multiply at twice the int8 rate and which takes three quarters of the bytes.  The
+ * products and their sums are integers below 2^24 in binary32 accumulators, hence exact (the call
+ * checks the bound, as it does for int32); results are bit-identical to the int8 path.
+ * IMUNPACK_DIGITS_INT8 (default): one int8 per digit.  IMUNPACK_DIGITS_FP6: 96 bytes per 128 columns; a
+ * group of 64 columns takes 48 bytes: the 32 columns of each half form a 192-bit string (column j at
+ * bits 6j .. 6j+5), stored as the first 16 bytes of both strings followed by the last 8 bytes of both.  The request stays with the plan object
+ * across re-planning and is in effect whenever the plan's b <= 4 (a plan with b > 4 keeps int8);
+ * imunpack_plan_digits returns the format in effect.  Call after imunpack_plan and before
+ * imunpack_unpacked_bytes / imunpack_unpack: the format changes the sizes and the row pitches.
+ * Errors: EINVAL (no valid plan, unknown format, FP6 on a plan with b > 4). */
+enum { IMUNPACK_DIGITS_INT8 = 0, IMUNPACK_DIGITS_FP6 = 1 };
+int imunpack_plan_set_digits(imunpack_plan_t *plan, int format);
+int imunpack_plan_digits(const imunpack_plan_t *plan);
+
 /* ---- (4) digit scatter (Eq. (mod); Alg. 1 l.4-5, Alg. 2 l.4-6, Alg. 4 l.7-8, 11-13) -----------
  * Writes the unpacked operands as int8 in the plan's *physical* layout: rows grouped by source row (all
  * digit levels of a row of A inside one 64-row chunk of a GEMM tile, of a row of B inside one tile),

@@ -28,8 +28,10 @@ EXPORTS = [
     "imunpack_gemm", "imunpack_recombine", "imunpack_strerror", "imunpack_last_hip_error",
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
     "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout", "imunpack_rtn_step",
-    "imunpack_gemm_batched", "imunpack_batch_destroy", "imunpack_quantize_pair",
+    "imunpack_gemm_batched", "imunpack_batch_destroy", "imunpack_quantize_pair", "imunpack_plan_set_digits",
+    "imunpack_plan_digits",
 ]
+DIGITS_INT8, DIGITS_FP6 = 0, 1
 
 
 class _Stats(C.Structure):
@@ -53,6 +55,8 @@ _lib.imunpack_gemm_batched.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _
                                        _f32, _f32, _i32, _i32, _i32, _vp, _i64, _i64, C.POINTER(_vp), _vp]
 _lib.imunpack_batch_destroy.argtypes = [_vp]
 _lib.imunpack_plan_layout.argtypes = [_vp, C.POINTER(_i64)]
+_lib.imunpack_plan_set_digits.argtypes = [_vp, _i32]
+_lib.imunpack_plan_digits.argtypes = [_vp]
 _lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
 _lib.imunpack_unpack_canonical.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.imunpack_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _i32, _vp]
@@ -267,6 +271,13 @@ class Plan:
         a, b_, w = C.c_size_t(), C.c_size_t(), C.c_size_t()
         _check(_lib.imunpack_unpacked_bytes(self._h, C.byref(a), C.byref(b_), C.byref(w)), "imunpack_unpacked_bytes")
         return a.value, b_.value, w.value
+
+    def set_digits(self, fmt: int):
+        """DIGITS_INT8 or DIGITS_FP6 (b <= 4): the storage format of the digits from the next unpack on."""
+        _check(_lib.imunpack_plan_set_digits(self._h, int(fmt)), "imunpack_plan_set_digits")
+
+    def digits(self) -> int:
+        return int(_lib.imunpack_plan_digits(self._h))
 
     def layout(self):
         """((rows, stored columns, row pitch in bytes) of the A store, the same of B_eu)."""

@@ -166,6 +166,15 @@ __device__ __forceinline__ int half_wave_max_nonneg_last(int v) {
     v = max(v, IMU_DPP(v, 0x142, 0xa, false));
     return v;
 }
+// 6-bit floating-point digits in memory.  The matrix instruction takes, per lane, 32 consecutive columns of a
+// row as one 192-bit string (column j of the fragment at bits 6j .. 6j+5).  A row stores its columns in
+// groups of 64 (48 bytes): the first 128 bits of the group's two fragments (16 bytes each), then their
+// last 64 bits (8 bytes each), so that a lane reads its fragment as one aligned 16-byte and one aligned
+// 8-byte piece.  Returns the position, in 32-bit words from the start of the row, of word i (0..5) of
+// fragment `frag` (0, 1) of group `grp`.
+__host__ __device__ __forceinline__ int fp6_dword(int grp, int frag, int i) {
+    return 12 * grp + (i < 4 ? 4 * frag + i : 8 + 2 * frag + (i - 4));
+}
 // Lane 63's value in every lane (a scalar register).
 __device__ __forceinline__ int from_lane63(int v) { return __builtin_amdgcn_readlane(v, 63); }
 #endif
@@ -215,6 +224,8 @@ struct imunpack_plan {
     int fusable;      // set by imunpack_unpack
     int unpacked;
     int valid;
+    int digits_req;   // IMUNPACK_DIGITS_*: what imunpack_plan_set_digits asked for (kept across re-planning)
+    int fp6;          // in effect for the current plan: 6-bit floating-point digits (requested and b <= 4)
 };
 
 namespace imu {
@@ -226,4 +237,11 @@ using Plan = struct ::imunpack_plan;  // the C function imunpack_plan() hides th
 int fetch_header(Plan *p, size_t offset, size_t bytes, hipStream_t st);
 // Waits for the bounds that imunpack_unpack left in flight and sets p->fusable.
 int resolve_bound(Plan *p);
+// Bytes from one physical row to the next of the A store (op 0) / of B_eu (op 1) in the digit format in
+// effect.  6-bit digits: 96 bytes per k-tile of 128 columns, the same rule against power-of-two pitches.
+inline int64_t store_pitch(const Plan *p, int op) {
+    if (!p->fp6) return op ? p->hdr.ldB : p->hdr.ldA;
+    const int bytes = (op ? p->hdr.Kp : p->hdr.KA) / 4 * 3;
+    return bytes >= 2048 ? (((bytes + 255) / 256) | 1) * 256 : bytes;
+}
 }

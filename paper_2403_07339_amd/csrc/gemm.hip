@@ -23,6 +23,9 @@ namespace imu {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef long v2l __attribute__((ext_vector_type(2)));
 typedef float v4f_u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at any float boundary
@@ -103,13 +106,23 @@ __device__ __forceinline__ const int8_t *uniform_ptr(const int8_t *p) {
 // LDS half-stage: [256 rows][128 B] of one operand; the eight 16-byte chunks of a row are XOR-swizzled
 // with bits 1..3 of the row (chunk kc of row r lives at r*128 + ((kc ^ ((r >> 1) & 7)) << 4)), which
 // makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks) conflict-free.
-template <int MODE>  // 0: fused epilogue, 1: int64 segment into C_u
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs g) {
-    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+//
+// FP6 = true: the digits are 6-bit floating-point codes (b <= 4).  A k-tile is still 128 columns, now 96
+// bytes of a row; LDS rows are 112 bytes apart (seven 16-byte slots, the seventh a repeat of the sixth:
+// with 96 the rows that a wave reads together would share banks two by two); a lane's fragment of
+// v_mfma_f32_32x32x64_f8f6f4 is one 16-byte and one 8-byte read (see fp6_dword); a k-tile is two k-steps
+// of 16 matrix instructions; the accumulators are binary32 and hold integers below 2^24, exactly.
+template <int MODE, bool FP6>  // MODE 0: fused epilogue, 1: int64 segment into C_u
+__device__ __forceinline__ void gemm_body(const GemmArgs &g, int8_t *smem) {
+    constexpr int kRowB = FP6 ? 96 : BK;           // bytes of a row of the operand per k-tile
+    constexpr int kPitch = FP6 ? 112 : BK;         // bytes from row to row in LDS
+    constexpr int kHalfBytes = BM * kPitch;        // the A tile or the B tile of one k-tile in LDS
+    constexpr int kLoads = FP6 ? 7 : 8;            // direct-to-LDS loads per wave and half-stage
+    constexpr int kWaveBytes = 64 * kPitch;        // a wave's 64 rows of a half-stage
     if (MODE == 0 && g.guard) {
         const unsigned long long b0 = g.guard[0], b1 = g.guard[1];
         const unsigned long long m = b0 < b1 ? b0 : b1;
-        if (!(m < (1ull << 40) && m * (unsigned long long)g.guard_mul < (1ull << 31))) return;
+        if (!(m < (1ull << 40) && m * (unsigned long long)g.guard_mul < (1ull << (FP6 ? 24 : 31)))) return;
     }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -125,11 +138,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // which makes the 64-lane ds_read_b128 of an MFMA operand (32 rows x 2 chunks) conflict-free.
     unsigned voffA[8], voffB[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int row = 64 * wave + 8 * u + (lane >> 3);
-        const int kc = (lane & 7) ^ ((row >> 1) & 7);
-        voffA[u] = (unsigned)row * (unsigned)g.ldA + (unsigned)(kc * 16);
-        voffB[u] = (unsigned)row * (unsigned)g.ldB + (unsigned)(kc * 16);
+    for (int u = 0; u < kLoads; ++u) {
+        if (FP6) {  // slot u * 64 + lane of the wave's 64 x 7 slots: row slot / 7, piece slot % 7 (6 repeats 5)
+            const int slot = u * 64 + lane;
+            const int r = slot / 7, piece = min(slot - 7 * r, 5);
+            const int row = 64 * wave + r;
+            voffA[u] = (unsigned)row * (unsigned)g.ldA + (unsigned)(piece * 16);
+            voffB[u] = (unsigned)row * (unsigned)g.ldB + (unsigned)(piece * 16);
+        } else {
+            const int row = 64 * wave + 8 * u + (lane >> 3);
+            const int kc = (lane & 7) ^ ((row >> 1) & 7);
+            voffA[u] = (unsigned)row * (unsigned)g.ldA + (unsigned)(kc * 16);
+            voffB[u] = (unsigned)row * (unsigned)g.ldB + (unsigned)(kc * 16);
+        }
     }
     const int8_t *gA = g.A + (int64_t)m0 * g.ldA, *gB = g.B + (int64_t)n0 * g.ldB;
     // Loads past the end of the range are clamped to the last k-tile: they land in a free slot and
@@ -154,10 +175,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             la_delta = __builtin_amdgcn_readlane(v_delta, la_seg);
             blk = ktc + la_delta;
         }
-        pg = uniform_ptr((isA ? gA : gB) + (int64_t)blk * BK);
-        dl = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(slot * kHalfBytes) + (unsigned)(wave * 8192));
+        pg = uniform_ptr((isA ? gA : gB) + (int64_t)blk * kRowB);
+        dl = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(slot * kHalfBytes) + (unsigned)(wave * kWaveBytes));
     };
-    auto dma_one = [&](bool isA, int u) {  // u = 0..7: rows [64 wave + 8u, +8) of the half-stage set up last
+    auto dma_one = [&](bool isA, int u) {  // u = 0..kLoads-1: the u-th KiB of the wave's rows of the half-stage set up last
         dma16(dl + u * 1024, isA ? voffA[u] : voffB[u], pg);
     };
 
@@ -165,21 +186,44 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     // at chunk 2*ks + lane/32 of the row)
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int swz = (lrow >> 1) & 7;
-    const unsigned fa_base = (unsigned)((wm * 128 + lrow) * BK);
-    const unsigned fb_base = (unsigned)((wn * 128 + lrow) * BK);
+    const unsigned fa_base = (unsigned)((wm * 128 + lrow) * kPitch);
+    const unsigned fb_base = (unsigned)((wn * 128 + lrow) * kPitch);
     unsigned kc_off[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) kc_off[ks] = (unsigned)(((2 * ks + lhalf) ^ swz) << 4);
-    v4i fa[2][4], fb[2][4];
+    for (int ks = 0; ks < 4; ++ks) kc_off[ks] = FP6 ? (unsigned)(48 * ks + 16 * lhalf) : (unsigned)(((2 * ks + lhalf) ^ swz) << 4);
+    using FragT = std::conditional_t<FP6, v8i, v4i>;
+    using AccT = std::conditional_t<FP6, v16f, v16i>;
+    FragT fa[2][4], fb[2][4];
+    if (FP6) {
+#pragma unroll
+        for (int bq = 0; bq < 8; ++bq)
+#pragma unroll
+            for (int r = 0; r < (int)(sizeof(FragT) / 4); ++r) {
+                fa[bq >> 2][bq & 3][r] = 0;
+                fb[bq >> 2][bq & 3][r] = 0;
+            }
+    }
     // fragment q of a k-step in the order the MFMA sequence below first needs them: a0 b0 b1 a1 b2 b3 a2 a3
     auto load_frag = [&](const int8_t *sta, const int8_t *stb, int ks, int buf, int q) {
         constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
         constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
-        if (isA[q]) fa[buf][idx[q]] = *reinterpret_cast<const v4i *>(sta + fa_base + kc_off[ks] + idx[q] * 32 * BK);
-        else fb[buf][idx[q]] = *reinterpret_cast<const v4i *>(stb + fb_base + kc_off[ks] + idx[q] * 32 * BK);
+        const int8_t *src = isA[q] ? sta + fa_base + idx[q] * 32 * kPitch : stb + fb_base + idx[q] * 32 * kPitch;
+        FragT &dst = isA[q] ? fa[buf][idx[q]] : fb[buf][idx[q]];
+        if constexpr (FP6) {
+            const v4i lo = *reinterpret_cast<const v4i *>(src + kc_off[ks]);
+            const v2i hi = *reinterpret_cast<const v2i *>(src + 48 * ks + 32 + 8 * lhalf);
+            dst[0] = lo[0]; dst[1] = lo[1]; dst[2] = lo[2]; dst[3] = lo[3];
+            dst[4] = hi[0]; dst[5] = hi[1];
+        } else {
+            dst = *reinterpret_cast<const v4i *>(src + kc_off[ks]);
+        }
+    };
+    auto mma = [&](const FragT &a, const FragT &b, AccT &c) {
+        if constexpr (FP6) c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 2, 0, 0, 0, 0);  // e2m3 x e2m3, no scaling
+        else c = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
     };
 
-    v16i acc[4][4];
+    AccT acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -197,11 +241,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             load_frag(sta, stb, next_ks, cur ^ 1, q);
-            acc[mi[2 * q]][mj[2 * q]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                fa[cur][mi[2 * q]], fb[cur][mj[2 * q]], acc[mi[2 * q]][mj[2 * q]], 0, 0, 0);
+            mma(fa[cur][mi[2 * q]], fb[cur][mj[2 * q]], acc[mi[2 * q]][mj[2 * q]]);
             if (q < ndma) dma_one(isA, dma0 + q);
-            acc[mi[2 * q + 1]][mj[2 * q + 1]] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                fa[cur][mi[2 * q + 1]], fb[cur][mj[2 * q + 1]], acc[mi[2 * q + 1]][mj[2 * q + 1]], 0, 0, 0);
+            mma(fa[cur][mi[2 * q + 1]], fb[cur][mj[2 * q + 1]], acc[mi[2 * q + 1]][mj[2 * q + 1]]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -216,17 +258,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     int sa = 0;  // ring slot of A(kt); B(kt) is sa+1, A(kt+1) sa+2, B(kt+1) sa+3, A(kt+2) sa+4, B(kt+2) sa
     half_setup(true, kt0, 0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(true, u);
+    for (int u = 0; u < kLoads; ++u) dma_one(true, u);
     half_setup(false, kt0, 1);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(false, u);
+    for (int u = 0; u < kLoads; ++u) dma_one(false, u);
     half_setup(true, kt0 + 1, 2);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(true, u);
+    for (int u = 0; u < kLoads; ++u) dma_one(true, u);
     half_setup(false, kt0 + 1, 3);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) dma_one(false, u);
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    for (int u = 0; u < kLoads; ++u) dma_one(false, u);
+    if (FP6) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -245,6 +288,30 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             // out by hand: left to the compiler, this step spills three blocks to scratch memory.
             const int shv = g.bound_sh[seg - 1];
             int t0, t1, t2, t3;
+            if constexpr (FP6) {  // binary32 accumulators: times 2^shift, exact
+                asm volatile(
+                    "s_nop 15\n\ts_nop 7\n\t"
+                    ".irp n," IMU_ACC_QUADS "\n\t"
+                    "v_accvgpr_read_b32 %[t0], a[\\n]\n\t"
+                    "v_accvgpr_read_b32 %[t1], a[\\n+1]\n\t"
+                    "v_accvgpr_read_b32 %[t2], a[\\n+2]\n\t"
+                    "v_accvgpr_read_b32 %[t3], a[\\n+3]\n\t"
+                    "v_ldexp_f32 %[t0], %[t0], %[sh]\n\t"
+                    "v_ldexp_f32 %[t1], %[t1], %[sh]\n\t"
+                    "v_ldexp_f32 %[t2], %[t2], %[sh]\n\t"
+                    "v_ldexp_f32 %[t3], %[t3], %[sh]\n\t"
+                    "v_accvgpr_write_b32 a[\\n], %[t0]\n\t"
+                    "v_accvgpr_write_b32 a[\\n+1], %[t1]\n\t"
+                    "v_accvgpr_write_b32 a[\\n+2], %[t2]\n\t"
+                    "v_accvgpr_write_b32 a[\\n+3], %[t3]\n\t"
+                    ".endr\n\t"
+                    "s_nop 7"
+                    : [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3), "+a"(acc[0][0]), "+a"(acc[0][1]),
+                      "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]),
+                      "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                      "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
+                    : [sh] "s"(shv));
+            } else
             asm volatile(
                 "s_nop 15\n\ts_nop 7\n\t"  // the last MFMA results must have landed
                 ".irp n," IMU_ACC_QUADS "\n\t"
@@ -274,15 +341,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
             const int8_t *stA1 = smem + ring(sa, 2) * kHalfBytes, *stB1 = smem + ring(sa, 3) * kHalfBytes;
             half_setup(true, kt + 2, ring(sa, 4));
             __builtin_amdgcn_sched_barrier(0);
-            step(0, stA, stB, 1, true, 0, 3);
-            step(1, stA, stB, 2, true, 3, 3);
-            step(0, stA, stB, 3, true, 6, 2);
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            if constexpr (FP6) {  // two k-steps of 64 columns: the first streams A(kt+2), the second B(kt+2)
+                step(0, stA, stB, 1, true, 0, 7);
+                asm volatile("s_waitcnt vmcnt(7) lgkmcnt(0)" ::: "memory");
+            } else {
+                step(0, stA, stB, 1, true, 0, 3);
+                step(1, stA, stB, 2, true, 3, 3);
+                step(0, stA, stB, 3, true, 6, 2);
+                asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             half_setup(false, kt + 2, sa);
             __builtin_amdgcn_sched_barrier(0);
-            step(1, stA1, stB1, 0, false, 0, 8);
+            step(1, stA1, stB1, 0, false, 0, kLoads);
             sa = ring(sa, 2);
         }
     }
@@ -309,7 +381,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
                             buf[(ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD1 + wn * 128 + jj * 32 + lrow] =
-                                acc[(c & 1) * 2 + ii][jj][r];
+                                (int32_t)acc[(c & 1) * 2 + ii][jj][r];
             }
             __syncthreads();
             const int col4 = (tid & 63) * 4;
@@ -412,7 +484,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     foldbuf[(wm * kChunk + ii * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)) * FLD + wn * 128 + jj * 32 + lrow] =
-                        acc[half * 2 + ii][jj][r];
+                        (int32_t)acc[half * 2 + ii][jj][r];
         __syncthreads();
 #pragma unroll 1
         for (int reg = 0; reg < 2; ++reg) {
@@ -577,6 +649,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs
     }
 }
 
+template <int MODE>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_i8_kernel(const GemmArgs g) {
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    gemm_body<MODE, false>(g, smem);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_f6_kernel(const GemmArgs g) {
+    extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+    gemm_body<MODE, true>(g, smem);
+}
+
 // C_int = Pi_A C_u Pi_B^T from the int64 unpacked product, then dequantise.
 __global__ __launch_bounds__(256) void recombine_kernel(const int64_t *__restrict__ C_u, int Np, RowLayout layA,
                                                         RowLayout layB, int n, int h, int sh,
@@ -638,6 +722,8 @@ static int gemm_lds_opt_in() {
     if (!done.load(std::memory_order_acquire)) {
         IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
         IMU_HIP(hipFuncSetAttribute((const void *)gemm_i8_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
+        IMU_HIP(hipFuncSetAttribute((const void *)gemm_f6_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
+        IMU_HIP(hipFuncSetAttribute((const void *)gemm_f6_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds));
         done.store(1, std::memory_order_release);
     }
     return IMUNPACK_OK;
@@ -684,7 +770,7 @@ int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = A_ue; g.B = B_eu;
-    g.ldA = h.ldA; g.ldB = h.ldB; g.Kp = h.Kp; g.mtiles = h.mtiles; g.ntiles = h.ntiles;
+    g.ldA = (int)store_pitch(p, 0); g.ldB = (int)store_pitch(p, 1); g.Kp = h.Kp; g.mtiles = h.mtiles; g.ntiles = h.ntiles;
     g.layA = p->layA; g.layB = p->layB;
     g.flatA = p->layA.tile_flat; g.flatB = p->layB.tile_flat;
     g.sh = p->sh;
@@ -729,7 +815,8 @@ int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *
         g.clock_probe = g_clock_probe.load(std::memory_order_relaxed);
         // |accumulator| < 2^31, weights up to s^(levels of a row - 1 + levels of a column - 1)
         g.fold_f64 = !C_int && 31 + p->sh * ((h.lmaxA - 1) + (h.lmaxB - 1)) <= 52;
-        hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
+        if (p->fp6) hipLaunchKernelGGL(gemm_f6_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
+        else hipLaunchKernelGGL(gemm_i8_kernel<0>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
         IMU_TRY(launch_status());
         if (!speculate) return IMUNPACK_OK;
         IMU_TRY(resolve_bound(p));
@@ -746,7 +833,8 @@ int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *
         g.seg_delta[0] = h.run_blk0[r] - h.run_kt0[r];
         g.seg_shift = p->sh * h.grp_exp[h.run_grp[r]];
         g.seg_first = r == 0;
-        hipLaunchKernelGGL(gemm_i8_kernel<1>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
+        if (p->fp6) hipLaunchKernelGGL(gemm_f6_kernel<1>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
+        else hipLaunchKernelGGL(gemm_i8_kernel<1>, dim3(grid), dim3(kGemmThreads), kGemmLds, st, g);
     }
     IMU_TRY(launch_status());
     if (fuse != 0)  // the caller asked for final outputs: finish the job here

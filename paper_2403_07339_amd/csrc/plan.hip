@@ -1490,6 +1490,7 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         if (!p->hdr.overflow) {
             p->valid = 1;
             p->canon_valid = 0;
+            p->fp6 = p->digits_req == IMUNPACK_DIGITS_FP6 && b <= 4;
             p->bothA = strategy_A == IMUNPACK_BOTH;
             p->bothB = strategy_B == IMUNPACK_BOTH;
             break;

@@ -49,6 +49,7 @@ struct ScatterArgs {
     const unsigned long long *unit_w;  // per unit: the weight its columns share (nullptr: s^exponent of the unit)
     int rows, W, ld, s, sh;      // physical rows, stored columns, bytes from one row of `out` to the next
     int nwin;                    // windows of 1024 stored columns
+    int fp6;                     // store 6-bit floating-point codes (12 bytes per unit) instead of int8 digits
     int items;                   // waves that serve this operand: (rows / kBandRows) * nwin
     int8_t *out;
     unsigned long long *wavesum; // [rows][nwin]: every wave leaves its part of the row norm
@@ -88,6 +89,22 @@ __device__ __forceinline__ int digit0x4(const int (&x)[4], unsigned mask4, unsig
     mag = __builtin_amdgcn_sad_u8(r ^ 0x80808080u, 0x80808080u, mag);  // sum of |int8|
     return (int)r;
 }
+
+// Four int8 digits in [-7, 7] (one per byte) -> their four e2m3 codes (one per byte): magnitudes 0..7 are
+// 0, 1, 2, 1.5*2, 4, 1.25*4, 1.5*4, 1.75*4, i.e. the codes 0, 8, 16, 20, 24, 26, 28, 30; bit 5 is the sign.
+__device__ __forceinline__ unsigned fp6_codes4(unsigned w) {
+    const unsigned n = (w >> 7) & 0x01010101u;   // 1 in the negative bytes
+    const unsigned s = (n << 8) - n;             // 0xff in the negative bytes
+    const unsigned mag = (w ^ s) + n;            // |digit| per byte (no carries: every byte stays below 8)
+    return __builtin_amdgcn_perm(0x1e1c1a18u, 0x14100800u, mag) | (n << 5);
+}
+// ... and squeezed to 24 bits, the first code lowest
+__device__ __forceinline__ unsigned fp6_pack4(unsigned w) {
+    const unsigned c = fp6_codes4(w);
+    return (c & 0x3fu) | ((c >> 2) & 0xfc0u) | ((c >> 4) & 0x3f000u) | ((c >> 6) & 0xfc0000u);
+}
+typedef int v3i_u __attribute__((ext_vector_type(3), aligned(4)));
+typedef int v2i_u __attribute__((ext_vector_type(2), aligned(4)));
 
 __device__ __forceinline__ unsigned long long sat44(unsigned long long m, unsigned long long w) {
     if (m == 0) return 0;
@@ -201,7 +218,28 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0
                 }
                 o = make_int4(pk[0], pk[1], pk[2], pk[3]);
             }
-            if (inside) *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.ld + q0) = o;
+            if (inside) {
+                if (a.fp6) {  // uniform: 16 digits -> 96 bits
+                    const unsigned t0 = fp6_pack4((unsigned)o.x), t1 = fp6_pack4((unsigned)o.y), t2 = fp6_pack4((unsigned)o.z),
+                                   t3 = fp6_pack4((unsigned)o.w);
+                    // the unit is the lower or the upper half of a 32-column fragment (see fp6_dword in common.h)
+                    const int d0 = (int)(t0 | (t1 << 24)), d1 = (int)((t1 >> 8) | (t2 << 16)), d2 = (int)((t2 >> 16) | (t3 << 8));
+                    int8_t *row = a.out + (int64_t)p * a.ld;
+                    const int grp = upos >> 2, frag = (upos >> 1) & 1;
+                    if ((upos & 1) == 0) {
+                        v3i_u w3;
+                        w3.x = d0; w3.y = d1; w3.z = d2;
+                        *reinterpret_cast<v3i_u *>(row + 4 * fp6_dword(grp, frag, 0)) = w3;
+                    } else {
+                        *reinterpret_cast<int *>(row + 4 * fp6_dword(grp, frag, 3)) = d0;
+                        v2i_u w2;
+                        w2.x = d1; w2.y = d2;
+                        *reinterpret_cast<v2i_u *>(row + 4 * fp6_dword(grp, frag, 4)) = w2;
+                    }
+                } else {
+                    *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.ld + q0) = o;
+                }
+            }
             // ---- the wave's part of the row norm
             const unsigned long long nz = __ballot(mag != 0 || wsum != 0);
             unsigned long long total = 0;
@@ -245,6 +283,7 @@ struct FixupArgs {
     const int32_t *out_col;     // per column slot of the second unpacking: the stored column that holds it
     const int32_t *col_phys, *col_sexp;  // its column of B_eu, and per such column the exponent of S
     int W, s, sh;               // bytes from one row of `out` to the next
+    int fp6;                    // `out` holds 6-bit floating-point codes
     int8_t *out;
     unsigned long long *rowsum; // per physical row: what the digits placed here add to the row norm
 };
@@ -315,7 +354,17 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
                 const int p = f.row_phys[R];
                 const int8_t dg = (int8_t)(v < 0 ? -m : m);
                 for (int c = C, hops = 0; c >= 0 && hops < 4096; c = f.second ? -1 : f.c2_child[c], ++hops) {
-                    f.out[(int64_t)p * f.W + f.out_col[c]] = dg;
+                    if (f.fp6) {  // the position holds 0 (the scatter wrote it): OR the code in, 6 bits at bit 6 * column
+                        const unsigned code = (fp6_codes4((unsigned)(uint8_t)dg) & 0x3fu);
+                        const int col = f.out_col[c];
+                        const unsigned bit = 6u * (unsigned)(col & 31);  // inside the 32-column fragment
+                        unsigned *row = reinterpret_cast<unsigned *>(f.out + (int64_t)p * f.W);
+                        const int grp = col >> 6, frag = (col >> 5) & 1, i = (int)(bit >> 5);
+                        atomicOr(row + fp6_dword(grp, frag, i), code << (bit & 31u));
+                        if ((bit & 31u) > 26u) atomicOr(row + fp6_dword(grp, frag, i + 1), code >> (32u - (bit & 31u)));
+                    } else {
+                        f.out[(int64_t)p * f.W + f.out_col[c]] = dg;
+                    }
                     const unsigned nsft = (unsigned)(f.sh * f.col_sexp[f.col_phys[c]]);
                     const unsigned long long term = nsft >= 40u ? (1ull << 44) : ((unsigned long long)m << nsft);
                     add_to_row(f.rowsum, p, term);
@@ -358,11 +407,29 @@ __global__ void reset_bound_kernel(PlanHeader *hdr, unsigned long long *rowsum_a
 
 // canon[R][c] = phys[row_phys[R]][col_phys[c]]; Kp: stored columns per physical row
 __global__ void canonical_kernel(const int8_t *__restrict__ phys, int Kp, const int32_t *row_phys,
-                                 const int32_t *col_phys, int nrows, int ncols, int8_t *__restrict__ canon) {
+                                 const int32_t *col_phys, int nrows, int ncols, int8_t *__restrict__ canon, int fp6) {
     const int R = blockIdx.x;
     if (R >= nrows) return;
     const int8_t *src = phys + (int64_t)row_phys[R] * Kp;
-    for (int c = threadIdx.x; c < ncols; c += blockDim.x) canon[(int64_t)R * ncols + c] = src[col_phys[c]];
+    for (int c = threadIdx.x; c < ncols; c += blockDim.x) {
+        int8_t v;
+        if (fp6) {  // e2m3 code at bit 6 * column -> the integer it stands for (digits are integers)
+            const int col = col_phys[c];
+            const unsigned bit = 6u * (unsigned)(col & 31);
+            const unsigned *row = reinterpret_cast<const unsigned *>(src);
+            const int grp = col >> 6, frag = (col >> 5) & 1, i = (int)(bit >> 5);
+            unsigned long long two = row[fp6_dword(grp, frag, i)];
+            if ((bit & 31u) > 26u) two |= (unsigned long long)row[fp6_dword(grp, frag, i + 1)] << 32;
+            const unsigned code = (unsigned)(two >> (bit & 31u)) & 0x3fu;
+            const unsigned e = (code >> 3) & 3u, m = code & 7u;
+            const unsigned eighths = e == 0 ? m : ((8u + m) << (e - 1));   // value * 8
+            const int mag = (int)(eighths >> 3);
+            v = (int8_t)((code & 32u) ? -mag : mag);
+        } else {
+            v = src[col_phys[c]];
+        }
+        canon[(int64_t)R * ncols + c] = v;
+    }
 }
 
 }  // namespace imu
@@ -372,15 +439,28 @@ using namespace imu;
 extern "C" int imunpack_unpacked_bytes(const imunpack_plan_t *p, size_t *bytes_A, size_t *bytes_B,
                                        size_t *bytes_workspace) {
     if (!p || !p->valid) return IMUNPACK_EINVAL;
-    if (bytes_A) *bytes_A = (size_t)p->hdr.Mp * p->hdr.ldA;
-    if (bytes_B) *bytes_B = (size_t)p->hdr.Np * p->hdr.ldB;
+    if (bytes_A) *bytes_A = (size_t)p->hdr.Mp * (size_t)store_pitch(p, 0);
+    if (bytes_B) *bytes_B = (size_t)p->hdr.Np * (size_t)store_pitch(p, 1);
     if (bytes_workspace) *bytes_workspace = (size_t)p->hdr.Mp * p->hdr.Np * sizeof(int64_t);
     return IMUNPACK_OK;
 }
 
+extern "C" int imunpack_plan_set_digits(imunpack_plan_t *p, int format) {
+    if (!p || !p->valid || (format != IMUNPACK_DIGITS_INT8 && format != IMUNPACK_DIGITS_FP6)) return IMUNPACK_EINVAL;
+    if (format == IMUNPACK_DIGITS_FP6 && p->b > 4) return IMUNPACK_EINVAL;
+    if (p->bound_pending) IMU_TRY(resolve_bound(p));  // of an unpack in the other format
+    p->digits_req = format;
+    p->fp6 = format == IMUNPACK_DIGITS_FP6;
+    return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_plan_digits(const imunpack_plan_t *p) {
+    return (p && p->valid && p->fp6) ? IMUNPACK_DIGITS_FP6 : IMUNPACK_DIGITS_INT8;
+}
+
 extern "C" int imunpack_plan_layout(const imunpack_plan_t *p, int64_t *shape) {
     if (!p || !p->valid || !shape) return IMUNPACK_EINVAL;
-    const int64_t v[6] = {p->hdr.Mp, p->hdr.KA, p->hdr.ldA, p->hdr.Np, p->hdr.Kp, p->hdr.ldB};
+    const int64_t v[6] = {p->hdr.Mp, p->hdr.KA, store_pitch(p, 0), p->hdr.Np, p->hdr.Kp, store_pitch(p, 1)};
     memcpy(shape, v, sizeof(v));
     return IMUNPACK_OK;
 }
@@ -414,7 +494,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         a.col_w = op ? nullptr : p->cols.colA_w;
         a.unit = op ? p->cols.unitB : p->cols.unitA;
         a.unit_w = op ? nullptr : p->cols.unitA_w;
-        a.rows = rowsP; a.W = W; a.ld = op ? h.ldB : h.ldA; a.s = p->s; a.sh = p->sh;
+        a.rows = rowsP; a.W = W; a.ld = (int)store_pitch(p, op); a.s = p->s; a.sh = p->sh; a.fp6 = p->fp6;
         a.nwin = (W + 1023) / 1024;
         a.items = (rowsP / kBandRows) * a.nwin;
         a.out = op ? B_eu : A_ue;
@@ -435,7 +515,7 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
             f.row_phys = lay.row_phys;
             f.out_col = op ? p->cols.col_phys : p->cols.acol_phys;
             f.col_phys = p->cols.col_phys; f.col_sexp = p->cols.col_sexp;
-            f.W = op ? h.ldB : h.ldA; f.s = p->s; f.sh = p->sh;
+            f.W = (int)store_pitch(p, op); f.s = p->s; f.sh = p->sh; f.fp6 = p->fp6;
             f.out = a.out; f.rowsum = lay.rowsum;
             fblocks[op] = (nob + 255) / 256;
         }
@@ -489,7 +569,8 @@ int resolve_bound(Plan *p) {
     // |sum_c s^e(c) a_c b_c| <= (s - 1) * min(bound_A, bound_B): the shifted sum of all groups
     // fits int32 iff that is below 2^31.
     const unsigned long long m = p->hdr.bound[0] < p->hdr.bound[1] ? p->hdr.bound[0] : p->hdr.bound[1];
-    p->fusable = (m < (1ull << 40)) && (m * (unsigned long long)(p->s - 1) < (1ull << 31));
+    // (6-bit floating-point digits accumulate in binary32: exact below 2^24)
+    p->fusable = (m < (1ull << 40)) && (m * (unsigned long long)(p->s - 1) < (1ull << (p->fp6 ? 24 : 31)));
     p->guess_fusable = p->fusable;
     return IMUNPACK_OK;
 }
@@ -518,10 +599,10 @@ extern "C" int imunpack_unpack_canonical(imunpack_plan_t *p, const int8_t *A_ue,
     hipStream_t st = (hipStream_t)stream;
     const PlanHeader &h = p->hdr;
     if (A_ue && A_canon && h.n_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, h.ldA, p->canon_rowphysA,
-                           p->canon_acolphys, h.n_u, h.d_u, A_canon);
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.n_u), dim3(256), 0, st, A_ue, (int)store_pitch(p, 0), p->canon_rowphysA,
+                           p->canon_acolphys, h.n_u, h.d_u, A_canon, p->fp6);
     if (B_eu && B_canon && h.h_u > 0)
-        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, h.ldB, p->canon_rowphysB,
-                           p->canon_colphys, h.h_u, h.d_u, B_canon);
+        hipLaunchKernelGGL(canonical_kernel, dim3(h.h_u), dim3(256), 0, st, B_eu, (int)store_pitch(p, 1), p->canon_rowphysB,
+                           p->canon_colphys, h.h_u, h.d_u, B_canon, p->fp6);
     return launch_status();
 }

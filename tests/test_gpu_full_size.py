@@ -107,6 +107,27 @@ def test_workload_full_size(imu, index):
     imu.imunpack_recombine(plan, ws, w.scale_a, w.scale_b, C2, C2_fp)
     assert np.array_equal(C2.cpu().numpy(), want)
     assert torch.equal(C2_fp, C_fp)          # the same single rounding of the same integers
+    if w.b <= 4:
+        # the same workload with the digits stored as 6-bit floating-point codes (Sec. 4.2, low bit widths):
+        # decoded operands against the oracle's, then the fused launch on the f8f6f4 matrix instruction
+        plan.set_digits(imu.DIGITS_FP6)
+        A6, B6 = imu.imunpack_unpack(plan, Qa, Qb)
+        assert A6.numel() * 4 == A_ue.numel() * 3 or A6.numel() < A_ue.numel()
+        Ac, Bc = imu.imunpack_unpack_canonical(plan, A6, B6)
+        oa, ob_ = hnd.operands_i8()
+        assert np.array_equal(Ac.cpu().numpy(), oa) and np.array_equal(Bc.cpu().numpy(), ob_)
+        del Ac, Bc, oa, ob_
+        assert plan.fusable(), "workload 5 is expected to stay below 2^24 in the binary32 accumulators"
+        C6 = torch.full((w.n, w.h), -1, dtype=torch.int64, device="cuda")
+        C6_fp = torch.full((w.n, w.h), float("nan"), dtype=torch.float32, device="cuda")
+        imu.imunpack_gemm(plan, A6, B6, w.scale_a, w.scale_b, C6, C6_fp, None, fuse=True)
+        assert np.array_equal(C6.cpu().numpy(), want) and torch.equal(C6_fp, C_fp)
+        C6.fill_(-1)
+        imu.imunpack_gemm(plan, A6, B6, w.scale_a, w.scale_b, None, None, ws, fuse=False)
+        imu.imunpack_recombine(plan, ws, w.scale_a, w.scale_b, C6, None)
+        assert np.array_equal(C6.cpu().numpy(), want)
+        del A6, B6, C6, C6_fp
+        plan.set_digits(imu.DIGITS_INT8)
     del ws, C2, C2_fp, want
     # every fp32 output is the rounded dequantisation of its own int64 (checked on the device in fp64)
     ref = C_int.to(torch.float64) * (float(np.float32(w.scale_a)) * float(np.float32(w.scale_b)))

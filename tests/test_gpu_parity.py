@@ -177,9 +177,9 @@ def test_quantize_flags_bad_input(imu):
 
 
 # ------------------------------------------------------------------ plan + operands + product
-def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, full_product=True):
+def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, full_product=True, fp6=False):
     """Aq, Bq: int32 numpy.  Compares plan, unpacked operands, int64 product (fused and un-fused)
-    and the fp32 output with the oracle."""
+    and the fp32 output with the oracle.  fp6: the digits are stored as 6-bit floating-point codes."""
     n, h = Aq.shape[0], Bq.shape[0]
     s = 1 << (b - 1)
     hnd = oracle.unpack_pair_handle(Aq, Bq, b, sa, sb)
@@ -197,6 +197,9 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     assert np.array_equal(rb_s, pbs) and np.array_equal(s ** rb_e.astype(object), pbw.astype(object))
     assert np.array_equal(s ** c_e.astype(object), S.astype(object))
     assert ng == len(np.unique(S))
+    if fp6:
+        plan.set_digits(imu.DIGITS_FP6)
+    assert plan.digits() == (imu.DIGITS_FP6 if fp6 else imu.DIGITS_INT8)
     A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d)
     Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
     oa, ob = hnd.operands_i8()
@@ -207,12 +210,18 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     # repeated columns are read from there), plus a few gathered copies: never more than A_ue holds.
     (ra, wa, pa), (rb, wb, pb) = plan.layout()
     assert A_ue.numel() == ra * pa == plan.unpacked_bytes()[0] and B_eu.numel() == rb * pb == plan.unpacked_bytes()[1]
-    stored_b = B_eu.view(rb, pb)[:, :wb].to(torch.int64)
-    assert int(stored_b.abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
-    stored_a = A_ue.view(ra, pa)[:, :wa].to(torch.int64)
-    assert int(stored_a.abs().sum().item()) <= int(np.abs(oa.astype(np.int64)).sum())
+    if fp6:  # 96 bytes per 128 columns; a zero digit is the code 0, so the number of non-zero bits bounds the padding
+        assert pa >= wa * 3 // 4 and pb >= wb * 3 // 4
+        nz_b = int((B_eu.view(rb, pb)[:, :wb * 3 // 4] != 0).sum().item())
+        assert nz_b <= int((ob != 0).sum())  # every stored non-zero byte holds bits of a non-zero digit...
+        assert nz_b * 2 >= int((ob != 0).sum())  # ... and a byte holds bits of at most two digits
+    else:
+        stored_b = B_eu.view(rb, pb)[:, :wb].to(torch.int64)
+        assert int(stored_b.abs().sum().item()) == int(np.abs(ob.astype(np.int64)).sum())
+        stored_a = A_ue.view(ra, pa)[:, :wa].to(torch.int64)
+        assert int(stored_a.abs().sum().item()) <= int(np.abs(oa.astype(np.int64)).sum())
     assert wa <= wb and wa % 128 == 0 and wb % 128 == 0
-    check_bounds(plan, oa, ob, S, s)
+    check_bounds(plan, oa, ob, S, s, fp6)
     want = oracle.int_gemm(Aq, Bq)
     want_fp = oracle.dequantize(want, scale_a, scale_b)
     ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
@@ -242,7 +251,7 @@ def check_against_oracle(imu, Aq, Bq, b, sa, sb, scale_a=0.013, scale_b=0.0021, 
     return plan
 
 
-def check_bounds(plan, oa, ob, S, s):
+def check_bounds(plan, oa, ob, S, s, fp6=False):
     """The accumulator bounds the scatter measured against their definition, evaluated on the
     oracle's unpacked operands: max over rows of sum_c S[c] |digit|; and the path they select."""
     w = np.array([int(x) for x in S], dtype=object)
@@ -257,7 +266,7 @@ def check_bounds(plan, oa, ob, S, s):
     for g, t in zip(got, want):
         assert g == t if t < (1 << 44) else g >= (1 << 44), (got, want)
     m = min(want)
-    assert plan.fusable() == (m < (1 << 40) and m * (s - 1) < (1 << 31))
+    assert plan.fusable() == (m < (1 << 40) and m * (s - 1) < (1 << (24 if fp6 else 31)))
 
 
 def rand_ints(rng, rows, cols, s, p_ob, depth):
@@ -287,6 +296,42 @@ def test_structured_multi_tile(imu, kind, sa, sb):
     Aq = oracle_quant(w.A, w.scale_a)
     Bq = oracle_quant(w.B, w.scale_b)
     check_against_oracle(imu, Aq, Bq, 8, sa, sb, w.scale_a, w.scale_b)
+
+
+@pytest.mark.parametrize("sa,sb", [(ROW, COL), (BOTH, BOTH), (COL, COL), (COL, ROW), (BOTH, ROW)])
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_six_bit_floating_point_digits(imu, sa, sb, b):
+    """b <= 4 (Sec. 4.2, low bit widths): the digits stored as e2m3 codes and multiplied by the
+    f8f6f4 matrix instruction give the same unpacked operands (decoded) and the same product, bit for bit."""
+    rng = np.random.default_rng(1000 * b + 10 * sa + sb)
+    s = 1 << (b - 1)
+    Aq = rand_ints(rng, 150, 300, s, 0.05, 3 if b > 2 else 5)
+    Bq = rand_ints(rng, 270, 300, s, 0.05, 3 if b > 2 else 5)
+    check_against_oracle(imu, Aq, Bq, b, sa, sb, fp6=True)
+
+
+def test_six_bit_digits_fused_path_and_format_rules(imu):
+    """A case whose accumulator bound stays below 2^24 runs the fused 6-bit kernel (Horner step as a
+    multiplication by a power of two in binary32); the format is refused for b > 4, and a plan object
+    that asked for it goes back to int8 when it is re-planned with b > 4."""
+    rng = np.random.default_rng(77)
+    b, s = 4, 8
+    Aq = rand_ints(rng, 300, 700, s, 0.02, 2)
+    Bq = rand_ints(rng, 520, 700, s, 0.02, 2)
+    plan = check_against_oracle(imu, Aq, Bq, b, COL, COL, fp6=True)
+    assert plan.fusable() and plan.digits() == imu.DIGITS_FP6 and plan.dims()[3] >= 2
+    A8 = rand_ints(rng, 64, 128, 128, 0.02, 2)
+    B8 = rand_ints(rng, 64, 128, 128, 0.02, 2)
+    imu.imunpack_plan(dev(torch.from_numpy(A8)), dev(torch.from_numpy(B8)), 8, ROW, ROW, plan=plan)
+    assert plan.digits() == imu.DIGITS_INT8
+    with pytest.raises(imu.ImunpackError):
+        plan.set_digits(imu.DIGITS_FP6)
+    with pytest.raises(imu.ImunpackError):
+        plan.set_digits(7)
+    imu.imunpack_plan(dev(torch.from_numpy(Aq)), dev(torch.from_numpy(Bq)), b, COL, COL, plan=plan)
+    assert plan.digits() == imu.DIGITS_FP6          # the request stayed with the plan object
+    plan.set_digits(imu.DIGITS_INT8)
+    assert plan.digits() == imu.DIGITS_INT8
 
 
 @pytest.mark.parametrize("b", [3, 5, 6, 7])
