@@ -216,7 +216,8 @@ int imunpack_plan_destroy(imunpack_plan_t *plan);
  * checks the bound, as it does for int32); results are bit-identical to the int8 path.
  * IMUNPACK_DIGITS_INT8 (default): one int8 per digit.  IMUNPACK_DIGITS_FP6: 96 bytes per 128 columns; a
  * group of 64 columns takes 48 bytes: the 32 columns of each half form a 192-bit string (column j at
- * bits 6j .. 6j+5), stored as the first 16 bytes of both strings followed by the last 8 bytes of both.  The request stays with the plan object
+ * bits 6j .. 6j+5), stored as the first 16 bytes of both strings followed by the last 8 bytes of both
+ * (those two in the other order in physical rows whose index has bit 4 set).  The request stays with the plan object
  * across re-planning and is in effect whenever the plan's b <= 4 (a plan with b > 4 keeps int8);
  * imunpack_plan_digits returns the format in effect.  Call after imunpack_plan and before
  * imunpack_unpacked_bytes / imunpack_unpack: the format changes the sizes and the row pitches.

@@ -170,10 +170,12 @@ __device__ __forceinline__ int half_wave_max_nonneg_last(int v) {
 // row as one 192-bit string (column j of the fragment at bits 6j .. 6j+5).  A row stores its columns in
 // groups of 64 (48 bytes): the first 128 bits of the group's two fragments (16 bytes each), then their
 // last 64 bits (8 bytes each), so that a lane reads its fragment as one aligned 16-byte and one aligned
-// 8-byte piece.  Returns the position, in 32-bit words from the start of the row, of word i (0..5) of
-// fragment `frag` (0, 1) of group `grp`.
-__host__ __device__ __forceinline__ int fp6_dword(int grp, int frag, int i) {
-    return 12 * grp + (i < 4 ? 4 * frag + i : 8 + 2 * frag + (i - 4));
+// 8-byte piece.  The two 8-byte pieces change places in the rows whose index has bit 4 set: the thirty-two
+// rows that an 8-byte LDS read serves together then fall on different banks (rows 112 bytes apart).
+// Returns the position, in 32-bit words from the start of the row, of word i (0..5) of fragment `frag`
+// (0, 1) of group `grp` in physical row `row`.
+__host__ __device__ __forceinline__ int fp6_dword(int row, int grp, int frag, int i) {
+    return 12 * grp + (i < 4 ? 4 * frag + i : 8 + 2 * (frag ^ ((row >> 4) & 1)) + (i - 4));
 }
 // Lane 63's value in every lane (a scalar register).
 __device__ __forceinline__ int from_lane63(int v) { return __builtin_amdgcn_readlane(v, 63); }

@@ -211,7 +211,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &g, int8_t *smem) {
         FragT &dst = isA[q] ? fa[buf][idx[q]] : fb[buf][idx[q]];
         if constexpr (FP6) {
             const v4i lo = *reinterpret_cast<const v4i *>(src + kc_off[ks]);
-            const v2i hi = *reinterpret_cast<const v2i *>(src + 48 * ks + 32 + 8 * lhalf);
+            const v2i hi = *reinterpret_cast<const v2i *>(src + 48 * ks + 32 + 8 * (lhalf ^ ((lrow >> 4) & 1)));
             dst[0] = lo[0]; dst[1] = lo[1]; dst[2] = lo[2]; dst[3] = lo[3];
             dst[4] = hi[0]; dst[5] = hi[1];
         } else {

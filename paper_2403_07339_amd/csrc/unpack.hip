@@ -229,12 +229,12 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(ScatterArgs a0
                     if ((upos & 1) == 0) {
                         v3i_u w3;
                         w3.x = d0; w3.y = d1; w3.z = d2;
-                        *reinterpret_cast<v3i_u *>(row + 4 * fp6_dword(grp, frag, 0)) = w3;
+                        *reinterpret_cast<v3i_u *>(row + 4 * fp6_dword(p, grp, frag, 0)) = w3;
                     } else {
-                        *reinterpret_cast<int *>(row + 4 * fp6_dword(grp, frag, 3)) = d0;
+                        *reinterpret_cast<int *>(row + 4 * fp6_dword(p, grp, frag, 3)) = d0;
                         v2i_u w2;
                         w2.x = d1; w2.y = d2;
-                        *reinterpret_cast<v2i_u *>(row + 4 * fp6_dword(grp, frag, 4)) = w2;
+                        *reinterpret_cast<v2i_u *>(row + 4 * fp6_dword(p, grp, frag, 4)) = w2;
                     }
                 } else {
                     *reinterpret_cast<int4 *>(a.out + (int64_t)p * a.ld + q0) = o;
@@ -360,8 +360,8 @@ __global__ void fixup_kernel(FixupArgs fa, FixupArgs fb, int blocks_a, int block
                         const unsigned bit = 6u * (unsigned)(col & 31);  // inside the 32-column fragment
                         unsigned *row = reinterpret_cast<unsigned *>(f.out + (int64_t)p * f.W);
                         const int grp = col >> 6, frag = (col >> 5) & 1, i = (int)(bit >> 5);
-                        atomicOr(row + fp6_dword(grp, frag, i), code << (bit & 31u));
-                        if ((bit & 31u) > 26u) atomicOr(row + fp6_dword(grp, frag, i + 1), code >> (32u - (bit & 31u)));
+                        atomicOr(row + fp6_dword(p, grp, frag, i), code << (bit & 31u));
+                        if ((bit & 31u) > 26u) atomicOr(row + fp6_dword(p, grp, frag, i + 1), code >> (32u - (bit & 31u)));
                     } else {
                         f.out[(int64_t)p * f.W + f.out_col[c]] = dg;
                     }
@@ -418,8 +418,9 @@ __global__ void canonical_kernel(const int8_t *__restrict__ phys, int Kp, const 
             const unsigned bit = 6u * (unsigned)(col & 31);
             const unsigned *row = reinterpret_cast<const unsigned *>(src);
             const int grp = col >> 6, frag = (col >> 5) & 1, i = (int)(bit >> 5);
-            unsigned long long two = row[fp6_dword(grp, frag, i)];
-            if ((bit & 31u) > 26u) two |= (unsigned long long)row[fp6_dword(grp, frag, i + 1)] << 32;
+            const int pr = row_phys[R];
+            unsigned long long two = row[fp6_dword(pr, grp, frag, i)];
+            if ((bit & 31u) > 26u) two |= (unsigned long long)row[fp6_dword(pr, grp, frag, i + 1)] << 32;
             const unsigned code = (unsigned)(two >> (bit & 31u)) & 0x3fu;
             const unsigned e = (code >> 3) & 3u, m = code & 7u;
             const unsigned eighths = e == 0 ? m : ((8u + m) << (e - 1));   // value * 8
