@@ -28,10 +28,10 @@ FP6_PEAK_TOPS = 10100.0   # dense fp6 / fp4 MFMA peak, 10.1 PFLOP/s
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
 
-def profiled_traffic(workload: int):
+def profiled_traffic(workload: int, digits: str = "int8"):
     """HBM bytes per launch by kernel from the tracked rocprofv3 summary of this workload's step
     (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or {} if none is there."""
-    path = os.path.join(ROOT, "profiles", f"bench_workload{workload}_kernels.json")
+    path = os.path.join(ROOT, "profiles", f"bench_workload{workload}{'_fp6' if digits == 'fp6' else ''}_kernels.json")
     if not os.path.exists(path):
         return {}, None
     doc = json.load(open(path))
@@ -285,7 +285,7 @@ def main():
     gemm_ops = 2.0 * n_u * d_u * h_u
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
     value = w.ops / (ms_step * 1e-3) / 1e12
-    traffic, traffic_file = profiled_traffic(args.workload)
+    traffic, traffic_file = profiled_traffic(args.workload, args.digits)
     # algorithmic bytes per launch of the memory-bound passes: quantize + scan moves 4 B in and 4 B out
     # per element; the scatter reads 4 B per source element and owes 1 B per element of the unpacked
     # operands (n' d' + h' d'), of which it stores fewer (repeated columns of A_ue are not stored)
@@ -365,6 +365,30 @@ def main():
         imu.imunpack_diag_clock_probe(None)
         cyc, wall = ticks.tolist()
         clock_mhz = 100.0 * cyc / wall if wall > 0 else None
+    # b <= 4 (Sec. 4.2, low bit widths): the same step with the digits stored as 6-bit floating-point codes and
+    # multiplied by the f8f6f4 matrix instruction; the configuration itself asks for int8, so this is a side figure
+    if w.b <= 4 and not fp6:
+        step()                                  # a plan to hang the request on
+        plan.set_digits(imu.DIGITS_FP6)         # stays with the plan object through the re-planning of every step
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        ev6 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(ev6[k])
+        torch.cuda.synchronize()
+        ms6 = (time.perf_counter() - t0) * 1e3 / args.steps
+        gemm6 = sum(e[4].elapsed_time(e[5]) for e in ev6) / args.steps
+        out["fp6_digits_step"] = {"ms_per_step": ms6, "value": w.ops / (ms6 * 1e-3) / 1e12, "unit": "TOPS",
+                                  "gemm_ms": gemm6, "gemm_kernel": "gemm_f6_kernel<0>",
+                                  "gemm_frac_of_fp6_peak": gemm_ops / (gemm6 * 1e-3) / 1e12 / FP6_PEAK_TOPS,
+                                  "stored_bytes": dict(zip(("A_store", "B_eu"), plan.unpacked_bytes()[:2])),
+                                  "note": "same step, digits as e2m3 codes (96 bytes per 128 columns) on "
+                                          "v_mfma_f32_32x32x64_f8f6f4; results bit-identical; not the headline value"}
+        plan.set_digits(imu.DIGITS_INT8)
+        step()
+        torch.cuda.synchronize()
     extra = measure_extras(torch, imu, workloads, w, Qa, Qb, st_a, st_b, status, A, B, C_fp, args)
     if clock_mhz:
         out["roofline"]["clock_mhz_in_k_loop"] = clock_mhz
