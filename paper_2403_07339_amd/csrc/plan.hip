@@ -283,7 +283,7 @@ __device__ __forceinline__ unsigned long long pack_edge(int row, int col, int le
 template <bool LDS>
 __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g) {
     extern __shared__ __attribute__((aligned(16))) int32_t lds_counts[];
-    __shared__ int s_top[2];
+    __shared__ int s_top[2], s_T[2][4];
     __shared__ int s_pick[kPlanWaves][256];  // per wave: the slots picked in one 256-slot step
     __shared__ int s_found[kPlanWaves], s_positive[kPlanWaves];
     __shared__ int lds[40];
@@ -343,6 +343,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         return;
     }
     int E = (int)Etotal, cur = 0;  // live edges; they are in list `cur`
+    int prev_kind = -1;            // 1: the batch before split rows, 0: columns
     const long long max_batches = 32ll * Etotal + 64;  // every batch retires >= one digit of one entry
     for (long long bid = 0;; ++bid) {
         if (bid > max_batches || bid >= 65535) {
@@ -390,7 +391,99 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         const int N = isrow ? nr : nc;
         // (2) slots with lo <= count <= hi are split in this batch, numbered in index order
         const int hi = isrow ? c0 : c1;
-        const int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
+        int lo = deep ? hi : (isrow ? max(c1, 1) : c0 + 1);
+        // (1b) While the sequential algorithm stays on one side, the counts of that side do not change (no
+        // entry has three digits) and only the top count of the other side falls, so the next batch would
+        // be of the same kind with a lower bound: rows with count >= G(lo), G(lo) = top column count once
+        // the rows with count >= lo are gone (columns: count >= F(lo) + 1).  Every slot down to the fixed
+        // point of that recursion is split before the other side gets a turn, in (count descending, index)
+        // order: one batch.  A read-only pass over the live entries evaluates G at lo, lo-1, lo-2, lo-3 at
+        // once (four 8-bit counters per slot of the other side, kept in the unused upper half of that
+        // side's count vector), which usually covers several steps of the recursion.
+        // Tried only when the batch before was of the same kind: a side's first batch often is its only one.
+        const bool again = prev_kind == (isrow ? 1 : 0);
+        prev_kind = isrow ? 1 : 0;
+        if (LDS && !deep && E > 0 && lo > 1 && again) {
+            const int No = isrow ? nc : nr, No4 = (No + 3) & ~3;
+            const int top_o = isrow ? c1 : c0;
+            if (2 * No4 <= (isrow ? cpad : rpad) - 4 && top_o <= 255) {
+                int32_t *tmp = other + No4;  // zero on entry (slots that do not exist yet) and on exit
+                const unsigned long long *__restrict__ src = cur ? list1 : list0;
+                if (threadIdx.x < 8) (&s_T[0][0])[threadIdx.x] = 0;
+                __syncthreads();
+                for (int round = 0; round < 256; ++round) {
+                    int *T = s_T[round & 1];  // cleared above or during the round before
+                    constexpr int UW = 8;  // 16-byte loads (two entries each) per thread in flight
+                    for (int e0 = 0; e0 < E; e0 += kPlanThreads * 2 * UW) {
+                        unsigned long long ed[2 * UW];
+#pragma unroll
+                        for (int u = 0; u < UW; ++u) {
+                            const int idx = e0 + (u * kPlanThreads + (int)threadIdx.x) * 2;
+                            if (idx + 1 < E) {
+                                const ulonglong2 t = *reinterpret_cast<const ulonglong2 *>(src + idx);
+                                ed[2 * u] = t.x;
+                                ed[2 * u + 1] = t.y;
+                            } else {
+                                ed[2 * u] = idx < E ? src[idx] : 0ull;
+                                ed[2 * u + 1] = 0ull;
+                            }
+                        }
+#pragma unroll
+                        for (int u = 0; u < 2 * UW; ++u) {
+                            const unsigned elo = (unsigned)ed[u], ehi = (unsigned)(ed[u] >> 32);
+                            const unsigned xw = isrow ? elo : ehi, ow = isrow ? ehi : elo;
+                            const int c = cnt[xw & kEdgeSlotMask];  // slot 0's count is harmless for an absent entry ...
+                            const int k = (elo | ehi) ? min(4, max(0, lo - c)) : 0;  // the entry outlives the bounds lo, .., lo - k + 1
+                            if (k) atomicAdd(reinterpret_cast<unsigned *>(&tmp[ow & kEdgeSlotMask]), 0x01010101u >> (8 * (4 - k)));
+                        }
+                    }
+                    __syncthreads();
+                    int m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+                    if (threadIdx.x < 4) s_T[(round & 1) ^ 1][threadIdx.x] = 0;
+                    for (int x = threadIdx.x * 4; x < No4; x += kPlanThreads * 4) {  // read and clear
+                        const int4 v = *reinterpret_cast<const int4 *>(&tmp[x]);
+                        *reinterpret_cast<int4 *>(&tmp[x]) = make_int4(0, 0, 0, 0);
+                        const unsigned w4[4] = {(unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w};
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            m0 = max(m0, (int)(w4[u] & 255u));
+                            m1 = max(m1, (int)((w4[u] >> 8) & 255u));
+                            m2 = max(m2, (int)((w4[u] >> 16) & 255u));
+                            m3 = max(m3, (int)(w4[u] >> 24));
+                        }
+                    }
+                    m0 = wave_max_nonneg_lane63(m0);
+                    m1 = wave_max_nonneg_lane63(m1);
+                    m2 = wave_max_nonneg_lane63(m2);
+                    m3 = wave_max_nonneg_lane63(m3);
+                    if (lane == 63) {
+                        atomicMax(&T[0], m0);
+                        atomicMax(&T[1], m1);
+                        atomicMax(&T[2], m2);
+                        atomicMax(&T[3], m3);
+                    }
+                    __syncthreads();
+                    int now = lo;
+                    bool stable = false;
+                    for (int j = 0; j < 4; j = lo - now) {  // T[j]: the other side's top count with the bound lo - j
+                        const int t = T[j];
+                        const int next = isrow ? max(t, 1) : t + 1;
+                        if (next >= now) {
+                            stable = true;
+                            break;
+                        }
+                        now = next;
+                        if (now <= 1) {  // nothing below: every slot that holds an entry is taken
+                            stable = true;
+                            break;
+                        }
+                    }
+                    lo = now;
+                    if (stable) break;
+                }
+                __syncthreads();  // the cleared counters and the last reads of T, before anything else touches them
+            }
+        }
         const int seg = isrow ? segR : segC;
         const int wlo = wave * seg, whi = min(N, wlo + seg);
         int found = 0, positive = 0;
