@@ -16,6 +16,8 @@
 // persistent workgroup.
 #include "common.h"
 
+#include <type_traits>
+
 #include <algorithm>
 #include <atomic>
 #include <cstring>
@@ -413,30 +415,35 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
                 __syncthreads();
                 for (int round = 0; round < 256; ++round) {
                     int *T = s_T[round & 1];  // cleared above or during the round before
-                    constexpr int UW = 8;  // 16-byte loads (two entries each) per thread in flight
-                    for (int e0 = 0; e0 < E; e0 += kPlanThreads * 2 * UW) {
-                        unsigned long long ed[2 * UW];
+                    auto count_pass = [&](auto isrow_c) {
+                        constexpr bool IR = decltype(isrow_c)::value;
+                        constexpr int UW = 8;  // 16-byte loads (two entries each) per thread in flight
+                        for (int e0 = 0; e0 < E; e0 += kPlanThreads * 2 * UW) {
+                            unsigned long long ed[2 * UW];
 #pragma unroll
-                        for (int u = 0; u < UW; ++u) {
-                            const int idx = e0 + (u * kPlanThreads + (int)threadIdx.x) * 2;
-                            if (idx + 1 < E) {
-                                const ulonglong2 t = *reinterpret_cast<const ulonglong2 *>(src + idx);
-                                ed[2 * u] = t.x;
-                                ed[2 * u + 1] = t.y;
-                            } else {
-                                ed[2 * u] = idx < E ? src[idx] : 0ull;
-                                ed[2 * u + 1] = 0ull;
+                            for (int u = 0; u < UW; ++u) {
+                                const int idx = e0 + (u * kPlanThreads + (int)threadIdx.x) * 2;
+                                if (idx + 1 < E) {
+                                    const ulonglong2 t = *reinterpret_cast<const ulonglong2 *>(src + idx);
+                                    ed[2 * u] = t.x;
+                                    ed[2 * u + 1] = t.y;
+                                } else {
+                                    ed[2 * u] = idx < E ? src[idx] : 0ull;
+                                    ed[2 * u + 1] = 0ull;
+                                }
+                            }
+#pragma unroll
+                            for (int u = 0; u < 2 * UW; ++u) {
+                                const unsigned elo = (unsigned)ed[u], ehi = (unsigned)(ed[u] >> 32);
+                                const unsigned xw = IR ? elo : ehi, ow = IR ? ehi : elo;
+                                const int c = cnt[xw & kEdgeSlotMask];  // slot 0's count is harmless for an absent entry ...
+                                const int k = (elo | ehi) ? min(4, max(0, lo - c)) : 0;  // the entry outlives the bounds lo, .., lo - k + 1
+                                if (k) atomicAdd(reinterpret_cast<unsigned *>(&tmp[ow & kEdgeSlotMask]), 0x01010101u >> (8 * (4 - k)));
                             }
                         }
-#pragma unroll
-                        for (int u = 0; u < 2 * UW; ++u) {
-                            const unsigned elo = (unsigned)ed[u], ehi = (unsigned)(ed[u] >> 32);
-                            const unsigned xw = isrow ? elo : ehi, ow = isrow ? ehi : elo;
-                            const int c = cnt[xw & kEdgeSlotMask];  // slot 0's count is harmless for an absent entry ...
-                            const int k = (elo | ehi) ? min(4, max(0, lo - c)) : 0;  // the entry outlives the bounds lo, .., lo - k + 1
-                            if (k) atomicAdd(reinterpret_cast<unsigned *>(&tmp[ow & kEdgeSlotMask]), 0x01010101u >> (8 * (4 - k)));
-                        }
-                    }
+                    };
+                    if (isrow) count_pass(std::true_type{});
+                    else count_pass(std::false_type{});
                     __syncthreads();
                     int m0 = 0, m1 = 0, m2 = 0, m3 = 0;
                     if (threadIdx.x < 4) s_T[(round & 1) ^ 1][threadIdx.x] = 0;
@@ -572,36 +579,47 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
         }
         // (4) the pass.  The survivors of U entries per lane are appended with one counter update per wave.
         unsigned long long *dst = cur ? list0 : list1;
-        auto process = [&](auto &e) {  // e[u]: packed edge, 0 if absent
+        // One CU's vector ALU bounds this pass, so it is written for few instructions: the side of the batch
+        // and whether entries can move on (three or more digits) are compile-time cases, the common case
+        // (two digits: an entry of a split slot is simply finished) has one predicated LDS update per entry.
+        auto process = [&](auto &e, auto isrow_c, auto deep_c) {  // e[u]: packed edge, 0 if absent
+            constexpr bool IR = decltype(isrow_c)::value, DP = decltype(deep_c)::value;
             constexpr int U = sizeof(e) / sizeof(unsigned long long);
             unsigned xw[U], ow[U];  // the word that names the slot on the batch's side, and the other one
             int c[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {  // marks do not change during a pass; slot 0's count is harmless for absent edges
                 const unsigned lo = (unsigned)e[u], hi = (unsigned)(e[u] >> 32);
-                xw[u] = isrow ? lo : hi;
-                ow[u] = isrow ? hi : lo;
+                xw[u] = IR ? lo : hi;
+                ow[u] = IR ? hi : lo;
                 c[u] = cnt[xw[u] & kEdgeSlotMask];
             }
             int off[U], all = 0;  // survivors are packed edge by edge: the lanes of a store write side by side
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 bool live = (xw[u] | ow[u]) != 0u;
-                if (live && c[u] < 0 && -c[u] - 1 < nb) {
-                    const unsigned lo = isrow ? xw[u] : ow[u], hi = isrow ? ow[u] : xw[u];
-                    const unsigned levels = (lo >> kEdgeSlotBits) | ((hi >> kEdgeSlotBits) << 3);
-                    if (levels > 2u) {  // still OB in the new slot: move on, one digit fewer
-                        const unsigned newX = (unsigned)(N + (-c[u] - 1)), lev = levels - 1u;
-                        atomicAdd(&cnt[newX], 1);
-                        const unsigned r = isrow ? newX : (lo & kEdgeSlotMask), q = isrow ? (hi & kEdgeSlotMask) : newX;
-                        e[u] = pack_edge((int)r, (int)q, (int)lev);
-                    } else {
-                        atomicSub(&other[ow[u] & kEdgeSlotMask], 1);
-                        live = false;
+                const bool split = live && c[u] < 0 && ~c[u] < nb;  // the mark -(k + 1) names new slot N + k
+                if constexpr (DP) {
+                    if (split) {
+                        const unsigned lo = IR ? xw[u] : ow[u], hi = IR ? ow[u] : xw[u];
+                        const unsigned levels = (lo >> kEdgeSlotBits) | ((hi >> kEdgeSlotBits) << 3);
+                        if (levels > 2u) {  // still OB in the new slot: move on, one digit fewer
+                            const unsigned newX = (unsigned)(N + ~c[u]), lev = levels - 1u;
+                            atomicAdd(&cnt[newX], 1);
+                            const unsigned r = IR ? newX : (lo & kEdgeSlotMask), q = IR ? (hi & kEdgeSlotMask) : newX;
+                            e[u] = pack_edge((int)r, (int)q, (int)lev);
+                        } else {
+                            atomicSub(&other[ow[u] & kEdgeSlotMask], 1);
+                            live = false;
+                        }
                     }
+                } else {
+                    if (split) atomicSub(&other[ow[u] & kEdgeSlotMask], 1);
+                    live = live && !split;
                 }
                 const unsigned long long m = __ballot(live);
-                off[u] = live ? all + __popcll(m & below) : -1;
+                const int before = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                off[u] = live ? all + before : -1;
                 all += __popcll(m);
             }
             if (!all) return;
@@ -612,7 +630,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             for (int u = 0; u < U; ++u)
                 if (off[u] >= 0) dst[base + off[u]] = e[u];
         };
-        {  // the list of packed edges, two per load
+        auto run_pass = [&](auto isrow_c, auto deep_c) {  // the list of packed edges, two per load
             constexpr int U2 = 8;
             const unsigned long long *__restrict__ src = cur ? list1 : list0;
             auto fetch = [&](int e0, unsigned long long (&fe)[U2]) {
@@ -634,10 +652,17 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
             for (int e0 = 0; e0 < E; e0 += kPlanThreads * U2) {
                 unsigned long long ed2[U2];
                 fetch(e0 + kPlanThreads * U2, ed2);
-                process(ed);
+                process(ed, isrow_c, deep_c);
 #pragma unroll
                 for (int u = 0; u < U2; ++u) ed[u] = ed2[u];
             }
+        };
+        if (deep) {
+            if (isrow) run_pass(std::true_type{}, std::true_type{});
+            else run_pass(std::false_type{}, std::true_type{});
+        } else {
+            if (isrow) run_pass(std::true_type{}, std::false_type{});
+            else run_pass(std::false_type{}, std::false_type{});
         }
         __syncthreads();
         E = s_count;
