@@ -277,7 +277,9 @@ int imunpack_gemm(imunpack_plan_t *plan, const int8_t *A_ue, const int8_t *B_eu,
  * release it with imunpack_batch_destroy.  The steps never leave the device; per item the host waits once,
  * inside the plan call, for the sizes of the unpacked problem.  Synchronises the stream before returning.
  * Errors: EINVAL; ERANGE if any operand held a NaN or Inf or a quotient beyond 32 bits (the outputs of
- * that item are then undefined); ENOMEM; EHIP. */
+ * that item are then undefined); ENOMEM; EHIP.
+ * For b <= 4 the digits are stored as six-bit floating-point codes (imunpack_plan_set_digits); the
+ * results are the same bits either way. */
 int imunpack_gemm_batched(const float *A, int64_t sa_b, int64_t sa_r, int64_t sa_c,
                           const float *B, int64_t sb_b, int64_t sb_r, int64_t sb_c,
                           int64_t batch, int64_t n, int64_t d, int64_t h,

@@ -129,6 +129,10 @@ extern "C" int imunpack_gemm_batched(const float *A, int64_t sa_b, int64_t sa_r,
                               b, flags + 2, st));
         hipLaunchKernelGGL(gather_status_kernel, dim3(1), dim3(64), 0, st, flags, 4, any);
         IMU_TRY(imunpack_plan(Qa, n, d, d, Qb, h, d, b, strategy_A, strategy_B, &stA, &stB, &c->plan, st));
+        // digits of at most three bits: six-bit floating-point codes on the f8f6f4 matrix instruction (the
+        // request stays with the context's plan object)
+        if (b <= 4 && imunpack_plan_digits(c->plan) != IMUNPACK_DIGITS_FP6)
+            IMU_TRY(imunpack_plan_set_digits(c->plan, IMUNPACK_DIGITS_FP6));
         size_t ba = 0, bb = 0, bw = 0;
         IMU_TRY(imunpack_unpacked_bytes(c->plan, &ba, &bb, &bw));
         const size_t ba_pad = (ba + 255) & ~(size_t)255;
