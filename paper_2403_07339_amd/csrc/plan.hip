@@ -1122,16 +1122,24 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         // per 16-column unit of B_eu: what the scatter kernel needs to pick its path without the per-column arrays
         for (int u = q0 / 16 + threadIdx.x; u < q1 / 16; u += kPlanThreads) {
             const int qq = 16 * u;
-            const int k0 = cols.colB_k[qq];
+            int kk[16], ee[16];  // all sixteen columns' words at once: one round trip instead of sixteen
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int4 a = reinterpret_cast<const int4 *>(cols.colB_k + qq)[v], b = reinterpret_cast<const int4 *>(cols.colB_e + qq)[v];
+                kk[4 * v] = a.x; kk[4 * v + 1] = a.y; kk[4 * v + 2] = a.z; kk[4 * v + 3] = a.w;
+                ee[4 * v] = b.x; ee[4 * v + 1] = b.y; ee[4 * v + 2] = b.z; ee[4 * v + 3] = b.w;
+            }
+            const int k0 = kk[0];
             int kmin = 0x7fffffff, kmax = -1, efirst = -1;
             bool run = k0 >= 0, uniform = true;
+#pragma unroll
             for (int j = 0; j < 16; ++j) {
-                const int k = cols.colB_k[qq + j];
+                const int k = kk[j];
                 run = run && k == k0 + j;
                 if (k < 0) continue;
                 kmin = min(kmin, k);
                 kmax = max(kmax, k);
-                const int eb = cols.colB_e[qq + j];
+                const int eb = ee[j];
                 if (efirst < 0) efirst = eb;
                 else uniform = uniform && eb == efirst;  // one level for all real columns
             }
@@ -1158,14 +1166,29 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
         int kmin = 0x7fffffff, kmax = -1, efirst = -1, kfirst = -1, jfirst = 0;
         unsigned long long wfirst = 0;
         bool run = true, uniform = true, onew = true;
+        int kk[16], ee[16];  // all sixteen columns' words at once (the fence above has dropped stale cached lines)
+        unsigned long long ww[16];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int4 a = reinterpret_cast<const int4 *>(cols.colA_k + qq)[v], b = reinterpret_cast<const int4 *>(cols.colA_e + qq)[v];
+            kk[4 * v] = a.x; kk[4 * v + 1] = a.y; kk[4 * v + 2] = a.z; kk[4 * v + 3] = a.w;
+            ee[4 * v] = b.x; ee[4 * v + 1] = b.y; ee[4 * v + 2] = b.z; ee[4 * v + 3] = b.w;
+        }
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const ulonglong2 t = reinterpret_cast<const ulonglong2 *>(cols.colA_w + qq)[v];
+            ww[2 * v] = t.x;
+            ww[2 * v + 1] = t.y;
+        }
+#pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int k = __hip_atomic_load(&cols.colA_k[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int k = kk[j];
             if (k < 0) {
                 run = false;
                 continue;
             }
-            const int ea = __hip_atomic_load(&cols.colA_e[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned long long w = __hip_atomic_load(&cols.colA_w[qq + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int ea = ee[j];
+            const unsigned long long w = ww[j];
             if (efirst < 0) { efirst = ea; kfirst = k; jfirst = j; wfirst = w; }
             run = run && k == kfirst + (j - jfirst) && jfirst == 0;
             uniform = uniform && ea == efirst;
