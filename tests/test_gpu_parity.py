@@ -109,6 +109,25 @@ def test_quantize_pair_matches_the_oracle_for_both_operands(imu, n, h, d, b):
         assert status.cpu().tolist() == [0, 1]
 
 
+def test_quantize_pair_with_operands_of_different_layouts(imu):
+    """One operand row-major, the other a transposed view (as in a backward GEMM): the pair call runs them
+    through their own kernels, one after the other, with the same results."""
+    g = torch.Generator().manual_seed(5)
+    xa, xb = torch.randn((256, 384), generator=g) * 4, torch.randn((128, 384), generator=g) * 4
+    xa[torch.rand((256, 384), generator=g) < 0.01] *= 80.0
+    sa, sb, b = float(np.float32(0.05)), float(np.float32(0.03)), 8
+    A_d, B_t = dev(xa), dev(xb.t().contiguous()).t()          # B: unit stride down its rows
+    Qa, Qb, sta, stb, status = imu.imunpack_quantize_pair(A_d, B_t, sa, sb, b, want_ob_list=(True, True))
+    assert status.cpu().tolist() == [0, 0]
+    for x, scale, Q, st in ((xa, sa, Qa, sta), (xb, sb, Qb, stb)):
+        want = oracle_quant(x, scale)
+        assert np.array_equal(Q.cpu().numpy(), want)
+        rc, cc, rm, cm = np_stats(want, 1 << (b - 1))
+        assert np.array_equal(st.rowcnt.cpu().numpy(), rc) and np.array_equal(st.colcnt.cpu().numpy(), cc)
+        assert np.array_equal(st.rowmax.cpu().numpy(), rm) and np.array_equal(st.colmax.cpu().numpy(), cm)
+        assert int(st.ob_count.item()) == int(rc.sum())
+
+
 @pytest.mark.parametrize("shape,b,frac", [((300, 520), 8, 0.01), ((132, 260), 4, 0.2), ((1024, 384), 8, 0.0005),
                                           ((256, 256), 2, 0.9)])
 def test_ob_entry_list_for_every_input_layout(imu, shape, b, frac):
@@ -320,6 +339,14 @@ def test_six_bit_digits_fused_path_and_format_rules(imu):
     Bq = rand_ints(rng, 520, 700, s, 0.02, 2)
     plan = check_against_oracle(imu, Aq, Bq, b, COL, COL, fp6=True)
     assert plan.fusable() and plan.digits() == imu.DIGITS_FP6 and plan.dims()[3] >= 2
+    # a second unpack of the same plan into fresh buffers (the row norms are cleared and measured again)
+    A_d, B_d = dev(torch.from_numpy(Aq)), dev(torch.from_numpy(Bq))
+    bounds = plan.bounds()
+    A6, B6 = imu.imunpack_unpack(plan, A_d, B_d)
+    assert plan.bounds() == bounds
+    C = torch.empty((Aq.shape[0], Bq.shape[0]), dtype=torch.int64, device="cuda")
+    imu.imunpack_gemm(plan, A6, B6, 1.0, 1.0, C, None, None, fuse=True)
+    assert np.array_equal(C.cpu().numpy(), oracle.int_gemm(Aq, Bq))
     A8 = rand_ints(rng, 64, 128, 128, 0.02, 2)
     B8 = rand_ints(rng, 64, 128, 128, 0.02, 2)
     imu.imunpack_plan(dev(torch.from_numpy(A8)), dev(torch.from_numpy(B8)), 8, ROW, ROW, plan=plan)
