@@ -26,7 +26,8 @@
  *
  * Conventions
  *   - Every pointer named "device" is GPU memory owned by the caller (hipMalloc / a PyTorch
- *     tensor); "host" pointers are ordinary host memory.  The library owns only plan objects.
+ *     tensor); "host" pointers are ordinary host memory.  The library owns only plan objects and
+ *     batch contexts.
  *   - A plan object belongs to one thread at a time.  Calls that take a const plan only read it;
  *     the others (re-planning, unpack, GEMM, the bound queries and the exports) update state kept in
  *     it (host mirrors of device results, lazily built tables) and must not run concurrently on the
@@ -35,7 +36,8 @@
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on it unless stated otherwise.
  *   - All matrices are row-major; ld* is the distance in elements between consecutive rows.
- *   - 2 <= b <= 8: unpacked operands are stored as int8 for every b.
+ *   - 2 <= b <= 8: unpacked operands are stored as int8 for every b, or on request as 6-bit
+ *     floating-point codes for b <= 4 (imunpack_plan_set_digits).
  */
 #ifndef IMUNPACK_H
 #define IMUNPACK_H
@@ -253,7 +255,8 @@ int imunpack_unpack_canonical(imunpack_plan_t *plan, const int8_t *A_ue, const i
 
 /* ---- (5) int8 MFMA GEMM (Alg. 3) ---------------------------------------------------------------
  * Runs C_g = A_ue[:, I_g] B_eu[:, I_g]^T for every group g of equal diagonal entry with int32
- * accumulation on v_mfma_i32_*_i8 and combines the groups by shifts.
+ * accumulation on v_mfma_i32_*_i8 and combines the groups by shifts (six-bit digits: binary32
+ * accumulation of integers below 2^24 on v_mfma_f32_32x32x64_f8f6f4, the bound below is 2^24 then).
  * fuse != 0: one launch; the recombination (6) and the dequantisation run in the epilogue and
  *   C_int (n x h int64, device, may be NULL) and/or C_fp (n x h fp32, device, may be NULL) are
  *   written directly.  This needs the shifted sum of all groups to fit int32 for this plan's
