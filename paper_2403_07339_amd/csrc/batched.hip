@@ -22,6 +22,10 @@ int gemm_impl(imunpack_plan_t *p, const int8_t *A_ue, const int8_t *B_eu, void *
               float *C_fp, int64_t ldc, float scale_A, float scale_B, const float *scale_a_dev,
               const float *scale_b_dev, int fuse, imunpack_stream_t stream);
 
+__global__ void clear_flag_kernel(int32_t *any) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *any = 0;
+}
+
 // status[item] |= what the two quantize passes and the two percentile passes of the item flagged
 __global__ void gather_status_kernel(const int32_t *flags, int nflags, int32_t *any) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -119,7 +123,7 @@ extern "C" int imunpack_gemm_batched(const float *A, int64_t sa_b, int64_t sa_r,
                             capA ? obcnt : nullptr};
     imunpack_stats_t stB = {sB, sB + h, sB + h + d, sB + 2 * h + d, capB ? (int32_t *)(c->arena + oLb) : nullptr, capB,
                             capB ? obcnt + 1 : nullptr};
-    IMU_HIP(hipMemsetAsync(any, 0, sizeof(int32_t), st));
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(64), 0, st, any);
     for (int64_t i = 0; i < batch; ++i) {
         const float *Ai = A + i * sa_b, *Bi = B + i * sb_b;
         // the steps stay on the device: percentile -> step -> division in the quantizer -> product in the epilogue
