@@ -29,7 +29,7 @@ EXPORTS = [
     "imunpack_plan_fusable", "imunpack_plan_bounds", "imunpack_diag_mfma_peak", "imunpack_diag_clock_probe", "imunpack_diag_copy", "imunpack_price",
     "imunpack_percentile", "imunpack_percentile_static", "imunpack_plan_layout", "imunpack_rtn_step",
     "imunpack_gemm_batched", "imunpack_batch_destroy", "imunpack_quantize_pair", "imunpack_plan_set_digits",
-    "imunpack_plan_digits",
+    "imunpack_plan_digits", "imunpack_plan_keep_weights", "imunpack_plan_weights_reused",
 ]
 DIGITS_INT8, DIGITS_FP6 = 0, 1
 
@@ -57,6 +57,8 @@ _lib.imunpack_batch_destroy.argtypes = [_vp]
 _lib.imunpack_plan_layout.argtypes = [_vp, C.POINTER(_i64)]
 _lib.imunpack_plan_set_digits.argtypes = [_vp, _i32]
 _lib.imunpack_plan_digits.argtypes = [_vp]
+_lib.imunpack_plan_keep_weights.argtypes = [_vp, _i32]
+_lib.imunpack_plan_weights_reused.argtypes = [_vp]
 _lib.imunpack_unpack.argtypes = [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
 _lib.imunpack_unpack_canonical.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.imunpack_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _i32, _vp]
@@ -278,6 +280,13 @@ class Plan:
 
     def digits(self) -> int:
         return int(_lib.imunpack_plan_digits(self._h))
+
+    def keep_weights(self, keep: bool = True):
+        """Promise that B (integers, statistics, OB list) is the same in every later plan on this object."""
+        _check(_lib.imunpack_plan_keep_weights(self._h, 1 if keep else 0), "imunpack_plan_keep_weights")
+
+    def weights_reused(self) -> bool:
+        return bool(_lib.imunpack_plan_weights_reused(self._h))
 
     def layout(self):
         """((rows, stored columns, row pitch in bytes) of the A store, the same of B_eu)."""

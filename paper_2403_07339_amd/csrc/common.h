@@ -79,8 +79,17 @@ struct PlanHeader {
     int32_t err;                     // IMUNPACK_ERANGE conditions found on the device
     uint32_t cols_done;              // column-layout workgroups that have finished (the last one orders the units)
     int32_t extras;                  // edges that the repeated columns of B_e add to B's OB entries (UnpackBoth on B)
-    int32_t pad_[3];
+    int32_t reusedB;                 // the second operand's unpacking was taken over from the plan before (keep-weights mode)
+    int32_t pad_[2];
     unsigned long long bound[2];     // max over rows of sum_c s^e(c) |digit| for A_ue, B_eu
+};
+
+// What a plan in keep-weights mode remembers of the plan before it, on the device: the column unpacking of
+// the first operand that the second operand's unpacking was computed for, and the header fields that unpacking left.
+struct KeepState {
+    int32_t valid, d1, diff, same;
+    int32_t h_u, d_u, nobB, edgesB, extras;
+    int32_t pad_[7];
 };
 
 enum CapIndex { CAP_ROWA = 0, CAP_ROWB = 1, CAP_C1 = 2, CAP_C2 = 3, CAP_EDGEA = 4, CAP_EDGEB = 5, CAP_OB = 6,
@@ -226,6 +235,11 @@ struct imunpack_plan {
     int fusable;      // set by imunpack_unpack
     int unpacked;
     int valid;
+    int keep_B;       // keep-weights mode: the second operand is the same from plan to plan
+    int keep_valid;   // the arena holds a complete unpacking of the second operand and the snapshot it belongs to
+    unsigned long long keep_sig;  // ... for the arena layout with this signature
+    int32_t *snapRoot, *snapExp, *snapChild;  // the first operand's column slots at that time
+    imu::KeepState *d_keep;
     int digits_req;   // IMUNPACK_DIGITS_*: what imunpack_plan_set_digits asked for (kept across re-planning)
     int fp6;          // in effect for the current plan: 6-bit floating-point digits (requested and b <= 4)
 };

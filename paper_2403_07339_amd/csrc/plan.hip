@@ -146,8 +146,9 @@ __device__ __forceinline__ void identity_slot(const SlotSet &set, int x) {
 // of 0 skips a set).  The counts are known to the host, which has sized the sets for them.
 __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_a, SlotSet b, int nb,
                              int32_t *count_b, SlotSet c, int nc, int32_t *count_c, int32_t *zeroed, int nzeroed,
-                             int32_t *zeroed2, int nzeroed2) {
+                             int32_t *zeroed2, int nzeroed2, KeepState *ks) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (ks) ks->diff = ks->same = 0;
         static_assert(sizeof(PlanHeader) % sizeof(int32_t) == 0, "header is cleared word by word");
         for (size_t i = 0; i < sizeof(PlanHeader) / sizeof(int32_t); ++i) reinterpret_cast<int32_t *>(hdr)[i] = 0;
         if (na) *count_a = na;
@@ -247,6 +248,7 @@ struct GreedyArgs {
     PlanHeader *hdr;
     int whichR, whichC, whichE;
     int s, sh;
+    const int32_t *skip;           // keep-weights mode: non-zero there = nothing to do
 };
 
 // An edge of the greedy: an OB entry's current row slot, column slot and the number of base-s digits
@@ -292,6 +294,7 @@ __global__ __launch_bounds__(kPlanThreads) void greedy_both_kernel(GreedyArgs g)
     __shared__ int s_count;
     PlanHeader *hdr = g.hdr;
     if (hdr->overflow) return;
+    if (g.skip && *g.skip) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned long long below = (1ull << lane) - 1ull;
     int nr = *g.nr_io, nc;
@@ -1362,6 +1365,10 @@ static size_t carve(Plan *p, char *base, bool own_statsA, bool own_statsB) {
         p->ccnt = cv.take<int32_t>(ccap + 8);
         p->ob = cv.take<int32_t>((size_t)3 * p->cap[CAP_OB]);
     }
+    p->snapRoot = cv.take<int32_t>(p->cap[CAP_C1]);
+    p->snapExp = cv.take<int32_t>(p->cap[CAP_C1]);
+    p->snapChild = cv.take<int32_t>(p->cap[CAP_C1]);
+    p->d_keep = cv.take<KeepState>(1);
     return cv.off + 256;
 }
 
@@ -1381,7 +1388,8 @@ static inline int grid_for(int64_t items, int threads, int maxblocks = 2048) {
 __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict__ ob, int ob_cap,
                                                       const int32_t *ob_count, int32_t *__restrict__ keep, int keep_cap,
                                                       const int32_t *chain_child, unsigned long long *edges, int ecap,
-                                                      int32_t *extras, int32_t *extra_rows, int sh) {
+                                                      int32_t *extras, int32_t *extra_rows, int sh, const int32_t *skip) {
+    if (skip && *skip) return;  // keep-weights mode: this operand's unpacking is taken over as it stands
     const int n = min(*ob_count, ob_cap);
     for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < n; t += gridDim.x * blockDim.x) {
         const int j = ob[t], k = ob[ob_cap + t], v = ob[2 * (size_t)ob_cap + t];
@@ -1403,12 +1411,77 @@ __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict_
     }
 }
 
+// ---- keep-weights mode (Sec. 4.2: weights are unpacked once, when they are loaded).  The unpacking of the
+// second operand depends on the first only through the column slots of the first operand's unpacking
+// (which columns of B_e are repeats, and their exponents).  If those are what they were for the plan
+// before, the second operand's slots, its kept OB entries and its header fields are taken over.
+__global__ void keep_compare_kernel(SlotSet c1, const int32_t *d1_dev, const int32_t *sroot, const int32_t *sexp,
+                                    const int32_t *schild, KeepState *ks, int host_valid) {
+    const int d1 = *d1_dev;
+    if (!host_valid || !ks->valid || d1 != ks->d1 || d1 > c1.cap) {
+        if (threadIdx.x == 0) ks->diff = 1;
+        return;
+    }
+    bool differs = false;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < d1; x += gridDim.x * blockDim.x)
+        differs = differs || c1.root[x] != sroot[x] || c1.exp[x] != sexp[x] || c1.child[x] != schild[x];
+    if (differs) ks->diff = 1;
+}
+
+// Every workgroup reaches the same verdict; if the slots differ, the second operand's rows start afresh.
+__global__ void keep_decide_kernel(KeepState *ks, PlanHeader *hdr, SlotSet rowB, int h, int32_t *extra_rows) {
+    const bool same = !ks->diff && !hdr->overflow;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ks->same = same;
+        hdr->reusedB = same;
+        if (same) {
+            hdr->h_u = ks->h_u;
+            hdr->d_u = ks->d_u;
+            hdr->nobB = ks->nobB;
+            hdr->edgesB = ks->edgesB;
+            hdr->extras = ks->extras;
+        } else {
+            hdr->h_u = h;
+        }
+    }
+    if (same) return;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < h; x += gridDim.x * blockDim.x) {
+        identity_slot(rowB, x);
+        extra_rows[x] = 0;
+    }
+}
+
+// After the second operand has been unpacked anew: remember what it was unpacked for.
+__global__ void keep_snapshot_kernel(SlotSet c1, const PlanHeader *hdr, int32_t *sroot, int32_t *sexp, int32_t *schild,
+                                     KeepState *ks) {
+    if (ks->same) return;
+    if (hdr->overflow || hdr->err || hdr->d1 > c1.cap) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) ks->valid = 0;
+        return;
+    }
+    const int d1 = hdr->d1;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < d1; x += gridDim.x * blockDim.x) {
+        sroot[x] = c1.root[x];
+        sexp[x] = c1.exp[x];
+        schild[x] = c1.child[x];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ks->d1 = d1;
+        ks->h_u = hdr->h_u;
+        ks->d_u = hdr->d_u;
+        ks->nobB = hdr->nobB;
+        ks->edgesB = hdr->edgesB;
+        ks->extras = hdr->extras;
+        ks->valid = 1;
+    }
+}
+
 static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
 static constexpr int kLayoutLdsMax = 128 * 1024;  // dynamic LDS the layouts kernel may use (its static tables take about 12 KiB)
 
 // ob: the operand's OB entry list ([3][ob_cap], count on the device)
 static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const int32_t *ob_count,
-                      int which_list, hipStream_t st) {
+                      int which_list, hipStream_t st, const int32_t *skip = nullptr) {
     PlanHeader *hdr = p->d_hdr;
     const bool first = phase == 1;
     SlotSet &rows = first ? p->rowA : p->rowB;
@@ -1434,6 +1507,7 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     g.whichC = first ? CAP_C1 : CAP_C2;
     g.whichE = first ? CAP_EDGEA : CAP_EDGEB;
     g.s = p->s; g.sh = p->sh;
+    g.skip = skip;
     const size_t lds_bytes = ((size_t)((rows.cap + 7) & ~3) + (size_t)((cols.cap + 7) & ~3)) * sizeof(int32_t);
     static std::atomic<int> opted_in{0};  // the attribute is idempotent: a race sets the same value twice
     if (!opted_in.load(std::memory_order_acquire)) {
@@ -1444,7 +1518,7 @@ static int run_greedy(Plan *p, int phase, const int32_t *ob, int ob_cap, const i
     const int keep_cap = p->cap[first ? CAP_EDGEA : CAP_EDGEB];  // the stride the fix-up pass reads with
     hipLaunchKernelGGL(ob_copy_kernel, dim3(grid_for(ob_cap, 256, 128)), dim3(256), 0, st, ob, ob_cap, ob_count,
                        first ? p->obcopyA : p->obcopyB, keep_cap, (const int32_t *)g.chain_child, g.edges, g.ecap,
-                       &hdr->extras, p->extraRows, p->sh);
+                       &hdr->extras, p->extraRows, p->sh, skip);
     if (lds_bytes <= (size_t)kGreedyLdsMax)
         hipLaunchKernelGGL(greedy_both_kernel<true>, dim3(1), dim3(kPlanThreads), lds_bytes, st, g);
     else
@@ -1463,10 +1537,13 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     if (idA > p->rowA.cap || idC1 > p->c1.cap || idB > p->rowB.cap) return IMUNPACK_EINVAL;
     // also cleared: the weights of the stored columns of A (the column layout adds to them)
     const int kcA = phys_cap_cols(p->cap[CAP_C2]);
+    // keep-weights mode (UnpackBoth on the second operand): its rows are set up only once it is known that its
+    // unpacking has to be redone
+    const bool keep = p->keep_B && p->sB == IMUNPACK_BOTH;
     hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, kcA)), 256, 64)),
-                       dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, idB,
-                       &hdr->h_u, p->extraRows, p->sB == IMUNPACK_BOTH ? h : 0,
-                       reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA);
+                       dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, keep ? 0 : idB,
+                       &hdr->h_u, p->extraRows, (p->sB == IMUNPACK_BOTH && !keep) ? h : 0,
+                       reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA, keep ? p->d_keep : nullptr);
     // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
     // this call's own scan produces one.  The two operands are planned one after the other, so one
     // own buffer serves both.
@@ -1508,8 +1585,20 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                            (const int32_t *)p->c1.root, 0, (const int32_t *)&hdr->d1, p->sh, p->tmpL,
                            p->tmpCur, &hdr->d_u, hdr, (int)CAP_C2);
     } else {
-        if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st));
-        else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
+        const int32_t *skip = nullptr;
+        if (keep) {
+            hipLaunchKernelGGL(keep_compare_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 64)), dim3(256), 0, st, p->c1,
+                               (const int32_t *)&hdr->d1, (const int32_t *)p->snapRoot, (const int32_t *)p->snapExp,
+                               (const int32_t *)p->snapChild, p->d_keep, p->keep_valid);
+            hipLaunchKernelGGL(keep_decide_kernel, dim3(grid_for(h, 256, 64)), dim3(256), 0, st, p->d_keep, hdr, p->rowB, h,
+                               p->extraRows);
+            skip = &p->d_keep->same;
+        }
+        if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st, skip));
+        else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st, skip));
+        if (keep)
+            hipLaunchKernelGGL(keep_snapshot_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 64)), dim3(256), 0, st, p->c1,
+                               (const PlanHeader *)hdr, p->snapRoot, p->snapExp, p->snapChild, p->d_keep);
     }
     // ---- physical layouts
     // the row layouts keep two ints per source row in LDS when that fits beside the column layout's tables
@@ -1621,21 +1710,31 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
             p->arena_bytes = want;
         }
         carve(p, p->arena, ownA, ownB);
+        {  // what is kept of the plan before is only good for the same arrays at the same addresses
+            unsigned long long sig = (unsigned long long)(uintptr_t)p->arena * 1000003ull + (unsigned long long)(uintptr_t)p->d_keep;
+            const long long parts[] = {n, d, h, b, strategy_A, strategy_B, ownA, ownB, (long long)(uintptr_t)B, (long long)ldb};
+            for (long long v : parts) sig = sig * 1099511628211ull + (unsigned long long)v;
+            for (int c = 0; c <= CAP_OB; ++c) sig = sig * 1099511628211ull + (unsigned long long)p->cap[c];
+            if (sig != p->keep_sig) p->keep_valid = 0;
+            p->keep_sig = sig;
+        }
         if (!ownA) { p->statsA[0] = stats_A->rowcnt; p->statsA[1] = stats_A->colcnt; p->statsA[2] = stats_A->rowmax; p->statsA[3] = stats_A->colmax; }
         if (!ownB) { p->statsB[0] = stats_B->rowcnt; p->statsB[1] = stats_B->colcnt; p->statsB[2] = stats_B->rowmax; p->statsB[3] = stats_B->colmax; }
         rc = enqueue_plan(p, A, lda, B, ldb, stats_A, stats_B, ownA, ownB, st);
         if (rc != IMUNPACK_OK) break;
         rc = fetch_header(p, 0, sizeof(PlanHeader), st);
         if (rc != IMUNPACK_OK) break;
-        if (p->hdr.err) { rc = p->hdr.err; break; }
+        if (p->hdr.err) { rc = p->hdr.err; p->keep_valid = 0; break; }
         if (!p->hdr.overflow) {
             p->valid = 1;
             p->canon_valid = 0;
+            p->keep_valid = p->keep_B && strategy_B == IMUNPACK_BOTH;
             p->fp6 = p->digits_req == IMUNPACK_DIGITS_FP6 && b <= 4;
             p->bothA = strategy_A == IMUNPACK_BOTH;
             p->bothB = strategy_B == IMUNPACK_BOTH;
             break;
         }
+        p->keep_valid = 0;
         if (p->hdr.overflow & (1 << CAP_LISTA)) p->ignore_listA = 1;
         if (p->hdr.overflow & (1 << CAP_LISTB)) p->ignore_listB = 1;
         for (int c = 0; c <= CAP_OB; ++c)
@@ -1670,6 +1769,17 @@ extern "C" int imunpack_plan_dims(const imunpack_plan_t *p, int64_t *n_u, int64_
     if (h_u) *h_u = p->hdr.h_u;
     if (n_groups) *n_groups = p->hdr.ngroups;
     return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_plan_keep_weights(imunpack_plan_t *p, int keep) {
+    if (!p) return IMUNPACK_EINVAL;
+    p->keep_B = keep != 0;
+    if (!keep) p->keep_valid = 0;
+    return IMUNPACK_OK;
+}
+
+extern "C" int imunpack_plan_weights_reused(const imunpack_plan_t *p) {
+    return (p && p->valid && p->hdr.reusedB) ? 1 : 0;
 }
 
 namespace imu {

@@ -361,6 +361,66 @@ def test_six_bit_digits_fused_path_and_format_rules(imu):
     assert plan.digits() == imu.DIGITS_INT8
 
 
+@pytest.mark.parametrize("sa", [BOTH, ROW, COL])
+def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
+    """Keep-weights mode (Sec. 4.2: weights unpacked once): with B fixed, a plan call reuses B's unpacking
+    exactly when the column slots of A's unpacking are those of the call before.  Every call's plan (every
+    split in order), unpacked operands and product are compared with the oracle's, reused or not."""
+    rng = np.random.default_rng(4242 + sa)
+    b, s = 8, 128
+    n, d, h = 150, 300, 270
+    Bq = rand_ints(rng, h, d, s, 0.02, 2)
+    def make_A(cols, seed):
+        r = np.random.default_rng(seed)
+        A = r.integers(-(s - 1), s, size=(n, d)).astype(np.int32)
+        for c in cols:                                  # heavy columns: the column splits of A's unpacking
+            A[:, c] = r.integers(s, s * s, size=n).astype(np.int32) * r.choice([-1, 1], size=n)
+        if sa == ROW:
+            A[r.integers(0, n, 5), :] = r.integers(-(s * s - 1), s * s, size=(5, d)).astype(np.int32)
+        return A
+    B_d = dev(torch.from_numpy(Bq))
+    plan = imu.Plan()
+    seq = [((3, 77, 200), 1, False),     # first call in this mode: B is unpacked
+           ((3, 77, 200), 2, True),      # other values, same heavy columns: the same column slots
+           ((3, 77, 200), 3, True),
+           ((5, 77, 201), 4, False),     # other columns split: B is unpacked again
+           ((5, 77, 201), 5, True),
+           ((3, 77, 200), 6, False)]
+    if sa == ROW:                        # no column of A is ever split: always the same column slots
+        seq = [(c, k, i > 0) for i, (c, k, _) in enumerate(seq)]
+    for i, (cols, seed, want_reuse) in enumerate(seq):
+        Aq = make_A(cols, seed)
+        A_d = dev(torch.from_numpy(Aq))
+        imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+        if i == 0:
+            assert not plan.weights_reused()
+            plan.keep_weights(True)      # from the next call on
+            imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+            assert not plan.weights_reused()
+        else:
+            assert plan.weights_reused() == want_reuse, (i, cols)
+        hnd = oracle.unpack_pair_handle(Aq, Bq, b, sa, BOTH)
+        assert plan.dims()[:3] == (hnd.n_u, hnd.d_u, hnd.h_u)
+        got = [t.numpy().astype(np.int64) for t in plan.export_all()]
+        S, pas, paw, pbs, pbw = hnd.meta()
+        want_parent, want_ops = hnd.trace()
+        assert np.array_equal(got[0], pas) and np.array_equal(got[2], pbs) and np.array_equal(got[4], hnd.col_src())
+        assert np.array_equal(got[6], want_parent) and np.array_equal(got[7], want_ops)
+        assert np.array_equal(s ** got[5].astype(object), S.astype(object))
+        A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d)
+        Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
+        oa, ob = hnd.operands_i8()
+        assert np.array_equal(Ac.cpu().numpy(), oa) and np.array_equal(Bc.cpu().numpy(), ob)
+        C = torch.empty((n, h), dtype=torch.int64, device="cuda")
+        ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C, None, ws, fuse=True)
+        assert np.array_equal(C.cpu().numpy(), oracle.int_gemm(Aq, Bq)), i
+        hnd.close()
+    plan.keep_weights(False)
+    imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+    assert not plan.weights_reused()
+
+
 @pytest.mark.parametrize("b", [3, 5, 6, 7])
 def test_other_bit_widths(imu, b):
     w = workloads.small(11, 130, 200, 140, kind="scattered", b=b)

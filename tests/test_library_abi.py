@@ -103,7 +103,8 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert handle.value is None
     for name, nargs in (("imunpack_unpacked_bytes", 4), ("imunpack_unpack", 8), ("imunpack_unpack_canonical", 6),
                         ("imunpack_gemm", 11), ("imunpack_recombine", 8), ("imunpack_plan_export", 10),
-                        ("imunpack_plan_bounds", 2), ("imunpack_plan_layout", 2), ("imunpack_plan_set_digits", 2)):
+                        ("imunpack_plan_bounds", 2), ("imunpack_plan_layout", 2), ("imunpack_plan_set_digits", 2),
+                        ("imunpack_plan_keep_weights", 2)):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = None
