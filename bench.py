@@ -352,6 +352,7 @@ def main():
     torch.cuda.synchronize()
     ms_step_keep = (time.perf_counter() - t0) * 1e3 / args.steps
     plan_keep_ms = sum(e[1].elapsed_time(e[2]) for e in ev_k) / args.steps
+    scatter_keep_ms = sum(e[2].elapsed_time(e[3]) for e in ev_k) / args.steps
     plan.keep_weights(False)
     step()
     torch.cuda.synchronize()
@@ -414,9 +415,10 @@ def main():
                                    "note": "same step with the RTN integers and scan statistics of B kept from an "
                                            "earlier step (weights are quantised once); not the headline value",
                                    "keep_weights": {"ms_per_step": ms_step_keep, "value": w.ops / (ms_step_keep * 1e-3) / 1e12,
-                                                    "plan_ms": plan_keep_ms, "unpacking_of_B_reused": bool(reused),
-                                                    "note": "and the plan in keep-weights mode: B's unpacking is taken "
-                                                            "over while the column splits of A stay the same"}}
+                                                    "plan_ms": plan_keep_ms, "scatter_ms": scatter_keep_ms,
+                                                    "unpacking_of_B_reused": bool(reused),
+                                                    "note": "and the plan in keep-weights mode: B's unpacking, its layouts and "
+                                                            "B_eu itself are taken over while the column splits of A stay the same"}}
     out["unpack"]["time_ratio_vs_plain_int8_gemm"] = ms_step / extra["plain_gemm_ms"]
     out["unpack"]["priced_r_all_pairs"] = extra["priced_r"]   # Sec. 4.2, "Mix": r of all nine strategy pairs
     out["priced_best_pair_step"] = {"strategy": extra["priced_best"], "ms_per_step": extra["mix_ms"],

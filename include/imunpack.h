@@ -218,8 +218,11 @@ int imunpack_plan_destroy(imunpack_plan_t *plan);
  * column slots of A's unpacking with those of the call before and, if they are the same, takes the
  * second operand's unpacking over instead of running Alg. 4 on it again (no extra host wait; the result
  * is the same plan either way).  Otherwise, and in the first call after keep was set, B is unpacked as
- * usual.  imunpack_plan_weights_reused tells which of the two the last plan call did.  keep == 0 (the
- * default) ends the promise.  Other strategies of B are planned in closed form and are not affected.
+ * usual.  When it was taken over, the layouts of B's rows and of the columns stand as they are too, and
+ * the first imunpack_unpack after that plan call writes only the A store if it is given the B_eu buffer
+ * that the unpack before wrote (same address, same digit format): B_eu and its row norms are already
+ * what they would become.  imunpack_plan_weights_reused tells which of the two the last plan call did.
+ * keep == 0 (the default) ends the promise.  Other strategies of B are planned in closed form and are not affected.
  * Errors: EINVAL (null plan). */
 int imunpack_plan_keep_weights(imunpack_plan_t *plan, int keep);
 int imunpack_plan_weights_reused(const imunpack_plan_t *plan);

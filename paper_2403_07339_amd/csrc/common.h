@@ -90,6 +90,7 @@ struct KeepState {
     int32_t valid, d1, diff, same;
     int32_t h_u, d_u, nobB, edgesB, extras;
     int32_t pad_[7];
+    PlanHeader saved;  // the header as that plan left it: the layout of the second operand and of the columns
 };
 
 enum CapIndex { CAP_ROWA = 0, CAP_ROWB = 1, CAP_C1 = 2, CAP_C2 = 3, CAP_EDGEA = 4, CAP_EDGEB = 5, CAP_OB = 6,
@@ -239,6 +240,8 @@ struct imunpack_plan {
     int keep_valid;   // the arena holds a complete unpacking of the second operand and the snapshot it belongs to
     unsigned long long keep_sig;  // ... for the arena layout with this signature
     int32_t *snapRoot, *snapExp, *snapChild;  // the first operand's column slots at that time
+    const int8_t *kept_Beu;  // the buffer the last imunpack_unpack wrote B_eu to, while it still matches the plan
+    int kept_Beu_fp6;
     imu::KeepState *d_keep;
     int digits_req;   // IMUNPACK_DIGITS_*: what imunpack_plan_set_digits asked for (kept across re-planning)
     int fp6;          // in effect for the current plan: 6-bit floating-point digits (requested and b <= 4)

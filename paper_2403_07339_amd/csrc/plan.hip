@@ -1213,10 +1213,11 @@ __device__ void cols_layout(const SlotSet &c1, const SlotSet &c2, const ColLayou
 __global__ __launch_bounds__(kPlanThreads) void layouts_kernel(
     SlotSet rowA, int n, RowLayout layA, int cap_physA, int32_t *tmpPA, SlotSet rowB, int h, RowLayout layB,
     int cap_physB, int32_t *tmpPB, SlotSet c1, SlotSet c2, ColLayout cols, int d, int cap_physC, int s, int sh,
-    int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr, int fast_lds) {
+    int32_t *tmpE, int32_t *tmpK, int32_t *tmpR, int32_t *tmpOff, PlanHeader *hdr, int fast_lds, const int32_t *skipB) {
     __shared__ int lds[40];
     extern __shared__ __attribute__((aligned(16))) int32_t fast_rows[];  // 2 * max(n, h) ints, if the launch gave them
     if (hdr->overflow) return;
+    if (blockIdx.x >= 1 && skipB && *skipB) return;  // keep-weights mode: these layouts stand as they are
     // rows of A: the GEMM epilogue folds them chunk by chunk; rows of B (columns of C): tile by tile
     if (blockIdx.x == 0)
         rows_layout(rowA, n, &hdr->n_u, layA, cap_physA, cap_physA / kTile + 2, tmpPA, hdr, 0, kChunk, lds, fast_lds ? fast_rows : nullptr);
@@ -1428,27 +1429,41 @@ __global__ void keep_compare_kernel(SlotSet c1, const int32_t *d1_dev, const int
     if (differs) ks->diff = 1;
 }
 
-// Every workgroup reaches the same verdict; if the slots differ, the second operand's rows start afresh.
-__global__ void keep_decide_kernel(KeepState *ks, PlanHeader *hdr, SlotSet rowB, int h, int32_t *extra_rows) {
+// Every workgroup reaches the same verdict.  Same slots: the header fields that the second operand's unpacking
+// and the layouts of its rows and of the columns left are put back.  Different: its rows start afresh and the
+// column weights are cleared for the column layout to come.
+__global__ void keep_decide_kernel(KeepState *ks, PlanHeader *hdr, SlotSet rowB, int h, int32_t *extra_rows,
+                                   int32_t *col_weights, int nweights) {
     const bool same = !ks->diff && !hdr->overflow;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         ks->same = same;
         hdr->reusedB = same;
         if (same) {
-            hdr->h_u = ks->h_u;
-            hdr->d_u = ks->d_u;
-            hdr->nobB = ks->nobB;
-            hdr->edgesB = ks->edgesB;
-            hdr->extras = ks->extras;
+            const PlanHeader &o = ks->saved;
+            hdr->h_u = o.h_u; hdr->d_u = o.d_u; hdr->nobB = o.nobB; hdr->edgesB = o.edgesB; hdr->extras = o.extras;
+            hdr->Np = o.Np; hdr->Kp = o.Kp; hdr->KA = o.KA; hdr->ldA = o.ldA; hdr->ldB = o.ldB;
+            hdr->ntiles = o.ntiles; hdr->lmaxB = o.lmaxB; hdr->ngroups = o.ngroups; hdr->nruns = o.nruns;
         } else {
             hdr->h_u = h;
         }
     }
-    if (same) return;
-    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < h; x += gridDim.x * blockDim.x) {
+    if (same) {  // the group and run tables, by the first workgroup's threads
+        if (blockIdx.x == 0) {
+            constexpr size_t g0 = offsetof(PlanHeader, grp_exp) / sizeof(int32_t), g1 = offsetof(PlanHeader, nruns) / sizeof(int32_t);
+            constexpr size_t r0 = offsetof(PlanHeader, run_kt0) / sizeof(int32_t), r1 = offsetof(PlanHeader, edgesA) / sizeof(int32_t);
+            const int32_t *src = reinterpret_cast<const int32_t *>(&ks->saved);
+            int32_t *dst = reinterpret_cast<int32_t *>(hdr);
+            for (size_t i = g0 + threadIdx.x; i < g1; i += blockDim.x) dst[i] = src[i];
+            for (size_t i = r0 + threadIdx.x; i < r1; i += blockDim.x) dst[i] = src[i];
+        }
+        return;
+    }
+    const int stride = gridDim.x * blockDim.x, t0 = blockIdx.x * blockDim.x + threadIdx.x;
+    for (int x = t0; x < h; x += stride) {
         identity_slot(rowB, x);
         extra_rows[x] = 0;
     }
+    for (int x = t0; x < nweights; x += stride) col_weights[x] = 0;
 }
 
 // After the second operand has been unpacked anew: remember what it was unpacked for.
@@ -1474,6 +1489,18 @@ __global__ void keep_snapshot_kernel(SlotSet c1, const PlanHeader *hdr, int32_t 
         ks->extras = hdr->extras;
         ks->valid = 1;
     }
+}
+
+// ... and, once the layouts are done, the header they completed.
+__global__ void keep_save_header_kernel(const PlanHeader *hdr, KeepState *ks) {
+    if (ks->same) return;
+    if (hdr->overflow || hdr->err) {
+        if (threadIdx.x == 0) ks->valid = 0;
+        return;
+    }
+    const int32_t *src = reinterpret_cast<const int32_t *>(hdr);
+    int32_t *dst = reinterpret_cast<int32_t *>(&ks->saved);
+    for (size_t i = threadIdx.x; i < sizeof(PlanHeader) / sizeof(int32_t); i += blockDim.x) dst[i] = src[i];
 }
 
 static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
@@ -1543,7 +1570,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, kcA)), 256, 64)),
                        dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, keep ? 0 : idB,
                        &hdr->h_u, p->extraRows, (p->sB == IMUNPACK_BOTH && !keep) ? h : 0,
-                       reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA, keep ? p->d_keep : nullptr);
+                       reinterpret_cast<int32_t *>(p->cols.colA_w), keep ? 0 : 2 * kcA, keep ? p->d_keep : nullptr);
     // OB entry lists for UnpackBoth: the caller's (from the fused quantize pass) if complete, else
     // this call's own scan produces one.  The two operands are planned one after the other, so one
     // own buffer serves both.
@@ -1590,8 +1617,8 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
             hipLaunchKernelGGL(keep_compare_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 64)), dim3(256), 0, st, p->c1,
                                (const int32_t *)&hdr->d1, (const int32_t *)p->snapRoot, (const int32_t *)p->snapExp,
                                (const int32_t *)p->snapChild, p->d_keep, p->keep_valid);
-            hipLaunchKernelGGL(keep_decide_kernel, dim3(grid_for(h, 256, 64)), dim3(256), 0, st, p->d_keep, hdr, p->rowB, h,
-                               p->extraRows);
+            hipLaunchKernelGGL(keep_decide_kernel, dim3(grid_for(std::max(h, 2 * kcA), 256, 64)), dim3(256), 0, st, p->d_keep,
+                               hdr, p->rowB, h, p->extraRows, reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA);
             skip = &p->d_keep->same;
         }
         if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st, skip));
@@ -1612,7 +1639,9 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     hipLaunchKernelGGL(layouts_kernel, dim3(2 + kColBlocks), dim3(kPlanThreads), fast_lds ? fast_bytes : 0, st, p->rowA, n, p->layA,
                        phys_cap_rows(p->cap[CAP_ROWA]), p->tmpPA, p->rowB, h, p->layB,
                        phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
-                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr, fast_lds);
+                       phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr, fast_lds,
+                       keep ? (const int32_t *)&p->d_keep->same : (const int32_t *)nullptr);
+    if (keep) hipLaunchKernelGGL(keep_save_header_kernel, dim3(1), dim3(256), 0, st, (const PlanHeader *)hdr, p->d_keep);
     return launch_status();
 }
 
@@ -1729,6 +1758,7 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
             p->valid = 1;
             p->canon_valid = 0;
             p->keep_valid = p->keep_B && strategy_B == IMUNPACK_BOTH;
+            if (!p->hdr.reusedB) p->kept_Beu = nullptr;  // what an earlier unpack wrote belongs to another plan
             p->fp6 = p->digits_req == IMUNPACK_DIGITS_FP6 && b <= 4;
             p->bothA = strategy_A == IMUNPACK_BOTH;
             p->bothB = strategy_B == IMUNPACK_BOTH;
@@ -1774,7 +1804,10 @@ extern "C" int imunpack_plan_dims(const imunpack_plan_t *p, int64_t *n_u, int64_
 extern "C" int imunpack_plan_keep_weights(imunpack_plan_t *p, int keep) {
     if (!p) return IMUNPACK_EINVAL;
     p->keep_B = keep != 0;
-    if (!keep) p->keep_valid = 0;
+    if (!keep) {
+        p->keep_valid = 0;
+        p->kept_Beu = nullptr;
+    }
     return IMUNPACK_OK;
 }
 

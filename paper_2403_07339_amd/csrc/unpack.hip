@@ -452,6 +452,7 @@ extern "C" int imunpack_plan_set_digits(imunpack_plan_t *p, int format) {
     if (p->bound_pending) IMU_TRY(resolve_bound(p));  // of an unpack in the other format
     p->digits_req = format;
     p->fp6 = format == IMUNPACK_DIGITS_FP6;
+    p->kept_Beu = nullptr;
     return IMUNPACK_OK;
 }
 
@@ -481,6 +482,9 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     ScatterArgs sc[2];
     memset(sc, 0, sizeof(sc));
     bool launch[2] = {false, false}, dense[2] = {false, false};
+    // keep-weights mode: the plan took the second operand's unpacking over, and the caller's buffer still holds
+    // what the unpack before wrote for exactly that unpacking (same buffer, same format, row norms in place)
+    const bool keepB = p->keep_B && h.reusedB && !p->unpacked && p->kept_Beu == B_eu && p->kept_Beu_fp6 == p->fp6;
     for (int op = 0; op < 2; ++op) {
         const int rowsP = op ? h.Np : h.Mp;
         const int W = op ? h.Kp : h.KA;
@@ -500,10 +504,10 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
         a.items = (rowsP / kBandRows) * a.nwin;
         a.out = op ? B_eu : A_ue;
         a.wavesum = lay.wavesum;
-        launch[op] = true;
+        launch[op] = !(op == 1 && keepB);
         dense[op] = !both;
         const int nob = op ? h.nobB : h.nobA;
-        if (both && nob > 0) {
+        if (both && nob > 0 && launch[op]) {
             FixupArgs &f = fx[op];
             f.ob = op ? p->obcopyB : p->obcopyA;
             f.ob_cap = p->cap[op ? CAP_EDGEB : CAP_EDGEA];
@@ -558,6 +562,8 @@ extern "C" int imunpack_unpack(imunpack_plan_t *p, const int32_t *A, int64_t lda
     IMU_HIP(hipEventRecord(p->ready, p->side));
     p->bound_pending = 1;
     p->unpacked = 1;
+    p->kept_Beu = p->keep_B ? B_eu : nullptr;
+    p->kept_Beu_fp6 = p->fp6;
     return IMUNPACK_OK;
 }
 

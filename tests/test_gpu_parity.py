@@ -380,6 +380,8 @@ def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
         return A
     B_d = dev(torch.from_numpy(Bq))
     plan = imu.Plan()
+    buf_a = torch.empty(8 << 20, dtype=torch.int8, device="cuda")
+    buf_b = torch.empty(8 << 20, dtype=torch.int8, device="cuda")
     seq = [((3, 77, 200), 1, False),     # first call in this mode: B is unpacked
            ((3, 77, 200), 2, True),      # other values, same heavy columns: the same column slots
            ((3, 77, 200), 3, True),
@@ -407,14 +409,21 @@ def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
         assert np.array_equal(got[0], pas) and np.array_equal(got[2], pbs) and np.array_equal(got[4], hnd.col_src())
         assert np.array_equal(got[6], want_parent) and np.array_equal(got[7], want_ops)
         assert np.array_equal(s ** got[5].astype(object), S.astype(object))
-        A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d)
+        # the same two buffers in every call: with B's unpacking taken over, B_eu is left as the unpack before wrote it
+        ba, bb, bw = plan.unpacked_bytes()
+        assert ba <= buf_a.numel() and bb <= buf_b.numel()
+        A_ue, B_eu = imu.imunpack_unpack(plan, A_d, B_d, buf_a, buf_b)
         Ac, Bc = imu.imunpack_unpack_canonical(plan, A_ue, B_eu)
         oa, ob = hnd.operands_i8()
         assert np.array_equal(Ac.cpu().numpy(), oa) and np.array_equal(Bc.cpu().numpy(), ob)
+        check_bounds(plan, oa, ob, S, s)
         C = torch.empty((n, h), dtype=torch.int64, device="cuda")
-        ws = torch.empty(plan.unpacked_bytes()[2] // 8, dtype=torch.int64, device="cuda")
+        ws = torch.empty(bw // 8, dtype=torch.int64, device="cuda")
         imu.imunpack_gemm(plan, A_ue, B_eu, 1.0, 1.0, C, None, ws, fuse=True)
         assert np.array_equal(C.cpu().numpy(), oracle.int_gemm(Aq, Bq)), i
+        if i == 2:  # a second unpack of the same plan measures the row norms again: nothing may be left out then
+            imu.imunpack_unpack(plan, A_d, B_d, buf_a, buf_b)
+            check_bounds(plan, oa, ob, S, s)
         hnd.close()
     plan.keep_weights(False)
     imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
