@@ -211,19 +211,18 @@ int imunpack_plan_export(imunpack_plan_t *plan,
 int imunpack_plan_destroy(imunpack_plan_t *plan);
 
 /* ---- weights that stay resident (Sec. 4.2: weights are unpacked once, when they are loaded) -----
- * With UnpackBoth on the second operand, its unpacking Unpack(B_e, A_u, S_u, b, strategy_B) depends on
- * the first operand only through the column slots of A's unpacking (which columns B_e repeats, and their
- * exponents).  keep != 0 is the caller's promise that from now on B, its statistics and its OB list are
- * the same in every imunpack_plan on this plan object: a plan call then compares, on the device, the
- * column slots of A's unpacking with those of the call before and, if they are the same, takes the
- * second operand's unpacking over instead of running Alg. 4 on it again (no extra host wait; the result
- * is the same plan either way).  Otherwise, and in the first call after keep was set, B is unpacked as
- * usual.  When it was taken over, the layouts of B's rows and of the columns stand as they are too, and
- * the first imunpack_unpack after that plan call writes only the A store if it is given the B_eu buffer
- * that the unpack before wrote (same address, same digit format): B_eu and its row norms are already
- * what they would become.  imunpack_plan_weights_reused tells which of the two the last plan call did.
- * keep == 0 (the default) ends the promise.  Other strategies of B are planned in closed form and are not affected.
- * Errors: EINVAL (null plan). */
+ * The unpacking of the second operand, Unpack(B_e, A_u, S_u, b, strategy_B), depends on the first operand
+ * only through the column slots of A's unpacking (which columns B_e repeats, and their exponents).
+ * keep != 0 is the caller's promise that from now on B, its statistics and its OB list are the same in
+ * every imunpack_plan on this plan object: a plan call then compares, on the device, the column slots of
+ * A's unpacking with those of the call before and, if they are the same, takes the second operand's
+ * unpacking (for UnpackBoth: without running Alg. 4 on it again) and the layouts of B's rows and of the
+ * columns over as they stand (no extra host wait; the result is the same plan either way); the first
+ * imunpack_unpack after such a plan call writes only the A store if it is given the B_eu buffer that the
+ * unpack before wrote (same address, same digit format): B_eu and its row norms are already what they
+ * would become.  Otherwise, and in the first call after keep was set, B is unpacked as usual.
+ * imunpack_plan_weights_reused tells which of the two the last plan call did.  keep == 0 (the default)
+ * ends the promise.  Errors: EINVAL (null plan). */
 int imunpack_plan_keep_weights(imunpack_plan_t *plan, int keep);
 int imunpack_plan_weights_reused(const imunpack_plan_t *plan);
 

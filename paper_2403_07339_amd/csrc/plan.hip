@@ -165,8 +165,9 @@ __global__ void setup_kernel(PlanHeader *hdr, SlotSet a, int na, int32_t *count_
 
 // slots 0..N-1 become unsplit originals, N read from the device
 __global__ void identity_slots_kernel(SlotSet set, const int32_t *n_dev, int32_t *count_out, PlanHeader *hdr,
-                                      int which) {
+                                      int which, const int32_t *skip) {
     if (hdr->overflow) return;
+    if (skip && *skip) return;  // keep-weights mode: this set is taken over as it stands
     const int N = *n_dev;
     if (N > set.cap) {
         if (blockIdx.x == 0 && threadIdx.x == 0) flag_overflow(hdr, which, N);
@@ -183,9 +184,10 @@ __global__ void identity_slots_kernel(SlotSet set, const int32_t *n_dev, int32_t
 // the items that still have a digit there, in ascending x.
 __global__ __launch_bounds__(kPlanThreads) void level_major_kernel(
     SlotSet set, const int32_t *maxabs, const int32_t *via, int n_host, const int32_t *n_dev, int sh,
-    int32_t *tmpL, int32_t *tmpCur, int32_t *count_out, PlanHeader *hdr, int which) {
+    int32_t *tmpL, int32_t *tmpCur, int32_t *count_out, PlanHeader *hdr, int which, const int32_t *skip) {
     __shared__ int lds[40];
     if (hdr->overflow) return;
+    if (skip && *skip) return;  // keep-weights mode: this set is taken over as it stands
     const int N = n_dev ? *n_dev : n_host;
     if (N > set.cap) {
         if (threadIdx.x == 0) flag_overflow(hdr, which, N);
@@ -1416,26 +1418,20 @@ __global__ __launch_bounds__(256) void ob_copy_kernel(const int32_t *__restrict_
 // second operand depends on the first only through the column slots of the first operand's unpacking
 // (which columns of B_e are repeats, and their exponents).  If those are what they were for the plan
 // before, the second operand's slots, its kept OB entries and its header fields are taken over.
-__global__ void keep_compare_kernel(SlotSet c1, const int32_t *d1_dev, const int32_t *sroot, const int32_t *sexp,
-                                    const int32_t *schild, KeepState *ks, int host_valid) {
-    const int d1 = *d1_dev;
-    if (!host_valid || !ks->valid || d1 != ks->d1 || d1 > c1.cap) {
-        if (threadIdx.x == 0) ks->diff = 1;
-        return;
-    }
-    bool differs = false;
-    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < d1; x += gridDim.x * blockDim.x)
-        differs = differs || c1.root[x] != sroot[x] || c1.exp[x] != sexp[x] || c1.child[x] != schild[x];
-    if (differs) ks->diff = 1;
-}
-
-// Every workgroup reaches the same verdict.  Same slots: the header fields that the second operand's unpacking
-// and the layouts of its rows and of the columns left are put back.  Different: its rows start afresh and the
-// column weights are cleared for the column layout to come.
-__global__ void keep_decide_kernel(KeepState *ks, PlanHeader *hdr, SlotSet rowB, int h, int32_t *extra_rows,
-                                   int32_t *col_weights, int nweights) {
-    const bool same = !ks->diff && !hdr->overflow;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+// One workgroup: compares the column slots with the remembered ones and acts on the verdict.  Same slots: the
+// header fields that the second operand's unpacking and the layouts of its rows and of the columns left are
+// put back.  Different: its rows start afresh and the column weights are cleared for the column layout to come.
+__global__ __launch_bounds__(kPlanThreads) void keep_decide_kernel(
+    SlotSet c1, const int32_t *sroot, const int32_t *sexp, const int32_t *schild, KeepState *ks, int host_valid,
+    PlanHeader *hdr, SlotSet rowB, int h /* rows that start as unsplit originals */, int32_t *extra_rows, int nextra,
+    int32_t *col_weights, int nweights) {
+    const int d1 = hdr->d1;
+    bool differs = !host_valid || !ks->valid || d1 != ks->d1 || d1 > c1.cap || hdr->overflow != 0;
+    if (!differs)
+        for (int x = threadIdx.x; x < d1; x += kPlanThreads)
+            differs = differs || c1.root[x] != sroot[x] || c1.exp[x] != sexp[x] || c1.child[x] != schild[x];
+    const bool same = !__syncthreads_or(differs);
+    if (threadIdx.x == 0) {
         ks->same = same;
         hdr->reusedB = same;
         if (same) {
@@ -1443,31 +1439,27 @@ __global__ void keep_decide_kernel(KeepState *ks, PlanHeader *hdr, SlotSet rowB,
             hdr->h_u = o.h_u; hdr->d_u = o.d_u; hdr->nobB = o.nobB; hdr->edgesB = o.edgesB; hdr->extras = o.extras;
             hdr->Np = o.Np; hdr->Kp = o.Kp; hdr->KA = o.KA; hdr->ldA = o.ldA; hdr->ldB = o.ldB;
             hdr->ntiles = o.ntiles; hdr->lmaxB = o.lmaxB; hdr->ngroups = o.ngroups; hdr->nruns = o.nruns;
-        } else {
+        } else if (h) {
             hdr->h_u = h;
         }
     }
-    if (same) {  // the group and run tables, by the first workgroup's threads
-        if (blockIdx.x == 0) {
-            constexpr size_t g0 = offsetof(PlanHeader, grp_exp) / sizeof(int32_t), g1 = offsetof(PlanHeader, nruns) / sizeof(int32_t);
-            constexpr size_t r0 = offsetof(PlanHeader, run_kt0) / sizeof(int32_t), r1 = offsetof(PlanHeader, edgesA) / sizeof(int32_t);
-            const int32_t *src = reinterpret_cast<const int32_t *>(&ks->saved);
-            int32_t *dst = reinterpret_cast<int32_t *>(hdr);
-            for (size_t i = g0 + threadIdx.x; i < g1; i += blockDim.x) dst[i] = src[i];
-            for (size_t i = r0 + threadIdx.x; i < r1; i += blockDim.x) dst[i] = src[i];
-        }
+    if (same) {  // the group and run tables
+        constexpr size_t g0 = offsetof(PlanHeader, grp_exp) / sizeof(int32_t), g1 = offsetof(PlanHeader, nruns) / sizeof(int32_t);
+        constexpr size_t r0 = offsetof(PlanHeader, run_kt0) / sizeof(int32_t), r1 = offsetof(PlanHeader, edgesA) / sizeof(int32_t);
+        const int32_t *src = reinterpret_cast<const int32_t *>(&ks->saved);
+        int32_t *dst = reinterpret_cast<int32_t *>(hdr);
+        for (size_t i = g0 + threadIdx.x; i < g1; i += kPlanThreads) dst[i] = src[i];
+        for (size_t i = r0 + threadIdx.x; i < r1; i += kPlanThreads) dst[i] = src[i];
         return;
     }
-    const int stride = gridDim.x * blockDim.x, t0 = blockIdx.x * blockDim.x + threadIdx.x;
-    for (int x = t0; x < h; x += stride) {
-        identity_slot(rowB, x);
-        extra_rows[x] = 0;
-    }
-    for (int x = t0; x < nweights; x += stride) col_weights[x] = 0;
+    for (int x = threadIdx.x; x < h; x += kPlanThreads) identity_slot(rowB, x);
+    for (int x = threadIdx.x; x < nextra; x += kPlanThreads) extra_rows[x] = 0;
+    for (int x = threadIdx.x; x < nweights; x += kPlanThreads) col_weights[x] = 0;
 }
 
-// After the second operand has been unpacked anew: remember what it was unpacked for.
-__global__ void keep_snapshot_kernel(SlotSet c1, const PlanHeader *hdr, int32_t *sroot, int32_t *sexp, int32_t *schild,
+// After a plan that unpacked the second operand anew: remember the column slots it was unpacked for and the
+// header the plan completed.
+__global__ void keep_remember_kernel(SlotSet c1, const PlanHeader *hdr, int32_t *sroot, int32_t *sexp, int32_t *schild,
                                      KeepState *ks) {
     if (ks->same) return;
     if (hdr->overflow || hdr->err || hdr->d1 > c1.cap) {
@@ -1480,27 +1472,15 @@ __global__ void keep_snapshot_kernel(SlotSet c1, const PlanHeader *hdr, int32_t 
         sexp[x] = c1.exp[x];
         schild[x] = c1.child[x];
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        ks->d1 = d1;
-        ks->h_u = hdr->h_u;
-        ks->d_u = hdr->d_u;
-        ks->nobB = hdr->nobB;
-        ks->edgesB = hdr->edgesB;
-        ks->extras = hdr->extras;
-        ks->valid = 1;
+    if (blockIdx.x == 0) {
+        const int32_t *src = reinterpret_cast<const int32_t *>(hdr);
+        int32_t *dst = reinterpret_cast<int32_t *>(&ks->saved);
+        for (size_t i = threadIdx.x; i < sizeof(PlanHeader) / sizeof(int32_t); i += blockDim.x) dst[i] = src[i];
+        if (threadIdx.x == 0) {
+            ks->d1 = d1;
+            ks->valid = 1;
+        }
     }
-}
-
-// ... and, once the layouts are done, the header they completed.
-__global__ void keep_save_header_kernel(const PlanHeader *hdr, KeepState *ks) {
-    if (ks->same) return;
-    if (hdr->overflow || hdr->err) {
-        if (threadIdx.x == 0) ks->valid = 0;
-        return;
-    }
-    const int32_t *src = reinterpret_cast<const int32_t *>(hdr);
-    int32_t *dst = reinterpret_cast<int32_t *>(&ks->saved);
-    for (size_t i = threadIdx.x; i < sizeof(PlanHeader) / sizeof(int32_t); i += blockDim.x) dst[i] = src[i];
 }
 
 static constexpr int kGreedyLdsMax = 136 * 1024;  // dynamic LDS the greedy may use for the two count vectors
@@ -1566,7 +1546,7 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     const int kcA = phys_cap_cols(p->cap[CAP_C2]);
     // keep-weights mode (UnpackBoth on the second operand): its rows are set up only once it is known that its
     // unpacking has to be redone
-    const bool keep = p->keep_B && p->sB == IMUNPACK_BOTH;
+    const bool keep = p->keep_B != 0;
     hipLaunchKernelGGL(setup_kernel, dim3(grid_for(std::max(std::max(idA, idC1), std::max(idB, kcA)), 256, 64)),
                        dim3(256), 0, st, hdr, p->rowA, idA, &hdr->n_u, p->c1, idC1, &hdr->d1, p->rowB, keep ? 0 : idB,
                        &hdr->h_u, p->extraRows, (p->sB == IMUNPACK_BOTH && !keep) ? h : 0,
@@ -1590,42 +1570,38 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
     if (p->sA == IMUNPACK_ROW) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowA, p->statsA[2],
                            (const int32_t *)nullptr, n, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
-                           &hdr->n_u, hdr, (int)CAP_ROWA);
+                           &hdr->n_u, hdr, (int)CAP_ROWA, (const int32_t *)nullptr);
     } else if (p->sA == IMUNPACK_COL) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c1, p->statsA[3],
                            (const int32_t *)nullptr, d, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
-                           &hdr->d1, hdr, (int)CAP_C1);
+                           &hdr->d1, hdr, (int)CAP_C1, (const int32_t *)nullptr);
     } else {
         if (callerA) IMU_TRY(run_greedy(p, 1, stA->ob, (int)stA->ob_cap, stA->ob_count, CAP_LISTA, st));
         else IMU_TRY(run_greedy(p, 1, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st));
     }
     if (scanB) IMU_TRY(scan_operand(B, h, ldb, p->statsB, own_statsB, listB && !callerB));
     // ---- phase 2: Unpack(B_e, A_u, S_u, b, strategy_B); B_e has d1 columns
+    const int32_t *skip = nullptr;
+    if (keep) {
+        hipLaunchKernelGGL(keep_decide_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c1, (const int32_t *)p->snapRoot,
+                           (const int32_t *)p->snapExp, (const int32_t *)p->snapChild, p->d_keep, p->keep_valid, hdr, p->rowB,
+                           idB, p->extraRows, p->sB == IMUNPACK_BOTH ? h : 0, reinterpret_cast<int32_t *>(p->cols.colA_w),
+                           2 * kcA);
+        skip = &p->d_keep->same;
+    }
     if (p->sB == IMUNPACK_ROW) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->rowB, p->statsB[2],
                            (const int32_t *)nullptr, h, (const int32_t *)nullptr, p->sh, p->tmpL, p->tmpCur,
-                           &hdr->h_u, hdr, (int)CAP_ROWB);
+                           &hdr->h_u, hdr, (int)CAP_ROWB, skip);
         hipLaunchKernelGGL(identity_slots_kernel, dim3(grid_for(p->cap[CAP_C2], 256, 64)), dim3(256), 0, st,
-                           p->c2, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2);
+                           p->c2, (const int32_t *)&hdr->d1, &hdr->d_u, hdr, (int)CAP_C2, skip);
     } else if (p->sB == IMUNPACK_COL) {
         hipLaunchKernelGGL(level_major_kernel, dim3(1), dim3(kPlanThreads), 0, st, p->c2, p->statsB[3],
                            (const int32_t *)p->c1.root, 0, (const int32_t *)&hdr->d1, p->sh, p->tmpL,
-                           p->tmpCur, &hdr->d_u, hdr, (int)CAP_C2);
+                           p->tmpCur, &hdr->d_u, hdr, (int)CAP_C2, skip);
     } else {
-        const int32_t *skip = nullptr;
-        if (keep) {
-            hipLaunchKernelGGL(keep_compare_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 64)), dim3(256), 0, st, p->c1,
-                               (const int32_t *)&hdr->d1, (const int32_t *)p->snapRoot, (const int32_t *)p->snapExp,
-                               (const int32_t *)p->snapChild, p->d_keep, p->keep_valid);
-            hipLaunchKernelGGL(keep_decide_kernel, dim3(grid_for(std::max(h, 2 * kcA), 256, 64)), dim3(256), 0, st, p->d_keep,
-                               hdr, p->rowB, h, p->extraRows, reinterpret_cast<int32_t *>(p->cols.colA_w), 2 * kcA);
-            skip = &p->d_keep->same;
-        }
         if (callerB) IMU_TRY(run_greedy(p, 2, stB->ob, (int)stB->ob_cap, stB->ob_count, CAP_LISTB, st, skip));
         else IMU_TRY(run_greedy(p, 2, p->ob, p->cap[CAP_OB], &hdr->obcount, CAP_OB, st, skip));
-        if (keep)
-            hipLaunchKernelGGL(keep_snapshot_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 64)), dim3(256), 0, st, p->c1,
-                               (const PlanHeader *)hdr, p->snapRoot, p->snapExp, p->snapChild, p->d_keep);
     }
     // ---- physical layouts
     // the row layouts keep two ints per source row in LDS when that fits beside the column layout's tables
@@ -1641,7 +1617,9 @@ static int enqueue_plan(Plan *p, const int32_t *A, int64_t lda, const int32_t *B
                        phys_cap_rows(p->cap[CAP_ROWB]), p->tmpPB, p->c1, p->c2, p->cols, d,
                        phys_cap_cols(p->cap[CAP_C2]), p->s, p->sh, p->tmpE, p->tmpK, p->tmpR, p->tmpOff, hdr, fast_lds,
                        keep ? (const int32_t *)&p->d_keep->same : (const int32_t *)nullptr);
-    if (keep) hipLaunchKernelGGL(keep_save_header_kernel, dim3(1), dim3(256), 0, st, (const PlanHeader *)hdr, p->d_keep);
+    if (keep)
+        hipLaunchKernelGGL(keep_remember_kernel, dim3(grid_for(p->cap[CAP_C1], 256, 16)), dim3(256), 0, st, p->c1,
+                           (const PlanHeader *)hdr, p->snapRoot, p->snapExp, p->snapChild, p->d_keep);
     return launch_status();
 }
 
@@ -1757,7 +1735,7 @@ extern "C" int imunpack_plan(const int32_t *A, int64_t n, int64_t d, int64_t lda
         if (!p->hdr.overflow) {
             p->valid = 1;
             p->canon_valid = 0;
-            p->keep_valid = p->keep_B && strategy_B == IMUNPACK_BOTH;
+            p->keep_valid = p->keep_B;
             if (!p->hdr.reusedB) p->kept_Beu = nullptr;  // what an earlier unpack wrote belongs to another plan
             p->fp6 = p->digits_req == IMUNPACK_DIGITS_FP6 && b <= 4;
             p->bothA = strategy_A == IMUNPACK_BOTH;

@@ -361,12 +361,12 @@ def test_six_bit_digits_fused_path_and_format_rules(imu):
     assert plan.digits() == imu.DIGITS_INT8
 
 
-@pytest.mark.parametrize("sa", [BOTH, ROW, COL])
-def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
+@pytest.mark.parametrize("sa,sb", [(BOTH, BOTH), (ROW, BOTH), (COL, BOTH), (BOTH, COL), (ROW, COL), (COL, ROW), (BOTH, ROW)])
+def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa, sb):
     """Keep-weights mode (Sec. 4.2: weights unpacked once): with B fixed, a plan call reuses B's unpacking
     exactly when the column slots of A's unpacking are those of the call before.  Every call's plan (every
     split in order), unpacked operands and product are compared with the oracle's, reused or not."""
-    rng = np.random.default_rng(4242 + sa)
+    rng = np.random.default_rng(4242 + 3 * sa + sb)
     b, s = 8, 128
     n, d, h = 150, 300, 270
     Bq = rand_ints(rng, h, d, s, 0.02, 2)
@@ -393,15 +393,15 @@ def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
     for i, (cols, seed, want_reuse) in enumerate(seq):
         Aq = make_A(cols, seed)
         A_d = dev(torch.from_numpy(Aq))
-        imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+        imu.imunpack_plan(A_d, B_d, b, sa, sb, plan=plan)
         if i == 0:
             assert not plan.weights_reused()
             plan.keep_weights(True)      # from the next call on
-            imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+            imu.imunpack_plan(A_d, B_d, b, sa, sb, plan=plan)
             assert not plan.weights_reused()
         else:
             assert plan.weights_reused() == want_reuse, (i, cols)
-        hnd = oracle.unpack_pair_handle(Aq, Bq, b, sa, BOTH)
+        hnd = oracle.unpack_pair_handle(Aq, Bq, b, sa, sb)
         assert plan.dims()[:3] == (hnd.n_u, hnd.d_u, hnd.h_u)
         got = [t.numpy().astype(np.int64) for t in plan.export_all()]
         S, pas, paw, pbs, pbw = hnd.meta()
@@ -426,7 +426,7 @@ def test_keep_weights_takes_the_second_operand_over_only_when_it_may(imu, sa):
             check_bounds(plan, oa, ob, S, s)
         hnd.close()
     plan.keep_weights(False)
-    imu.imunpack_plan(A_d, B_d, b, sa, BOTH, plan=plan)
+    imu.imunpack_plan(A_d, B_d, b, sa, sb, plan=plan)
     assert not plan.weights_reused()
 
 
